@@ -1,0 +1,219 @@
+/*
+ * spec.h -- C ABI of the MI355X (gfx950) library for batched greedy speculative
+ * decoding: the draft model proposes s tokens for each of B sequences, the
+ * target model verifies all B*(s+1) tokens in one forward pass, the longest
+ * matching prefix plus one target token is accepted, the KV caches are committed
+ * or rolled back, and a profiled look-up table picks s for each batch size
+ * (paper: Alg. 1 and Sec. 2 "Speculative Decoding"; Sec. 3.1 for the batched
+ * form; Sec. 4 for the adaptive policy).
+ *
+ * Conventions
+ *   - Every function returns an int status: SPEC_OK or a SPEC_ERR_* code.  Nothing
+ *     throws or aborts.  spec_last_error() returns a message for the most recent
+ *     failure on that context (or the most recent failure without a context).
+ *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  Structures
+ *     (descriptors, spec_weights itself, the layer_tensors array) live on the host;
+ *     the tensors they point to live on the device.
+ *   - The library never allocates or frees device memory.  The caller owns the
+ *     weights, the workspace and the HIP stream and keeps them alive until
+ *     spec_destroy.  spec_init re-packs the weights into the workspace; the
+ *     caller's weight tensors are not read after spec_init returns.
+ *   - Step calls (reset, draft_step, verify_step, accept_commit, round) enqueue
+ *     work on the context's stream and return without waiting.  Calls that hand
+ *     data back to the host (read_output, read_state, profile_and_choose_s)
+ *     synchronise the stream.
+ *   - A call that fails validation leaves all state untouched.  Arguments are
+ *     validated before any device call, so misuse is reported without a GPU.
+ *   - One context must not be used from two threads at once.
+ *
+ * Notation (per sequence b): n_b = committed length (prompt + emitted tokens);
+ * the "pending" token is the last committed one, x_{n_b-1}, whose target KV is
+ * not yet written; t_1..t_s are the proposals for positions n_b..n_b+s-1;
+ * o_0..o_s are the target logits, o_i predicting position n_b+i; a_i = argmax o_i;
+ * l_b = number of accepted proposals.
+ */
+#ifndef SPEC_H
+#define SPEC_H
+#include <stddef.h>
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  SPEC_OK = 0,
+  SPEC_ERR_INVALID_ARG = 1, /* null pointer, value out of range                       */
+  SPEC_ERR_WORKSPACE = 2,   /* workspace missing, too small or misaligned             */
+  SPEC_ERR_STATE = 3,       /* call out of order                                      */
+  SPEC_ERR_CAPACITY = 4,    /* B, s or sequence length beyond what spec_init reserved */
+  SPEC_ERR_UNSUPPORTED = 5, /* model shape / option this build has no kernel for      */
+  SPEC_ERR_HIP = 6          /* a HIP runtime call failed                              */
+};
+
+enum { SPEC_DTYPE_F32 = 0, SPEC_DTYPE_BF16 = 1, SPEC_DTYPE_F16 = 2 };
+enum { SPEC_FFN_SWIGLU = 0, SPEC_FFN_RELU = 1 };
+enum { SPEC_NORM_RMS = 0, SPEC_NORM_LAYER = 1 };
+enum { SPEC_POS_ROPE = 0, SPEC_POS_LEARNED = 1 };
+enum { SPEC_PROPOSALS_DRAFT = 0, SPEC_PROPOSALS_EXTERNAL = 1 };
+enum { SPEC_MODEL_TARGET = 0, SPEC_MODEL_DRAFT = 1 };
+
+/* Per-layer tensor slots of spec_weights.layer_tensors (n_layers * SPEC_T_COUNT
+   device pointers, layer-major).  Every matrix is row-major [out][in]; every
+   tensor has the run's dtype.  Unused slots may be NULL.                        */
+enum {
+  SPEC_T_ATTN_NORM_W = 0, SPEC_T_ATTN_NORM_B, /* [d]; _B for LayerNorm only                */
+  SPEC_T_WQ, SPEC_T_BQ, SPEC_T_WK, SPEC_T_BK, /* [d][d], [d]; biases only if has_bias      */
+  SPEC_T_WV, SPEC_T_BV, SPEC_T_WO, SPEC_T_BO,
+  SPEC_T_FFN_NORM_W, SPEC_T_FFN_NORM_B,
+  SPEC_T_W1, SPEC_T_B1, /* SwiGLU: gate [f][d], no bias | ReLU: fc1 [f][d], bias [f]       */
+  SPEC_T_W3,            /* SwiGLU: up   [f][d]          | ReLU: unused                     */
+  SPEC_T_W2, SPEC_T_B2, /* SwiGLU: down [d][f], no bias | ReLU: fc2 [d][f], bias [d]       */
+  SPEC_T_COUNT
+};
+
+typedef struct spec_ctx spec_ctx; /* opaque; host memory owned by the library */
+
+/* A decoder-only transformer.  LLaMA shape: RMSNorm, rotary positions (rotate-half
+   pairing, element i with i + head_dim/2), SwiGLU, no biases.  OPT shape: LayerNorm,
+   learned absolute positions (row p of pos_emb for position p), ReLU FFN, biases.
+   Pre-norm residual blocks, attention scale 1/sqrt(head_dim), untied LM head.
+   head_dim = d_model / n_heads must be 64 or 128 for 16-bit runs.                 */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, d_ffn, vocab, max_pos;
+  int32_t ffn_kind, norm_kind, pos_kind, has_bias;
+  float norm_eps, rope_theta;
+} spec_model_desc;
+
+typedef struct {
+  const void *d_tok_emb;           /* [vocab][d]                          */
+  const void *d_pos_emb;           /* [max_pos][d], learned positions only */
+  const void *d_final_norm_w;      /* [d]                                 */
+  const void *d_final_norm_b;      /* [d], LayerNorm only                 */
+  const void *d_lm_head;           /* [vocab][d]                          */
+  const void *const *layer_tensors; /* host array, n_layers * SPEC_T_COUNT device pointers */
+} spec_weights;
+
+typedef struct {
+  int32_t dtype;         /* SPEC_DTYPE_*: storage type of weights, activations and KV cache;
+                            accumulation, softmax, norms and the residual stream are fp32  */
+  int32_t B_max;         /* most sequences in one batch                                    */
+  int32_t s_max;         /* longest speculation length                                     */
+  int32_t L_max;         /* KV-cache positions per sequence; needs P + gen_max + s_max     */
+  int32_t gen_max;       /* tokens to emit per sequence; a sequence that reached it is
+                            frozen (still computed, emits nothing)                         */
+  int32_t eos_id;        /* must be -1 (fixed-length generation only)                      */
+  int32_t proposal_mode; /* SPEC_PROPOSALS_DRAFT: t_j = the draft model's greedy token.
+                            SPEC_PROPOSALS_EXTERNAL: t_j supplied by the caller; a draft
+                            model, if present, still runs and ingests those tokens          */
+} spec_run_desc;
+
+const char *spec_last_error(const spec_ctx *ctx_or_null);
+
+/* Bytes of device workspace spec_init needs (packed weights of both models, both KV
+   caches, activations, per-sequence state).  drf may be NULL (no draft model).        */
+int spec_workspace_bytes(const spec_model_desc *tgt, const spec_model_desc *drf,
+                         const spec_run_desc *run, size_t *bytes);
+
+/* Create a context.  d_workspace: device memory, 256-byte aligned, at least
+   spec_workspace_bytes() large, owned by the caller.  hip_stream: a hipStream_t
+   (NULL = the default stream).  Re-packs both weight sets into the workspace
+   (device-side; synchronises the stream before returning).  drf / drf_w may both be
+   NULL; then s > 0 needs SPEC_PROPOSALS_EXTERNAL.                                     */
+int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w,
+              const spec_model_desc *drf, const spec_weights *drf_w,
+              const spec_run_desc *run, void *d_workspace, size_t workspace_bytes,
+              void *hip_stream, spec_ctx **out);
+int spec_destroy(spec_ctx *ctx);
+
+/* Start a batch of B sequences, each with the P prompt tokens d_prompt[b][0..P-1]
+   (int32, device).  Runs the prompt's first P-1 tokens through both models to fill
+   their KV caches (the prefill the paper's runtime model leaves out, Sec. 3.3); the
+   last prompt token becomes the pending token.  Needs 1 <= B <= B_max, P >= 1,
+   P + gen_max + s_max <= L_max (and <= max_pos for learned positions), token ids in
+   [0, vocab) (ids are clamped on the device, not checked).                           */
+int spec_reset(spec_ctx *ctx, int32_t B, const int32_t *d_prompt, int32_t P);
+
+/* As spec_reset but without touching the KV caches: the caller provides positions
+   0..P-2 through spec_kv_import.  For micro-benchmarks and tests that start from a
+   given cache.                                                                        */
+int spec_reset_noprefill(spec_ctx *ctx, int32_t B, const int32_t *d_prompt, int32_t P);
+
+/* Back to the state right after the last reset (lengths, counters, emitted tokens);
+   cached prompt KV is kept.                                                           */
+int spec_rewind(spec_ctx *ctx);
+
+/* External proposals, one of:
+   - spec_set_proposal_table: d_table[b][pos] (int32, row stride L_max) is the proposal
+     for absolute position pos of sequence b; each round reads t_j = table[b][n_b+j-1]
+     on the device, so rounds need no host round-trip.  The table must stay alive.
+   - spec_set_proposals: explicit t_1..t_s for the coming round, d_tok[b][0..s-1];
+     call it before the round's first draft step.
+   Both need SPEC_PROPOSALS_EXTERNAL.                                                  */
+int spec_set_proposal_table(spec_ctx *ctx, const int32_t *d_table);
+int spec_set_proposals(spec_ctx *ctx, const int32_t *d_tok, int32_t s);
+
+/* Draft step j (1-based) of the current round: the call speculate(S, kv_SSM, s) of
+   Alg. 1 is s of these in order.  Step 1 ingests the committed tokens the draft has
+   not read yet (one or two per sequence), step j >= 2 ingests t_{j-1}; each appends
+   the draft's KV and, in SPEC_PROPOSALS_DRAFT mode, writes t_j = argmax.             */
+int spec_draft_step(spec_ctx *ctx, int32_t j);
+
+/* Target verification: the call LLM(S, t_1..t_s, kv_LLM) of Alg. 1.  One forward pass
+   over B*(s+1) rows -- the pending token and the s proposals of every sequence -- at
+   positions n_b-1 .. n_b+s-1, attending to the cached prefix plus, causally, each
+   other; appends their K/V provisionally and leaves a_0..a_s per sequence on the
+   device.  d_logits_or_null: if not NULL receives o_0..o_s as fp32
+   [B][s+1][vocab] (debug / parity; costs an extra B*(s+1)*vocab*4 bytes of writes).  */
+int spec_verify_step(spec_ctx *ctx, int32_t s, float *d_logits_or_null);
+
+/* Acceptance and commit (Sec. 2; Alg. 1): l_b = number of leading proposals with
+   t_j = a_{j-1}; emit t_1..t_l, a_l; n_b += l_b+1; target cache length n_b-1; draft
+   cache length n_old + min(l_b, s-1).  Rejected positions are dropped by length only
+   (Sec. 3.1 masks them; the result is the same) and overwritten next round.          */
+int spec_accept_commit(spec_ctx *ctx, int32_t s);
+
+/* n_rounds complete rounds at speculation length s: [proposals from the table] ->
+   s draft steps -> verify -> accept/commit.  Same effect as the single calls.        */
+int spec_round(spec_ctx *ctx, int32_t s, int32_t n_rounds);
+
+/* Sec. 4, profiling stage.  For every batch size h_batch_sizes[i] (ascending) and
+   every s in 0..s_max_profile: reset with the first B rows of d_prompt ([maxB][P]),
+   run rounds until every sequence emitted gen tokens (gen <= gen_max), time the decode
+   rounds with HIP events, and record microseconds per emitted token.  The LUT entry
+   is the s with the lowest value, the smaller s winning ties within 1 %.  The LUT is
+   kept in the context for spec_choose_s.  h_lut_out: [n_b]; h_grid_us_per_tok_or_null:
+   [n_b][s_max_profile+1].  In SPEC_PROPOSALS_EXTERNAL mode a proposal table must be
+   set.  Synchronises; leaves the context reset to the last profiled batch.           */
+int spec_profile_and_choose_s(spec_ctx *ctx, const int32_t *h_batch_sizes, int32_t n_b,
+                              int32_t s_max_profile, const int32_t *d_prompt, int32_t P,
+                              int32_t gen, int32_t *h_lut_out, float *h_grid_us_per_tok_or_null);
+
+/* Install a LUT measured elsewhere (h_batch_sizes ascending). */
+int spec_set_lut(spec_ctx *ctx, const int32_t *h_batch_sizes, const int32_t *h_lut, int32_t n_b);
+
+/* Sec. 4, execution stage: s for a batch of B.  A profiled B returns its entry; an
+   un-profiled B the smaller entry of its two nearest profiled sizes; B beyond the
+   profiled range the entry of the nearest end.                                        */
+int spec_choose_s(const spec_ctx *ctx, int32_t B, int32_t *h_s_out);
+
+/* Emitted tokens so far: h_tokens [B][gen_max] (row stride gen_max), h_len [B].
+   h_hist_or_null: [s_max+1] counts of rounds*sequences by accepted length l.         */
+int spec_read_output(spec_ctx *ctx, int32_t *h_tokens, int32_t *h_len, int64_t *h_hist_or_null);
+
+/* Per-sequence state for tests: any pointer may be NULL.  h_n [B] committed lengths,
+   h_kv_draft [B] draft cache lengths, h_l_last [B] accepted count of the last round,
+   h_argmax [B][s_max+1] the a_i of the last verify step.                             */
+int spec_read_state(spec_ctx *ctx, int32_t *h_n, int32_t *h_kv_draft, int32_t *h_l_last, int32_t *h_argmax);
+
+/* Copy KV-cache rows between the caller's canonical layout and the library's private
+   one.  d_k, d_v: [B][len][d_model] in the run's dtype (keys as stored, i.e. after the
+   rotary embedding); positions 0..len-1 of the first B sequences of one layer.        */
+int spec_kv_import(spec_ctx *ctx, int32_t which_model, int32_t layer, int32_t B, int32_t len,
+                   const void *d_k, const void *d_v);
+int spec_kv_export(spec_ctx *ctx, int32_t which_model, int32_t layer, int32_t B, int32_t len,
+                   void *d_k, void *d_v);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

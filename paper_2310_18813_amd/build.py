@@ -1,0 +1,58 @@
+"""Builds the gfx950 shared library behind include/spec.h with hipcc (cross-compiles
+without a GPU).  Run as `python -m paper_2310_18813_amd.build` or via build()."""
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+OUT = os.path.join(HERE, "libspecdec.so")
+OBJ_DIR = os.path.join(HERE, "_build")
+
+SOURCES = ["spec_api.hip", "kernels_state.hip", "kernels_generic.hip"]
+
+# packed-fp32 VALU forms are kept out of the generated code (they have produced wrong
+# results on the test machines); the host pass warns that it does not know the feature
+FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def _headers_mtime():
+    hs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
+    hs.append(os.path.join(HERE, "..", "include", "spec.h"))
+    return max(os.path.getmtime(h) for h in hs)
+
+
+def build(force=True, verbose=False):
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    hm = _headers_mtime()
+    jobs = []
+    objs = []
+    for src in SOURCES:
+        s = os.path.join(CSRC, src)
+        o = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
+        objs.append(o)
+        if force or not os.path.exists(o) or os.path.getmtime(o) < max(os.path.getmtime(s), hm):
+            jobs.append(["hipcc", "-c", s, "-o", o] + FLAGS)
+
+    def run(cmd):
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed:\n%s\n%s" % (" ".join(cmd), r.stderr[-8000:]))
+        return r.stderr
+
+    with ThreadPoolExecutor(max_workers=min(8, max(1, len(jobs)))) as ex:
+        for warn in ex.map(run, jobs):
+            if verbose and warn.strip():
+                print(warn)
+    if jobs or not os.path.exists(OUT):
+        run(["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", OUT] + objs)
+    return OUT
+
+
+if __name__ == "__main__":
+    build(force="--incremental" not in sys.argv, verbose=True)
+    print(OUT)

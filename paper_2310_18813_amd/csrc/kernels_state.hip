@@ -1,0 +1,272 @@
+// Kernels that move tokens and per-sequence state: pass assembly + embedding gather,
+// norms, arg-max, acceptance/commit, proposal handling, reset/rewind, KV import/export.
+#include "spec_internal.h"
+#include "device_utils.h"
+
+namespace spec {
+
+// -------------------------------------------------------------------------
+// Row assembly + embedding.  One block per row m = b*q + i.  Decides which token the
+// row carries and at which absolute position (pos = -1 marks a dead row: no KV write,
+// no attention, logits ignored), then gathers the embedding (plus the learned position
+// row for OPT-shape models) into the fp32 residual stream.
+// Verification rows follow Alg. 1's call LLM(S, t_1..t_s): pending token, then proposals.
+template <class T>
+__global__ void k_assemble_embed(int kind, int q, int j, int P, int s_max, int L_max, int vocab, int d,
+                                 int learned_pos, const int32_t *__restrict__ seq, const int32_t *__restrict__ n,
+                                 const int32_t *__restrict__ kv_draft, const int32_t *__restrict__ t,
+                                 const T *__restrict__ tok_emb, const T *__restrict__ pos_emb,
+                                 int32_t *__restrict__ row_tok, int32_t *__restrict__ row_pos, float *__restrict__ h) {
+  const int m = blockIdx.x, b = m / q, i = m % q;
+  int tok = 0, pos = -1;
+  const int nb = n[b];
+  if (kind == PASS_VERIFY) {
+    pos = nb - 1 + i;
+    tok = (i == 0) ? seq[(size_t)b * L_max + nb - 1] : t[(size_t)b * s_max + i - 1];
+  } else if (kind == PASS_DRAFT_FIRST) {
+    int p = nb - q + i;
+    if (p >= 0 && p >= kv_draft[b]) { pos = p; tok = seq[(size_t)b * L_max + p]; }
+  } else if (kind == PASS_DRAFT_NEXT) {
+    pos = nb + j - 2;
+    tok = t[(size_t)b * s_max + j - 2];
+  } else {  // PASS_PREFILL: j is the base position
+    int p = j + i;
+    if (p < P - 1) { pos = p; tok = seq[(size_t)b * L_max + p]; }
+  }
+  if (pos >= L_max) pos = -1;  // cannot happen when the host checks hold; never write out of range
+  tok = min(max(tok, 0), vocab - 1);
+  if (threadIdx.x == 0) { row_tok[m] = tok; row_pos[m] = pos; }
+  float *hr = h + (size_t)m * d;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    float e = 0.f;
+    if (pos >= 0) {
+      e = Conv<T>::ld(tok_emb, (size_t)tok * d + c);
+      if (learned_pos) e += Conv<T>::ld(pos_emb, (size_t)pos * d + c);
+    }
+    hr[c] = e;
+  }
+}
+
+void launch_assemble_embed(const spec_ctx *c, const Model &m, const PassArgs &pa, hipStream_t st) {
+  const int M = pa.B * pa.q;
+  SPEC_DISPATCH_DTYPE(c->run.dtype, T,
+    hipLaunchKernelGGL(k_assemble_embed<T>, dim3(M), dim3(256), 0, st, (int)pa.kind, pa.q, pa.j, pa.P,
+                       c->run.s_max, c->run.L_max, m.desc.vocab, m.desc.d_model,
+                       (int)(m.desc.pos_kind == SPEC_POS_LEARNED), c->st.seq, c->st.n, c->drf.kv_len, c->st.t,
+                       (const T *)m.tok_emb, (const T *)m.pos_emb, c->ws.row_tok, c->ws.row_pos, c->ws.h));
+}
+
+// -------------------------------------------------------------------------
+// RMSNorm / LayerNorm over rows of the fp32 residual stream, output in the model dtype.
+// One 256-thread block per output row; statistics in fp32 with a fixed reduction tree
+// (per-thread strided partial, wave butterfly, then the four wave results in order), so a
+// row's result never depends on which other rows are in the pass.
+__device__ __forceinline__ float block_sum_256(float v, float *sh) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[w] = v;
+  __syncthreads();
+  return ((sh[0] + sh[1]) + sh[2]) + sh[3];
+}
+
+template <class T>
+__global__ void k_norm(int kind, int d, float eps, const float *__restrict__ h, const T *__restrict__ gain,
+                       const T *__restrict__ bias, const int32_t *__restrict__ gather, T *__restrict__ x) {
+  __shared__ float sh[4];
+  const int r = blockIdx.x;
+  const float *hr = h + (size_t)(gather ? gather[r] : r) * d;
+  T *xr = x + (size_t)r * d;
+  if (kind == SPEC_NORM_RMS) {
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < d; c += 256) { float v = hr[c]; ss = fmaf(v, v, ss); }
+    ss = block_sum_256(ss, sh);
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    for (int c = threadIdx.x; c < d; c += 256) Conv<T>::st(xr, c, hr[c] * inv * Conv<T>::ld(gain, c));
+  } else {
+    float s = 0.f;
+    for (int c = threadIdx.x; c < d; c += 256) s += hr[c];
+    const float mean = block_sum_256(s, sh) / (float)d;
+    float vs = 0.f;
+    for (int c = threadIdx.x; c < d; c += 256) { float v = hr[c] - mean; vs = fmaf(v, v, vs); }
+    const float inv = 1.0f / sqrtf(block_sum_256(vs, sh) / (float)d + eps);
+    for (int c = threadIdx.x; c < d; c += 256)
+      Conv<T>::st(xr, c, (hr[c] - mean) * inv * Conv<T>::ld(gain, c) + Conv<T>::ld(bias, c));
+  }
+}
+
+void launch_norm(const spec_ctx *c, const Model &m, const float *h, const void *gain, const void *bias, void *x,
+                 int M, const int32_t *row_gather, hipStream_t st) {
+  if (M <= 0) return;
+  SPEC_DISPATCH_DTYPE(c->run.dtype, T,
+    hipLaunchKernelGGL(k_norm<T>, dim3(M), dim3(256), 0, st, m.desc.norm_kind, m.desc.d_model, m.desc.norm_eps, h,
+                       (const T *)gain, (const T *)bias, row_gather, (T *)x));
+}
+
+// -------------------------------------------------------------------------
+// Greedy token per row (Alg. 1 prints "argmin"; Sec. 2 and the caption say the most
+// probable token, so arg-max).  Lowest index wins ties.  Row m of the logits goes to
+// out[(m / q) * out_stride + m % q].
+__global__ void k_argmax_rows(const float *__restrict__ logits, int V, int q, int out_stride, int32_t *__restrict__ out) {
+  __shared__ float shv[4];
+  __shared__ int shi[4];
+  const int m = blockIdx.x;
+  const float *row = logits + (size_t)m * V;
+  float bv = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int c = threadIdx.x; c < V; c += 256) argmax_combine(bv, bi, row[c], c);
+  wave_argmax(bv, bi);
+  if ((threadIdx.x & 63) == 0) { shv[threadIdx.x >> 6] = bv; shi[threadIdx.x >> 6] = bi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) argmax_combine(bv, bi, shv[w], shi[w]);
+    if (bi < 0 || bi >= V) bi = 0;
+    out[(size_t)(m / q) * out_stride + m % q] = bi;
+  }
+}
+
+void launch_argmax_rows(const float *logits, int M, int V, int q, int out_stride, int32_t *out, hipStream_t st) {
+  if (M <= 0) return;
+  hipLaunchKernelGGL(k_argmax_rows, dim3(M), dim3(256), 0, st, logits, V, q, out_stride, out);
+}
+
+// -------------------------------------------------------------------------
+// head_rows: which rows of the pass need logits (all of them for verification, the last
+// row of every sequence for a draft step).
+__global__ void k_head_rows(int B, int q, int last_only, int32_t *__restrict__ rows) {
+  int r = blockIdx.x * blockDim.x + threadIdx.x;
+  int Mh = last_only ? B : B * q;
+  if (r < Mh) rows[r] = last_only ? r * q + q - 1 : r;
+}
+void launch_head_rows(spec_ctx *c, int B, int q, bool last_only, hipStream_t st) {
+  int Mh = last_only ? B : B * q;
+  hipLaunchKernelGGL(k_head_rows, dim3((Mh + 255) / 256), dim3(256), 0, st, B, q, (int)last_only, c->ws.head_rows);
+}
+
+// -------------------------------------------------------------------------
+// Draft step epilogue: in draft-proposal mode the draft's greedy token becomes t_j.
+__global__ void k_store_draft_token(int B, int j, int s_max, int write, const int32_t *__restrict__ arg,
+                                    int32_t *__restrict__ t) {
+  int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B && write) t[(size_t)b * s_max + j - 1] = arg[b];
+}
+void launch_store_draft_token(spec_ctx *c, int j, bool write_proposal, hipStream_t st) {
+  hipLaunchKernelGGL(k_store_draft_token, dim3((c->B + 63) / 64), dim3(64), 0, st, c->B, j, c->run.s_max,
+                     (int)write_proposal, c->st.draft_arg, c->st.t);
+}
+
+// External proposals: t_j = table[b][n_b + j - 1] (absolute position), or a plain copy.
+__global__ void k_fill_proposals(int B, int s, int s_max, int L_max, const int32_t *__restrict__ table,
+                                 const int32_t *__restrict__ n, int32_t *__restrict__ t) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B * s) return;
+  int b = i / s, jj = i % s;
+  int p = n[b] + jj;
+  t[(size_t)b * s_max + jj] = (p < L_max) ? table[(size_t)b * L_max + p] : 0;
+}
+void launch_fill_proposals(spec_ctx *c, int s, hipStream_t st) {
+  if (s <= 0) return;
+  hipLaunchKernelGGL(k_fill_proposals, dim3((c->B * s + 255) / 256), dim3(256), 0, st, c->B, s, c->run.s_max,
+                     c->run.L_max, c->prop_table, c->st.n, c->st.t);
+}
+__global__ void k_copy_proposals(int B, int s, int s_max, const int32_t *__restrict__ src, int32_t *__restrict__ t) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B * s) return;
+  t[(size_t)(i / s) * s_max + i % s] = src[i];
+}
+void launch_copy_proposals(spec_ctx *c, const int32_t *d_tok, int s, hipStream_t st) {
+  if (s <= 0) return;
+  hipLaunchKernelGGL(k_copy_proposals, dim3((c->B * s + 255) / 256), dim3(256), 0, st, c->B, s, c->run.s_max, d_tok,
+                     c->st.t);
+}
+
+// -------------------------------------------------------------------------
+// Acceptance + commit, one thread per sequence (Sec. 2, Alg. 1): a proposal survives
+// only while all earlier ones matched the target's greedy token; the target's token after
+// the last survivor is appended.  Rollback is by length only: the K/V rows written for
+// rejected positions stay in the cache and are overwritten by the next round.
+__global__ void k_accept(int B, int s, int s_max, int L_max, int P, int gen_max, int draft_steps,
+                         const int32_t *__restrict__ t, const int32_t *__restrict__ a, int32_t *__restrict__ seq,
+                         int32_t *__restrict__ n, int32_t *__restrict__ kv_draft, int32_t *__restrict__ l_last,
+                         unsigned long long *__restrict__ hist, unsigned long long *__restrict__ counters) {
+  int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b == 0) atomicAdd(&counters[1], 1ull);
+  if (b >= B) return;
+  const int n_old = n[b];
+  const int gen = n_old - P;
+  const int32_t *tb = t + (size_t)b * s_max;
+  const int32_t *ab = a + (size_t)b * (s_max + 1);
+  int l = 0;
+  while (l < s && tb[l] == ab[l]) ++l;
+  int take = min(l + 1, gen_max - gen);
+  if (take < 0) take = 0;
+  for (int i = 0; i < take; ++i) seq[(size_t)b * L_max + n_old + i] = (i < l) ? tb[i] : ab[l];
+  const int n_new = n_old + take;
+  n[b] = n_new;
+  l_last[b] = l;
+  if (draft_steps > 0 && kv_draft) {
+    int kd = n_old + min(l, draft_steps - 1);
+    kv_draft[b] = max(0, min(kd, n_new - 1));
+  }
+  if (gen < gen_max) {
+    atomicAdd(&hist[l], 1ull);
+    atomicAdd(&counters[0], (unsigned long long)take);
+  }
+}
+void launch_accept(spec_ctx *c, int s, hipStream_t st) {
+  hipLaunchKernelGGL(k_accept, dim3((c->B + 63) / 64), dim3(64), 0, st, c->B, s, c->run.s_max, c->run.L_max, c->P,
+                     c->run.gen_max, c->draft_j, c->st.t, c->st.a, c->st.seq, c->st.n, c->drf.kv_len, c->st.l_last,
+                     c->st.hist, c->st.counters);
+}
+
+// -------------------------------------------------------------------------
+__global__ void k_state_reset(int B, int P, int L_max, int s_max, const int32_t *__restrict__ prompt,
+                              int32_t *__restrict__ seq, int32_t *__restrict__ n, int32_t *__restrict__ kv_draft,
+                              int32_t *__restrict__ l_last, unsigned long long *__restrict__ hist,
+                              unsigned long long *__restrict__ counters) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (prompt && i < B * P) seq[(size_t)(i / P) * L_max + i % P] = prompt[i];
+  if (i < B) { n[i] = P; l_last[i] = 0; if (kv_draft) kv_draft[i] = P - 1; }
+  if (i <= s_max) hist[i] = 0ull;
+  if (i < 2) counters[i] = 0ull;
+}
+void launch_state_reset(spec_ctx *c, const int32_t *d_prompt, hipStream_t st) {
+  int work = c->B * c->P;
+  if (work < c->run.s_max + 1) work = c->run.s_max + 1;
+  if (work < 2) work = 2;
+  hipLaunchKernelGGL(k_state_reset, dim3((work + 255) / 256), dim3(256), 0, st, c->B, c->P, c->run.L_max,
+                     c->run.s_max, d_prompt, c->st.seq, c->st.n, c->drf.kv_len, c->st.l_last, c->st.hist,
+                     c->st.counters);
+}
+
+// -------------------------------------------------------------------------
+// KV import / export between the caller's [B][len][d_model] layout and the cache layout
+// (keys pair-interleaved inside each head, values blocked by 8 positions).
+template <class T>
+__global__ void k_kv_convert(int import_, int B, int len, int H, int hd, int L_pad, T *__restrict__ kc,
+                             T *__restrict__ vc, T *__restrict__ k_user, T *__restrict__ v_user) {
+  const int d = H * hd;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)B * len * d) return;
+  int c = (int)(i % d);
+  size_t r = i / d;
+  int pos = (int)(r % len), b = (int)(r / len);
+  int hh = c / hd, e = c % hd;
+  size_t ki = kv_k_index(L_pad, H, hd, b, hh, pos, hd_interleave(e, hd));
+  size_t vi = kv_v_index(L_pad, H, hd, b, hh, pos, e);
+  if (import_) { kc[ki] = k_user[i]; vc[vi] = v_user[i]; }
+  else { k_user[i] = kc[ki]; v_user[i] = vc[vi]; }
+}
+void launch_kv_convert(spec_ctx *c, const Model &m, int layer, int B, int len, void *k, void *v, bool import_,
+                       hipStream_t st) {
+  size_t total = (size_t)B * len * m.desc.d_model;
+  if (!total) return;
+  size_t esz = dtype_bytes(c->run.dtype);
+  char *kc = (char *)m.kcache + (size_t)layer * m.kv_area_elems * esz;
+  char *vc = (char *)m.vcache + (size_t)layer * m.kv_area_elems * esz;
+  SPEC_DISPATCH_DTYPE(c->run.dtype, T,
+    hipLaunchKernelGGL(k_kv_convert<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (int)import_, B, len,
+                       m.desc.n_heads, m.hd, m.L_pad, (T *)kc, (T *)vc, (T *)k, (T *)v));
+}
+
+}  // namespace spec

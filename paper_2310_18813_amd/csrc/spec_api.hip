@@ -1,0 +1,631 @@
+// Host runtime behind the C ABI of include/spec.h: argument validation, workspace
+// carving, launch sequencing of one speculative-decoding round (Alg. 1), the profiling
+// grid and the batch-size -> speculation-length table (Sec. 4).
+#include "spec_internal.h"
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+using namespace spec;
+
+
+static thread_local std::string g_err;
+
+static int fail(spec_ctx *c, int code, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  if (c) c->err = buf;
+  return code;
+}
+#define HIPCHK(c, call)                                                                      \
+  do {                                                                                       \
+    hipError_t e_ = (call);                                                                  \
+    if (e_ != hipSuccess) return fail((c), SPEC_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+extern "C" const char *spec_last_error(const spec_ctx *c) { return c ? c->err.c_str() : g_err.c_str(); }
+
+// ------------------------------------------------------------------ sizing
+static size_t al256(size_t b) { return (b + 255) & ~(size_t)255; }
+constexpr int PREFILL_CHUNK = 8;
+constexpr int Q_LIMIT = 16;  // rows per sequence in one pass (attention query tile)
+
+static int check_model(const spec_model_desc *d, const char *who, int dtype) {
+  if (d->n_layers < 1 || d->d_model < 2 || d->n_heads < 1 || d->d_ffn < 1 || d->vocab < 1)
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s: n_layers, d_model, n_heads, d_ffn, vocab must be positive", who);
+  if (d->d_model % d->n_heads != 0 || (d->d_model / d->n_heads) % 2 != 0)
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s: d_model must be a multiple of n_heads with an even head_dim", who);
+  if (d->ffn_kind != SPEC_FFN_SWIGLU && d->ffn_kind != SPEC_FFN_RELU)
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s: unknown ffn_kind %d", who, d->ffn_kind);
+  if (d->norm_kind != SPEC_NORM_RMS && d->norm_kind != SPEC_NORM_LAYER)
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s: unknown norm_kind %d", who, d->norm_kind);
+  if (d->pos_kind != SPEC_POS_ROPE && d->pos_kind != SPEC_POS_LEARNED)
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s: unknown pos_kind %d", who, d->pos_kind);
+  if (d->pos_kind == SPEC_POS_LEARNED && d->max_pos < 1)
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s: learned positions need max_pos >= 1", who);
+  if (!(d->norm_eps > 0.f)) return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s: norm_eps must be positive", who);
+  if (d->pos_kind == SPEC_POS_ROPE && !(d->rope_theta > 1.f))
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s: rope_theta must exceed 1", who);
+  (void)dtype;
+  return SPEC_OK;
+}
+
+static int check_run(const spec_run_desc *r) {
+  if (r->dtype < SPEC_DTYPE_F32 || r->dtype > SPEC_DTYPE_F16)
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "run: unknown dtype %d", r->dtype);
+  if (r->B_max < 1 || r->B_max > 4096) return fail(nullptr, SPEC_ERR_INVALID_ARG, "run: B_max must be in 1..4096");
+  if (r->s_max < 0 || r->s_max + 1 > Q_LIMIT)
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "run: s_max must be in 0..%d", Q_LIMIT - 1);
+  if (r->gen_max < 1) return fail(nullptr, SPEC_ERR_INVALID_ARG, "run: gen_max must be positive");
+  if (r->L_max < r->gen_max + r->s_max + 1)
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "run: L_max must be at least gen_max + s_max + 1");
+  if (r->eos_id != -1) return fail(nullptr, SPEC_ERR_UNSUPPORTED, "run: eos_id must be -1 (fixed-length generation)");
+  if (r->proposal_mode != SPEC_PROPOSALS_DRAFT && r->proposal_mode != SPEC_PROPOSALS_EXTERNAL)
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "run: unknown proposal_mode %d", r->proposal_mode);
+  return SPEC_OK;
+}
+
+struct Sizes {
+  int M_max, q_pass;
+  size_t state, act, tgt_w, tgt_kv, drf_w, drf_kv, total;
+  size_t kv_area_tgt, kv_area_drf;
+  int L_pad;
+};
+
+static size_t packed_bytes(const spec_model_desc &d, int dtype) { return generic_packed_bytes(d, dtype); }
+
+static Sizes compute_sizes(const spec_model_desc *tgt, const spec_model_desc *drf, const spec_run_desc *run) {
+  Sizes z{};
+  const size_t e = dtype_bytes(run->dtype);
+  z.q_pass = std::max(run->s_max + 1, PREFILL_CHUNK);
+  z.M_max = run->B_max * z.q_pass;
+  z.L_pad = (run->L_max + KV_VBLOCK - 1) / KV_VBLOCK * KV_VBLOCK;
+  const size_t B = run->B_max, L = run->L_max, s = run->s_max, M = z.M_max;
+  z.state = al256(B * L * 4) + 4 * al256(B * 4) + al256(B * std::max<size_t>(s, 1) * 4) + al256(B * (s + 1) * 4) +
+            al256((s + 1) * 8) + al256(16);
+  size_t d = tgt->d_model, f = tgt->d_ffn, V = tgt->vocab;
+  size_t kf = tgt->ffn_kind == SPEC_FFN_SWIGLU ? 2 : 1;
+  size_t wide = std::max(3 * d, kf * f);
+  if (drf) {
+    d = std::max<size_t>(d, drf->d_model);
+    f = std::max<size_t>(f, drf->d_ffn);
+    V = std::max<size_t>(V, drf->vocab);
+    size_t kfd = drf->ffn_kind == SPEC_FFN_SWIGLU ? 2 : 1;
+    wide = std::max(wide, std::max<size_t>(3 * (size_t)drf->d_model, kfd * drf->d_ffn));
+  }
+  z.act = al256(M * d * 4) + 3 * al256(M * d * e) + al256(M * f * e) + al256(M * wide * 4) + al256(M * V * 4) +
+          4 * al256(M * 4);
+  z.tgt_w = packed_bytes(*tgt, run->dtype);
+  z.kv_area_tgt = B * (size_t)tgt->d_model * z.L_pad;
+  z.tgt_kv = 2 * al256((size_t)tgt->n_layers * z.kv_area_tgt * e);
+  if (drf) {
+    z.drf_w = packed_bytes(*drf, run->dtype);
+    z.kv_area_drf = B * (size_t)drf->d_model * z.L_pad;
+    z.drf_kv = 2 * al256((size_t)drf->n_layers * z.kv_area_drf * e);
+  }
+  z.total = z.state + z.act + z.tgt_w + z.tgt_kv + z.drf_w + z.drf_kv;
+  return z;
+}
+
+extern "C" int spec_workspace_bytes(const spec_model_desc *tgt, const spec_model_desc *drf, const spec_run_desc *run,
+                                    size_t *bytes) {
+  if (!tgt || !run || !bytes) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_workspace_bytes: null argument");
+  int rc = check_run(run);
+  if (rc) return rc;
+  if ((rc = check_model(tgt, "target", run->dtype))) return rc;
+  if (drf && (rc = check_model(drf, "draft", run->dtype))) return rc;
+  if (drf && drf->vocab != tgt->vocab)
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "draft and target must share one vocabulary");
+  *bytes = compute_sizes(tgt, drf, run).total;
+  return SPEC_OK;
+}
+
+// ------------------------------------------------------------------ init
+static int check_weights(const spec_model_desc *d, const spec_weights *w, const char *who) {
+  if (!w->d_tok_emb || !w->d_final_norm_w || !w->d_lm_head || !w->layer_tensors)
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s weights: tok_emb, final_norm_w, lm_head, layer_tensors required", who);
+  if (d->pos_kind == SPEC_POS_LEARNED && !w->d_pos_emb)
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s weights: pos_emb required for learned positions", who);
+  if (d->norm_kind == SPEC_NORM_LAYER && !w->d_final_norm_b)
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s weights: final_norm_b required for LayerNorm", who);
+  const bool ln = d->norm_kind == SPEC_NORM_LAYER, hb = d->has_bias != 0, swi = d->ffn_kind == SPEC_FFN_SWIGLU;
+  for (int l = 0; l < d->n_layers; ++l) {
+    const void *const *T = w->layer_tensors + (size_t)l * SPEC_T_COUNT;
+    bool ok = T[SPEC_T_ATTN_NORM_W] && T[SPEC_T_WQ] && T[SPEC_T_WK] && T[SPEC_T_WV] && T[SPEC_T_WO] &&
+              T[SPEC_T_FFN_NORM_W] && T[SPEC_T_W1] && T[SPEC_T_W2];
+    if (ln) ok = ok && T[SPEC_T_ATTN_NORM_B] && T[SPEC_T_FFN_NORM_B];
+    if (hb) ok = ok && T[SPEC_T_BQ] && T[SPEC_T_BK] && T[SPEC_T_BV] && T[SPEC_T_BO];
+    if (swi) ok = ok && T[SPEC_T_W3];
+    if (hb && !swi) ok = ok && T[SPEC_T_B1] && T[SPEC_T_B2];
+    if (!ok) return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s weights: layer %d misses a required tensor", who, l);
+  }
+  return SPEC_OK;
+}
+
+static void *carve(char *&p, size_t bytes) {
+  void *r = p;
+  p += al256(bytes);
+  return r;
+}
+
+static int setup_model(spec_ctx *c, Model &m, const spec_model_desc *d, const spec_weights *w, char *&p,
+                       size_t w_bytes, size_t kv_area, size_t kv_bytes, int L_pad) {
+  m.present = true;
+  m.desc = *d;
+  m.hd = d->d_model / d->n_heads;
+  m.L_pad = L_pad;
+  m.fast = false;
+  m.layers.resize(d->n_layers);
+  void *cursor = p;
+  generic_repack_top(c, m, w, cursor, c->stream);
+  for (int l = 0; l < d->n_layers; ++l) generic_repack_layer(c, m, l, w, cursor, c->stream);
+  if ((size_t)((char *)cursor - p) > w_bytes) return fail(c, SPEC_ERR_WORKSPACE, "internal: packed weights overflow");
+  p += w_bytes;
+  m.kv_area_elems = kv_area;
+  m.kcache = p;
+  m.vcache = p + kv_bytes / 2;
+  p += kv_bytes;
+  return SPEC_OK;
+}
+
+extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, const spec_model_desc *drf,
+                         const spec_weights *drf_w, const spec_run_desc *run, void *d_workspace,
+                         size_t workspace_bytes, void *hip_stream, spec_ctx **out) {
+  if (!out) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_init: out is null");
+  *out = nullptr;
+  if (!tgt || !tgt_w || !run) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_init: target model, weights and run are required");
+  if ((drf == nullptr) != (drf_w == nullptr))
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_init: give both the draft description and its weights, or neither");
+  size_t need = 0;
+  int rc = spec_workspace_bytes(tgt, drf, run, &need);
+  if (rc) return rc;
+  if ((rc = check_weights(tgt, tgt_w, "target"))) return rc;
+  if (drf && (rc = check_weights(drf, drf_w, "draft"))) return rc;
+  if (!drf && run->proposal_mode == SPEC_PROPOSALS_DRAFT && run->s_max > 0)
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_init: s_max > 0 with SPEC_PROPOSALS_DRAFT needs a draft model");
+  if (!d_workspace) return fail(nullptr, SPEC_ERR_WORKSPACE, "spec_init: workspace is null");
+  if ((uintptr_t)d_workspace % 256 != 0) return fail(nullptr, SPEC_ERR_WORKSPACE, "spec_init: workspace must be 256-byte aligned");
+  if (workspace_bytes < need)
+    return fail(nullptr, SPEC_ERR_WORKSPACE, "spec_init: workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  // generic attention keeps one fp32 score per key in LDS
+  if ((size_t)run->L_max * 4 + 64 > 64 * 1024)
+    return fail(nullptr, SPEC_ERR_UNSUPPORTED, "spec_init: L_max above 16368 is not supported");
+
+  spec_ctx *c = new (std::nothrow) spec_ctx();
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_init: out of host memory");
+  c->run = *run;
+  c->stream = (hipStream_t)hip_stream;
+  Sizes z = compute_sizes(tgt, drf, run);
+  c->M_max = z.M_max;
+  char *p = (char *)d_workspace;
+  const size_t B = run->B_max, L = run->L_max, s = run->s_max, M = z.M_max, e = dtype_bytes(run->dtype);
+  State &S = c->st;
+  S.seq = (int32_t *)carve(p, B * L * 4);
+  S.n = (int32_t *)carve(p, B * 4);
+  S.l_last = (int32_t *)carve(p, B * 4);
+  S.draft_arg = (int32_t *)carve(p, B * 4);
+  c->drf.kv_len = (int32_t *)carve(p, B * 4);
+  S.t = (int32_t *)carve(p, B * std::max<size_t>(s, 1) * 4);
+  S.a = (int32_t *)carve(p, B * (s + 1) * 4);
+  S.hist = (unsigned long long *)carve(p, (s + 1) * 8);
+  S.counters = (unsigned long long *)carve(p, 16);
+  size_t d = tgt->d_model, f = tgt->d_ffn, V = tgt->vocab;
+  size_t wide = std::max(3 * d, (tgt->ffn_kind == SPEC_FFN_SWIGLU ? 2 : 1) * f);
+  if (drf) {
+    d = std::max<size_t>(d, drf->d_model);
+    f = std::max<size_t>(f, drf->d_ffn);
+    V = std::max<size_t>(V, drf->vocab);
+    wide = std::max(wide, std::max<size_t>(3 * (size_t)drf->d_model,
+                                           (drf->ffn_kind == SPEC_FFN_SWIGLU ? 2 : 1) * (size_t)drf->d_ffn));
+  }
+  Workspace &W = c->ws;
+  W.h = (float *)carve(p, M * d * 4);
+  W.x = carve(p, M * d * e);
+  W.q = carve(p, M * d * e);
+  W.attn = carve(p, M * d * e);
+  W.act = carve(p, M * f * e);
+  W.y32 = (float *)carve(p, M * wide * 4);
+  W.logits = (float *)carve(p, M * V * 4);
+  W.row_tok = (int32_t *)carve(p, M * 4);
+  W.row_pos = (int32_t *)carve(p, M * 4);
+  W.row_seq = (int32_t *)carve(p, M * 4);
+  W.head_rows = (int32_t *)carve(p, M * 4);
+
+  rc = setup_model(c, c->tgt, tgt, tgt_w, p, z.tgt_w, z.kv_area_tgt, z.tgt_kv, z.L_pad);
+  if (!rc && drf) {
+    int32_t *kvlen = c->drf.kv_len;
+    rc = setup_model(c, c->drf, drf, drf_w, p, z.drf_w, z.kv_area_drf, z.drf_kv, z.L_pad);
+    c->drf.kv_len = kvlen;
+  }
+  if (!drf) c->drf.kv_len = nullptr;
+  if (!rc && (size_t)(p - (char *)d_workspace) > workspace_bytes) rc = fail(c, SPEC_ERR_WORKSPACE, "internal: workspace overflow");
+  if (rc) { g_err = c->err; delete c; return rc; }
+  // state that kernels read before the first reset writes it
+  generic_zero(S.seq, (size_t)((char *)W.h - (char *)S.seq), c->stream);
+  hipError_t e1 = hipEventCreate(&c->ev0), e2 = hipEventCreate(&c->ev1);
+  hipError_t e3 = hipStreamSynchronize(c->stream);
+  hipError_t e4 = hipGetLastError();
+  if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess) {
+    hipError_t bad = e1 != hipSuccess ? e1 : e2 != hipSuccess ? e2 : e3 != hipSuccess ? e3 : e4;
+    rc = fail(nullptr, SPEC_ERR_HIP, "spec_init: %s", hipGetErrorString(bad));
+    delete c;
+    return rc;
+  }
+  *out = c;
+  return SPEC_OK;
+}
+
+extern "C" int spec_destroy(spec_ctx *c) {
+  if (!c) return SPEC_OK;
+  if (c->ev0) (void)hipEventDestroy(c->ev0);
+  if (c->ev1) (void)hipEventDestroy(c->ev1);
+  delete c;
+  return SPEC_OK;
+}
+
+// ------------------------------------------------------------------ forward pass
+enum HeadMode { HEAD_NONE = 0, HEAD_ALL = 1, HEAD_LAST = 2 };
+
+// One forward pass of a model over B*q rows: embed -> layers -> (final norm, LM head,
+// arg-max for the rows that need a token).
+static int forward_pass(spec_ctx *c, Model &m, const PassArgs &pa, HeadMode head, float *logits_out,
+                        int32_t *arg_out, int arg_stride) {
+  const int M = pa.B * pa.q;
+  hipStream_t st = c->stream;
+  launch_assemble_embed(c, m, pa, st);
+  for (int l = 0; l < m.desc.n_layers; ++l) generic_layer(c, m, l, M, pa.q, st);
+  if (head != HEAD_NONE) {
+    const bool last = head == HEAD_LAST;
+    const int Mh = last ? pa.B : M;
+    launch_head_rows(c, pa.B, pa.q, last, st);
+    float *lg = logits_out ? logits_out : c->ws.logits;
+    generic_head(c, m, Mh, lg, st);
+    launch_argmax_rows(lg, Mh, m.desc.vocab, last ? 1 : pa.q, arg_stride, arg_out, st);
+  }
+  HIPCHK(c, hipGetLastError());
+  return SPEC_OK;
+}
+
+// ------------------------------------------------------------------ reset
+static int do_reset(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32_t P, bool prefill, const char *who) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s: ctx is null", who);
+  if (!d_prompt) return fail(c, SPEC_ERR_INVALID_ARG, "%s: prompt is null", who);
+  if (B < 1 || B > c->run.B_max) return fail(c, SPEC_ERR_CAPACITY, "%s: B=%d outside 1..B_max=%d", who, B, c->run.B_max);
+  if (P < 1) return fail(c, SPEC_ERR_INVALID_ARG, "%s: P must be at least 1", who);
+  if ((long long)P + c->run.gen_max + c->run.s_max > c->run.L_max)
+    return fail(c, SPEC_ERR_CAPACITY, "%s: P + gen_max + s_max = %lld exceeds L_max = %d", who,
+                (long long)P + c->run.gen_max + c->run.s_max, c->run.L_max);
+  for (Model *m : {&c->tgt, &c->drf})
+    if (m->present && m->desc.pos_kind == SPEC_POS_LEARNED && P + c->run.gen_max + c->run.s_max > m->desc.max_pos)
+      return fail(c, SPEC_ERR_CAPACITY, "%s: positions would exceed the learned position table (max_pos=%d)", who,
+                  m->desc.max_pos);
+  c->B = B;
+  c->P = P;
+  c->active = true;
+  c->draft_j = 0;
+  c->draft_lag = 1;
+  c->verified_s = -1;
+  c->proposals_ready = false;
+  launch_state_reset(c, d_prompt, c->stream);
+  if (prefill) {
+    const int chunk = std::max(1, std::min(Q_LIMIT, c->M_max / B));
+    for (int base = 0; base < P - 1; base += chunk) {
+      PassArgs pa{PASS_PREFILL, B, std::min(chunk, P - 1 - base), base, P, c->run.s_max, c->run.L_max};
+      int rc = forward_pass(c, c->tgt, pa, HEAD_NONE, nullptr, nullptr, 0);
+      if (!rc && c->drf.present) rc = forward_pass(c, c->drf, pa, HEAD_NONE, nullptr, nullptr, 0);
+      if (rc) return rc;
+    }
+  }
+  HIPCHK(c, hipGetLastError());
+  return SPEC_OK;
+}
+
+extern "C" int spec_reset(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32_t P) {
+  return do_reset(c, B, d_prompt, P, true, "spec_reset");
+}
+extern "C" int spec_reset_noprefill(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32_t P) {
+  return do_reset(c, B, d_prompt, P, false, "spec_reset_noprefill");
+}
+
+extern "C" int spec_rewind(spec_ctx *c) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_rewind: ctx is null");
+  if (!c->active) return fail(c, SPEC_ERR_STATE, "spec_rewind: no batch; call spec_reset first");
+  c->draft_j = 0;
+  c->draft_lag = 1;
+  c->verified_s = -1;
+  c->proposals_ready = false;
+  launch_state_reset(c, nullptr, c->stream);
+  HIPCHK(c, hipGetLastError());
+  return SPEC_OK;
+}
+
+// ------------------------------------------------------------------ proposals
+extern "C" int spec_set_proposal_table(spec_ctx *c, const int32_t *d_table) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_set_proposal_table: ctx is null");
+  if (c->run.proposal_mode != SPEC_PROPOSALS_EXTERNAL)
+    return fail(c, SPEC_ERR_STATE, "spec_set_proposal_table: context was created with SPEC_PROPOSALS_DRAFT");
+  c->prop_table = d_table;  // NULL clears it
+  return SPEC_OK;
+}
+
+extern "C" int spec_set_proposals(spec_ctx *c, const int32_t *d_tok, int32_t s) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_set_proposals: ctx is null");
+  if (c->run.proposal_mode != SPEC_PROPOSALS_EXTERNAL)
+    return fail(c, SPEC_ERR_STATE, "spec_set_proposals: context was created with SPEC_PROPOSALS_DRAFT");
+  if (!c->active) return fail(c, SPEC_ERR_STATE, "spec_set_proposals: no batch; call spec_reset first");
+  if (s < 0 || s > c->run.s_max) return fail(c, SPEC_ERR_CAPACITY, "spec_set_proposals: s=%d outside 0..s_max=%d", s, c->run.s_max);
+  if (s > 0 && !d_tok) return fail(c, SPEC_ERR_INVALID_ARG, "spec_set_proposals: tokens are null");
+  if (c->draft_j != 0 || c->verified_s >= 0)
+    return fail(c, SPEC_ERR_STATE, "spec_set_proposals: call it before the round's first draft step");
+  launch_copy_proposals(c, d_tok, s, c->stream);
+  c->proposals_ready = true;
+  HIPCHK(c, hipGetLastError());
+  return SPEC_OK;
+}
+
+// proposals for the coming round from the table, if that is how they are supplied
+static int ensure_proposals(spec_ctx *c, int s, const char *who) {
+  if (c->run.proposal_mode != SPEC_PROPOSALS_EXTERNAL || s == 0 || c->proposals_ready) return SPEC_OK;
+  if (!c->prop_table)
+    return fail(c, SPEC_ERR_STATE, "%s: external proposals expected; call spec_set_proposals or spec_set_proposal_table", who);
+  launch_fill_proposals(c, s, c->stream);
+  c->proposals_ready = true;
+  return SPEC_OK;
+}
+
+// ------------------------------------------------------------------ draft step
+extern "C" int spec_draft_step(spec_ctx *c, int32_t j) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_draft_step: ctx is null");
+  if (!c->active) return fail(c, SPEC_ERR_STATE, "spec_draft_step: no batch; call spec_reset first");
+  if (!c->drf.present) return fail(c, SPEC_ERR_STATE, "spec_draft_step: no draft model");
+  if (c->verified_s >= 0) return fail(c, SPEC_ERR_STATE, "spec_draft_step: a verify step is waiting for spec_accept_commit");
+  if (j < 1 || j > c->run.s_max) return fail(c, SPEC_ERR_CAPACITY, "spec_draft_step: j=%d outside 1..s_max=%d", j, c->run.s_max);
+  if (j != c->draft_j + 1) return fail(c, SPEC_ERR_STATE, "spec_draft_step: step %d expected, got %d", c->draft_j + 1, j);
+  const bool ext = c->run.proposal_mode == SPEC_PROPOSALS_EXTERNAL;
+  if (ext && j >= 2 && !c->proposals_ready)
+    return fail(c, SPEC_ERR_STATE, "spec_draft_step: external proposals must be set before draft step 2");
+  int rc;
+  if (j == 1) {
+    const int q = c->draft_lag;
+    if (q > Q_LIMIT || c->B * q > c->M_max)
+      return fail(c, SPEC_ERR_STATE, "spec_draft_step: the draft cache is %d tokens behind (rounds ran without draft steps)", q);
+    if (ext && c->prop_table && !c->proposals_ready) {
+      // later draft steps ingest t_1.. : fetch them now (all s_max; verify uses the first s)
+      launch_fill_proposals(c, c->run.s_max, c->stream);
+      c->proposals_ready = true;
+    }
+    PassArgs pa{PASS_DRAFT_FIRST, c->B, q, 1, c->P, c->run.s_max, c->run.L_max};
+    rc = forward_pass(c, c->drf, pa, HEAD_LAST, nullptr, c->st.draft_arg, 1);
+  } else {
+    PassArgs pa{PASS_DRAFT_NEXT, c->B, 1, j, c->P, c->run.s_max, c->run.L_max};
+    rc = forward_pass(c, c->drf, pa, HEAD_LAST, nullptr, c->st.draft_arg, 1);
+  }
+  if (rc) return rc;
+  launch_store_draft_token(c, j, !ext, c->stream);
+  c->draft_j = j;
+  HIPCHK(c, hipGetLastError());
+  return SPEC_OK;
+}
+
+// ------------------------------------------------------------------ verify
+extern "C" int spec_verify_step(spec_ctx *c, int32_t s, float *d_logits_or_null) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_verify_step: ctx is null");
+  if (!c->active) return fail(c, SPEC_ERR_STATE, "spec_verify_step: no batch; call spec_reset first");
+  if (s < 0 || s > c->run.s_max) return fail(c, SPEC_ERR_CAPACITY, "spec_verify_step: s=%d outside 0..s_max=%d", s, c->run.s_max);
+  if (c->verified_s >= 0) return fail(c, SPEC_ERR_STATE, "spec_verify_step: previous verify step not committed yet");
+  if (c->run.proposal_mode == SPEC_PROPOSALS_DRAFT && c->draft_j != s)
+    return fail(c, SPEC_ERR_STATE, "spec_verify_step: s=%d needs %d draft steps first, %d were run", s, s, c->draft_j);
+  if (c->draft_j != 0 && c->draft_j != s)
+    return fail(c, SPEC_ERR_STATE, "spec_verify_step: %d draft steps were run for s=%d", c->draft_j, s);
+  int rc = ensure_proposals(c, s, "spec_verify_step");
+  if (rc) return rc;
+  PassArgs pa{PASS_VERIFY, c->B, s + 1, 0, c->P, c->run.s_max, c->run.L_max};
+  rc = forward_pass(c, c->tgt, pa, HEAD_ALL, d_logits_or_null, c->st.a, c->run.s_max + 1);
+  if (rc) return rc;
+  c->verified_s = s;
+  return SPEC_OK;
+}
+
+// ------------------------------------------------------------------ accept / commit
+extern "C" int spec_accept_commit(spec_ctx *c, int32_t s) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_accept_commit: ctx is null");
+  if (!c->active) return fail(c, SPEC_ERR_STATE, "spec_accept_commit: no batch; call spec_reset first");
+  if (c->verified_s < 0) return fail(c, SPEC_ERR_STATE, "spec_accept_commit: no verify step to commit");
+  if (s != c->verified_s) return fail(c, SPEC_ERR_STATE, "spec_accept_commit: verify step ran with s=%d, got s=%d", c->verified_s, s);
+  launch_accept(c, s, c->stream);
+  if (c->drf.present) c->draft_lag = c->draft_j > 0 ? 2 : std::min(c->draft_lag + 1, Q_LIMIT + 1);
+  c->draft_j = 0;
+  c->verified_s = -1;
+  c->proposals_ready = false;
+  HIPCHK(c, hipGetLastError());
+  return SPEC_OK;
+}
+
+extern "C" int spec_round(spec_ctx *c, int32_t s, int32_t n_rounds) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_round: ctx is null");
+  if (!c->active) return fail(c, SPEC_ERR_STATE, "spec_round: no batch; call spec_reset first");
+  if (s < 0 || s > c->run.s_max) return fail(c, SPEC_ERR_CAPACITY, "spec_round: s=%d outside 0..s_max=%d", s, c->run.s_max);
+  if (n_rounds < 0) return fail(c, SPEC_ERR_INVALID_ARG, "spec_round: n_rounds is negative");
+  if (c->draft_j != 0 || c->verified_s >= 0) return fail(c, SPEC_ERR_STATE, "spec_round: a round is already in progress");
+  const bool ext = c->run.proposal_mode == SPEC_PROPOSALS_EXTERNAL;
+  if (ext && s > 0 && !c->prop_table && !(n_rounds == 1 && c->proposals_ready))
+    return fail(c, SPEC_ERR_STATE, "spec_round: external proposals need a table (spec_set_proposal_table)");
+  if (!ext && s > 0 && !c->drf.present) return fail(c, SPEC_ERR_STATE, "spec_round: no draft model");
+  for (int r = 0; r < n_rounds; ++r) {
+    int rc = SPEC_OK;
+    if (c->drf.present)
+      for (int j = 1; j <= s && !rc; ++j) rc = spec_draft_step(c, j);
+    if (!rc) rc = spec_verify_step(c, s, nullptr);
+    if (!rc) rc = spec_accept_commit(c, s);
+    if (rc) return rc;
+  }
+  return SPEC_OK;
+}
+
+// ------------------------------------------------------------------ adaptive policy
+static int lut_lookup(const std::vector<int32_t> &Bs, const std::vector<int32_t> &lut, int B) {
+  // smaller entry of the two nearest profiled sizes; ends clamp
+  const int n = (int)Bs.size();
+  if (B <= Bs[0]) return lut[0];
+  if (B >= Bs[n - 1]) return lut[n - 1];
+  int hi = 0;
+  while (Bs[hi] < B) ++hi;
+  if (Bs[hi] == B) return lut[hi];
+  return std::min(lut[hi - 1], lut[hi]);
+}
+
+static int check_batch_list(spec_ctx *c, const int32_t *h_batch_sizes, int32_t n_b, const char *who) {
+  if (!h_batch_sizes || n_b < 1) return fail(c, SPEC_ERR_INVALID_ARG, "%s: batch size list is empty", who);
+  for (int i = 0; i < n_b; ++i) {
+    if (h_batch_sizes[i] < 1) return fail(c, SPEC_ERR_INVALID_ARG, "%s: batch sizes must be positive", who);
+    if (i && h_batch_sizes[i] <= h_batch_sizes[i - 1])
+      return fail(c, SPEC_ERR_INVALID_ARG, "%s: batch sizes must be strictly ascending", who);
+  }
+  return SPEC_OK;
+}
+
+extern "C" int spec_set_lut(spec_ctx *c, const int32_t *h_batch_sizes, const int32_t *h_lut, int32_t n_b) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_set_lut: ctx is null");
+  int rc = check_batch_list(c, h_batch_sizes, n_b, "spec_set_lut");
+  if (rc) return rc;
+  if (!h_lut) return fail(c, SPEC_ERR_INVALID_ARG, "spec_set_lut: lut is null");
+  for (int i = 0; i < n_b; ++i)
+    if (h_lut[i] < 0 || h_lut[i] > c->run.s_max)
+      return fail(c, SPEC_ERR_CAPACITY, "spec_set_lut: entry %d = %d outside 0..s_max=%d", i, h_lut[i], c->run.s_max);
+  c->lut_B.assign(h_batch_sizes, h_batch_sizes + n_b);
+  c->lut_s.assign(h_lut, h_lut + n_b);
+  return SPEC_OK;
+}
+
+extern "C" int spec_choose_s(const spec_ctx *c, int32_t B, int32_t *h_s_out) {
+  if (!c || !h_s_out) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_choose_s: null argument");
+  if (c->lut_B.empty()) return fail(const_cast<spec_ctx *>(c), SPEC_ERR_STATE, "spec_choose_s: no look-up table; profile or call spec_set_lut");
+  if (B < 1) return fail(const_cast<spec_ctx *>(c), SPEC_ERR_INVALID_ARG, "spec_choose_s: B must be positive");
+  *h_s_out = lut_lookup(c->lut_B, c->lut_s, B);
+  return SPEC_OK;
+}
+
+extern "C" int spec_profile_and_choose_s(spec_ctx *c, const int32_t *h_batch_sizes, int32_t n_b, int32_t s_max_profile,
+                                         const int32_t *d_prompt, int32_t P, int32_t gen, int32_t *h_lut_out,
+                                         float *h_grid) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_profile_and_choose_s: ctx is null");
+  int rc = check_batch_list(c, h_batch_sizes, n_b, "spec_profile_and_choose_s");
+  if (rc) return rc;
+  if (!h_lut_out || !d_prompt) return fail(c, SPEC_ERR_INVALID_ARG, "spec_profile_and_choose_s: null argument");
+  if (h_batch_sizes[n_b - 1] > c->run.B_max)
+    return fail(c, SPEC_ERR_CAPACITY, "spec_profile_and_choose_s: batch size %d exceeds B_max=%d", h_batch_sizes[n_b - 1], c->run.B_max);
+  if (s_max_profile < 0 || s_max_profile > c->run.s_max)
+    return fail(c, SPEC_ERR_CAPACITY, "spec_profile_and_choose_s: s_max_profile=%d outside 0..s_max=%d", s_max_profile, c->run.s_max);
+  if (gen < 1 || gen > c->run.gen_max)
+    return fail(c, SPEC_ERR_CAPACITY, "spec_profile_and_choose_s: gen=%d outside 1..gen_max=%d", gen, c->run.gen_max);
+  const bool ext = c->run.proposal_mode == SPEC_PROPOSALS_EXTERNAL;
+  if (ext && s_max_profile > 0 && !c->prop_table)
+    return fail(c, SPEC_ERR_STATE, "spec_profile_and_choose_s: external proposals need a table");
+  if (!ext && s_max_profile > 0 && !c->drf.present) return fail(c, SPEC_ERR_STATE, "spec_profile_and_choose_s: no draft model");
+  const int nS = s_max_profile + 1;
+  std::vector<double> grid((size_t)n_b * nS);
+  std::vector<int32_t> lut(n_b);
+  for (int bi = 0; bi < n_b; ++bi) {
+    const int B = h_batch_sizes[bi];
+    // rows of d_prompt have stride P: the first B rows are the batch
+    rc = spec_reset(c, B, d_prompt, P);
+    if (rc) return rc;
+    for (int s = 0; s < nS; ++s) {
+      if ((rc = spec_rewind(c))) return rc;
+      // a round emits at most s+1 tokens per sequence: this many rounds cannot finish any sequence,
+      // so every round of the timed region does full work
+      const int rounds = std::max(1, gen / (s + 1));
+      if ((rc = spec_round(c, s, 1))) return rc;  // warm-up round
+      if ((rc = spec_rewind(c))) return rc;
+      HIPCHK(c, hipEventRecord(c->ev0, c->stream));
+      if ((rc = spec_round(c, s, rounds))) return rc;
+      HIPCHK(c, hipEventRecord(c->ev1, c->stream));
+      HIPCHK(c, hipEventSynchronize(c->ev1));
+      float ms = 0.f;
+      HIPCHK(c, hipEventElapsedTime(&ms, c->ev0, c->ev1));
+      unsigned long long cnt[2] = {0, 0};
+      HIPCHK(c, hipMemcpy(cnt, c->st.counters, sizeof cnt, hipMemcpyDeviceToHost));
+      const double per_seq = (double)cnt[0] / (double)B;
+      grid[(size_t)bi * nS + s] = per_seq > 0 ? (double)ms * 1000.0 / per_seq : 1e30;
+    }
+    // arg-min over s; within 1 % of the minimum the smaller s wins
+    const double *row = &grid[(size_t)bi * nS];
+    double best = *std::min_element(row, row + nS);
+    int pick = 0;
+    while (row[pick] > best * 1.01) ++pick;
+    lut[bi] = pick;
+  }
+  if ((rc = spec_rewind(c))) return rc;
+  c->lut_B.assign(h_batch_sizes, h_batch_sizes + n_b);
+  c->lut_s = lut;
+  std::copy(lut.begin(), lut.end(), h_lut_out);
+  if (h_grid) for (size_t i = 0; i < grid.size(); ++i) h_grid[i] = (float)grid[i];
+  return SPEC_OK;
+}
+
+// ------------------------------------------------------------------ read-back
+extern "C" int spec_read_output(spec_ctx *c, int32_t *h_tokens, int32_t *h_len, int64_t *h_hist) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_read_output: ctx is null");
+  if (!c->active) return fail(c, SPEC_ERR_STATE, "spec_read_output: no batch; call spec_reset first");
+  if (!h_tokens || !h_len) return fail(c, SPEC_ERR_INVALID_ARG, "spec_read_output: null argument");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  std::vector<int32_t> n(c->B);
+  HIPCHK(c, hipMemcpy(n.data(), c->st.n, (size_t)c->B * 4, hipMemcpyDeviceToHost));
+  const int G = c->run.gen_max;
+  for (int b = 0; b < c->B; ++b) {
+    int len = std::max(0, std::min(n[b] - c->P, G));
+    h_len[b] = len;
+    if (len)
+      HIPCHK(c, hipMemcpy(h_tokens + (size_t)b * G, c->st.seq + (size_t)b * c->run.L_max + c->P, (size_t)len * 4,
+                          hipMemcpyDeviceToHost));
+  }
+  if (h_hist) {
+    static_assert(sizeof(unsigned long long) == sizeof(int64_t), "hist width");
+    HIPCHK(c, hipMemcpy(h_hist, c->st.hist, (size_t)(c->run.s_max + 1) * 8, hipMemcpyDeviceToHost));
+  }
+  return SPEC_OK;
+}
+
+extern "C" int spec_read_state(spec_ctx *c, int32_t *h_n, int32_t *h_kv_draft, int32_t *h_l_last, int32_t *h_argmax) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_read_state: ctx is null");
+  if (!c->active) return fail(c, SPEC_ERR_STATE, "spec_read_state: no batch; call spec_reset first");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  const size_t B = c->B;
+  if (h_n) HIPCHK(c, hipMemcpy(h_n, c->st.n, B * 4, hipMemcpyDeviceToHost));
+  if (h_kv_draft) {
+    if (c->drf.kv_len) HIPCHK(c, hipMemcpy(h_kv_draft, c->drf.kv_len, B * 4, hipMemcpyDeviceToHost));
+    else std::fill(h_kv_draft, h_kv_draft + B, 0);
+  }
+  if (h_l_last) HIPCHK(c, hipMemcpy(h_l_last, c->st.l_last, B * 4, hipMemcpyDeviceToHost));
+  if (h_argmax) HIPCHK(c, hipMemcpy(h_argmax, c->st.a, B * (size_t)(c->run.s_max + 1) * 4, hipMemcpyDeviceToHost));
+  return SPEC_OK;
+}
+
+// ------------------------------------------------------------------ KV import / export
+static int kv_io(spec_ctx *c, int32_t which, int32_t layer, int32_t B, int32_t len, void *k, void *v, bool import_,
+                 const char *who) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s: ctx is null", who);
+  if (which != SPEC_MODEL_TARGET && which != SPEC_MODEL_DRAFT) return fail(c, SPEC_ERR_INVALID_ARG, "%s: unknown model %d", who, which);
+  Model &m = which == SPEC_MODEL_TARGET ? c->tgt : c->drf;
+  if (!m.present) return fail(c, SPEC_ERR_STATE, "%s: no draft model", who);
+  if (layer < 0 || layer >= m.desc.n_layers) return fail(c, SPEC_ERR_INVALID_ARG, "%s: layer %d outside 0..%d", who, layer, m.desc.n_layers - 1);
+  if (B < 1 || B > c->run.B_max) return fail(c, SPEC_ERR_CAPACITY, "%s: B=%d outside 1..B_max=%d", who, B, c->run.B_max);
+  if (len < 0 || len > c->run.L_max) return fail(c, SPEC_ERR_CAPACITY, "%s: len=%d outside 0..L_max=%d", who, len, c->run.L_max);
+  if (len > 0 && (!k || !v)) return fail(c, SPEC_ERR_INVALID_ARG, "%s: null buffer", who);
+  launch_kv_convert(c, m, layer, B, len, k, v, import_, c->stream);
+  HIPCHK(c, hipGetLastError());
+  return SPEC_OK;
+}
+extern "C" int spec_kv_import(spec_ctx *c, int32_t which, int32_t layer, int32_t B, int32_t len, const void *d_k,
+                              const void *d_v) {
+  return kv_io(c, which, layer, B, len, const_cast<void *>(d_k), const_cast<void *>(d_v), true, "spec_kv_import");
+}
+extern "C" int spec_kv_export(spec_ctx *c, int32_t which, int32_t layer, int32_t B, int32_t len, void *d_k, void *d_v) {
+  return kv_io(c, which, layer, B, len, d_k, d_v, false, "spec_kv_export");
+}

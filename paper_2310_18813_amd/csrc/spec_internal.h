@@ -1,0 +1,150 @@
+// Internal declarations shared by the host runtime and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <string>
+#include <vector>
+#include "../../include/spec.h"
+
+namespace spec {
+
+constexpr int WAVE = 64;
+constexpr int KV_VBLOCK = 8;  // values of 8 consecutive positions are stored together (see kv_v_index)
+
+// ---------------------------------------------------------------- layouts
+// KV cache of one model: for each layer a K area and a V area, each
+// [B_max][H][L_pad][hd] elements, L_pad = L_max rounded up to KV_VBLOCK.
+//   K: row-major over positions; inside a row the head's elements are stored
+//      pair-interleaved: canonical element i (i < hd/2) sits at 2i, its rotary
+//      partner i + hd/2 at 2i+1.  Q is produced in the same order, so q.k is unchanged.
+//   V: blocked by KV_VBLOCK positions: [pos / 8][hd][pos % 8], canonical element order,
+//      so that 8 consecutive positions of one element are one 16-byte load.
+__host__ __device__ inline int hd_interleave(int i, int hd) {
+  int half = hd >> 1;
+  return i < half ? 2 * i : 2 * (i - half) + 1;
+}
+__host__ __device__ inline size_t kv_k_index(int L_pad, int H, int hd, int b, int h, int pos, int i_stored) {
+  return (((size_t)b * H + h) * L_pad + pos) * hd + i_stored;
+}
+__host__ __device__ inline size_t kv_v_index(int L_pad, int H, int hd, int b, int h, int pos, int i) {
+  return ((((size_t)b * H + h) * (L_pad / KV_VBLOCK) + pos / KV_VBLOCK) * hd + i) * KV_VBLOCK + pos % KV_VBLOCK;
+}
+
+// ---------------------------------------------------------------- model on device
+struct LayerW {
+  // canonical-layout copies used by the generic kernels, or packed tiles for the MFMA kernels
+  const void *attn_norm_w, *attn_norm_b, *ffn_norm_w, *ffn_norm_b;
+  const void *wqkv, *bqkv;  // [3d][d] (rows: q heads, k heads, v heads), bias [3d]
+  const void *wo, *bo;      // [d][d]
+  const void *w13, *b13;    // SwiGLU: [2f][d] gate/up rows; ReLU: [f][d]
+  const void *w2, *b2;      // [d][f]
+};
+
+struct Model {
+  bool present = false;
+  spec_model_desc desc{};
+  int hd = 0, L_pad = 0;
+  bool fast = false;  // MFMA kernels (16-bit dtypes with supported shapes) or generic kernels
+  const void *tok_emb = nullptr, *pos_emb = nullptr, *final_norm_w = nullptr, *final_norm_b = nullptr,
+             *lm_head = nullptr;
+  std::vector<LayerW> layers;
+  void *kcache = nullptr, *vcache = nullptr;  // [n_layers] x area
+  size_t kv_area_elems = 0;                   // elements per layer per K (or V) area
+  int32_t *kv_len = nullptr;                  // draft only: device [B_max] valid cache length
+};
+
+// What a forward pass feeds in.
+enum PassKind {
+  PASS_VERIFY = 0,      // rows (b,i), i=0..q-1: pending token then proposals, positions n_b-1+i
+  PASS_DRAFT_FIRST = 1, // rows (b,i): committed tokens at positions n_b-q+i; rows before kv_len_b are dead
+  PASS_DRAFT_NEXT = 2,  // q = 1: proposal t_{j-1} at position n_b+j-2
+  PASS_PREFILL = 3      // rows (b,i): prompt tokens at positions base+i; rows >= P-1 are dead
+};
+
+struct Workspace {
+  // activations (shared by both models; sized for the larger)
+  float *h = nullptr;       // [M_max][d]   fp32 residual stream
+  void *x = nullptr;        // [M_max][d]   normed rows, model dtype
+  void *q = nullptr;        // [M_max][d]   queries, model dtype, pair-interleaved per head
+  void *attn = nullptr;     // [M_max][d]   attention output, model dtype
+  void *act = nullptr;      // [M_max][f]   FFN activation, model dtype
+  float *y32 = nullptr;     // [M_max][max(3d, 2f)] fp32 GEMM output (generic path)
+  float *logits = nullptr;  // [M_max][vocab] fp32 (generic path / debug)
+  float *attn_part = nullptr;  // split-KV partials (MFMA path)
+  float *head_part = nullptr;  // per-tile argmax partials (MFMA path)
+  int32_t *row_tok = nullptr, *row_pos = nullptr, *row_seq = nullptr;  // [M_max]
+  int32_t *head_rows = nullptr;                                        // [M_max] rows that need logits
+};
+
+struct State {
+  int32_t *seq = nullptr;     // [B_max][L_max] committed tokens (prompt + emitted)
+  int32_t *n = nullptr;       // [B_max] committed length
+  int32_t *t = nullptr;       // [B_max][s_max]   proposals of the round
+  int32_t *a = nullptr;       // [B_max][s_max+1] target greedy tokens of the round
+  int32_t *l_last = nullptr;  // [B_max]
+  int32_t *draft_arg = nullptr;  // [B_max] the draft's own greedy token of the last step
+  unsigned long long *hist = nullptr;  // [s_max+1]
+  unsigned long long *counters = nullptr;  // [0] emitted tokens total, [1] rounds
+};
+
+}  // namespace spec
+
+struct spec_ctx {
+  spec_run_desc run{};
+  spec::Model tgt, drf;
+  spec::Workspace ws;
+  spec::State st;
+  hipStream_t stream = nullptr;
+  int M_max = 0;
+  // host-side bookkeeping
+  int B = 0, P = 0;
+  bool active = false;
+  int draft_j = 0;        // draft steps done this round
+  int draft_lag = 1;      // upper bound of n_b - kv_draft_b
+  int verified_s = -1;    // s of the verify step waiting for accept_commit, or -1
+  bool proposals_ready = false;
+  const int32_t *prop_table = nullptr;
+  std::vector<int32_t> lut_B, lut_s;
+  std::string err;
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;
+};
+
+namespace spec {
+
+// ---- launchers implemented in the kernel files (all asynchronous on `st`) ----
+struct PassArgs {
+  PassKind kind;
+  int B, q;      // rows M = B*q
+  int j;         // draft step index (PASS_DRAFT_NEXT) / prefill base position (PASS_PREFILL)
+  int P;         // prompt length (PASS_PREFILL)
+  int s_max, L_max;
+};
+
+void launch_assemble_embed(const spec_ctx *c, const Model &m, const PassArgs &pa, hipStream_t st);
+void launch_norm(const spec_ctx *c, const Model &m, const float *h, const void *gain, const void *bias, void *x,
+                 int M, const int32_t *row_gather, hipStream_t st);
+void launch_argmax_rows(const float *logits, int M, int V, int q, int out_stride, int32_t *out, hipStream_t st);
+void launch_accept(spec_ctx *c, int s, hipStream_t st);
+void launch_fill_proposals(spec_ctx *c, int s, hipStream_t st);
+void launch_copy_proposals(spec_ctx *c, const int32_t *d_tok, int s, hipStream_t st);
+void launch_store_draft_token(spec_ctx *c, int j, bool write_proposal, hipStream_t st);
+void launch_state_reset(spec_ctx *c, const int32_t *d_prompt_or_null, hipStream_t st);
+void launch_kv_convert(spec_ctx *c, const Model &m, int layer, int B, int len, void *k, void *v, bool import_,
+                       hipStream_t st);
+void launch_head_rows(spec_ctx *c, int B, int q, bool last_only, hipStream_t st);
+
+// generic kernels (any dtype, any shape)
+void generic_repack_top(spec_ctx *c, Model &m, const spec_weights *w, void *&cursor, hipStream_t st);
+void generic_repack_layer(spec_ctx *c, Model &m, int layer, const spec_weights *w, void *&cursor, hipStream_t st);
+void generic_layer(spec_ctx *c, const Model &m, int layer, int M, int q_rows, hipStream_t st);
+void generic_head(spec_ctx *c, const Model &m, int Mh, float *logits, hipStream_t st);
+size_t generic_packed_bytes(const spec_model_desc &d, int dtype);
+void generic_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
+void generic_zero(void *dst, size_t bytes, hipStream_t st);
+
+size_t dtype_bytes(int dtype);
+
+}  // namespace spec

@@ -1,0 +1,45 @@
+"""Shared helpers of the GPU parity tests: build the same model for the CPU oracle and the
+GPU library from one seeded parameter set."""
+import numpy as np
+import torch
+
+import synth_inputs as si
+
+ORC_WDTYPE = {"fp32": 0, "bf16": 1, "fp16": 2}
+# max |logit| error the GPU path may show against the fp64 oracle fed the same rounded
+# parameters: fp32 arithmetic 1e-4, bf16 storage of activations 2e-2, fp16 1e-2
+LOGIT_TOL = {"fp32": 1e-4, "bf16": 2e-2, "fp16": 1e-2}
+
+
+def build_pair(orc, tdesc, ddesc, dtype, seed, device, emb_std=0.02, random_norms=False):
+    """-> (oracle target, oracle draft or None, gpu weights target, gpu weights draft or None)"""
+    out = []
+    gw = []
+    for tag, desc in (("tgt.", tdesc), ("drf.", ddesc)):
+        if desc is None:
+            out.append(None)
+            gw.append(None)
+            continue
+        w = si.make_weights(desc, dtype, seed, device="cpu", emb_std=emb_std, tag=tag)
+        if random_norms:
+            si.randomize_norms(w, desc, dtype, seed)
+        out.append(orc.model(desc, si.weights_to_numpy(w), ORC_WDTYPE[dtype]))
+        wg = {k: (v.to(device) if v is not None else None) for k, v in w.items() if k != "layers"}
+        wg["layers"] = [{k: (v.to(device) if v is not None else None) for k, v in L.items()} for L in w["layers"]]
+        gw.append(wg)
+    return out[0], out[1], gw[0], gw[1]
+
+
+def truth_table(ref, P, L_max):
+    """ref: [B][n] greedy continuation -> [B][L_max] table of true tokens by absolute position."""
+    ref = np.asarray(ref)
+    B, n = ref.shape
+    t = np.zeros((B, L_max), dtype=np.int32)
+    m = min(n, L_max - P)
+    t[:, P:P + m] = ref[:, :m]
+    return t
+
+
+def top2_margin(logits):
+    s = np.sort(np.asarray(logits, dtype=np.float64), axis=-1)
+    return s[..., -1] - s[..., -2]
