@@ -1,0 +1,183 @@
+// The 16-bit path: model set-up (weight packing) and the per-layer launch sequence built
+// from the matrix-core kernels.
+#include "spec_internal.h"
+#include "mfma_gemm.h"
+#include <algorithm>
+
+namespace spec {
+
+static size_t al256f(size_t b) { return (b + 255) & ~(size_t)255; }
+
+bool fast_supported(const spec_model_desc &D, int dtype) {
+  if (dtype != SPEC_DTYPE_BF16 && dtype != SPEC_DTYPE_F16) return false;
+  const int hd = D.d_model / D.n_heads;
+  if (hd != 64 && hd != 128) return false;
+  if (D.d_model % 32 != 0 || D.d_ffn % 32 != 0) return false;
+  return true;
+}
+
+struct FastDims {
+  PackedDims qkv, o, w13, w2, head;
+};
+static FastDims fast_dims(const spec_model_desc &D) {
+  FastDims f;
+  const int d = D.d_model, ff = D.d_ffn;
+  f.qkv = packed_dims(3 * d, d);
+  f.o = packed_dims(d, d);
+  f.w13 = packed_dims(D.ffn_kind == SPEC_FFN_SWIGLU ? 2 * ff : ff, d);
+  f.w2 = packed_dims(d, ff);
+  f.head = packed_dims(D.vocab, d);
+  return f;
+}
+
+size_t fast_packed_bytes(const spec_model_desc &D, int dtype, int L_max) {
+  const size_t e = dtype_bytes(dtype), d = D.d_model;
+  FastDims f = fast_dims(D);
+  size_t per_layer = 4 * al256f(d * e) + al256f(f.qkv.bytes(e)) + al256f(f.o.bytes(e)) + al256f(f.w13.bytes(e)) +
+                     al256f(f.w2.bytes(e)) +
+                     al256f((size_t)f.qkv.N_pad * 4) + al256f((size_t)f.o.N_pad * 4) + al256f((size_t)f.w13.N_pad * 4) +
+                     al256f((size_t)f.w2.N_pad * 4);
+  size_t top = al256f((size_t)D.vocab * d * e) + al256f((size_t)D.max_pos * d * e) + 2 * al256f(d * e) +
+               al256f(f.head.bytes(e)) + al256f((size_t)L_max * (d / D.n_heads / 2) * sizeof(float2));
+  return top + per_layer * (size_t)D.n_layers;
+}
+
+static void *bumpf(void *&cursor, size_t bytes) {
+  void *p = cursor;
+  cursor = (char *)cursor + al256f(bytes);
+  return p;
+}
+static const void *takef(const void *src, size_t bytes, void *&cursor, hipStream_t st) {
+  if (!src) return nullptr;
+  void *dst = bumpf(cursor, bytes);
+  generic_copy(src, dst, bytes, st);
+  return dst;
+}
+
+void fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&cursor, hipStream_t st) {
+  const spec_model_desc &D = m.desc;
+  const int dt = c->run.dtype;
+  const size_t e = dtype_bytes(dt), d = D.d_model;
+  const int hd = m.hd;
+  FastDims f = fast_dims(D);
+  m.p_qkv = f.qkv; m.p_o = f.o; m.p_13 = f.w13; m.p_2 = f.w2; m.p_head = f.head;
+  const bool ln = D.norm_kind == SPEC_NORM_LAYER, hb = D.has_bias != 0, swi = D.ffn_kind == SPEC_FFN_SWIGLU;
+
+  m.tok_emb = takef(w->d_tok_emb, (size_t)D.vocab * d * e, cursor, st);
+  m.pos_emb = D.pos_kind == SPEC_POS_LEARNED ? takef(w->d_pos_emb, (size_t)D.max_pos * d * e, cursor, st) : nullptr;
+  m.final_norm_w = takef(w->d_final_norm_w, d * e, cursor, st);
+  m.final_norm_b = ln ? takef(w->d_final_norm_b, d * e, cursor, st) : nullptr;
+  void *head = bumpf(cursor, f.head.bytes(e));
+  launch_pack_weight(dt, 0, f.head, (int)d, hd, w->d_lm_head, nullptr, nullptr, head, st);
+  m.lm_head = head;
+  m.rope = nullptr;
+  if (D.pos_kind == SPEC_POS_ROPE) {
+    float2 *tab = (float2 *)bumpf(cursor, (size_t)c->run.L_max * (hd / 2) * sizeof(float2));
+    launch_rope_table(c->run.L_max, hd, D.rope_theta, tab, st);
+    m.rope = tab;
+  }
+  for (int l = 0; l < D.n_layers; ++l) {
+    const void *const *T = w->layer_tensors + (size_t)l * SPEC_T_COUNT;
+    LayerW &L = m.layers[l];
+    L.attn_norm_w = takef(T[SPEC_T_ATTN_NORM_W], d * e, cursor, st);
+    L.attn_norm_b = ln ? takef(T[SPEC_T_ATTN_NORM_B], d * e, cursor, st) : nullptr;
+    L.ffn_norm_w = takef(T[SPEC_T_FFN_NORM_W], d * e, cursor, st);
+    L.ffn_norm_b = ln ? takef(T[SPEC_T_FFN_NORM_B], d * e, cursor, st) : nullptr;
+    void *p;
+    p = bumpf(cursor, f.qkv.bytes(e));
+    launch_pack_weight(dt, 1, f.qkv, (int)d, hd, T[SPEC_T_WQ], T[SPEC_T_WK], T[SPEC_T_WV], p, st);
+    L.wqkv = p;
+    p = bumpf(cursor, f.o.bytes(e));
+    launch_pack_weight(dt, 0, f.o, (int)d, hd, T[SPEC_T_WO], nullptr, nullptr, p, st);
+    L.wo = p;
+    p = bumpf(cursor, f.w13.bytes(e));
+    if (swi) launch_pack_weight(dt, 2, f.w13, (int)d, hd, T[SPEC_T_W1], T[SPEC_T_W3], nullptr, p, st);
+    else launch_pack_weight(dt, 0, f.w13, (int)d, hd, T[SPEC_T_W1], nullptr, nullptr, p, st);
+    L.w13 = p;
+    p = bumpf(cursor, f.w2.bytes(e));
+    launch_pack_weight(dt, 0, f.w2, (int)d, hd, T[SPEC_T_W2], nullptr, nullptr, p, st);
+    L.w2 = p;
+    L.bqkv = L.bo = L.b13 = L.b2 = nullptr;
+    if (hb) {
+      float *b = (float *)bumpf(cursor, (size_t)f.qkv.N_pad * 4);
+      launch_pack_bias(dt, 1, f.qkv, (int)d, hd, T[SPEC_T_BQ], T[SPEC_T_BK], T[SPEC_T_BV], b, st);
+      L.bqkv = b;
+      b = (float *)bumpf(cursor, (size_t)f.o.N_pad * 4);
+      launch_pack_bias(dt, 0, f.o, (int)d, hd, T[SPEC_T_BO], nullptr, nullptr, b, st);
+      L.bo = b;
+      if (!swi) {
+        b = (float *)bumpf(cursor, (size_t)f.w13.N_pad * 4);
+        launch_pack_bias(dt, 0, f.w13, (int)d, hd, T[SPEC_T_B1], nullptr, nullptr, b, st);
+        L.b13 = b;
+        b = (float *)bumpf(cursor, (size_t)f.w2.N_pad * 4);
+        launch_pack_bias(dt, 0, f.w2, (int)d, hd, T[SPEC_T_B2], nullptr, nullptr, b, st);
+        L.b2 = b;
+      }
+    }
+  }
+}
+
+static GemmArgs base_args(const PackedDims &p, const void *W, const void *bias, const void *X, int M) {
+  GemmArgs a{};
+  a.W = W; a.bias = (const float *)bias; a.X = X;
+  a.M = M; a.N = p.N; a.NT = p.NT; a.KT = p.KT; a.KS = p.KS; a.K_pad = p.K_pad;
+  return a;
+}
+
+// One pre-norm decoder layer over the M rows of the pass; max_pos is an upper bound of the
+// largest row position (sizes the attention grid; chunks past a sequence's end exit at once).
+void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int max_pos, hipStream_t st) {
+  const spec_model_desc &D = m.desc;
+  const int dt = c->run.dtype, M = B * q_rows, d = D.d_model;
+  const LayerW &L = m.layers[layer];
+  Workspace &ws = c->ws;
+  const size_t esz = dtype_bytes(dt);
+  void *kc = (char *)m.kcache + (size_t)layer * m.kv_area_elems * esz;
+  void *vc = (char *)m.vcache + (size_t)layer * m.kv_area_elems * esz;
+
+  launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, nullptr, st);
+  {
+    GemmArgs a = base_args(m.p_qkv, L.wqkv, L.bqkv, ws.x, M);
+    a.q = ws.q; a.kc = kc; a.vc = vc; a.row_pos = ws.row_pos; a.rope = m.rope;
+    a.q_rows = q_rows; a.d = d; a.hd = m.hd; a.H = D.n_heads; a.L_pad = m.L_pad;
+    launch_gemm_mfma(dt, a, EPI_QKV, st);
+  }
+  {
+    AttnArgs t{};
+    t.q = ws.q; t.kc = kc; t.vc = vc; t.row_pos = ws.row_pos; t.out = ws.attn;
+    t.part_acc = ws.attn_part; t.part_ml = ws.attn_ml;
+    t.B = B; t.q_rows = q_rows; t.H = D.n_heads; t.hd = m.hd; t.L_pad = m.L_pad;
+    t.NC = std::min(c->NC_max, max_pos / ATTN_CHUNK + 1);
+    launch_attention_mfma(dt, t, st);
+  }
+  {
+    GemmArgs a = base_args(m.p_o, L.wo, L.bo, ws.attn, M);
+    a.h = ws.h;
+    launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
+  }
+  launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, nullptr, st);
+  {
+    GemmArgs a = base_args(m.p_13, L.w13, L.b13, ws.x, M);
+    a.act = ws.act; a.f = D.d_ffn;
+    launch_gemm_mfma(dt, a, D.ffn_kind == SPEC_FFN_SWIGLU ? EPI_SWIGLU : EPI_RELU, st);
+  }
+  {
+    GemmArgs a = base_args(m.p_2, L.w2, L.b2, ws.act, M);
+    a.h = ws.h;
+    launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
+  }
+}
+
+// Final norm over the rows that need a token, LM head with the arg-max fused in.
+void fast_head(spec_ctx *c, const Model &m, int Mh, float *logits_or_null, int q, int arg_stride, int32_t *arg_out,
+               hipStream_t st) {
+  launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, c->ws.head_rows, st);
+  GemmArgs a = base_args(m.p_head, m.lm_head, nullptr, c->ws.x, Mh);
+  a.logits = logits_or_null;
+  a.part_val = c->ws.head_part;
+  a.part_idx = c->ws.head_part_idx;
+  launch_gemm_mfma(c->run.dtype, a, EPI_LOGITS, st);
+  launch_argmax_partials(a.part_val, a.part_idx, Mh, m.p_head.NT, m.desc.vocab, q, arg_stride, arg_out, st);
+}
+
+}  // namespace spec

@@ -1,0 +1,388 @@
+// Weight-streaming GEMMs on the matrix cores (16-bit storage, fp32 accumulate) with the
+// layer's element-wise work fused into the epilogue.
+//
+//   Y^T[n][m] = sum_k W[n][k] * X[m][k]        W: weights [N][K], X: activations [M][K]
+//
+// One instruction, v_mfma_f32_16x16x32 (bf16 or f16), everywhere: the weight tile is the A
+// operand (16 output features x 32 k), the activation tile the B operand (16 rows x 32 k).
+//
+// Packed weights.  Each 16x32 tile is stored as the 1 KB a wave loads with one 16-byte load
+// per lane: lane L = 16*g + r holds W[n0 + r][k0 + 8g .. k0 + 8g + 7].  Tiles of one
+// 16-row strip are contiguous in k, strips follow each other, so a wave streams its strip
+// slice as one linear run of HBM addresses.
+//
+// Numerics are a function of the weight shape only.  K is cut into KS equal slices (KS =
+// 8, 4, 2 or 1, the largest that divides K/32).  Every output element is
+//     (((P_0 + P_1) + P_2) + ... + P_{KS-1}) (+ bias)
+// where P_w is the chain of MFMAs over slice w in ascending k, starting from zero.  Neither
+// the number of rows M, nor a row's index, nor the tiling chosen for a given M changes
+// that order, so a sequence's results are bit-identical at every batch size and
+// speculation length.
+#include "spec_internal.h"
+#include "device_utils.h"
+#include "mfma_gemm.h"
+
+namespace spec {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_v;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_v;
+typedef __attribute__((ext_vector_type(4))) float f32x4_v;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_v;
+
+template <class T> struct Mfma16;
+template <> struct Mfma16<bf16_t> {
+  static __device__ __forceinline__ f32x4_v run(u32x4_v a, u32x4_v b, f32x4_v c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_v, a), __builtin_bit_cast(bf16x8_v, b), c,
+                                                   0, 0, 0);
+  }
+};
+template <> struct Mfma16<f16_t> {
+  static __device__ __forceinline__ f32x4_v run(u32x4_v a, u32x4_v b, f32x4_v c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_v, a), __builtin_bit_cast(f16x8_v, b), c,
+                                                  0, 0, 0);
+  }
+};
+
+// ------------------------------------------------------------------------- packing
+// mode 0: rows of one matrix in natural order
+// mode 1: q | k | v stacked; inside every head the q and k rows are pair-interleaved
+//         (stored row 2i <- canonical i, 2i+1 <- i + hd/2) so a rotary pair is lane-local
+// mode 2: gate / up interleaved: stored rows 4p.. = gate[2p], up[2p], gate[2p+1], up[2p+1]
+template <class T>
+__global__ void k_pack_weight(int mode, int N, int K, int N_pad, int K_pad, int d, int hd, const T *__restrict__ s0,
+                              const T *__restrict__ s1, const T *__restrict__ s2, T *__restrict__ dst) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // one thread per 8 packed elements
+  const int KT = K_pad / 32;
+  const size_t total = (size_t)(N_pad / 16) * KT * 64;
+  if (idx >= total) return;
+  const int lane = (int)(idx & 63);
+  const size_t tile = idx >> 6;
+  const int kt = (int)(tile % KT), nt = (int)(tile / KT);
+  const int r = lane & 15, g = lane >> 4;
+  const int n = nt * 16 + r, k0 = kt * 32 + g * 8;
+  const T *src = nullptr;
+  int row = 0;
+  if (n < N) {
+    if (mode == 0) { src = s0; row = n; }
+    else if (mode == 1) {
+      int region = n / d, c = n % d, hh = c / hd, e = c % hd;
+      if (region < 2) { int half = hd >> 1; e = (e & 1) ? (e >> 1) + half : (e >> 1); }
+      src = region == 0 ? s0 : region == 1 ? s1 : s2;
+      row = hh * hd + e;
+    } else {
+      int p = n >> 2, q = n & 3;
+      src = (q & 1) ? s1 : s0;
+      row = 2 * p + (q >> 1);
+    }
+  }
+  T out[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    T z;
+    Conv<T>::st(&z, 0, 0.f);
+    out[i] = (src && k0 + i < K) ? src[(size_t)row * K + k0 + i] : z;
+  }
+  T *o = dst + idx * 8;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = out[i];
+}
+
+template <class T>
+__global__ void k_pack_bias(int mode, int N, int N_pad, int d, int hd, const T *__restrict__ s0,
+                            const T *__restrict__ s1, const T *__restrict__ s2, float *__restrict__ dst) {
+  int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N_pad) return;
+  float v = 0.f;
+  if (n < N) {
+    if (mode == 0) v = Conv<T>::ld(s0, n);
+    else if (mode == 1) {
+      int region = n / d, c = n % d, hh = c / hd, e = c % hd;
+      if (region < 2) { int half = hd >> 1; e = (e & 1) ? (e >> 1) + half : (e >> 1); }
+      const T *src = region == 0 ? s0 : region == 1 ? s1 : s2;
+      v = Conv<T>::ld(src, hh * hd + e);
+    } else {
+      int p = n >> 2, q = n & 3;
+      v = Conv<T>::ld((q & 1) ? s1 : s0, 2 * p + (q >> 1));
+    }
+  }
+  dst[n] = v;
+}
+
+PackedDims packed_dims(int N, int K) {
+  PackedDims p;
+  p.N = N; p.K = K;
+  p.N_pad = (N + 15) / 16 * 16;
+  p.K_pad = (K + 31) / 32 * 32;
+  p.NT = p.N_pad / 16;
+  p.KT = p.K_pad / 32;
+  p.KS = (p.KT % 8 == 0) ? 8 : (p.KT % 4 == 0) ? 4 : (p.KT % 2 == 0) ? 2 : 1;
+  return p;
+}
+
+void launch_pack_weight(int dtype, int mode, const PackedDims &p, int d, int hd, const void *s0, const void *s1,
+                        const void *s2, void *dst, hipStream_t st) {
+  size_t total = (size_t)p.NT * p.KT * 64;
+  unsigned blocks = (unsigned)((total + 255) / 256);
+  if (dtype == SPEC_DTYPE_BF16)
+    hipLaunchKernelGGL(k_pack_weight<bf16_t>, dim3(blocks), dim3(256), 0, st, mode, p.N, p.K, p.N_pad, p.K_pad, d, hd,
+                       (const bf16_t *)s0, (const bf16_t *)s1, (const bf16_t *)s2, (bf16_t *)dst);
+  else
+    hipLaunchKernelGGL(k_pack_weight<f16_t>, dim3(blocks), dim3(256), 0, st, mode, p.N, p.K, p.N_pad, p.K_pad, d, hd,
+                       (const f16_t *)s0, (const f16_t *)s1, (const f16_t *)s2, (f16_t *)dst);
+}
+
+void launch_pack_bias(int dtype, int mode, const PackedDims &p, int d, int hd, const void *s0, const void *s1,
+                      const void *s2, float *dst, hipStream_t st) {
+  unsigned blocks = (unsigned)((p.N_pad + 255) / 256);
+  if (dtype == SPEC_DTYPE_BF16)
+    hipLaunchKernelGGL(k_pack_bias<bf16_t>, dim3(blocks), dim3(256), 0, st, mode, p.N, p.N_pad, d, hd,
+                       (const bf16_t *)s0, (const bf16_t *)s1, (const bf16_t *)s2, dst);
+  else
+    hipLaunchKernelGGL(k_pack_bias<f16_t>, dim3(blocks), dim3(256), 0, st, mode, p.N, p.N_pad, d, hd,
+                       (const f16_t *)s0, (const f16_t *)s1, (const f16_t *)s2, dst);
+}
+
+// Rotary table: rope[pos][i] = (cos, sin) of pos * theta^(-2i/hd), i < hd/2.
+__global__ void k_rope_table(int L, int hd, float theta, float2 *__restrict__ tab) {
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  int half = hd >> 1;
+  if (idx >= L * half) return;
+  int pos = idx / half, i = idx % half;
+  float inv_freq = powf(theta, -2.0f * (float)i / (float)hd);
+  float s, c;
+  sincosf((float)pos * inv_freq, &s, &c);
+  tab[idx] = make_float2(c, s);
+}
+void launch_rope_table(int L, int hd, float theta, float2 *tab, hipStream_t st) {
+  int total = L * (hd / 2);
+  hipLaunchKernelGGL(k_rope_table, dim3((total + 255) / 256), dim3(256), 0, st, L, hd, theta, tab);
+}
+
+// ------------------------------------------------------------------------- the kernel
+// Workgroup = KS waves; wave w owns k-slice w of NB consecutive 16-row strips of W and
+// MT 16-row tiles of X.  grid.x walks the strips, grid.y the 16*MT-row blocks of X.
+// After the k loop the KS partial tiles meet in LDS and are added in slice order.
+template <class T, int MT, int NB, int EPI>
+__global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
+  extern __shared__ float red[];  // [KS][NB*MT][256]
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int KS = blockDim.x >> 6;
+  const int nt0 = blockIdx.x * NB;
+  const int m_base = blockIdx.y * (MT * 16);
+  const int kt_per = a.KT / KS;
+  const int kt0 = w * kt_per, kt1 = kt0 + kt_per;
+
+  const u32x4_v *Wp[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    int nt = min(nt0 + nb, a.NT - 1);
+    Wp[nb] = (const u32x4_v *)a.W + (size_t)nt * a.KT * 64 + lane;
+  }
+  const u32x4_v *Xp[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    int m = min(m_base + mt * 16 + c, a.M - 1);
+    Xp[mt] = (const u32x4_v *)a.X + (size_t)m * (a.K_pad / 8) + g;
+  }
+
+  f32x4_v acc[NB][MT];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
+
+  constexpr int U = (NB * MT >= 8) ? 2 : 4;
+  int kt = kt0;
+  for (; kt + U <= kt1; kt += U) {
+    u32x4_v wf[U][NB], xf[U][MT];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) wf[u][nb] = __builtin_nontemporal_load(Wp[nb] + (size_t)(kt + u) * 64);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) xf[u][mt] = Xp[mt][(size_t)(kt + u) * 4];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = Mfma16<T>::run(wf[u][nb], xf[u][mt], acc[nb][mt]);
+  }
+  for (; kt < kt1; ++kt) {
+    u32x4_v wf[NB], xf[MT];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) wf[nb] = __builtin_nontemporal_load(Wp[nb] + (size_t)kt * 64);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) xf[mt] = Xp[mt][(size_t)kt * 4];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = Mfma16<T>::run(wf[nb], xf[mt], acc[nb][mt]);
+  }
+
+  // ---- slice partials -> LDS, then tile t is summed in slice order by wave t % KS
+  constexpr int TILES = NB * MT;
+  if (KS > 1) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        *(f32x4_v *)&red[((size_t)(w * TILES + nb * MT + mt) * 64 + lane) * 4] = acc[nb][mt];
+    __syncthreads();
+  }
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int t = nb * MT + mt;
+      if (KS > 1 && (t % KS) != w) continue;
+      if (KS == 1 && w != 0) continue;
+      f32x4_v v;
+      if (KS > 1) {
+        v = *(const f32x4_v *)&red[((size_t)(0 * TILES + t) * 64 + lane) * 4];
+        for (int s = 1; s < KS; ++s) {
+          f32x4_v p = *(const f32x4_v *)&red[((size_t)(s * TILES + t) * 64 + lane) * 4];
+          v[0] += p[0]; v[1] += p[1]; v[2] += p[2]; v[3] += p[3];
+        }
+      } else {
+        v = acc[nb][mt];
+      }
+      const int nt = nt0 + nb;
+      const int m = m_base + mt * 16 + c;
+      if (nt >= a.NT) continue;
+      const int n = nt * 16 + 4 * g;  // this lane: stored rows n .. n+3, activation row m
+      if (a.bias) {
+        const float4 b4 = *(const float4 *)(a.bias + n);
+        v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
+      }
+      const bool live = m < a.M;
+
+      if (EPI == EPI_RESIDUAL) {
+        if (live && n < a.N) {
+          float4 *p = (float4 *)(a.h + (size_t)m * a.N + n);
+          float4 o = *p;
+          o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
+          *p = o;
+        }
+      } else if (EPI == EPI_QKV) {
+        if (live && n < a.N) {
+          const int region = n / a.d, cc = n % a.d, hh = cc / a.hd, e = cc % a.hd;
+          const int pos = a.row_pos[m], b = m / a.q_rows;
+          if (region < 2) {
+            float r0 = v[0], r1 = v[1], r2 = v[2], r3 = v[3];
+            if (a.rope && pos >= 0) {
+              const float2 cs0 = a.rope[(size_t)pos * (a.hd >> 1) + (e >> 1)];
+              const float2 cs1 = a.rope[(size_t)pos * (a.hd >> 1) + (e >> 1) + 1];
+              r0 = v[0] * cs0.x - v[1] * cs0.y; r1 = v[1] * cs0.x + v[0] * cs0.y;
+              r2 = v[2] * cs1.x - v[3] * cs1.y; r3 = v[3] * cs1.x + v[2] * cs1.y;
+            }
+            T o4[4];
+            Conv<T>::st(o4, 0, r0); Conv<T>::st(o4, 1, r1); Conv<T>::st(o4, 2, r2); Conv<T>::st(o4, 3, r3);
+            if (region == 0) {
+              *(uint2 *)((T *)a.q + (size_t)m * a.d + cc) = *(const uint2 *)o4;
+            } else if (pos >= 0) {
+              *(uint2 *)((T *)a.kc + kv_k_index(a.L_pad, a.H, a.hd, b, hh, pos, e)) = *(const uint2 *)o4;
+            }
+          } else if (pos >= 0) {
+            T *vc = (T *)a.vc;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) Conv<T>::st(vc, kv_v_index(a.L_pad, a.H, a.hd, b, hh, pos, e + i), v[i]);
+          }
+        }
+      } else if (EPI == EPI_SWIGLU) {
+        const int j = n >> 1;  // stored rows n..n+3 = gate_j, up_j, gate_{j+1}, up_{j+1}
+        if (live && j < a.f) {
+          T o2[2];
+          Conv<T>::st(o2, 0, v[0] / (1.0f + __expf(-v[0])) * v[1]);
+          Conv<T>::st(o2, 1, v[2] / (1.0f + __expf(-v[2])) * v[3]);
+          *(uint32_t *)((T *)a.act + (size_t)m * a.f + j) = *(const uint32_t *)o2;
+        }
+      } else if (EPI == EPI_RELU) {
+        if (live && n < a.N) {
+          T o4[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) Conv<T>::st(o4, i, v[i] > 0.f ? v[i] : 0.f);
+          *(uint2 *)((T *)a.act + (size_t)m * a.N + n) = *(const uint2 *)o4;
+        }
+      } else {  // EPI_LOGITS: optional dump, per-strip arg-max partial (lowest index wins ties)
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (n + i < a.N) {
+            if (live && a.logits) a.logits[(size_t)m * a.N + n + i] = v[i];
+            argmax_combine(bv, bi, v[i], n + i);
+          }
+        for (int o = 16; o <= 32; o <<= 1) {
+          float ov = __shfl_xor(bv, o, 64);
+          int oi = __shfl_xor(bi, o, 64);
+          argmax_combine(bv, bi, ov, oi);
+        }
+        if (live && g == 0) {
+          a.part_val[(size_t)m * a.NT + nt] = bv;
+          a.part_idx[(size_t)m * a.NT + nt] = bi;
+        }
+      }
+    }
+}
+
+template <class T, int MT, int NB>
+static void launch_epi(const GemmArgs &a, int epi, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
+  switch (epi) {
+    case EPI_RESIDUAL: hipLaunchKernelGGL((k_gemm_stream<T, MT, NB, EPI_RESIDUAL>), grid, block, lds, st, a); break;
+    case EPI_QKV: hipLaunchKernelGGL((k_gemm_stream<T, MT, NB, EPI_QKV>), grid, block, lds, st, a); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL((k_gemm_stream<T, MT, NB, EPI_SWIGLU>), grid, block, lds, st, a); break;
+    case EPI_RELU: hipLaunchKernelGGL((k_gemm_stream<T, MT, NB, EPI_RELU>), grid, block, lds, st, a); break;
+    default: hipLaunchKernelGGL((k_gemm_stream<T, MT, NB, EPI_LOGITS>), grid, block, lds, st, a); break;
+  }
+}
+
+template <class T>
+static void launch_gemm_t(const GemmArgs &a, int epi, hipStream_t st) {
+  if (a.M <= 0) return;
+  const int KS = a.KS;
+  // rows per pass: MT tiles of 16; strips per workgroup: NB.  Neither changes any result.
+  int MT = a.M <= 16 ? 1 : a.M <= 32 ? 2 : 4;
+  int NB = 1;
+  if (MT == 4 && a.NT >= 1024) NB = 2;
+  const int passes = (a.M + MT * 16 - 1) / (MT * 16);
+  dim3 grid((a.NT + NB - 1) / NB, passes), block(KS * 64);
+  size_t lds = KS > 1 ? (size_t)KS * NB * MT * 1024 : 0;
+  if (MT == 1) launch_epi<T, 1, 1>(a, epi, grid, block, lds, st);
+  else if (MT == 2) launch_epi<T, 2, 1>(a, epi, grid, block, lds, st);
+  else if (NB == 1) launch_epi<T, 4, 1>(a, epi, grid, block, lds, st);
+  else launch_epi<T, 4, 2>(a, epi, grid, block, lds, st);
+}
+
+void launch_gemm_mfma(int dtype, const GemmArgs &a, int epi, hipStream_t st) {
+  if (dtype == SPEC_DTYPE_BF16) launch_gemm_t<bf16_t>(a, epi, st);
+  else launch_gemm_t<f16_t>(a, epi, st);
+}
+
+// Second stage of the fused arg-max: one block per row over the per-strip partials.
+__global__ void k_argmax_partials(const float *__restrict__ pv, const int32_t *__restrict__ pi, int NT, int V, int q,
+                                  int out_stride, int32_t *__restrict__ out) {
+  __shared__ float shv[4];
+  __shared__ int shi[4];
+  const int m = blockIdx.x;
+  float bv = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int t = threadIdx.x; t < NT; t += 256) argmax_combine(bv, bi, pv[(size_t)m * NT + t], pi[(size_t)m * NT + t]);
+  wave_argmax(bv, bi);
+  if ((threadIdx.x & 63) == 0) { shv[threadIdx.x >> 6] = bv; shi[threadIdx.x >> 6] = bi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) argmax_combine(bv, bi, shv[w], shi[w]);
+    if (bi < 0 || bi >= V) bi = 0;
+    out[(size_t)(m / q) * out_stride + m % q] = bi;
+  }
+}
+void launch_argmax_partials(const float *pv, const int32_t *pi, int M, int NT, int V, int q, int out_stride,
+                            int32_t *out, hipStream_t st) {
+  if (M <= 0) return;
+  hipLaunchKernelGGL(k_argmax_partials, dim3(M), dim3(256), 0, st, pv, pi, NT, V, q, out_stride, out);
+}
+
+}  // namespace spec

@@ -1,0 +1,62 @@
+// Declarations of the matrix-core kernels (GEMM with fused epilogues, attention).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace spec {
+
+enum GemmEpilogue {
+  EPI_RESIDUAL = 0,  // h[m][n] += y            (O projection, down projection / fc2)
+  EPI_QKV = 1,       // rotary on q,k; q -> buffer, k,v -> cache at the row's position
+  EPI_SWIGLU = 2,    // act[m][j] = silu(gate_j) * up_j
+  EPI_RELU = 3,      // act[m][n] = max(y, 0)
+  EPI_LOGITS = 4     // per-strip arg-max partials (+ optional fp32 logits dump)
+};
+
+struct PackedDims {
+  int N, K, N_pad, K_pad, NT, KT, KS;
+  size_t bytes(size_t esz) const { return (size_t)N_pad * K_pad * esz; }
+};
+PackedDims packed_dims(int N, int K);
+
+struct GemmArgs {
+  // operands
+  const void *W;      // packed tiles
+  const float *bias;  // [N_pad] in stored-row order, or null
+  const void *X;      // [M][K_pad] activations
+  int M, N, NT, KT, KS, K_pad;
+  // epilogue targets (those the chosen epilogue uses)
+  float *h;                  // EPI_RESIDUAL: [M][N] fp32
+  void *q, *kc, *vc;         // EPI_QKV
+  const int32_t *row_pos;    // EPI_QKV: absolute position per row, -1 = dead row
+  const float2 *rope;        // EPI_QKV: (cos, sin) table [L][hd/2] or null
+  int q_rows, d, hd, H, L_pad;
+  void *act;                 // EPI_SWIGLU / EPI_RELU
+  int f;
+  float *logits;             // EPI_LOGITS: optional [M][N] fp32
+  float *part_val;           // EPI_LOGITS: [M][NT]
+  int32_t *part_idx;
+};
+
+void launch_pack_weight(int dtype, int mode, const PackedDims &p, int d, int hd, const void *s0, const void *s1,
+                        const void *s2, void *dst, hipStream_t st);
+void launch_pack_bias(int dtype, int mode, const PackedDims &p, int d, int hd, const void *s0, const void *s1,
+                      const void *s2, float *dst, hipStream_t st);
+void launch_rope_table(int L, int hd, float theta, float2 *tab, hipStream_t st);
+void launch_gemm_mfma(int dtype, const GemmArgs &a, int epi, hipStream_t st);
+void launch_argmax_partials(const float *pv, const int32_t *pi, int M, int NT, int V, int q, int out_stride,
+                            int32_t *out, hipStream_t st);
+
+struct AttnArgs {
+  const void *q;            // [M][d] model dtype, pair-interleaved heads
+  const void *kc, *vc;      // this layer's cache areas
+  const int32_t *row_pos;   // [M]
+  void *out;                // [M][d] model dtype, canonical order
+  float *part_acc;          // [M][H][NC][hd] un-normalised partial outputs
+  float *part_ml;           // [M][H][NC][2] running max (raw score units) and sum
+  int B, q_rows, H, hd, L_pad, NC;  // NC = chunks launched (upper bound over the batch)
+};
+constexpr int ATTN_CHUNK = 256;  // keys per split; boundaries at multiples of this position
+void launch_attention_mfma(int dtype, const AttnArgs &a, hipStream_t st);
+
+}  // namespace spec

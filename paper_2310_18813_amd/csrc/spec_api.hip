@@ -78,14 +78,16 @@ struct Sizes {
   int L_pad;
 };
 
-static size_t packed_bytes(const spec_model_desc &d, int dtype) { return generic_packed_bytes(d, dtype); }
+static size_t packed_bytes(const spec_model_desc &d, int dtype, int L_max) {
+  return fast_supported(d, dtype) ? fast_packed_bytes(d, dtype, L_max) : generic_packed_bytes(d, dtype);
+}
 
 static Sizes compute_sizes(const spec_model_desc *tgt, const spec_model_desc *drf, const spec_run_desc *run) {
   Sizes z{};
   const size_t e = dtype_bytes(run->dtype);
   z.q_pass = std::max(run->s_max + 1, PREFILL_CHUNK);
   z.M_max = run->B_max * z.q_pass;
-  z.L_pad = (run->L_max + KV_VBLOCK - 1) / KV_VBLOCK * KV_VBLOCK;
+  z.L_pad = (run->L_max + KV_LPAD - 1) / KV_LPAD * KV_LPAD;
   const size_t B = run->B_max, L = run->L_max, s = run->s_max, M = z.M_max;
   z.state = al256(B * L * 4) + 4 * al256(B * 4) + al256(B * std::max<size_t>(s, 1) * 4) + al256(B * (s + 1) * 4) +
             al256((s + 1) * 8) + al256(16);
@@ -101,11 +103,14 @@ static Sizes compute_sizes(const spec_model_desc *tgt, const spec_model_desc *dr
   }
   z.act = al256(M * d * 4) + 3 * al256(M * d * e) + al256(M * f * e) + al256(M * wide * 4) + al256(M * V * 4) +
           4 * al256(M * 4);
-  z.tgt_w = packed_bytes(*tgt, run->dtype);
+  // matrix-core path: split-KV attention partials and per-strip arg-max partials
+  const size_t NC = (L + ATTN_CHUNK - 1) / ATTN_CHUNK, NTh = (V + 15) / 16;
+  z.act += al256(M * d * NC * 4) + al256(M * (d / 64 + 1) * NC * 2 * 4) + 2 * al256(M * NTh * 4);
+  z.tgt_w = packed_bytes(*tgt, run->dtype, run->L_max);
   z.kv_area_tgt = B * (size_t)tgt->d_model * z.L_pad;
   z.tgt_kv = 2 * al256((size_t)tgt->n_layers * z.kv_area_tgt * e);
   if (drf) {
-    z.drf_w = packed_bytes(*drf, run->dtype);
+    z.drf_w = packed_bytes(*drf, run->dtype, run->L_max);
     z.kv_area_drf = B * (size_t)drf->d_model * z.L_pad;
     z.drf_kv = 2 * al256((size_t)drf->n_layers * z.kv_area_drf * e);
   }
@@ -160,16 +165,22 @@ static int setup_model(spec_ctx *c, Model &m, const spec_model_desc *d, const sp
   m.desc = *d;
   m.hd = d->d_model / d->n_heads;
   m.L_pad = L_pad;
-  m.fast = false;
+  m.fast = fast_supported(*d, c->run.dtype);
   m.layers.resize(d->n_layers);
   void *cursor = p;
-  generic_repack_top(c, m, w, cursor, c->stream);
-  for (int l = 0; l < d->n_layers; ++l) generic_repack_layer(c, m, l, w, cursor, c->stream);
+  if (m.fast) {
+    fast_setup_model(c, m, w, cursor, c->stream);
+  } else {
+    generic_repack_top(c, m, w, cursor, c->stream);
+    for (int l = 0; l < d->n_layers; ++l) generic_repack_layer(c, m, l, w, cursor, c->stream);
+  }
   if ((size_t)((char *)cursor - p) > w_bytes) return fail(c, SPEC_ERR_WORKSPACE, "internal: packed weights overflow");
   p += w_bytes;
   m.kv_area_elems = kv_area;
   m.kcache = p;
   m.vcache = p + kv_bytes / 2;
+  // stale cache rows are read (and multiplied by exact zeros) by the attention kernel: keep them finite
+  generic_zero(p, kv_bytes, c->stream);
   p += kv_bytes;
   return SPEC_OK;
 }
@@ -236,6 +247,14 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
   W.row_pos = (int32_t *)carve(p, M * 4);
   W.row_seq = (int32_t *)carve(p, M * 4);
   W.head_rows = (int32_t *)carve(p, M * 4);
+  {
+    const size_t NC = (L + ATTN_CHUNK - 1) / ATTN_CHUNK, NTh = (V + 15) / 16;
+    c->NC_max = (int)NC;
+    W.attn_part = (float *)carve(p, M * d * NC * 4);
+    W.attn_ml = (float *)carve(p, M * (d / 64 + 1) * NC * 2 * 4);
+    W.head_part = (float *)carve(p, M * NTh * 4);
+    W.head_part_idx = (int32_t *)carve(p, M * NTh * 4);
+  }
 
   rc = setup_model(c, c->tgt, tgt, tgt_w, p, z.tgt_w, z.kv_area_tgt, z.tgt_kv, z.L_pad);
   if (!rc && drf) {
@@ -275,18 +294,26 @@ enum HeadMode { HEAD_NONE = 0, HEAD_ALL = 1, HEAD_LAST = 2 };
 // One forward pass of a model over B*q rows: embed -> layers -> (final norm, LM head,
 // arg-max for the rows that need a token).
 static int forward_pass(spec_ctx *c, Model &m, const PassArgs &pa, HeadMode head, float *logits_out,
-                        int32_t *arg_out, int arg_stride) {
+                        int32_t *arg_out, int arg_stride, int max_pos) {
   const int M = pa.B * pa.q;
   hipStream_t st = c->stream;
+  max_pos = std::max(0, std::min(max_pos, c->run.L_max - 1));
   launch_assemble_embed(c, m, pa, st);
-  for (int l = 0; l < m.desc.n_layers; ++l) generic_layer(c, m, l, M, pa.q, st);
+  for (int l = 0; l < m.desc.n_layers; ++l) {
+    if (m.fast) fast_layer(c, m, l, pa.B, pa.q, max_pos, st);
+    else generic_layer(c, m, l, M, pa.q, st);
+  }
   if (head != HEAD_NONE) {
     const bool last = head == HEAD_LAST;
     const int Mh = last ? pa.B : M;
     launch_head_rows(c, pa.B, pa.q, last, st);
-    float *lg = logits_out ? logits_out : c->ws.logits;
-    generic_head(c, m, Mh, lg, st);
-    launch_argmax_rows(lg, Mh, m.desc.vocab, last ? 1 : pa.q, arg_stride, arg_out, st);
+    if (m.fast) {
+      fast_head(c, m, Mh, logits_out, last ? 1 : pa.q, arg_stride, arg_out, st);
+    } else {
+      float *lg = logits_out ? logits_out : c->ws.logits;
+      generic_head(c, m, Mh, lg, st);
+      launch_argmax_rows(lg, Mh, m.desc.vocab, last ? 1 : pa.q, arg_stride, arg_out, st);
+    }
   }
   HIPCHK(c, hipGetLastError());
   return SPEC_OK;
@@ -307,6 +334,7 @@ static int do_reset(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32_t P, 
                   m->desc.max_pos);
   c->B = B;
   c->P = P;
+  c->n_ub = P;
   c->active = true;
   c->draft_j = 0;
   c->draft_lag = 1;
@@ -317,8 +345,8 @@ static int do_reset(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32_t P, 
     const int chunk = std::max(1, std::min(Q_LIMIT, c->M_max / B));
     for (int base = 0; base < P - 1; base += chunk) {
       PassArgs pa{PASS_PREFILL, B, std::min(chunk, P - 1 - base), base, P, c->run.s_max, c->run.L_max};
-      int rc = forward_pass(c, c->tgt, pa, HEAD_NONE, nullptr, nullptr, 0);
-      if (!rc && c->drf.present) rc = forward_pass(c, c->drf, pa, HEAD_NONE, nullptr, nullptr, 0);
+      int rc = forward_pass(c, c->tgt, pa, HEAD_NONE, nullptr, nullptr, 0, base + chunk - 1);
+      if (!rc && c->drf.present) rc = forward_pass(c, c->drf, pa, HEAD_NONE, nullptr, nullptr, 0, base + chunk - 1);
       if (rc) return rc;
     }
   }
@@ -340,6 +368,7 @@ extern "C" int spec_rewind(spec_ctx *c) {
   c->draft_lag = 1;
   c->verified_s = -1;
   c->proposals_ready = false;
+  c->n_ub = c->P;
   launch_state_reset(c, nullptr, c->stream);
   HIPCHK(c, hipGetLastError());
   return SPEC_OK;
@@ -401,10 +430,10 @@ extern "C" int spec_draft_step(spec_ctx *c, int32_t j) {
       c->proposals_ready = true;
     }
     PassArgs pa{PASS_DRAFT_FIRST, c->B, q, 1, c->P, c->run.s_max, c->run.L_max};
-    rc = forward_pass(c, c->drf, pa, HEAD_LAST, nullptr, c->st.draft_arg, 1);
+    rc = forward_pass(c, c->drf, pa, HEAD_LAST, nullptr, c->st.draft_arg, 1, c->n_ub - 1);
   } else {
     PassArgs pa{PASS_DRAFT_NEXT, c->B, 1, j, c->P, c->run.s_max, c->run.L_max};
-    rc = forward_pass(c, c->drf, pa, HEAD_LAST, nullptr, c->st.draft_arg, 1);
+    rc = forward_pass(c, c->drf, pa, HEAD_LAST, nullptr, c->st.draft_arg, 1, c->n_ub + j - 2);
   }
   if (rc) return rc;
   launch_store_draft_token(c, j, !ext, c->stream);
@@ -426,7 +455,7 @@ extern "C" int spec_verify_step(spec_ctx *c, int32_t s, float *d_logits_or_null)
   int rc = ensure_proposals(c, s, "spec_verify_step");
   if (rc) return rc;
   PassArgs pa{PASS_VERIFY, c->B, s + 1, 0, c->P, c->run.s_max, c->run.L_max};
-  rc = forward_pass(c, c->tgt, pa, HEAD_ALL, d_logits_or_null, c->st.a, c->run.s_max + 1);
+  rc = forward_pass(c, c->tgt, pa, HEAD_ALL, d_logits_or_null, c->st.a, c->run.s_max + 1, c->n_ub - 1 + s);
   if (rc) return rc;
   c->verified_s = s;
   return SPEC_OK;
@@ -439,6 +468,7 @@ extern "C" int spec_accept_commit(spec_ctx *c, int32_t s) {
   if (c->verified_s < 0) return fail(c, SPEC_ERR_STATE, "spec_accept_commit: no verify step to commit");
   if (s != c->verified_s) return fail(c, SPEC_ERR_STATE, "spec_accept_commit: verify step ran with s=%d, got s=%d", c->verified_s, s);
   launch_accept(c, s, c->stream);
+  c->n_ub = std::min(c->n_ub + s + 1, c->P + c->run.gen_max);
   if (c->drf.present) c->draft_lag = c->draft_j > 0 ? 2 : std::min(c->draft_lag + 1, Q_LIMIT + 1);
   c->draft_j = 0;
   c->verified_s = -1;

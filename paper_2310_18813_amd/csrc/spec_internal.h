@@ -8,15 +8,17 @@
 #include <string>
 #include <vector>
 #include "../../include/spec.h"
+#include "mfma_gemm.h"
 
 namespace spec {
 
 constexpr int WAVE = 64;
 constexpr int KV_VBLOCK = 8;  // values of 8 consecutive positions are stored together (see kv_v_index)
+constexpr int KV_LPAD = 32;   // cache rows per sequence are padded to the attention kernel's 32-key step
 
 // ---------------------------------------------------------------- layouts
 // KV cache of one model: for each layer a K area and a V area, each
-// [B_max][H][L_pad][hd] elements, L_pad = L_max rounded up to KV_VBLOCK.
+// [B_max][H][L_pad][hd] elements, L_pad = L_max rounded up to KV_LPAD.
 //   K: row-major over positions; inside a row the head's elements are stored
 //      pair-interleaved: canonical element i (i < hd/2) sits at 2i, its rotary
 //      partner i + hd/2 at 2i+1.  Q is produced in the same order, so q.k is unchanged.
@@ -51,6 +53,8 @@ struct Model {
   const void *tok_emb = nullptr, *pos_emb = nullptr, *final_norm_w = nullptr, *final_norm_b = nullptr,
              *lm_head = nullptr;
   std::vector<LayerW> layers;
+  PackedDims p_qkv{}, p_o{}, p_13{}, p_2{}, p_head{};  // MFMA path: packed shapes
+  const float2 *rope = nullptr;                        // MFMA path: (cos, sin) table [L_max][hd/2]
   void *kcache = nullptr, *vcache = nullptr;  // [n_layers] x area
   size_t kv_area_elems = 0;                   // elements per layer per K (or V) area
   int32_t *kv_len = nullptr;                  // draft only: device [B_max] valid cache length
@@ -73,8 +77,9 @@ struct Workspace {
   void *act = nullptr;      // [M_max][f]   FFN activation, model dtype
   float *y32 = nullptr;     // [M_max][max(3d, 2f)] fp32 GEMM output (generic path)
   float *logits = nullptr;  // [M_max][vocab] fp32 (generic path / debug)
-  float *attn_part = nullptr;  // split-KV partials (MFMA path)
-  float *head_part = nullptr;  // per-tile argmax partials (MFMA path)
+  float *attn_part = nullptr, *attn_ml = nullptr;  // split-KV partials (MFMA path)
+  float *head_part = nullptr;                      // per-strip arg-max partials (MFMA path)
+  int32_t *head_part_idx = nullptr;
   int32_t *row_tok = nullptr, *row_pos = nullptr, *row_seq = nullptr;  // [M_max]
   int32_t *head_rows = nullptr;                                        // [M_max] rows that need logits
 };
@@ -99,6 +104,8 @@ struct spec_ctx {
   spec::State st;
   hipStream_t stream = nullptr;
   int M_max = 0;
+  int NC_max = 1;         // attention chunks that cover L_max
+  int n_ub = 0;           // host upper bound of every sequence's committed length
   // host-side bookkeeping
   int B = 0, P = 0;
   bool active = false;
@@ -146,5 +153,13 @@ void generic_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
 void generic_zero(void *dst, size_t bytes, hipStream_t st);
 
 size_t dtype_bytes(int dtype);
+
+// matrix-core path (16-bit dtypes)
+bool fast_supported(const spec_model_desc &D, int dtype);
+size_t fast_packed_bytes(const spec_model_desc &D, int dtype, int L_max);
+void fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&cursor, hipStream_t st);
+void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int max_pos, hipStream_t st);
+void fast_head(spec_ctx *c, const Model &m, int Mh, float *logits_or_null, int q, int arg_stride, int32_t *arg_out,
+               hipStream_t st);
 
 }  // namespace spec
