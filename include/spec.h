@@ -178,12 +178,15 @@ int spec_round(spec_ctx *ctx, int32_t s, int32_t n_rounds);
 
 /* Sec. 4, profiling stage.  For every batch size h_batch_sizes[i] (ascending) and
    every s in 0..s_max_profile: reset with the first B rows of d_prompt ([maxB][P]),
-   run rounds until every sequence emitted gen tokens (gen <= gen_max), time the decode
-   rounds with HIP events, and record microseconds per emitted token.  The LUT entry
-   is the s with the lowest value, the smaller s winning ties within 1 %.  The LUT is
-   kept in the context for spec_choose_s.  h_lut_out: [n_b]; h_grid_us_per_tok_or_null:
-   [n_b][s_max_profile+1].  In SPEC_PROPOSALS_EXTERNAL mode a proposal table must be
-   set.  Synchronises; leaves the context reset to the last profiled batch.           */
+   run one untimed warm-up round, rewind, then time max(1, gen / (s+1)) rounds with HIP
+   events (that many rounds cannot finish a sequence, so every timed round does full
+   work) and record microseconds per emitted token per sequence (elapsed / (tokens
+   emitted / B)), the per-token latency of the paper's Fig. 1.  The LUT entry is the s
+   with the lowest value, the smaller s winning ties within 1 %.  The LUT is kept in
+   the context for spec_choose_s.  h_lut_out: [n_b]; h_grid_us_per_tok_or_null:
+   [n_b][s_max_profile+1].  Needs gen <= gen_max.  In SPEC_PROPOSALS_EXTERNAL mode a
+   proposal table must be set.  Synchronises; leaves the context rewound on the last
+   profiled batch.                                                                     */
 int spec_profile_and_choose_s(spec_ctx *ctx, const int32_t *h_batch_sizes, int32_t n_b,
                               int32_t s_max_profile, const int32_t *d_prompt, int32_t P,
                               int32_t gen, int32_t *h_lut_out, float *h_grid_us_per_tok_or_null);
@@ -212,6 +215,26 @@ int spec_kv_import(spec_ctx *ctx, int32_t which_model, int32_t layer, int32_t B,
                    const void *d_k, const void *d_v);
 int spec_kv_export(spec_ctx *ctx, int32_t which_model, int32_t layer, int32_t B, int32_t len,
                    void *d_k, void *d_v);
+
+/* Per-kernel timing for benchmarks.  While enabled, every launch of the target model's
+   kernels is bracketed by a HIP event pair on the context's stream (this adds a few
+   microseconds per launch: leave it off in production).  spec_read_kernel_timing
+   synchronises, adds up the elapsed time per kernel class since the last read and clears
+   the record.  h_count, h_ms: [SPEC_KCLASS_COUNT].                                        */
+enum {
+  SPEC_KCLASS_GEMM_QKV = 0,   /* QKV projection + rotary + KV append            */
+  SPEC_KCLASS_GEMM_O,         /* attention output projection + residual         */
+  SPEC_KCLASS_GEMM_FFN_IN,    /* gate/up (or fc1) projection + activation       */
+  SPEC_KCLASS_GEMM_FFN_OUT,   /* down (or fc2) projection + residual            */
+  SPEC_KCLASS_GEMM_HEAD,      /* LM head + arg-max partials                     */
+  SPEC_KCLASS_ATTENTION,      /* verify attention (both kernels)                */
+  SPEC_KCLASS_NORM,           /* RMSNorm / LayerNorm                            */
+  SPEC_KCLASS_OTHER,          /* embedding, arg-max merge, accept/commit        */
+  SPEC_KCLASS_DRAFT_PASS,     /* one whole forward pass of the draft model      */
+  SPEC_KCLASS_COUNT
+};
+int spec_kernel_timing(spec_ctx *ctx, int32_t enable);
+int spec_read_kernel_timing(spec_ctx *ctx, int64_t *h_count, double *h_ms);
 
 #ifdef __cplusplus
 }

@@ -28,7 +28,10 @@ EXPORTS = ["spec_last_error", "spec_workspace_bytes", "spec_init", "spec_destroy
            "spec_reset_noprefill", "spec_rewind", "spec_set_proposal_table", "spec_set_proposals",
            "spec_draft_step", "spec_verify_step", "spec_accept_commit", "spec_round",
            "spec_profile_and_choose_s", "spec_set_lut", "spec_choose_s", "spec_read_output",
-           "spec_read_state", "spec_kv_import", "spec_kv_export"]
+           "spec_read_state", "spec_kv_import", "spec_kv_export", "spec_kernel_timing",
+           "spec_read_kernel_timing"]
+KCLASS_NAMES = ["gemm_qkv", "gemm_o", "gemm_ffn_in", "gemm_ffn_out", "gemm_head", "attention", "norm", "other",
+                "draft_pass"]
 
 
 class ModelDesc(C.Structure):
@@ -70,6 +73,8 @@ lib.spec_read_output.argtypes = [_vp, _i32p, _i32p, _i64p]
 lib.spec_read_state.argtypes = [_vp, _i32p, _i32p, _i32p, _i32p]
 lib.spec_kv_import.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp]
 lib.spec_kv_export.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp]
+lib.spec_kernel_timing.argtypes = [_vp, _i32]
+lib.spec_read_kernel_timing.argtypes = [_vp, _i64p, C.POINTER(C.c_double)]
 
 
 class SpecError(RuntimeError):
@@ -245,6 +250,17 @@ class Context:
         _check(lib.spec_read_state(self.h, n, kd, ll, am), self.h)
         a = [[am[b * (self.s_max + 1) + i] for i in range(self.s_max + 1)] for b in range(self.B)]
         return list(n), list(kd), list(ll), a
+
+    def spec_kernel_timing(self, enable):
+        _check(lib.spec_kernel_timing(self.h, 1 if enable else 0), self.h)
+
+    def spec_read_kernel_timing(self):
+        """-> {class name: (launch count, total ms)}"""
+        n = len(KCLASS_NAMES)
+        cnt = (C.c_int64 * n)()
+        ms = (C.c_double * n)()
+        _check(lib.spec_read_kernel_timing(self.h, cnt, ms), self.h)
+        return {KCLASS_NAMES[i]: (cnt[i], ms[i]) for i in range(n)}
 
     def spec_kv_import(self, which, layer, K, V):
         K, V = K.contiguous(), V.contiguous()

@@ -135,14 +135,17 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int m
   void *kc = (char *)m.kcache + (size_t)layer * m.kv_area_elems * esz;
   void *vc = (char *)m.vcache + (size_t)layer * m.kv_area_elems * esz;
 
-  launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, nullptr, st);
+  const bool tgt = &m == &c->tgt;  // only the target model's kernels are timed one by one
+  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, nullptr, st); }
   {
+    KScope k(c, tgt ? SPEC_KCLASS_GEMM_QKV : -1);
     GemmArgs a = base_args(m.p_qkv, L.wqkv, L.bqkv, ws.x, M);
     a.q = ws.q; a.kc = kc; a.vc = vc; a.row_pos = ws.row_pos; a.rope = m.rope;
     a.q_rows = q_rows; a.d = d; a.hd = m.hd; a.H = D.n_heads; a.L_pad = m.L_pad;
     launch_gemm_mfma(dt, a, EPI_QKV, st);
   }
   {
+    KScope k(c, tgt ? SPEC_KCLASS_ATTENTION : -1);
     AttnArgs t{};
     t.q = ws.q; t.kc = kc; t.vc = vc; t.row_pos = ws.row_pos; t.out = ws.attn;
     t.part_acc = ws.attn_part; t.part_ml = ws.attn_ml;
@@ -151,17 +154,20 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int m
     launch_attention_mfma(dt, t, st);
   }
   {
+    KScope k(c, tgt ? SPEC_KCLASS_GEMM_O : -1);
     GemmArgs a = base_args(m.p_o, L.wo, L.bo, ws.attn, M);
     a.h = ws.h;
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
   }
-  launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, nullptr, st);
+  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, nullptr, st); }
   {
+    KScope k(c, tgt ? SPEC_KCLASS_GEMM_FFN_IN : -1);
     GemmArgs a = base_args(m.p_13, L.w13, L.b13, ws.x, M);
     a.act = ws.act; a.f = D.d_ffn;
     launch_gemm_mfma(dt, a, D.ffn_kind == SPEC_FFN_SWIGLU ? EPI_SWIGLU : EPI_RELU, st);
   }
   {
+    KScope k(c, tgt ? SPEC_KCLASS_GEMM_FFN_OUT : -1);
     GemmArgs a = base_args(m.p_2, L.w2, L.b2, ws.act, M);
     a.h = ws.h;
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
@@ -171,13 +177,15 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int m
 // Final norm over the rows that need a token, LM head with the arg-max fused in.
 void fast_head(spec_ctx *c, const Model &m, int Mh, float *logits_or_null, int q, int arg_stride, int32_t *arg_out,
                hipStream_t st) {
-  launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, c->ws.head_rows, st);
+  const bool tgt = &m == &c->tgt;
+  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, c->ws.head_rows, st); }
   GemmArgs a = base_args(m.p_head, m.lm_head, nullptr, c->ws.x, Mh);
   a.logits = logits_or_null;
   a.part_val = c->ws.head_part;
   a.part_idx = c->ws.head_part_idx;
-  launch_gemm_mfma(c->run.dtype, a, EPI_LOGITS, st);
-  launch_argmax_partials(a.part_val, a.part_idx, Mh, m.p_head.NT, m.desc.vocab, q, arg_stride, arg_out, st);
+  { KScope k(c, tgt ? SPEC_KCLASS_GEMM_HEAD : -1); launch_gemm_mfma(c->run.dtype, a, EPI_LOGITS, st); }
+  { KScope k(c, tgt ? SPEC_KCLASS_OTHER : -1);
+    launch_argmax_partials(a.part_val, a.part_idx, Mh, m.p_head.NT, m.desc.vocab, q, arg_stride, arg_out, st); }
 }
 
 }  // namespace spec

@@ -5,6 +5,7 @@
 // depend on batch size or speculation length.
 #include "spec_internal.h"
 #include "device_utils.h"
+#include <algorithm>
 
 namespace spec {
 
@@ -40,8 +41,20 @@ __global__ void k_fill_zero(unsigned char *p, size_t n) {
   size_t stride = (size_t)gridDim.x * blockDim.x;
   for (; i < n; i += stride) p[i] = 0;
 }
+__global__ void k_fill_zero16(uint4 *p, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  const uint4 z = make_uint4(0u, 0u, 0u, 0u);
+  for (; i < n16; i += stride) p[i] = z;
+}
 void generic_zero(void *dst, size_t bytes, hipStream_t st) {
   if (!bytes) return;
+  if (((uintptr_t)dst | bytes) % 16 == 0) {
+    size_t n16 = bytes / 16;
+    unsigned blocks16 = (unsigned)std::min<size_t>((n16 + 255) / 256, 65535);
+    hipLaunchKernelGGL(k_fill_zero16, dim3(blocks16), dim3(256), 0, st, (uint4 *)dst, n16);
+    return;
+  }
   unsigned blocks = (unsigned)((bytes + 255) / 256);
   if (blocks > 65535u) blocks = 65535u;
   hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(256), 0, st, (unsigned char *)dst, bytes);

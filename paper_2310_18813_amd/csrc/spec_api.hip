@@ -280,8 +280,29 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
   return SPEC_OK;
 }
 
+extern "C" int spec_kernel_timing(spec_ctx *c, int32_t enable) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_kernel_timing: ctx is null");
+  c->kt_on = enable != 0;
+  return SPEC_OK;
+}
+
+extern "C" int spec_read_kernel_timing(spec_ctx *c, int64_t *h_count, double *h_ms) {
+  if (!c || !h_count || !h_ms) return fail(c, SPEC_ERR_INVALID_ARG, "spec_read_kernel_timing: null argument");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  for (int i = 0; i < SPEC_KCLASS_COUNT; ++i) { h_count[i] = 0; h_ms[i] = 0.0; }
+  for (size_t i = 0; i < c->kt_used; ++i) {
+    float ms = 0.f;
+    HIPCHK(c, hipEventElapsedTime(&ms, c->kt_ev[2 * i], c->kt_ev[2 * i + 1]));
+    const int cls = c->kt_cls[i];
+    if (cls >= 0 && cls < SPEC_KCLASS_COUNT) { h_count[cls] += 1; h_ms[cls] += ms; }
+  }
+  c->kt_used = 0;
+  return SPEC_OK;
+}
+
 extern "C" int spec_destroy(spec_ctx *c) {
   if (!c) return SPEC_OK;
+  for (hipEvent_t e : c->kt_ev) (void)hipEventDestroy(e);
   if (c->ev0) (void)hipEventDestroy(c->ev0);
   if (c->ev1) (void)hipEventDestroy(c->ev1);
   delete c;
@@ -298,7 +319,8 @@ static int forward_pass(spec_ctx *c, Model &m, const PassArgs &pa, HeadMode head
   const int M = pa.B * pa.q;
   hipStream_t st = c->stream;
   max_pos = std::max(0, std::min(max_pos, c->run.L_max - 1));
-  launch_assemble_embed(c, m, pa, st);
+  KScope whole(c, &m == &c->drf ? SPEC_KCLASS_DRAFT_PASS : -1);
+  { KScope k(c, &m == &c->tgt ? SPEC_KCLASS_OTHER : -1); launch_assemble_embed(c, m, pa, st); }
   for (int l = 0; l < m.desc.n_layers; ++l) {
     if (m.fast) fast_layer(c, m, l, pa.B, pa.q, max_pos, st);
     else generic_layer(c, m, l, M, pa.q, st);
@@ -467,7 +489,7 @@ extern "C" int spec_accept_commit(spec_ctx *c, int32_t s) {
   if (!c->active) return fail(c, SPEC_ERR_STATE, "spec_accept_commit: no batch; call spec_reset first");
   if (c->verified_s < 0) return fail(c, SPEC_ERR_STATE, "spec_accept_commit: no verify step to commit");
   if (s != c->verified_s) return fail(c, SPEC_ERR_STATE, "spec_accept_commit: verify step ran with s=%d, got s=%d", c->verified_s, s);
-  launch_accept(c, s, c->stream);
+  { KScope k(c, SPEC_KCLASS_OTHER); launch_accept(c, s, c->stream); }
   c->n_ub = std::min(c->n_ub + s + 1, c->P + c->run.gen_max);
   if (c->drf.present) c->draft_lag = c->draft_j > 0 ? 2 : std::min(c->draft_lag + 1, Q_LIMIT + 1);
   c->draft_j = 0;

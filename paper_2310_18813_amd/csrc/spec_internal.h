@@ -117,7 +117,37 @@ struct spec_ctx {
   std::vector<int32_t> lut_B, lut_s;
   std::string err;
   hipEvent_t ev0 = nullptr, ev1 = nullptr;
+  // optional per-kernel-class timing (spec_kernel_timing)
+  bool kt_on = false;
+  std::vector<hipEvent_t> kt_ev;   // start/stop pairs
+  std::vector<int> kt_cls;         // class of pair i
+  size_t kt_used = 0;              // pairs recorded since the last read
 };
+
+namespace spec {
+// Brackets the launches of one kernel class with a HIP event pair while timing is on.
+struct KScope {
+  spec_ctx *c;
+  size_t slot = 0;
+  bool on;
+  KScope(spec_ctx *ctx, int cls) : c(ctx), on(ctx->kt_on && cls >= 0) {
+    if (!on) return;
+    if (c->kt_used * 2 + 2 > c->kt_ev.size()) {
+      hipEvent_t a = nullptr, b = nullptr;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
+      c->kt_ev.push_back(a);
+      c->kt_ev.push_back(b);
+      c->kt_cls.push_back(cls);
+    }
+    slot = c->kt_used++;
+    c->kt_cls[slot] = cls;
+    (void)hipEventRecord(c->kt_ev[2 * slot], c->stream);
+  }
+  ~KScope() {
+    if (on) (void)hipEventRecord(c->kt_ev[2 * slot + 1], c->stream);
+  }
+};
+}  // namespace spec
 
 namespace spec {
 
