@@ -2,8 +2,9 @@
 // sequence against that sequence's KV cache, causal among the new rows.
 //
 // HBM-bound on the cache (a handful of flops per cached byte), so the layout is built
-// around the loads: one wave owns one (sequence, head, 256-key chunk); keys stream in as
-// full 256-byte rows, values as 16-byte runs of 8 consecutive positions.
+// around the loads: keys stream in as full rows (256 bytes at head_dim 128), values as
+// 16-byte runs of 8 consecutive positions, and the next 32-key step is in flight while
+// the current one is computed.
 //
 // Transposed formulation, so that scores never move between lanes:
 //   S^T[key][query]  = K . Q^T     A operand = 16 key rows,  B operand = 16 query rows
@@ -12,10 +13,16 @@
 // lane and tile) is already the B-operand layout of the second once the key rows fed to
 // the first product are permuted: tile t, row 4g'+i carries key ks + 8g' + 4t + i.
 //
-// Numerics depend on (sequence, absolute positions) only: chunks start at multiples of 256,
-// steps of 32 keys ascend inside a chunk, the chunk partials are merged in ascending order
-// by a second kernel.  Masked keys contribute exact zeros and leave the running maximum
-// unchanged, so the other rows of a pass never change a row's bits.
+// Numerics depend on (sequence, absolute positions) only.  The cache is cut into chunks of
+// 256 positions starting at multiples of 256.  Each chunk yields a fresh partial (running
+// maximum, sum, un-normalised output) from an online softmax over ascending 32-key steps;
+// the partials are merged pairwise in ascending chunk order.  Masked keys contribute exact
+// zeros and leave the running maximum unchanged, and merging an all-masked partial is an
+// exact no-op, so neither the other rows of a pass nor the launch shape change a row's
+// bits.  Two launch shapes compute exactly that: one wave per (sequence, head, chunk) with
+// the partials merged by a second kernel (few sequences: parallelism over chunks), or one
+// wave per (sequence, head) walking its chunks and merging in registers (many sequences:
+// no partial traffic).
 #include "spec_internal.h"
 #include "device_utils.h"
 #include "mfma_gemm.h"
@@ -53,109 +60,157 @@ template <> struct MfmaA<f16_t> {
 
 constexpr float NEG_BIG = -1.0e30f;
 
+// (m, l, acc) <- (m, l, acc) (+) (mc, lc, accc): the one merge rule, used by both launch shapes.
+__device__ __forceinline__ void merge_weights(float m, float mc, float scale, float &m_new, float &wa, float &wb) {
+  m_new = fmaxf(m, mc);
+  wa = __expf((m - m_new) * scale);
+  wb = __expf((mc - m_new) * scale);
+}
+__device__ __forceinline__ float merge_value(float a, float wa, float b, float wb) { return fmaf(a, wa, b * wb); }
+
+template <int HD> struct Frags {
+  u32x4_v k0[HD / 32], k1[HD / 32], v[HD / 16];
+};
+
 template <class T, int HD>
-__global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
+__device__ __forceinline__ void load_step(Frags<HD> &f, const T *kbase, const T *vbase, int ks, int r, int g) {
+  const T *kr0 = kbase + (size_t)(ks + 8 * (r >> 2) + (r & 3)) * HD + 8 * g;
+  const T *kr1 = kr0 + 4 * HD;
+#pragma unroll
+  for (int kk = 0; kk < HD / 32; ++kk) {
+    f.k0[kk] = *(const u32x4_v *)(kr0 + kk * 32);
+    f.k1[kk] = *(const u32x4_v *)(kr1 + kk * 32);
+  }
+  const T *vr = vbase + ((size_t)(ks / KV_VBLOCK + g) * HD + r) * KV_VBLOCK;
+#pragma unroll
+  for (int ht = 0; ht < HD / 16; ++ht) f.v[ht] = *(const u32x4_v *)(vr + (size_t)ht * 16 * KV_VBLOCK);
+}
+
+// One 32-key step of the online softmax for the 16 query columns of the wave.
+template <class T, int HD>
+__device__ __forceinline__ void compute_step(const Frags<HD> &f, const u32x4_v (&qf)[HD / 32], int ks, int g,
+                                             int pos_j, float scale, float &m_run, float &l_run,
+                                             f32x4_v (&acc)[HD / 16]) {
+  f32x4_v s0 = (f32x4_v){0.f, 0.f, 0.f, 0.f}, s1 = s0;
+#pragma unroll
+  for (int kk = 0; kk < HD / 32; ++kk) {
+    s0 = MfmaA<T>::run(f.k0[kk], qf[kk], s0);
+    s1 = MfmaA<T>::run(f.k1[kk], qf[kk], s1);
+  }
+  // lane (query j, group g): s0[i] <-> key ks + 8g + i, s1[i] <-> key ks + 8g + 4 + i
+  float sv[8];
+  const int kfirst = ks + 8 * g;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    sv[i] = (kfirst + i <= pos_j) ? s0[i] : NEG_BIG;
+    sv[4 + i] = (kfirst + 4 + i <= pos_j) ? s1[i] : NEG_BIG;
+  }
+  float smax = sv[0];
+#pragma unroll
+  for (int i = 1; i < 8; ++i) smax = fmaxf(smax, sv[i]);
+  smax = fmaxf(smax, __shfl_xor(smax, 16, 64));
+  smax = fmaxf(smax, __shfl_xor(smax, 32, 64));
+  const float m_new = fmaxf(m_run, smax);
+  const float corr = __expf((m_run - m_new) * scale);
+  float p[8];
+  float psum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float e = (sv[i] > 0.5f * NEG_BIG) ? __expf((sv[i] - m_new) * scale) : 0.f;
+    p[i] = Conv<T>::round(e);  // the product below sees the rounded weight; sum the same value
+    psum += p[i];
+  }
+  psum += __shfl_xor(psum, 16, 64);
+  psum += __shfl_xor(psum, 32, 64);
+  l_run = fmaf(l_run, corr, psum);
+  m_run = m_new;
+  u32x4_v pf;
+  pf[0] = MfmaA<T>::pack2(p[0], p[1]);
+  pf[1] = MfmaA<T>::pack2(p[2], p[3]);
+  pf[2] = MfmaA<T>::pack2(p[4], p[5]);
+  pf[3] = MfmaA<T>::pack2(p[6], p[7]);
+#pragma unroll
+  for (int ht = 0; ht < HD / 16; ++ht) {
+    acc[ht][0] *= corr; acc[ht][1] *= corr; acc[ht][2] *= corr; acc[ht][3] *= corr;
+    acc[ht] = MfmaA<T>::run(f.v[ht], pf, acc[ht]);
+  }
+}
+
+// Fresh partial of the chunk [k0, kend): steps of 32 keys, next step's loads in flight.
+template <class T, int HD>
+__device__ __forceinline__ void chunk_partial(const T *kbase, const T *vbase, const u32x4_v (&qf)[HD / 32], int k0,
+                                              int kend, int r, int g, int pos_j, float scale, float &m_run,
+                                              float &l_run, f32x4_v (&acc)[HD / 16]) {
+  m_run = NEG_BIG;
+  l_run = 0.f;
+#pragma unroll
+  for (int ht = 0; ht < HD / 16; ++ht) acc[ht] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
+  Frags<HD> fa, fb;
+  load_step<T, HD>(fa, kbase, vbase, k0, r, g);
+  int ks = k0;
+  while (true) {
+    if (ks + 32 < kend) load_step<T, HD>(fb, kbase, vbase, ks + 32, r, g);
+    compute_step<T, HD>(fa, qf, ks, g, pos_j, scale, m_run, l_run, acc);
+    ks += 32;
+    if (ks >= kend) break;
+    if (ks + 32 < kend) load_step<T, HD>(fa, kbase, vbase, ks + 32, r, g);
+    compute_step<T, HD>(fb, qf, ks, g, pos_j, scale, m_run, l_run, acc);
+    ks += 32;
+    if (ks >= kend) break;
+  }
+}
+
+struct WaveSetup {
+  int j, g, pos_j, pmax, m_row;
+};
+__device__ __forceinline__ WaveSetup wave_setup(const AttnArgs &a, int b, int lane) {
+  WaveSetup w;
+  w.j = lane & 15;
+  w.g = lane >> 4;
+  w.m_row = b * a.q_rows + min(w.j, a.q_rows - 1);
+  w.pos_j = (w.j < a.q_rows) ? a.row_pos[b * a.q_rows + w.j] : -1;
+  int pmax = w.pos_j;
+#pragma unroll
+  for (int o = 1; o <= 8; o <<= 1) pmax = max(pmax, __shfl_xor(pmax, o, 64));
+  w.pmax = pmax;
+  return w;
+}
+
+// Launch shape 1: one wave per (sequence, head, chunk); partials go to the workspace.
+template <class T, int HD>
+__global__ __launch_bounds__(256) void k_attn_split(AttnArgs a) {
   constexpr int KK = HD / 32, HT = HD / 16;
   const int lane = threadIdx.x & 63;
   const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (unit >= a.B * a.H * a.NC) return;
   const int c = unit % a.NC, bh = unit / a.NC, hh = bh % a.H, b = bh / a.H;
-  const int j = lane & 15, g = lane >> 4, r = j;
-  const int d = a.H * HD;
-  const int m_row = b * a.q_rows + min(j, a.q_rows - 1);
-  const int pos_j = (j < a.q_rows) ? a.row_pos[b * a.q_rows + j] : -1;
-  int pmax = pos_j;
-#pragma unroll
-  for (int o = 1; o <= 8; o <<= 1) pmax = max(pmax, __shfl_xor(pmax, o, 64));
+  const WaveSetup w = wave_setup(a, b, lane);
   const int k0 = c * ATTN_CHUNK;
-  if (k0 > pmax) return;  // same for the whole wave
-  const int kend = min(k0 + ATTN_CHUNK, pmax + 1);
+  if (k0 > w.pmax) return;  // same for the whole wave
+  const int kend = min(k0 + ATTN_CHUNK, w.pmax + 1);
   const float scale = rsqrtf((float)HD);
-
+  const int d = a.H * HD;
   u32x4_v qf[KK];
-  const T *qrow = (const T *)a.q + (size_t)m_row * d + (size_t)hh * HD;
+  const T *qrow = (const T *)a.q + (size_t)w.m_row * d + (size_t)hh * HD;
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) qf[kk] = *(const u32x4_v *)(qrow + kk * 32 + 8 * g);
-
+  for (int kk = 0; kk < KK; ++kk) qf[kk] = *(const u32x4_v *)(qrow + kk * 32 + 8 * w.g);
   const T *kbase = (const T *)a.kc + (size_t)bh * a.L_pad * HD;
   const T *vbase = (const T *)a.vc + (size_t)bh * (a.L_pad / KV_VBLOCK) * HD * KV_VBLOCK;
-
-  float m_run = NEG_BIG, l_run = 0.f;
+  float m_run, l_run;
   f32x4_v acc[HT];
-#pragma unroll
-  for (int ht = 0; ht < HT; ++ht) acc[ht] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
-
-  for (int ks = k0; ks < kend; ks += 32) {
-    // key rows of the two score tiles (see the permutation in the header comment)
-    const T *kr0 = kbase + (size_t)(ks + 8 * (r >> 2) + (r & 3)) * HD + 8 * g;
-    const T *kr1 = kr0 + 4 * HD;
-    u32x4_v kf0[KK], kf1[KK], vf[HT];
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      kf0[kk] = *(const u32x4_v *)(kr0 + kk * 32);
-      kf1[kk] = *(const u32x4_v *)(kr1 + kk * 32);
-    }
-    const T *vr = vbase + ((size_t)(ks / KV_VBLOCK + g) * HD + r) * KV_VBLOCK;
-#pragma unroll
-    for (int ht = 0; ht < HT; ++ht) vf[ht] = *(const u32x4_v *)(vr + (size_t)ht * 16 * KV_VBLOCK);
-
-    f32x4_v s0 = (f32x4_v){0.f, 0.f, 0.f, 0.f}, s1 = s0;
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      s0 = MfmaA<T>::run(kf0[kk], qf[kk], s0);
-      s1 = MfmaA<T>::run(kf1[kk], qf[kk], s1);
-    }
-    // lane (query j, group g): s0[i] <-> key ks + 8g + i, s1[i] <-> key ks + 8g + 4 + i
-    float sv[8];
-    const int kfirst = ks + 8 * g;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      sv[i] = (kfirst + i <= pos_j) ? s0[i] : NEG_BIG;
-      sv[4 + i] = (kfirst + 4 + i <= pos_j) ? s1[i] : NEG_BIG;
-    }
-    float smax = sv[0];
-#pragma unroll
-    for (int i = 1; i < 8; ++i) smax = fmaxf(smax, sv[i]);
-    smax = fmaxf(smax, __shfl_xor(smax, 16, 64));
-    smax = fmaxf(smax, __shfl_xor(smax, 32, 64));
-    const float m_new = fmaxf(m_run, smax);
-    const float corr = __expf((m_run - m_new) * scale);
-    float p[8];
-    float psum = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float e = (sv[i] > 0.5f * NEG_BIG) ? __expf((sv[i] - m_new) * scale) : 0.f;
-      p[i] = Conv<T>::round(e);  // the product below sees the rounded weight; sum the same value
-      psum += p[i];
-    }
-    psum += __shfl_xor(psum, 16, 64);
-    psum += __shfl_xor(psum, 32, 64);
-    l_run = l_run * corr + psum;
-    m_run = m_new;
-    u32x4_v pf;
-    pf[0] = MfmaA<T>::pack2(p[0], p[1]);
-    pf[1] = MfmaA<T>::pack2(p[2], p[3]);
-    pf[2] = MfmaA<T>::pack2(p[4], p[5]);
-    pf[3] = MfmaA<T>::pack2(p[6], p[7]);
-#pragma unroll
-    for (int ht = 0; ht < HT; ++ht) {
-      acc[ht][0] *= corr; acc[ht][1] *= corr; acc[ht][2] *= corr; acc[ht][3] *= corr;
-      acc[ht] = MfmaA<T>::run(vf[ht], pf, acc[ht]);
-    }
-  }
-
-  if (j < a.q_rows && pos_j >= k0) {
-    const size_t slot = ((size_t)(b * a.q_rows + j) * a.H + hh) * a.NC + c;
-    if (g == 0) { a.part_ml[slot * 2] = m_run; a.part_ml[slot * 2 + 1] = l_run; }
-    float *pa = a.part_acc + slot * HD + 4 * g;
+  chunk_partial<T, HD>(kbase, vbase, qf, k0, kend, w.j, w.g, w.pos_j, scale, m_run, l_run, acc);
+  if (w.j < a.q_rows && w.pos_j >= k0) {
+    const size_t slot = ((size_t)(b * a.q_rows + w.j) * a.H + hh) * a.NC + c;
+    if (w.g == 0) { a.part_ml[slot * 2] = m_run; a.part_ml[slot * 2 + 1] = l_run; }
+    float *pa = a.part_acc + slot * HD + 4 * w.g;
 #pragma unroll
     for (int ht = 0; ht < HT; ++ht) *(f32x4_v *)(pa + ht * 16) = acc[ht];
   }
 }
 
-// Merge of the chunk partials of one (row, head) in ascending chunk order.
+// Merge of the chunk partials of one (row, head), ascending.
 template <class T, int HD>
-__global__ void k_attn_combine(AttnArgs a) {
+__global__ void k_attn_merge(AttnArgs a) {
   const int m = blockIdx.x, hh = blockIdx.y, e = threadIdx.x;
   const int d = a.H * HD;
   const int pos = a.row_pos[m];
@@ -164,29 +219,88 @@ __global__ void k_attn_combine(AttnArgs a) {
   const int nc = pos / ATTN_CHUNK + 1;
   const size_t slot0 = ((size_t)m * a.H + hh) * a.NC;
   const float scale = rsqrtf((float)HD);
-  float mx = a.part_ml[slot0 * 2];
-  for (int c = 1; c < nc; ++c) mx = fmaxf(mx, a.part_ml[(slot0 + c) * 2]);
-  float den = 0.f, num = 0.f;
-  for (int c = 0; c < nc; ++c) {
-    const float wgt = __expf((a.part_ml[(slot0 + c) * 2] - mx) * scale);
-    den += a.part_ml[(slot0 + c) * 2 + 1] * wgt;
-    num += a.part_acc[(slot0 + c) * HD + e] * wgt;
+  float mr = a.part_ml[slot0 * 2], lr = a.part_ml[slot0 * 2 + 1], ar = a.part_acc[slot0 * HD + e];
+  for (int c = 1; c < nc; ++c) {
+    float mn, wa, wb;
+    merge_weights(mr, a.part_ml[(slot0 + c) * 2], scale, mn, wa, wb);
+    lr = merge_value(lr, wa, a.part_ml[(slot0 + c) * 2 + 1], wb);
+    ar = merge_value(ar, wa, a.part_acc[(slot0 + c) * HD + e], wb);
+    mr = mn;
   }
-  Conv<T>::st(out, e, num / den);
+  Conv<T>::st(out, e, ar * (1.0f / lr));
+}
+
+// Launch shape 2: one wave per (sequence, head) walks all chunks, merging in registers.
+template <class T, int HD>
+__global__ __launch_bounds__(256) void k_attn_seq(AttnArgs a) {
+  constexpr int KK = HD / 32, HT = HD / 16;
+  const int lane = threadIdx.x & 63;
+  const int bh = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (bh >= a.B * a.H) return;
+  const int hh = bh % a.H, b = bh / a.H;
+  const WaveSetup w = wave_setup(a, b, lane);
+  const int d = a.H * HD;
+  const float scale = rsqrtf((float)HD);
+  u32x4_v qf[KK];
+  const T *qrow = (const T *)a.q + (size_t)w.m_row * d + (size_t)hh * HD;
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) qf[kk] = *(const u32x4_v *)(qrow + kk * 32 + 8 * w.g);
+  const T *kbase = (const T *)a.kc + (size_t)bh * a.L_pad * HD;
+  const T *vbase = (const T *)a.vc + (size_t)bh * (a.L_pad / KV_VBLOCK) * HD * KV_VBLOCK;
+  float mr = NEG_BIG, lr = 0.f;
+  f32x4_v ar[HT];
+#pragma unroll
+  for (int ht = 0; ht < HT; ++ht) ar[ht] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
+  for (int k0 = 0; k0 <= w.pmax; k0 += ATTN_CHUNK) {
+    const int kend = min(k0 + ATTN_CHUNK, w.pmax + 1);
+    float mc, lc;
+    f32x4_v ac[HT];
+    chunk_partial<T, HD>(kbase, vbase, qf, k0, kend, w.j, w.g, w.pos_j, scale, mc, lc, ac);
+    if (k0 == 0) {
+      mr = mc; lr = lc;
+#pragma unroll
+      for (int ht = 0; ht < HT; ++ht) ar[ht] = ac[ht];
+    } else {
+      float mn, wa, wb;
+      merge_weights(mr, mc, scale, mn, wa, wb);
+      lr = merge_value(lr, wa, lc, wb);
+#pragma unroll
+      for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ar[ht][i] = merge_value(ar[ht][i], wa, ac[ht][i], wb);
+      mr = mn;
+    }
+  }
+  if (w.j < a.q_rows) {
+    T *out = (T *)a.out + (size_t)(b * a.q_rows + w.j) * d + (size_t)hh * HD + 4 * w.g;
+    const float inv = (w.pos_j >= 0) ? 1.0f / lr : 0.f;
+#pragma unroll
+    for (int ht = 0; ht < HT; ++ht) {
+      T o4[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) Conv<T>::st(o4, i, w.pos_j >= 0 ? ar[ht][i] * inv : 0.f);
+      *(uint2 *)(out + ht * 16) = *(const uint2 *)o4;
+    }
+  }
+}
+
+template <class T, int HD>
+static void launch_attn_hd(const AttnArgs &a, hipStream_t st) {
+  const int M = a.B * a.q_rows;
+  const int pairs = a.B * a.H;
+  if (pairs >= ATTN_SEQ_MIN_PAIRS || a.NC == 1) {
+    hipLaunchKernelGGL((k_attn_seq<T, HD>), dim3((pairs + 3) / 4), dim3(256), 0, st, a);
+  } else {
+    hipLaunchKernelGGL((k_attn_split<T, HD>), dim3((pairs * a.NC + 3) / 4), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((k_attn_merge<T, HD>), dim3(M, a.H), dim3(HD), 0, st, a);
+  }
 }
 
 template <class T>
 static void launch_attn_t(const AttnArgs &a, hipStream_t st) {
-  const int M = a.B * a.q_rows;
-  if (M <= 0) return;
-  const int units = a.B * a.H * a.NC;
-  if (a.hd == 128) {
-    hipLaunchKernelGGL((k_attn_partial<T, 128>), dim3((units + 3) / 4), dim3(256), 0, st, a);
-    hipLaunchKernelGGL((k_attn_combine<T, 128>), dim3(M, a.H), dim3(128), 0, st, a);
-  } else {
-    hipLaunchKernelGGL((k_attn_partial<T, 64>), dim3((units + 3) / 4), dim3(256), 0, st, a);
-    hipLaunchKernelGGL((k_attn_combine<T, 64>), dim3(M, a.H), dim3(64), 0, st, a);
-  }
+  if (a.B * a.q_rows <= 0) return;
+  if (a.hd == 128) launch_attn_hd<T, 128>(a, st);
+  else launch_attn_hd<T, 64>(a, st);
 }
 
 void launch_attention_mfma(int dtype, const AttnArgs &a, hipStream_t st) {

@@ -192,7 +192,7 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
 
-  constexpr int U = (NB * MT >= 8) ? 2 : 4;
+  constexpr int U = (NB * MT >= 8) ? 2 : (NB * MT >= 4) ? 4 : 8;
   int kt = kt0;
   for (; kt + U <= kt1; kt += U) {
     u32x4_v wf[U][NB], xf[U][MT];

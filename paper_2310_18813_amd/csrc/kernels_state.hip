@@ -70,28 +70,62 @@ __device__ __forceinline__ float block_sum_256(float v, float *sh) {
   return ((sh[0] + sh[1]) + sh[2]) + sh[3];
 }
 
+// Row held in registers: thread t owns the float4 groups t, t+256, ... (all loads issued
+// before any arithmetic, so the kernel costs one memory round trip, not d/256 of them).
+constexpr int NORM_MAX_V4 = 8;  // d <= 8192
 template <class T>
-__global__ void k_norm(int kind, int d, float eps, const float *__restrict__ h, const T *__restrict__ gain,
-                       const T *__restrict__ bias, const int32_t *__restrict__ gather, T *__restrict__ x) {
+__global__ __launch_bounds__(256) void k_norm(int kind, int d, float eps, const float *__restrict__ h,
+                                              const T *__restrict__ gain, const T *__restrict__ bias,
+                                              const int32_t *__restrict__ gather, T *__restrict__ x) {
   __shared__ float sh[4];
   const int r = blockIdx.x;
-  const float *hr = h + (size_t)(gather ? gather[r] : r) * d;
+  const float4 *hr = (const float4 *)(h + (size_t)(gather ? gather[r] : r) * d);
   T *xr = x + (size_t)r * d;
+  const int nv = d >> 2;
+  float4 v[NORM_MAX_V4];
+#pragma unroll
+  for (int i = 0; i < NORM_MAX_V4; ++i) {
+    const int c = threadIdx.x + i * 256;
+    v[i] = c < nv ? hr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  float mean = 0.f, inv;
   if (kind == SPEC_NORM_RMS) {
     float ss = 0.f;
-    for (int c = threadIdx.x; c < d; c += 256) { float v = hr[c]; ss = fmaf(v, v, ss); }
+#pragma unroll
+    for (int i = 0; i < NORM_MAX_V4; ++i) {
+      ss = fmaf(v[i].x, v[i].x, ss); ss = fmaf(v[i].y, v[i].y, ss);
+      ss = fmaf(v[i].z, v[i].z, ss); ss = fmaf(v[i].w, v[i].w, ss);
+    }
     ss = block_sum_256(ss, sh);
-    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
-    for (int c = threadIdx.x; c < d; c += 256) Conv<T>::st(xr, c, hr[c] * inv * Conv<T>::ld(gain, c));
+    inv = 1.0f / sqrtf(ss / (float)d + eps);
   } else {
     float s = 0.f;
-    for (int c = threadIdx.x; c < d; c += 256) s += hr[c];
-    const float mean = block_sum_256(s, sh) / (float)d;
+#pragma unroll
+    for (int i = 0; i < NORM_MAX_V4; ++i) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    mean = block_sum_256(s, sh) / (float)d;
     float vs = 0.f;
-    for (int c = threadIdx.x; c < d; c += 256) { float v = hr[c] - mean; vs = fmaf(v, v, vs); }
-    const float inv = 1.0f / sqrtf(block_sum_256(vs, sh) / (float)d + eps);
-    for (int c = threadIdx.x; c < d; c += 256)
-      Conv<T>::st(xr, c, (hr[c] - mean) * inv * Conv<T>::ld(gain, c) + Conv<T>::ld(bias, c));
+#pragma unroll
+    for (int i = 0; i < NORM_MAX_V4; ++i) {
+      const int c = threadIdx.x + i * 256;
+      if (c < nv) {
+        float a0 = v[i].x - mean, a1 = v[i].y - mean, a2 = v[i].z - mean, a3 = v[i].w - mean;
+        vs = fmaf(a0, a0, vs); vs = fmaf(a1, a1, vs); vs = fmaf(a2, a2, vs); vs = fmaf(a3, a3, vs);
+      }
+    }
+    inv = 1.0f / sqrtf(block_sum_256(vs, sh) / (float)d + eps);
+  }
+#pragma unroll
+  for (int i = 0; i < NORM_MAX_V4; ++i) {
+    const int c = threadIdx.x + i * 256;
+    if (c < nv) {
+      const float e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        float o = (e[k] - mean) * inv * Conv<T>::ld(gain, 4 * c + k);
+        if (kind != SPEC_NORM_RMS) o += Conv<T>::ld(bias, 4 * c + k);
+        Conv<T>::st(xr, 4 * c + k, o);
+      }
+    }
   }
 }
 

@@ -57,6 +57,7 @@ struct AttnArgs {
   int B, q_rows, H, hd, L_pad, NC;  // NC = chunks launched (upper bound over the batch)
 };
 constexpr int ATTN_CHUNK = 256;  // keys per split; boundaries at multiples of this position
+constexpr int ATTN_SEQ_MIN_PAIRS = 1024;  // (sequence, head) pairs from which one wave walks all chunks
 void launch_attention_mfma(int dtype, const AttnArgs &a, hipStream_t st);
 
 }  // namespace spec

@@ -41,6 +41,8 @@ static int check_model(const spec_model_desc *d, const char *who, int dtype) {
     return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s: n_layers, d_model, n_heads, d_ffn, vocab must be positive", who);
   if (d->d_model % d->n_heads != 0 || (d->d_model / d->n_heads) % 2 != 0)
     return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s: d_model must be a multiple of n_heads with an even head_dim", who);
+  if (d->d_model % 4 != 0 || d->d_model > 8192)
+    return fail(nullptr, SPEC_ERR_UNSUPPORTED, "%s: d_model must be a multiple of 4 and at most 8192", who);
   if (d->ffn_kind != SPEC_FFN_SWIGLU && d->ffn_kind != SPEC_FFN_RELU)
     return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s: unknown ffn_kind %d", who, d->ffn_kind);
   if (d->norm_kind != SPEC_NORM_RMS && d->norm_kind != SPEC_NORM_LAYER)
