@@ -34,6 +34,13 @@ template <> struct Conv<f16_t> {
   static __device__ __forceinline__ float round(float f) { return (float)(f16_t)f; }
 };
 
+// Activations that feed a matrix-core GEMM are stored in the order the B operand is loaded:
+// 16-row x 32-k tiles of 1 KB, tile (m/16, k/32) at ((m/16) * KT + k/32), inside a tile lane
+// 16*((k%32)/8) + m%16 owns 8 consecutive k.  Element index of X[m][k] for a row length of 32*KT:
+__host__ __device__ __forceinline__ size_t xpack_index(int m, int k, int KT) {
+  return ((((size_t)(m >> 4) * KT + (k >> 5)) * 64 + (((k & 31) >> 3) << 4) + (m & 15)) << 3) + (k & 7);
+}
+
 // Butterfly sum over the 64 lanes of a wave: every lane ends with the same value and
 // the order of additions is fixed by the lane numbers alone.
 __device__ __forceinline__ float wave_sum(float v) {

@@ -214,8 +214,8 @@ __global__ void k_attn_merge(AttnArgs a) {
   const int m = blockIdx.x, hh = blockIdx.y, e = threadIdx.x;
   const int d = a.H * HD;
   const int pos = a.row_pos[m];
-  T *out = (T *)a.out + (size_t)m * d + (size_t)hh * HD;
-  if (pos < 0) { Conv<T>::st(out, e, 0.f); return; }
+  T *out = (T *)a.out + xpack_index(m, hh * HD + e, d >> 5);
+  if (pos < 0) { Conv<T>::st(out, 0, 0.f); return; }
   const int nc = pos / ATTN_CHUNK + 1;
   const size_t slot0 = ((size_t)m * a.H + hh) * a.NC;
   const float scale = rsqrtf((float)HD);
@@ -227,7 +227,7 @@ __global__ void k_attn_merge(AttnArgs a) {
     ar = merge_value(ar, wa, a.part_acc[(slot0 + c) * HD + e], wb);
     mr = mn;
   }
-  Conv<T>::st(out, e, ar * (1.0f / lr));
+  Conv<T>::st(out, 0, ar * (1.0f / lr));
 }
 
 // Launch shape 2: one wave per (sequence, head) walks all chunks, merging in registers.
@@ -272,14 +272,14 @@ __global__ __launch_bounds__(256) void k_attn_seq(AttnArgs a) {
     }
   }
   if (w.j < a.q_rows) {
-    T *out = (T *)a.out + (size_t)(b * a.q_rows + w.j) * d + (size_t)hh * HD + 4 * w.g;
+    const int m = b * a.q_rows + w.j;
     const float inv = (w.pos_j >= 0) ? 1.0f / lr : 0.f;
 #pragma unroll
     for (int ht = 0; ht < HT; ++ht) {
       T o4[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) Conv<T>::st(o4, i, w.pos_j >= 0 ? ar[ht][i] * inv : 0.f);
-      *(uint2 *)(out + ht * 16) = *(const uint2 *)o4;
+      *(uint2 *)((T *)a.out + xpack_index(m, hh * HD + ht * 16 + 4 * w.g, d >> 5)) = *(const uint2 *)o4;
     }
   }
 }

@@ -158,20 +158,114 @@ void launch_rope_table(int L, int hd, float theta, float2 *tab, hipStream_t st) 
   hipLaunchKernelGGL(k_rope_table, dim3((total + 255) / 256), dim3(256), 0, st, L, hd, theta, tab);
 }
 
+// ------------------------------------------------------------------------- epilogues
+// One finished 16x16 tile: this lane holds stored rows n .. n+3 (n = 16*nt + 4g) of
+// activation row m.  The element-wise work of the layer happens here, on fp32 sums.
+template <class T, int EPI>
+__device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int nt, int m, int g) {
+  if (nt >= a.NT) return;
+  const int n = nt * 16 + 4 * g;
+  if (a.bias) {
+    const float4 b4 = *(const float4 *)(a.bias + n);
+    v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
+  }
+  const bool live = m < a.M;
+
+  if (EPI == EPI_RESIDUAL) {
+    if (live && n < a.N) {
+      float4 *p = (float4 *)(a.h + (size_t)m * a.N + n);
+      float4 o = *p;
+      o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
+      *p = o;
+    }
+  } else if (EPI == EPI_QKV) {
+    if (live && n < a.N) {
+      const int region = n / a.d, cc = n % a.d, hh = cc / a.hd, e = cc % a.hd;
+      const int pos = a.row_pos[m], b = m / a.q_rows;
+      if (region < 2) {
+        float r0 = v[0], r1 = v[1], r2 = v[2], r3 = v[3];
+        if (a.rope && pos >= 0) {
+          const float2 cs0 = a.rope[(size_t)pos * (a.hd >> 1) + (e >> 1)];
+          const float2 cs1 = a.rope[(size_t)pos * (a.hd >> 1) + (e >> 1) + 1];
+          r0 = v[0] * cs0.x - v[1] * cs0.y; r1 = v[1] * cs0.x + v[0] * cs0.y;
+          r2 = v[2] * cs1.x - v[3] * cs1.y; r3 = v[3] * cs1.x + v[2] * cs1.y;
+        }
+        T o4[4];
+        Conv<T>::st(o4, 0, r0); Conv<T>::st(o4, 1, r1); Conv<T>::st(o4, 2, r2); Conv<T>::st(o4, 3, r3);
+        if (region == 0) {
+          *(uint2 *)((T *)a.q + (size_t)m * a.d + cc) = *(const uint2 *)o4;
+        } else if (pos >= 0) {
+          *(uint2 *)((T *)a.kc + kv_k_index(a.L_pad, a.H, a.hd, b, hh, pos, e)) = *(const uint2 *)o4;
+        }
+      } else if (pos >= 0) {
+        T *vc = (T *)a.vc;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) Conv<T>::st(vc, kv_v_index(a.L_pad, a.H, a.hd, b, hh, pos, e + i), v[i]);
+      }
+    }
+  } else if (EPI == EPI_SWIGLU) {
+    const int j = n >> 1;  // stored rows n..n+3 = gate_j, up_j, gate_{j+1}, up_{j+1}
+    if (live && j < a.f) {
+      T o2[2];
+      Conv<T>::st(o2, 0, v[0] / (1.0f + __expf(-v[0])) * v[1]);
+      Conv<T>::st(o2, 1, v[2] / (1.0f + __expf(-v[2])) * v[3]);
+      *(uint32_t *)((T *)a.act + xpack_index(m, j, a.f >> 5)) = *(const uint32_t *)o2;
+    }
+  } else if (EPI == EPI_RELU) {
+    if (live && n < a.N) {
+      T o4[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) Conv<T>::st(o4, i, v[i] > 0.f ? v[i] : 0.f);
+      *(uint2 *)((T *)a.act + xpack_index(m, n, a.N >> 5)) = *(const uint2 *)o4;
+    }
+  } else {  // EPI_LOGITS: optional dump, per-strip arg-max partial (lowest index wins ties)
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (n + i < a.N) {
+        if (live && a.logits) a.logits[(size_t)m * a.N + n + i] = v[i];
+        argmax_combine(bv, bi, v[i], n + i);
+      }
+    for (int o = 16; o <= 32; o <<= 1) {
+      float ov = __shfl_xor(bv, o, 64);
+      int oi = __shfl_xor(bi, o, 64);
+      argmax_combine(bv, bi, ov, oi);
+    }
+    if (live && g == 0) {
+      a.part_val[(size_t)m * a.NT + nt] = bv;
+      a.part_idx[(size_t)m * a.NT + nt] = bi;
+    }
+  }
+}
+
 // ------------------------------------------------------------------------- the kernel
-// Workgroup = KS waves; wave w owns k-slice w of NB consecutive 16-row strips of W and
-// MT 16-row tiles of X.  grid.x walks the strips, grid.y the 16*MT-row blocks of X.
-// After the k loop the KS partial tiles meet in LDS and are added in slice order.
+// Workgroup = KS waves; wave w owns k-slice w of NB consecutive 16-row strips of W (a strip
+// group) and MT 16-row tiles of X (a pass).  Weights and activations are both read in
+// fragment order, 1 KB per wave per load.  After the k loop the KS partial tiles meet in
+// LDS, eight tiles at a time, and are added in slice order.
+// With more than one pass the linear workgroup id is decoded so that all passes of a strip
+// group run on the same XCD (workgroups are dealt round-robin to the 8 XCDs): the group's
+// weights are fetched from HBM once and hit that XCD's L2 for the other passes.
 template <class T, int MT, int NB, int EPI>
 __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
-  extern __shared__ float red[];  // [KS][NB*MT][256]
+  extern __shared__ float red[];  // [KS][min(NB*MT, 8)][256]
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int c = lane & 15, g = lane >> 4;
   const int KS = blockDim.x >> 6;
-  const int nt0 = blockIdx.x * NB;
-  const int m_base = blockIdx.y * (MT * 16);
+  int G, pass;
+  if (a.passes == 1) { G = blockIdx.x; pass = 0; }
+  else {
+    const int id = blockIdx.x, rest = id >> 3;
+    pass = rest % a.passes;
+    G = (rest / a.passes) * 8 + (id & 7);
+  }
+  if (G >= a.groups) return;
+  const int nt0 = G * NB;
+  const int m_base = pass * (MT * 16);
   const int kt_per = a.KT / KS;
   const int kt0 = w * kt_per, kt1 = kt0 + kt_per;
+  const int m_tiles = (a.M + 15) >> 4;
 
   const u32x4_v *Wp[NB];
 #pragma unroll
@@ -182,8 +276,8 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
   const u32x4_v *Xp[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    int m = min(m_base + mt * 16 + c, a.M - 1);
-    Xp[mt] = (const u32x4_v *)a.X + (size_t)m * (a.K_pad / 8) + g;
+    int tile = min((m_base >> 4) + mt, m_tiles - 1);
+    Xp[mt] = (const u32x4_v *)a.X + (size_t)tile * a.KT * 64 + lane;
   }
 
   f32x4_v acc[NB][MT];
@@ -192,7 +286,7 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
 
-  constexpr int U = (NB * MT >= 8) ? 2 : (NB * MT >= 4) ? 4 : 8;
+  constexpr int U = (NB + MT >= 6) ? 2 : (NB + MT >= 3) ? 4 : 8;
   int kt = kt0;
   for (; kt + U <= kt1; kt += U) {
     u32x4_v wf[U][NB], xf[U][MT];
@@ -201,7 +295,7 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) wf[u][nb] = __builtin_nontemporal_load(Wp[nb] + (size_t)(kt + u) * 64);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) xf[u][mt] = Xp[mt][(size_t)(kt + u) * 4];
+      for (int mt = 0; mt < MT; ++mt) xf[u][mt] = Xp[mt][(size_t)(kt + u) * 64];
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
@@ -215,117 +309,44 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) wf[nb] = __builtin_nontemporal_load(Wp[nb] + (size_t)kt * 64);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) xf[mt] = Xp[mt][(size_t)kt * 4];
+    for (int mt = 0; mt < MT; ++mt) xf[mt] = Xp[mt][(size_t)kt * 64];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = Mfma16<T>::run(wf[nb], xf[mt], acc[nb][mt]);
   }
 
-  // ---- slice partials -> LDS, then tile t is summed in slice order by wave t % KS
   constexpr int TILES = NB * MT;
-  if (KS > 1) {
+  if (KS == 1) {
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        *(f32x4_v *)&red[((size_t)(w * TILES + nb * MT + mt) * 64 + lane) * 4] = acc[nb][mt];
-    __syncthreads();
+    for (int t = 0; t < TILES; ++t)
+      tile_epilogue<T, EPI>(a, acc[t / MT][t % MT], nt0 + t / MT, m_base + (t % MT) * 16 + c, g);
+    return;
   }
+  constexpr int ROUNDS = (TILES + 7) / 8;
+  constexpr int SLOTS = TILES < 8 ? TILES : 8;
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb)
+  for (int r = 0; r < ROUNDS; ++r) {
+    if (r > 0) __syncthreads();
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int t = nb * MT + mt;
-      if (KS > 1 && (t % KS) != w) continue;
-      if (KS == 1 && w != 0) continue;
-      f32x4_v v;
-      if (KS > 1) {
-        v = *(const f32x4_v *)&red[((size_t)(0 * TILES + t) * 64 + lane) * 4];
-        for (int s = 1; s < KS; ++s) {
-          f32x4_v p = *(const f32x4_v *)&red[((size_t)(s * TILES + t) * 64 + lane) * 4];
-          v[0] += p[0]; v[1] += p[1]; v[2] += p[2]; v[3] += p[3];
-        }
-      } else {
-        v = acc[nb][mt];
-      }
-      const int nt = nt0 + nb;
-      const int m = m_base + mt * 16 + c;
-      if (nt >= a.NT) continue;
-      const int n = nt * 16 + 4 * g;  // this lane: stored rows n .. n+3, activation row m
-      if (a.bias) {
-        const float4 b4 = *(const float4 *)(a.bias + n);
-        v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
-      }
-      const bool live = m < a.M;
-
-      if (EPI == EPI_RESIDUAL) {
-        if (live && n < a.N) {
-          float4 *p = (float4 *)(a.h + (size_t)m * a.N + n);
-          float4 o = *p;
-          o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
-          *p = o;
-        }
-      } else if (EPI == EPI_QKV) {
-        if (live && n < a.N) {
-          const int region = n / a.d, cc = n % a.d, hh = cc / a.hd, e = cc % a.hd;
-          const int pos = a.row_pos[m], b = m / a.q_rows;
-          if (region < 2) {
-            float r0 = v[0], r1 = v[1], r2 = v[2], r3 = v[3];
-            if (a.rope && pos >= 0) {
-              const float2 cs0 = a.rope[(size_t)pos * (a.hd >> 1) + (e >> 1)];
-              const float2 cs1 = a.rope[(size_t)pos * (a.hd >> 1) + (e >> 1) + 1];
-              r0 = v[0] * cs0.x - v[1] * cs0.y; r1 = v[1] * cs0.x + v[0] * cs0.y;
-              r2 = v[2] * cs1.x - v[3] * cs1.y; r3 = v[3] * cs1.x + v[2] * cs1.y;
-            }
-            T o4[4];
-            Conv<T>::st(o4, 0, r0); Conv<T>::st(o4, 1, r1); Conv<T>::st(o4, 2, r2); Conv<T>::st(o4, 3, r3);
-            if (region == 0) {
-              *(uint2 *)((T *)a.q + (size_t)m * a.d + cc) = *(const uint2 *)o4;
-            } else if (pos >= 0) {
-              *(uint2 *)((T *)a.kc + kv_k_index(a.L_pad, a.H, a.hd, b, hh, pos, e)) = *(const uint2 *)o4;
-            }
-          } else if (pos >= 0) {
-            T *vc = (T *)a.vc;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) Conv<T>::st(vc, kv_v_index(a.L_pad, a.H, a.hd, b, hh, pos, e + i), v[i]);
-          }
-        }
-      } else if (EPI == EPI_SWIGLU) {
-        const int j = n >> 1;  // stored rows n..n+3 = gate_j, up_j, gate_{j+1}, up_{j+1}
-        if (live && j < a.f) {
-          T o2[2];
-          Conv<T>::st(o2, 0, v[0] / (1.0f + __expf(-v[0])) * v[1]);
-          Conv<T>::st(o2, 1, v[2] / (1.0f + __expf(-v[2])) * v[3]);
-          *(uint32_t *)((T *)a.act + (size_t)m * a.f + j) = *(const uint32_t *)o2;
-        }
-      } else if (EPI == EPI_RELU) {
-        if (live && n < a.N) {
-          T o4[4];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) Conv<T>::st(o4, i, v[i] > 0.f ? v[i] : 0.f);
-          *(uint2 *)((T *)a.act + (size_t)m * a.N + n) = *(const uint2 *)o4;
-        }
-      } else {  // EPI_LOGITS: optional dump, per-strip arg-max partial (lowest index wins ties)
-        float bv = -INFINITY;
-        int bi = 0x7fffffff;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (n + i < a.N) {
-            if (live && a.logits) a.logits[(size_t)m * a.N + n + i] = v[i];
-            argmax_combine(bv, bi, v[i], n + i);
-          }
-        for (int o = 16; o <= 32; o <<= 1) {
-          float ov = __shfl_xor(bv, o, 64);
-          int oi = __shfl_xor(bi, o, 64);
-          argmax_combine(bv, bi, ov, oi);
-        }
-        if (live && g == 0) {
-          a.part_val[(size_t)m * a.NT + nt] = bv;
-          a.part_idx[(size_t)m * a.NT + nt] = bi;
-        }
-      }
+    for (int slot = 0; slot < 8; ++slot) {
+      const int t = r * 8 + slot;
+      if (t < TILES) *(f32x4_v *)&red[((size_t)(w * SLOTS + slot) * 64 + lane) * 4] = acc[t / MT][t % MT];
     }
+    __syncthreads();
+#pragma unroll
+    for (int slot = 0; slot < 8; ++slot) {
+      const int t = r * 8 + slot;
+      if (t >= TILES) continue;
+      if ((slot % KS) != w) continue;
+      f32x4_v v = *(const f32x4_v *)&red[((size_t)(0 * SLOTS + slot) * 64 + lane) * 4];
+      for (int s = 1; s < KS; ++s) {
+        f32x4_v p = *(const f32x4_v *)&red[((size_t)(s * SLOTS + slot) * 64 + lane) * 4];
+        v[0] += p[0]; v[1] += p[1]; v[2] += p[2]; v[3] += p[3];
+      }
+      tile_epilogue<T, EPI>(a, v, nt0 + t / MT, m_base + (t % MT) * 16 + c, g);
+    }
+  }
 }
 
 template <class T, int MT, int NB>
@@ -340,20 +361,27 @@ static void launch_epi(const GemmArgs &a, int epi, dim3 grid, dim3 block, size_t
 }
 
 template <class T>
-static void launch_gemm_t(const GemmArgs &a, int epi, hipStream_t st) {
+static void launch_gemm_t(GemmArgs a, int epi, hipStream_t st) {
   if (a.M <= 0) return;
   const int KS = a.KS;
   // rows per pass: MT tiles of 16; strips per workgroup: NB.  Neither changes any result.
-  int MT = a.M <= 16 ? 1 : a.M <= 32 ? 2 : 4;
+  const int MT = a.M <= 16 ? 1 : a.M <= 32 ? 2 : 4;
+  a.passes = (a.M + MT * 16 - 1) / (MT * 16);
+  // as many strips per workgroup as row tiles (activation traffic = weight traffic), while the
+  // launch still has at least one workgroup per CU
   int NB = 1;
-  if (MT == 4 && a.NT >= 1024) NB = 2;
-  const int passes = (a.M + MT * 16 - 1) / (MT * 16);
-  dim3 grid((a.NT + NB - 1) / NB, passes), block(KS * 64);
-  size_t lds = KS > 1 ? (size_t)KS * NB * MT * 1024 : 0;
+  while (NB < MT && (a.NT / (NB * 2)) * a.passes >= 256) NB *= 2;
+  a.groups = (a.NT + NB - 1) / NB;
+  const int blocks = a.passes == 1 ? a.groups : ((a.groups + 7) / 8) * 8 * a.passes;
+  dim3 grid(blocks), block(KS * 64);
+  const int tiles = NB * MT;
+  const size_t lds = KS > 1 ? (size_t)KS * (tiles < 8 ? tiles : 8) * 1024 : 0;
   if (MT == 1) launch_epi<T, 1, 1>(a, epi, grid, block, lds, st);
-  else if (MT == 2) launch_epi<T, 2, 1>(a, epi, grid, block, lds, st);
+  else if (MT == 2 && NB == 1) launch_epi<T, 2, 1>(a, epi, grid, block, lds, st);
+  else if (MT == 2) launch_epi<T, 2, 2>(a, epi, grid, block, lds, st);
   else if (NB == 1) launch_epi<T, 4, 1>(a, epi, grid, block, lds, st);
-  else launch_epi<T, 4, 2>(a, epi, grid, block, lds, st);
+  else if (NB == 2) launch_epi<T, 4, 2>(a, epi, grid, block, lds, st);
+  else launch_epi<T, 4, 4>(a, epi, grid, block, lds, st);
 }
 
 void launch_gemm_mfma(int dtype, const GemmArgs &a, int epi, hipStream_t st) {

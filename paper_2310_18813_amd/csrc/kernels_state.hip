@@ -76,11 +76,11 @@ constexpr int NORM_MAX_V4 = 8;  // d <= 8192
 template <class T>
 __global__ __launch_bounds__(256) void k_norm(int kind, int d, float eps, const float *__restrict__ h,
                                               const T *__restrict__ gain, const T *__restrict__ bias,
-                                              const int32_t *__restrict__ gather, T *__restrict__ x) {
+                                              const int32_t *__restrict__ gather, T *__restrict__ x,
+                                              int pack_kt) {
   __shared__ float sh[4];
   const int r = blockIdx.x;
   const float4 *hr = (const float4 *)(h + (size_t)(gather ? gather[r] : r) * d);
-  T *xr = x + (size_t)r * d;
   const int nv = d >> 2;
   float4 v[NORM_MAX_V4];
 #pragma unroll
@@ -123,7 +123,8 @@ __global__ __launch_bounds__(256) void k_norm(int kind, int d, float eps, const 
       for (int k = 0; k < 4; ++k) {
         float o = (e[k] - mean) * inv * Conv<T>::ld(gain, 4 * c + k);
         if (kind != SPEC_NORM_RMS) o += Conv<T>::ld(bias, 4 * c + k);
-        Conv<T>::st(xr, 4 * c + k, o);
+        // pack_kt > 0: the consumer is a matrix-core GEMM, rows are stored in fragment order
+        Conv<T>::st(x, pack_kt > 0 ? xpack_index(r, 4 * c + k, pack_kt) : (size_t)r * d + 4 * c + k, o);
       }
     }
   }
@@ -132,9 +133,10 @@ __global__ __launch_bounds__(256) void k_norm(int kind, int d, float eps, const 
 void launch_norm(const spec_ctx *c, const Model &m, const float *h, const void *gain, const void *bias, void *x,
                  int M, const int32_t *row_gather, hipStream_t st) {
   if (M <= 0) return;
+  const int pack_kt = m.fast ? m.desc.d_model / 32 : 0;
   SPEC_DISPATCH_DTYPE(c->run.dtype, T,
     hipLaunchKernelGGL(k_norm<T>, dim3(M), dim3(256), 0, st, m.desc.norm_kind, m.desc.d_model, m.desc.norm_eps, h,
-                       (const T *)gain, (const T *)bias, row_gather, (T *)x));
+                       (const T *)gain, (const T *)bias, row_gather, (T *)x, pack_kt));
 }
 
 // -------------------------------------------------------------------------
