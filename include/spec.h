@@ -216,6 +216,17 @@ int spec_kv_import(spec_ctx *ctx, int32_t which_model, int32_t layer, int32_t B,
 int spec_kv_export(spec_ctx *ctx, int32_t which_model, int32_t layer, int32_t B, int32_t len,
                    void *d_k, void *d_v);
 
+/* Parity aid: if d_hidden is not NULL, every following target pass (verify step or prefill
+   chunk) also copies its fp32 residual stream into d_hidden as [n_layers + 1][M][d_model]:
+   slice 0 after the embedding, slice l after layer l (M = rows of that pass).  NULL turns it
+   off.  The buffer is the caller's and must hold (n_layers + 1) * B_max * 16 * d_model floats. */
+int spec_set_hidden_dump(spec_ctx *ctx, float *d_hidden);
+
+/* Test aid: pin the launch shape of the 16-bit verify attention.  0 = chosen from the batch size
+   (default), 1 = one wave per (sequence, head, chunk) plus a merge kernel, 2 = one wave per
+   (sequence, head).  Results must not depend on it.                                          */
+int spec_set_attention_shape(spec_ctx *ctx, int32_t shape);
+
 /* Per-kernel timing for benchmarks.  While enabled, every launch of the target model's
    kernels is bracketed by a HIP event pair on the context's stream (this adds a few
    microseconds per launch: leave it off in production).  spec_read_kernel_timing

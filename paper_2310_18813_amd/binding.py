@@ -29,7 +29,7 @@ EXPORTS = ["spec_last_error", "spec_workspace_bytes", "spec_init", "spec_destroy
            "spec_draft_step", "spec_verify_step", "spec_accept_commit", "spec_round",
            "spec_profile_and_choose_s", "spec_set_lut", "spec_choose_s", "spec_read_output",
            "spec_read_state", "spec_kv_import", "spec_kv_export", "spec_kernel_timing",
-           "spec_read_kernel_timing"]
+           "spec_read_kernel_timing", "spec_set_hidden_dump", "spec_set_attention_shape"]
 KCLASS_NAMES = ["gemm_qkv", "gemm_o", "gemm_ffn_in", "gemm_ffn_out", "gemm_head", "attention", "norm", "other",
                 "draft_pass"]
 
@@ -73,6 +73,8 @@ lib.spec_read_output.argtypes = [_vp, _i32p, _i32p, _i64p]
 lib.spec_read_state.argtypes = [_vp, _i32p, _i32p, _i32p, _i32p]
 lib.spec_kv_import.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp]
 lib.spec_kv_export.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp]
+lib.spec_set_hidden_dump.argtypes = [_vp, _vp]
+lib.spec_set_attention_shape.argtypes = [_vp, _i32]
 lib.spec_kernel_timing.argtypes = [_vp, _i32]
 lib.spec_read_kernel_timing.argtypes = [_vp, _i64p, C.POINTER(C.c_double)]
 
@@ -250,6 +252,20 @@ class Context:
         _check(lib.spec_read_state(self.h, n, kd, ll, am), self.h)
         a = [[am[b * (self.s_max + 1) + i] for i in range(self.s_max + 1)] for b in range(self.B)]
         return list(n), list(kd), list(ll), a
+
+    def spec_set_hidden_dump(self, on):
+        """on=True allocates the dump tensor [n_layers + 1][B_max * 16][d_model] and returns it."""
+        if not on:
+            self._hidden = None
+            _check(lib.spec_set_hidden_dump(self.h, None), self.h)
+            return None
+        nl, d = self.tgt_desc["n_layers"], self.tgt_desc["d_model"]
+        self._hidden = torch.zeros((nl + 1) * self.B_max * 16 * d, dtype=torch.float32, device=self.device)
+        _check(lib.spec_set_hidden_dump(self.h, _dp(self._hidden)), self.h)
+        return self._hidden
+
+    def spec_set_attention_shape(self, shape):
+        _check(lib.spec_set_attention_shape(self.h, shape), self.h)
 
     def spec_kernel_timing(self, enable):
         _check(lib.spec_kernel_timing(self.h, 1 if enable else 0), self.h)

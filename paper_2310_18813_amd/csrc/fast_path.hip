@@ -117,9 +117,10 @@ void fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&curso
   }
 }
 
-static GemmArgs base_args(const PackedDims &p, const void *W, const void *bias, const void *X, int M) {
+static GemmArgs base_args(const PackedDims &p, const void *W, const void *bias, const void *X, const void *X2,
+                          int M) {
   GemmArgs a{};
-  a.W = W; a.bias = (const float *)bias; a.X = X;
+  a.W = W; a.bias = (const float *)bias; a.X = X; a.X2 = X2;
   a.M = M; a.N = p.N; a.NT = p.NT; a.KT = p.KT; a.KS = p.KS; a.K_pad = p.K_pad;
   return a;
 }
@@ -136,10 +137,10 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int m
   void *vc = (char *)m.vcache + (size_t)layer * m.kv_area_elems * esz;
 
   const bool tgt = &m == &c->tgt;  // only the target model's kernels are timed one by one
-  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, nullptr, st); }
+  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, nullptr, st, ws.x_lo); }
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_QKV : -1);
-    GemmArgs a = base_args(m.p_qkv, L.wqkv, L.bqkv, ws.x, M);
+    GemmArgs a = base_args(m.p_qkv, L.wqkv, L.bqkv, ws.x, ws.x_lo, M);
     a.q = ws.q; a.kc = kc; a.vc = vc; a.row_pos = ws.row_pos; a.rope = m.rope;
     a.q_rows = q_rows; a.d = d; a.hd = m.hd; a.H = D.n_heads; a.L_pad = m.L_pad;
     launch_gemm_mfma(dt, a, EPI_QKV, st);
@@ -147,28 +148,29 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int m
   {
     KScope k(c, tgt ? SPEC_KCLASS_ATTENTION : -1);
     AttnArgs t{};
-    t.q = ws.q; t.kc = kc; t.vc = vc; t.row_pos = ws.row_pos; t.out = ws.attn;
+    t.q = ws.q; t.kc = kc; t.vc = vc; t.row_pos = ws.row_pos; t.out = ws.attn; t.out2 = ws.attn_lo;
     t.part_acc = ws.attn_part; t.part_ml = ws.attn_ml;
     t.B = B; t.q_rows = q_rows; t.H = D.n_heads; t.hd = m.hd; t.L_pad = m.L_pad;
+    t.shape = c->attn_shape;
     t.NC = std::min(c->NC_max, max_pos / ATTN_CHUNK + 1);
     launch_attention_mfma(dt, t, st);
   }
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_O : -1);
-    GemmArgs a = base_args(m.p_o, L.wo, L.bo, ws.attn, M);
+    GemmArgs a = base_args(m.p_o, L.wo, L.bo, ws.attn, ws.attn_lo, M);
     a.h = ws.h;
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
   }
-  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, nullptr, st); }
+  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, nullptr, st, ws.x_lo); }
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_FFN_IN : -1);
-    GemmArgs a = base_args(m.p_13, L.w13, L.b13, ws.x, M);
-    a.act = ws.act; a.f = D.d_ffn;
+    GemmArgs a = base_args(m.p_13, L.w13, L.b13, ws.x, ws.x_lo, M);
+    a.act = ws.act; a.act2 = ws.act_lo; a.f = D.d_ffn;
     launch_gemm_mfma(dt, a, D.ffn_kind == SPEC_FFN_SWIGLU ? EPI_SWIGLU : EPI_RELU, st);
   }
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_FFN_OUT : -1);
-    GemmArgs a = base_args(m.p_2, L.w2, L.b2, ws.act, M);
+    GemmArgs a = base_args(m.p_2, L.w2, L.b2, ws.act, ws.act_lo, M);
     a.h = ws.h;
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
   }
@@ -178,8 +180,8 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int m
 void fast_head(spec_ctx *c, const Model &m, int Mh, float *logits_or_null, int q, int arg_stride, int32_t *arg_out,
                hipStream_t st) {
   const bool tgt = &m == &c->tgt;
-  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, c->ws.head_rows, st); }
-  GemmArgs a = base_args(m.p_head, m.lm_head, nullptr, c->ws.x, Mh);
+  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, c->ws.head_rows, st, c->ws.x_lo); }
+  GemmArgs a = base_args(m.p_head, m.lm_head, nullptr, c->ws.x, c->ws.x_lo, Mh);
   a.logits = logits_or_null;
   a.part_val = c->ws.head_part;
   a.part_idx = c->ws.head_part_idx;

@@ -27,6 +27,11 @@
 #include "device_utils.h"
 #include "mfma_gemm.h"
 
+// No implicit fusing of multiplies and adds: which product a compiler folds into an FMA can
+// differ between two instantiations of the same source, and results here must be bit-identical
+// across launch shapes.  Fused operations are written out with fmaf where they are wanted.
+#pragma clang fp contract(off)
+
 namespace spec {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_v;
@@ -59,12 +64,20 @@ template <> struct MfmaA<f16_t> {
 };
 
 constexpr float NEG_BIG = -1.0e30f;
+constexpr float LOG2E = 1.4426950408889634f;
+
+// exp((a - b) * scale) with the scale pre-multiplied by log2(e): one subtraction, one
+// multiplication, one hardware exp2 -- nothing the optimiser may legally rearrange, so every
+// kernel that uses it produces the same bits.
+__device__ __forceinline__ float exp_diff(float a, float b, float sl2) {
+  return __builtin_amdgcn_exp2f((a - b) * sl2);
+}
 
 // (m, l, acc) <- (m, l, acc) (+) (mc, lc, accc): the one merge rule, used by both launch shapes.
 __device__ __forceinline__ void merge_weights(float m, float mc, float scale, float &m_new, float &wa, float &wb) {
   m_new = fmaxf(m, mc);
-  wa = __expf((m - m_new) * scale);
-  wb = __expf((mc - m_new) * scale);
+  wa = exp_diff(m, m_new, scale);
+  wb = exp_diff(mc, m_new, scale);
 }
 __device__ __forceinline__ float merge_value(float a, float wa, float b, float wb) { return fmaf(a, wa, b * wb); }
 
@@ -111,12 +124,12 @@ __device__ __forceinline__ void compute_step(const Frags<HD> &f, const u32x4_v (
   smax = fmaxf(smax, __shfl_xor(smax, 16, 64));
   smax = fmaxf(smax, __shfl_xor(smax, 32, 64));
   const float m_new = fmaxf(m_run, smax);
-  const float corr = __expf((m_run - m_new) * scale);
+  const float corr = exp_diff(m_run, m_new, scale);
   float p[8];
   float psum = 0.f;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    float e = (sv[i] > 0.5f * NEG_BIG) ? __expf((sv[i] - m_new) * scale) : 0.f;
+    float e = (sv[i] > 0.5f * NEG_BIG) ? exp_diff(sv[i], m_new, scale) : 0.f;
     p[i] = Conv<T>::round(e);  // the product below sees the rounded weight; sum the same value
     psum += p[i];
   }
@@ -188,7 +201,7 @@ __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a) {
   const int k0 = c * ATTN_CHUNK;
   if (k0 > w.pmax) return;  // same for the whole wave
   const int kend = min(k0 + ATTN_CHUNK, w.pmax + 1);
-  const float scale = rsqrtf((float)HD);
+  const float scale = rsqrtf((float)HD) * LOG2E;  // score scale in base-2 exponent units
   const int d = a.H * HD;
   u32x4_v qf[KK];
   const T *qrow = (const T *)a.q + (size_t)w.m_row * d + (size_t)hh * HD;
@@ -214,11 +227,12 @@ __global__ void k_attn_merge(AttnArgs a) {
   const int m = blockIdx.x, hh = blockIdx.y, e = threadIdx.x;
   const int d = a.H * HD;
   const int pos = a.row_pos[m];
-  T *out = (T *)a.out + xpack_index(m, hh * HD + e, d >> 5);
-  if (pos < 0) { Conv<T>::st(out, 0, 0.f); return; }
+  const size_t at = xpack_index(m, hh * HD + e, d >> 5);
+  T *out = (T *)a.out + at, *out2 = (T *)a.out2 + at;
+  if (pos < 0) { Conv<T>::st(out, 0, 0.f); Conv<T>::st(out2, 0, 0.f); return; }
   const int nc = pos / ATTN_CHUNK + 1;
   const size_t slot0 = ((size_t)m * a.H + hh) * a.NC;
-  const float scale = rsqrtf((float)HD);
+  const float scale = rsqrtf((float)HD) * LOG2E;  // score scale in base-2 exponent units
   float mr = a.part_ml[slot0 * 2], lr = a.part_ml[slot0 * 2 + 1], ar = a.part_acc[slot0 * HD + e];
   for (int c = 1; c < nc; ++c) {
     float mn, wa, wb;
@@ -227,7 +241,9 @@ __global__ void k_attn_merge(AttnArgs a) {
     ar = merge_value(ar, wa, a.part_acc[(slot0 + c) * HD + e], wb);
     mr = mn;
   }
-  Conv<T>::st(out, 0, ar * (1.0f / lr));
+  const float res = ar * (1.0f / lr);
+  Conv<T>::st(out, 0, res);
+  Conv<T>::st(out2, 0, res - Conv<T>::round(res));
 }
 
 // Launch shape 2: one wave per (sequence, head) walks all chunks, merging in registers.
@@ -240,7 +256,7 @@ __global__ __launch_bounds__(256) void k_attn_seq(AttnArgs a) {
   const int hh = bh % a.H, b = bh / a.H;
   const WaveSetup w = wave_setup(a, b, lane);
   const int d = a.H * HD;
-  const float scale = rsqrtf((float)HD);
+  const float scale = rsqrtf((float)HD) * LOG2E;  // score scale in base-2 exponent units
   u32x4_v qf[KK];
   const T *qrow = (const T *)a.q + (size_t)w.m_row * d + (size_t)hh * HD;
 #pragma unroll
@@ -276,10 +292,16 @@ __global__ __launch_bounds__(256) void k_attn_seq(AttnArgs a) {
     const float inv = (w.pos_j >= 0) ? 1.0f / lr : 0.f;
 #pragma unroll
     for (int ht = 0; ht < HT; ++ht) {
-      T o4[4];
+      T o4[4], l4[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) Conv<T>::st(o4, i, w.pos_j >= 0 ? ar[ht][i] * inv : 0.f);
-      *(uint2 *)((T *)a.out + xpack_index(m, hh * HD + ht * 16 + 4 * w.g, d >> 5)) = *(const uint2 *)o4;
+      for (int i = 0; i < 4; ++i) {
+        const float res = w.pos_j >= 0 ? ar[ht][i] * inv : 0.f;
+        Conv<T>::st(o4, i, res);
+        Conv<T>::st(l4, i, res - Conv<T>::round(res));
+      }
+      const size_t at = xpack_index(m, hh * HD + ht * 16 + 4 * w.g, d >> 5);
+      *(uint2 *)((T *)a.out + at) = *(const uint2 *)o4;
+      *(uint2 *)((T *)a.out2 + at) = *(const uint2 *)l4;
     }
   }
 }
@@ -288,7 +310,8 @@ template <class T, int HD>
 static void launch_attn_hd(const AttnArgs &a, hipStream_t st) {
   const int M = a.B * a.q_rows;
   const int pairs = a.B * a.H;
-  if (pairs >= ATTN_SEQ_MIN_PAIRS || a.NC == 1) {
+  const bool seq = a.shape == 2 || (a.shape == 0 && (pairs >= ATTN_SEQ_MIN_PAIRS || a.NC == 1));
+  if (seq) {
     hipLaunchKernelGGL((k_attn_seq<T, HD>), dim3((pairs + 3) / 4), dim3(256), 0, st, a);
   } else {
     hipLaunchKernelGGL((k_attn_split<T, HD>), dim3((pairs * a.NC + 3) / 4), dim3(256), 0, st, a);

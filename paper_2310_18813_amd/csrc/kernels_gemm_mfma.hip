@@ -22,6 +22,11 @@
 #include "device_utils.h"
 #include "mfma_gemm.h"
 
+// No implicit fusing of multiplies and adds: which product a compiler folds into an FMA can
+// differ between two instantiations of the same source, and results here must be bit-identical
+// across launch shapes.  Fused operations are written out with fmaf where they are wanted.
+#pragma clang fp contract(off)
+
 namespace spec {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_v;
@@ -206,17 +211,26 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int 
   } else if (EPI == EPI_SWIGLU) {
     const int j = n >> 1;  // stored rows n..n+3 = gate_j, up_j, gate_{j+1}, up_{j+1}
     if (live && j < a.f) {
-      T o2[2];
-      Conv<T>::st(o2, 0, v[0] / (1.0f + __expf(-v[0])) * v[1]);
-      Conv<T>::st(o2, 1, v[2] / (1.0f + __expf(-v[2])) * v[3]);
-      *(uint32_t *)((T *)a.act + xpack_index(m, j, a.f >> 5)) = *(const uint32_t *)o2;
+      const float r0 = v[0] / (1.0f + __expf(-v[0])) * v[1], r1 = v[2] / (1.0f + __expf(-v[2])) * v[3];
+      T o2[2], l2[2];
+      Conv<T>::st(o2, 0, r0); Conv<T>::st(o2, 1, r1);
+      Conv<T>::st(l2, 0, r0 - Conv<T>::round(r0)); Conv<T>::st(l2, 1, r1 - Conv<T>::round(r1));
+      const size_t at = xpack_index(m, j, a.f >> 5);
+      *(uint32_t *)((T *)a.act + at) = *(const uint32_t *)o2;
+      *(uint32_t *)((T *)a.act2 + at) = *(const uint32_t *)l2;
     }
   } else if (EPI == EPI_RELU) {
     if (live && n < a.N) {
-      T o4[4];
+      T o4[4], l4[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) Conv<T>::st(o4, i, v[i] > 0.f ? v[i] : 0.f);
-      *(uint2 *)((T *)a.act + xpack_index(m, n, a.N >> 5)) = *(const uint2 *)o4;
+      for (int i = 0; i < 4; ++i) {
+        const float r = v[i] > 0.f ? v[i] : 0.f;
+        Conv<T>::st(o4, i, r);
+        Conv<T>::st(l4, i, r - Conv<T>::round(r));
+      }
+      const size_t at = xpack_index(m, n, a.N >> 5);
+      *(uint2 *)((T *)a.act + at) = *(const uint2 *)o4;
+      *(uint2 *)((T *)a.act2 + at) = *(const uint2 *)l4;
     }
   } else {  // EPI_LOGITS: optional dump, per-strip arg-max partial (lowest index wins ties)
     float bv = -INFINITY;
@@ -274,11 +288,20 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
     Wp[nb] = (const u32x4_v *)a.W + (size_t)nt * a.KT * 64 + lane;
   }
   const u32x4_v *Xp[MT];
+  bool xlive[MT];  // lanes whose activation row does not exist load nothing and feed zeros
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     int tile = min((m_base >> 4) + mt, m_tiles - 1);
     Xp[mt] = (const u32x4_v *)a.X + (size_t)tile * a.KT * 64 + lane;
+    xlive[mt] = m_base + mt * 16 + c < a.M;
   }
+  const u32x4_v zero4 = (u32x4_v){0u, 0u, 0u, 0u};
+  // Activation rows come as a high and a low 16-bit part (x = hi + lo, fragment order both),
+  // each multiplied with the weight tile in turn: the products then carry the fp32 activations to
+  // about 2^-16 relative instead of the 2^-8 of one 16-bit word, which is what keeps logits within
+  // the parity tolerance.  Weights are exact 16-bit values, so they need no such treatment.
+  constexpr bool SPLIT = true;
+  const ptrdiff_t x2off = SPLIT ? ((const u32x4_v *)a.X2 - (const u32x4_v *)a.X) : 0;
 
   f32x4_v acc[NB][MT];
 #pragma unroll
@@ -289,31 +312,43 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
   constexpr int U = (NB + MT >= 6) ? 2 : (NB + MT >= 3) ? 4 : 8;
   int kt = kt0;
   for (; kt + U <= kt1; kt += U) {
-    u32x4_v wf[U][NB], xf[U][MT];
+    u32x4_v wf[U][NB], xf[U][MT], xl[U][SPLIT ? MT : 1];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) wf[u][nb] = __builtin_nontemporal_load(Wp[nb] + (size_t)(kt + u) * 64);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) xf[u][mt] = Xp[mt][(size_t)(kt + u) * 64];
+      for (int mt = 0; mt < MT; ++mt) {
+        xf[u][mt] = xlive[mt] ? Xp[mt][(size_t)(kt + u) * 64] : zero4;
+        if (SPLIT) xl[u][mt] = xlive[mt] ? Xp[mt][(size_t)(kt + u) * 64 + x2off] : zero4;
+      }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = Mfma16<T>::run(wf[u][nb], xf[u][mt], acc[nb][mt]);
+        for (int mt = 0; mt < MT; ++mt) {
+          acc[nb][mt] = Mfma16<T>::run(wf[u][nb], xf[u][mt], acc[nb][mt]);
+          if (SPLIT) acc[nb][mt] = Mfma16<T>::run(wf[u][nb], xl[u][mt], acc[nb][mt]);
+        }
   }
   for (; kt < kt1; ++kt) {
-    u32x4_v wf[NB], xf[MT];
+    u32x4_v wf[NB], xf[MT], xl[SPLIT ? MT : 1];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) wf[nb] = __builtin_nontemporal_load(Wp[nb] + (size_t)kt * 64);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) xf[mt] = Xp[mt][(size_t)kt * 64];
+    for (int mt = 0; mt < MT; ++mt) {
+      xf[mt] = xlive[mt] ? Xp[mt][(size_t)kt * 64] : zero4;
+      if (SPLIT) xl[mt] = xlive[mt] ? Xp[mt][(size_t)kt * 64 + x2off] : zero4;
+    }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = Mfma16<T>::run(wf[nb], xf[mt], acc[nb][mt]);
+      for (int mt = 0; mt < MT; ++mt) {
+        acc[nb][mt] = Mfma16<T>::run(wf[nb], xf[mt], acc[nb][mt]);
+        if (SPLIT) acc[nb][mt] = Mfma16<T>::run(wf[nb], xl[mt], acc[nb][mt]);
+      }
   }
 
   constexpr int TILES = NB * MT;

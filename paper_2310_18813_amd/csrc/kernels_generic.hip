@@ -7,6 +7,11 @@
 #include "device_utils.h"
 #include <algorithm>
 
+// No implicit fusing of multiplies and adds: which product a compiler folds into an FMA can
+// differ between two instantiations of the same source, and results here must be bit-identical
+// across launch shapes.  Fused operations are written out with fmaf where they are wanted.
+#pragma clang fp contract(off)
+
 namespace spec {
 
 size_t dtype_bytes(int dtype) { return dtype == SPEC_DTYPE_F32 ? 4 : 2; }

@@ -24,6 +24,7 @@ struct GemmArgs {
   const void *W;      // packed tiles
   const float *bias;  // [N_pad] in stored-row order, or null
   const void *X;      // activations in fragment order (xpack_index), ceil(M/16) x KT tiles
+  const void *X2;     // low 16-bit parts of the same rows (same layout): x = X + X2
   int M, N, NT, KT, KS, K_pad;
   int passes, groups;  // filled by the launcher
   // epilogue targets (those the chosen epilogue uses)
@@ -32,7 +33,7 @@ struct GemmArgs {
   const int32_t *row_pos;    // EPI_QKV: absolute position per row, -1 = dead row
   const float2 *rope;        // EPI_QKV: (cos, sin) table [L][hd/2] or null
   int q_rows, d, hd, H, L_pad;
-  void *act;                 // EPI_SWIGLU / EPI_RELU: fragment order, row length f (resp. N)
+  void *act, *act2;          // EPI_SWIGLU / EPI_RELU: high / low parts, fragment order, row length f (resp. N)
   int f;
   float *logits;             // EPI_LOGITS: optional [M][N] fp32
   float *part_val;           // EPI_LOGITS: [M][NT]
@@ -52,9 +53,10 @@ struct AttnArgs {
   const void *q;            // [M][d] model dtype, pair-interleaved heads
   const void *kc, *vc;      // this layer's cache areas
   const int32_t *row_pos;   // [M]
-  void *out;                // [M][d] model dtype, canonical element order, fragment layout (xpack_index)
+  void *out, *out2;         // [M][d] high / low 16-bit parts, canonical element order, fragment layout
   float *part_acc;          // [M][H][NC][hd] un-normalised partial outputs
   float *part_ml;           // [M][H][NC][2] running max (raw score units) and sum
+  int shape;                // 0 auto, 1 split + merge, 2 one wave per (sequence, head)
   int B, q_rows, H, hd, L_pad, NC;  // NC = chunks launched (upper bound over the batch)
 };
 constexpr int ATTN_CHUNK = 256;  // keys per split; boundaries at multiples of this position

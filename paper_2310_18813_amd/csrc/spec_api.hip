@@ -104,7 +104,7 @@ static Sizes compute_sizes(const spec_model_desc *tgt, const spec_model_desc *dr
     wide = std::max(wide, std::max<size_t>(3 * (size_t)drf->d_model, kfd * drf->d_ffn));
   }
   const size_t Mp = (M + 15) / 16 * 16;  // fragment-order activation buffers hold whole 16-row tiles
-  z.act = al256(M * d * 4) + 3 * al256(Mp * d * e) + al256(Mp * f * e) + al256(M * wide * 4) + al256(M * V * 4) +
+  z.act = al256(M * d * 4) + 5 * al256(Mp * d * e) + 2 * al256(Mp * f * e) + al256(M * wide * 4) + al256(M * V * 4) +
           4 * al256(M * 4);
   // matrix-core path: split-KV attention partials and per-strip arg-max partials
   const size_t NC = (L + ATTN_CHUNK - 1) / ATTN_CHUNK, NTh = (V + 15) / 16;
@@ -245,6 +245,9 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
   W.q = carve(p, Mp * d * e);
   W.attn = carve(p, Mp * d * e);
   W.act = carve(p, Mp * f * e);
+  W.x_lo = carve(p, Mp * d * e);
+  W.attn_lo = carve(p, Mp * d * e);
+  W.act_lo = carve(p, Mp * f * e);
   W.y32 = (float *)carve(p, M * wide * 4);
   W.logits = (float *)carve(p, M * V * 4);
   W.row_tok = (int32_t *)carve(p, M * 4);
@@ -281,6 +284,19 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
     return rc;
   }
   *out = c;
+  return SPEC_OK;
+}
+
+extern "C" int spec_set_hidden_dump(spec_ctx *c, float *d_hidden) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_set_hidden_dump: ctx is null");
+  c->hidden_dump = d_hidden;
+  return SPEC_OK;
+}
+
+extern "C" int spec_set_attention_shape(spec_ctx *c, int32_t shape) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_set_attention_shape: ctx is null");
+  if (shape < 0 || shape > 2) return fail(c, SPEC_ERR_INVALID_ARG, "spec_set_attention_shape: shape must be 0, 1 or 2");
+  c->attn_shape = shape;
   return SPEC_OK;
 }
 
@@ -325,9 +341,13 @@ static int forward_pass(spec_ctx *c, Model &m, const PassArgs &pa, HeadMode head
   max_pos = std::max(0, std::min(max_pos, c->run.L_max - 1));
   KScope whole(c, &m == &c->drf ? SPEC_KCLASS_DRAFT_PASS : -1);
   { KScope k(c, &m == &c->tgt ? SPEC_KCLASS_OTHER : -1); launch_assemble_embed(c, m, pa, st); }
+  float *dump = (&m == &c->tgt) ? c->hidden_dump : nullptr;
+  const size_t hbytes = (size_t)M * m.desc.d_model * sizeof(float);
+  if (dump) generic_copy(c->ws.h, dump, hbytes, st);
   for (int l = 0; l < m.desc.n_layers; ++l) {
     if (m.fast) fast_layer(c, m, l, pa.B, pa.q, max_pos, st);
     else generic_layer(c, m, l, M, pa.q, st);
+    if (dump) generic_copy(c->ws.h, (char *)dump + (size_t)(l + 1) * hbytes, hbytes, st);
   }
   if (head != HEAD_NONE) {
     const bool last = head == HEAD_LAST;

@@ -72,6 +72,7 @@ struct Workspace {
   // activations (shared by both models; sized for the larger)
   float *h = nullptr;       // [M_max][d]   fp32 residual stream
   void *x = nullptr;        // [M_max][d]   normed rows, model dtype
+  void *x_lo = nullptr, *attn_lo = nullptr, *act_lo = nullptr;  // MFMA path: low 16-bit parts of x / attn / act
   void *q = nullptr;        // [M_max][d]   queries, model dtype, pair-interleaved per head
   void *attn = nullptr;     // [M_max][d]   attention output, model dtype
   void *act = nullptr;      // [M_max][f]   FFN activation, model dtype
@@ -114,6 +115,8 @@ struct spec_ctx {
   int verified_s = -1;    // s of the verify step waiting for accept_commit, or -1
   bool proposals_ready = false;
   const int32_t *prop_table = nullptr;
+  float *hidden_dump = nullptr;
+  int attn_shape = 0;
   std::vector<int32_t> lut_B, lut_s;
   std::string err;
   hipEvent_t ev0 = nullptr, ev1 = nullptr;
@@ -162,7 +165,7 @@ struct PassArgs {
 
 void launch_assemble_embed(const spec_ctx *c, const Model &m, const PassArgs &pa, hipStream_t st);
 void launch_norm(const spec_ctx *c, const Model &m, const float *h, const void *gain, const void *bias, void *x,
-                 int M, const int32_t *row_gather, hipStream_t st);
+                 int M, const int32_t *row_gather, hipStream_t st, void *x_lo = nullptr);
 void launch_argmax_rows(const float *logits, int M, int V, int q, int out_stride, int32_t *out, hipStream_t st);
 void launch_accept(spec_ctx *c, int s, hipStream_t st);
 void launch_fill_proposals(spec_ctx *c, int s, hipStream_t st);

@@ -245,3 +245,27 @@ def test_call_order_and_capacity_errors(orc, B):
     with pytest.raises(B.SpecError) as e:
         ctx.spec_reset(long)
     assert e.value.code == B.ERR_CAPACITY
+
+
+def test_attention_launch_shapes_give_identical_bits(orc, B):
+    """The two launch shapes of the verify attention (split over chunks + merge kernel; one wave
+    per sequence and head) must agree bit for bit: the batch size picks between them."""
+    dtype, seed = "bf16", 5
+    tdesc = si.llama_desc(1, 256, 2, 416, 300, 700)
+    w = si.make_weights(tdesc, dtype, seed, device=DEV, emb_std=1.0)
+    L_max, kv = 640, 600                       # three 256-key chunks, the last one ragged
+    ctx = B.Context(tdesc, w, None, None, dtype, 3, 4, L_max, 4, B.PROPOSALS_EXTERNAL, DEV)
+    K, V = si.make_kv(3, 256, kv, dtype, seed, DEV)
+    ctx.spec_kv_import(B.MODEL_TARGET, 0, K, V)
+    prompts = si.make_prompts(3, kv + 1, 300, seed)
+    props = si.make_prompts(3, 4, 300, seed + 1)
+    got = []
+    for shape in (1, 2, 0):
+        ctx.spec_set_attention_shape(shape)
+        ctx.spec_reset_noprefill(prompts)
+        ctx.spec_set_proposals(torch.tensor(props))
+        got.append(ctx.spec_verify_step(4, want_logits=True).clone())
+        ctx.spec_accept_commit(4)
+    assert torch.equal(got[0], got[1]) and torch.equal(got[0], got[2])
+    with pytest.raises(B.SpecError):
+        ctx.spec_set_attention_shape(3)
