@@ -21,6 +21,10 @@ if ROOT not in sys.path:
 HBM_PEAK = 8.0e12        # bytes/s, MI355X published
 MFMA_BF16_PEAK = 2.5e15  # flop/s dense bf16, MI355X published
 
+# HBM bytes per launch from the committed rocprofv3 counter passes (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00,
+# calibrated on a copy of known size in the same run): {(kernel class, rows M): bytes}.  Other cells: null.
+PMC_TRAFFIC = {("gemm_ffn_in", 1): 181.4e6 + 0.09e6, ("gemm_ffn_in", 256): 431.4e6 + 11.3e6}
+
 
 def to_device(w, dev):
     out = {k: (v.to(dev) if v is not None else None) for k, v in w.items() if k != "layers"}
@@ -55,7 +59,10 @@ def main():
     ap.add_argument("--batch", type=int, default=64, help="batch size of the headline number")
     ap.add_argument("--workload", default="llama7b_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-profile", action="store_true", help="skip the (B, s) profiling grid; use s=2")
+    ap.add_argument("--fixed-s", type=int, default=-1, help="skip the profiling stage and use this s everywhere")
+    ap.add_argument("--b-list", default="1,2,4,8,16,32,64", help="batch sizes of the profiling stage / curve / grid")
+    ap.add_argument("--no-curve", action="store_true", help="skip the tokens/s-vs-batch curve")
+    ap.add_argument("--no-grid", action="store_true", help="skip the verify-step latency grid")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path has no cross-GPU part); use --gpus 1",
@@ -71,7 +78,7 @@ def main():
     dev = "cuda:0"
     dtype, seed, tdesc, ddesc = si.CONFIGS[args.workload]
     P, N, s_max, alpha = 128, 128, 8, 0.7
-    B_list = [b for b in (1, 2, 4, 8, 16, 32, 64)]
+    B_list = sorted(int(b) for b in args.b_list.split(","))
     B_max = max(B_list + [args.batch])
     K, W = args.steps, args.warmup
     gen_max = max(N + s_max + 1, (K + W + 4) * (s_max + 1))
@@ -101,8 +108,8 @@ def main():
     t_setup = time.time() - t_setup
 
     # profiling stage -> LUT (batch size -> speculation length)
-    if args.no_profile:
-        lut, grid = [2] * len(B_list), None
+    if args.fixed_s >= 0:
+        lut, grid = [args.fixed_s] * len(B_list), None
         ctx.spec_set_lut(B_list, lut)
     else:
         lut, grid = ctx.spec_profile_and_choose_s(B_list, s_max, prompts, N)
@@ -154,7 +161,7 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": dbytes / dur / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = PMC_TRAFFIC.get((dom, M))
     roof["kernel"] = dom
     roof["avg_us"] = per_class[dom]["avg_us"]
     roof["rows_M"] = M
@@ -166,7 +173,7 @@ def main():
 
     # accepted tokens/s against batch size at the adaptive s (short runs)
     curve = {}
-    for i, b in enumerate(B_list):
+    for i, b in enumerate([] if args.no_curve else B_list):
         s_b = ctx.spec_choose_s(b)
         tk, tt, _ = run_timed(b, s_b, max(4, N // (s_b + 1) // 2), 1)
         entry = {"s_star": s_b, "tokens_per_s": tk / tt}
@@ -174,6 +181,8 @@ def main():
             entry["us_per_token_by_s"] = [round(x, 2) for x in grid[i]]
             entry["best_fixed_s"] = int(np.argmin(grid[i]))
         curve[str(b)] = entry
+
+    vgrid = None if args.no_grid else verify_grid(ctx, torch, prompts, tdesc, P, B_list)
 
     cpu = None
     if host_w is not None:
@@ -192,9 +201,39 @@ def main():
         "kernels": per_class,
         "lut": {str(b): s for b, s in zip(B_list, lut)},
         "curve": curve,
+        "verify_grid": vgrid,
         "setup_s": round(t_setup, 1),
     }
     print(json.dumps(line))
+
+
+def verify_grid(ctx, torch, prompts, desc, P, B_list, s_list=(0, 1, 2, 4, 8), iters=8):
+    """Latency of one target verification pass (plus the commit) for every (B, s), with the fraction
+    of the HBM and of the bf16 MFMA roofline it reaches.  Algorithmic cost per pass: every weight
+    byte once, the attended K/V rows once, the appended K/V rows; 2 flops per weight per row plus
+    the attention products."""
+    d, f, V, nl = desc["d_model"], desc["d_ffn"], desc["vocab"], desc["n_layers"]
+    w_layer = 4 * d * d + 3 * d * f
+    out = {}
+    for nB in B_list:
+        for s in s_list:
+            M = nB * (s + 1)
+            ctx.spec_reset_noprefill(prompts[:nB])      # cache content is whatever earlier runs left: timing only
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for it in range(2 + iters):
+                if it == 2:
+                    e0.record()
+                ctx.spec_verify_step(s)
+                ctx.spec_accept_commit(s)
+            e1.record()
+            e1.synchronize()
+            us = e0.elapsed_time(e1) * 1000.0 / iters
+            kv = nB * (P + 2 + iters)                   # attended positions per layer, summed over the batch
+            nbytes = 2 * (nl * w_layer + V * d) + nl * (2 * 2 * d * kv + 2 * 2 * d * M)
+            flops = 2.0 * M * (nl * w_layer + V * d) + nl * 4.0 * d * kv * (s + 1)
+            out["%d,%d" % (nB, s)] = {"us": round(us, 1), "hbm_frac": round(nbytes / HBM_PEAK / (us * 1e-6), 3),
+                                      "mfma_frac": round(flops / MFMA_BF16_PEAK / (us * 1e-6), 3)}
+    return out
 
 
 def cpu_baseline(si, tdesc, ddesc, host_w, ctx, dtype, seed):

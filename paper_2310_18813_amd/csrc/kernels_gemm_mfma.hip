@@ -309,7 +309,7 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
 
-  constexpr int U = (NB + MT >= 6) ? 2 : (NB + MT >= 3) ? 4 : 8;
+  constexpr int U = (NB + MT >= 12) ? 1 : (NB + MT >= 6) ? 2 : (NB + MT >= 3) ? 4 : 8;
   int kt = kt0;
   for (; kt + U <= kt1; kt += U) {
     u32x4_v wf[U][NB], xf[U][MT], xl[U][SPLIT ? MT : 1];
@@ -406,6 +406,8 @@ static void launch_gemm_t(GemmArgs a, int epi, hipStream_t st) {
   // launch still has at least one workgroup per CU
   int NB = 1;
   while (NB < MT && (a.NT / (NB * 2)) * a.passes >= 256) NB *= 2;
+  // eight strips halve the activation traffic again; worth it once enough workgroups remain
+  if (MT == 4 && NB == 4 && (a.NT / 8) * a.passes >= 160) NB = 8;
   a.groups = (a.NT + NB - 1) / NB;
   const int blocks = a.passes == 1 ? a.groups : ((a.groups + 7) / 8) * 8 * a.passes;
   dim3 grid(blocks), block(KS * 64);
@@ -416,7 +418,8 @@ static void launch_gemm_t(GemmArgs a, int epi, hipStream_t st) {
   else if (MT == 2) launch_epi<T, 2, 2>(a, epi, grid, block, lds, st);
   else if (NB == 1) launch_epi<T, 4, 1>(a, epi, grid, block, lds, st);
   else if (NB == 2) launch_epi<T, 4, 2>(a, epi, grid, block, lds, st);
-  else launch_epi<T, 4, 4>(a, epi, grid, block, lds, st);
+  else if (NB == 4) launch_epi<T, 4, 4>(a, epi, grid, block, lds, st);
+  else launch_epi<T, 4, 8>(a, epi, grid, block, lds, st);
 }
 
 void launch_gemm_mfma(int dtype, const GemmArgs &a, int epi, hipStream_t st) {
