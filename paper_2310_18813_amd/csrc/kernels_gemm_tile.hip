@@ -1,0 +1,234 @@
+// GEMM for more than 64 activation rows and wide outputs (QKV, gate-up / fc1, LM head).
+//
+// The streaming kernel covers 64 rows per pass and re-streams the weights for every pass.
+// Here one workgroup holds up to 256 rows of a group of weight strips, so a weight byte is
+// fetched once per 256 rows, and both operands reach the waves through LDS:
+//
+//   workgroup = 8 waves = 2 (strip halves) x 4 (row quarters); wave tile = NBW strips x MTW
+//   16-row tiles; workgroup tile = 2*NBW strips x 4*MTW row tiles.
+//   Per 32-k step the workgroup needs 2*NBW weight fragments and 2 * 4*MTW activation
+//   fragments (high and low parts) of 1 KB each.  Weights and activations are both stored in
+//   fragment order in global memory, so a fragment is one 16-byte load per lane, issued two
+//   steps ahead, parked in registers and written to the LDS stage the MFMAs are not reading; the
+//   waves then read their fragments back with one 16-byte LDS load per lane, conflict-free.
+//
+// Results are bit-identical to the streaming kernel: the same instruction, every k-slice a
+// chain of MFMAs from zero in ascending k (high part, then low part, per step), the slices
+// added in order, the same epilogue code.
+#include "mfma_tiles.h"
+
+namespace spec {
+
+#pragma clang fp contract(off)
+
+// Two LDS stages of fragments; global loads run two steps ahead of the MFMAs through a pair of
+// register sets (global -> VGPR -> LDS).  The direct global->LDS path was measured at about
+// 18 bytes per clock and CU on this part, a third of what the ordinary load path sustains, so
+// it is not used here.
+template <class T, int MTW, int NBW, int EPI>
+__global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int NBG = 2 * NBW, MTG = 4 * MTW;
+  constexpr int FRAGS = NBG + 2 * MTG;  // 1 KB fragments per stage
+  constexpr int STAGE = FRAGS * 1024;
+  constexpr int LPW = (FRAGS + 7) / 8;  // fragments each wave fetches per step
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int wn = w & 1, wm = w >> 1;
+  const int c = lane & 15, g = lane >> 4;
+  int G, pass;
+  if (a.passes == 1) { G = blockIdx.x; pass = 0; }
+  else {  // all passes of a strip group on one XCD (see the streaming kernel)
+    const int id = blockIdx.x, rest = id >> 3;
+    pass = rest % a.passes;
+    G = (rest / a.passes) * 8 + (id & 7);
+  }
+  if (G >= a.groups) return;
+  const int nt0 = G * NBG;
+  const int mtile0 = pass * MTG;
+  const int m_tiles = (a.M + 15) >> 4;
+
+  // fragment f of a stage: f < NBG weight strip nt0 + f; else activation tile (f - NBG) / 2, part (f - NBG) % 2.
+  // Wave w fetches fragments w, w + 8, ...; every wave issues exactly LPW loads per step (a wave with
+  // nothing left re-reads its last fragment and drops it) so that one vmcnt value fits all waves.
+  const u32x4_v *src[LPW];
+  int dst[LPW];
+#pragma unroll
+  for (int i = 0; i < LPW; ++i) {
+    const int f = w + 8 * i;
+    dst[i] = f < FRAGS ? f * 1024 + lane * 16 : -1;
+    const int fc = min(f, FRAGS - 1);
+    if (fc < NBG) {
+      const int nt = min(nt0 + fc, a.NT - 1);
+      src[i] = (const u32x4_v *)a.W + (size_t)nt * a.KT * 64 + lane;
+    } else {
+      const int idx = fc - NBG;
+      const int tile = min(mtile0 + (idx >> 1), m_tiles - 1);
+      src[i] = (const u32x4_v *)((idx & 1) ? a.X2 : a.X) + (size_t)tile * a.KT * 64 + lane;
+    }
+  }
+
+  f32x4_v cur[NBW][MTW], tot[NBW][MTW];
+#pragma unroll
+  for (int nb = 0; nb < NBW; ++nb)
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt) {
+      cur[nb][mt] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
+      tot[nb][mt] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
+    }
+
+  u32x4_v rA[LPW], rB[LPW];  // step kt+1 and step kt+2 on their way
+  auto fetch = [&](u32x4_v (&r)[LPW], int kt) {
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) r[i] = src[i][(size_t)min(kt, a.KT - 1) * 64];
+  };
+  auto stash = [&](const u32x4_v (&r)[LPW], int stage) {
+#pragma unroll
+    for (int i = 0; i < LPW; ++i)
+      if (dst[i] >= 0) *(u32x4_v *)(smem + stage * STAGE + dst[i]) = r[i];
+  };
+
+  const int kt_per = a.KT / a.KS;
+  int in_slice = 0, slice = 0;
+  // prologue: step 0 into LDS stage 0, steps 1 and 2 into the register sets
+  fetch(rA, 0);
+  fetch(rB, 1);
+  stash(rA, 0);
+  fetch(rA, 2);
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  // invariant at the top of step kt: LDS stage kt&1 holds step kt; (kt even ? rB : rA) holds step kt+1
+  // (possibly still in flight), the other set step kt+2 (in flight).
+  // The loop is unrolled by two so that each register set has one fixed role per half: the compiler's
+  // own wait-count bookkeeping then stays exact and it adds no waits of its own for the younger group.
+  auto compute = [&](int stage) {
+    const unsigned char *sb = smem + stage * STAGE + lane * 16;
+    u32x4_v wf[NBW], xh[MTW], xl[MTW];
+#pragma unroll
+    for (int nb = 0; nb < NBW; ++nb) wf[nb] = *(const u32x4_v *)(sb + (wn * NBW + nb) * 1024);
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt) {
+      xh[mt] = *(const u32x4_v *)(sb + (NBG + 2 * (wm * MTW + mt)) * 1024);
+      xl[mt] = *(const u32x4_v *)(sb + (NBG + 2 * (wm * MTW + mt) + 1) * 1024);
+    }
+#pragma unroll
+    for (int nb = 0; nb < NBW; ++nb)
+#pragma unroll
+      for (int mt = 0; mt < MTW; ++mt) {
+        cur[nb][mt] = Mfma16<T>::run(wf[nb], xh[mt], cur[nb][mt]);
+        cur[nb][mt] = Mfma16<T>::run(wf[nb], xl[mt], cur[nb][mt]);
+      }
+    if (++in_slice == kt_per) {  // slice finished: add it to the running total, in slice order
+#pragma unroll
+      for (int nb = 0; nb < NBW; ++nb)
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt) {
+          if (slice == 0) tot[nb][mt] = cur[nb][mt];
+          else {
+            tot[nb][mt][0] += cur[nb][mt][0]; tot[nb][mt][1] += cur[nb][mt][1];
+            tot[nb][mt][2] += cur[nb][mt][2]; tot[nb][mt][3] += cur[nb][mt][3];
+          }
+          cur[nb][mt] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
+        }
+      in_slice = 0;
+      ++slice;
+    }
+  };
+  // Step kt+1 goes from its register set into the other LDS stage (nobody reads that stage during this
+  // step: its last readers passed the previous barrier), then that set fetches step kt+3.  The compiler
+  // waits for each register right before its LDS write (loads complete in order, the younger group of
+  // step kt+2 stays in flight).
+  // A bare barrier, not __syncthreads(): the fence of the latter would wait for the loads in flight;
+  // ordered by hand: this wave's LDS reads returned (the MFMAs consumed them), its LDS writes are done.
+#define SPEC_TILE_HANDOVER(rset, kt_, stage_)                              \
+  stash(rset, (stage_) ^ 1);                                               \
+  fetch(rset, (kt_) + 3);                                                  \
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                      \
+  __builtin_amdgcn_s_barrier();                                            \
+  asm volatile("" ::: "memory");
+  int kt = 0;
+  for (; kt + 1 < a.KT; kt += 2) {
+    compute(0);
+    SPEC_TILE_HANDOVER(rB, kt, 0)
+    compute(1);
+    SPEC_TILE_HANDOVER(rA, kt + 1, 1)
+  }
+  if (kt < a.KT) {
+    compute(0);
+    SPEC_TILE_HANDOVER(rB, kt, 0)
+  }
+#undef SPEC_TILE_HANDOVER
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the over-fetched tail before the epilogue
+
+#pragma unroll
+  for (int nb = 0; nb < NBW; ++nb)
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt)
+      tile_epilogue<T, EPI>(a, tot[nb][mt], nt0 + wn * NBW + nb, (mtile0 + wm * MTW + mt) * 16 + c, g);
+}
+
+template <class T, int MTW, int NBW, int EPI>
+static void launch_one(const GemmArgs &a, int blocks, hipStream_t st) {
+  constexpr size_t lds = 2 * (size_t)(2 * NBW + 8 * MTW) * 1024;
+  static bool attr_set = false;  // the kernel may use more than the default 64 KB of LDS
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void *)k_gemm_tile<T, MTW, NBW, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)lds);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((k_gemm_tile<T, MTW, NBW, EPI>), dim3(blocks), dim3(512), lds, st, a);
+}
+
+template <class T, int MTW, int NBW>
+static void launch_epi_tile(const GemmArgs &a, int epi, int blocks, hipStream_t st) {
+  switch (epi) {
+    case EPI_QKV: launch_one<T, MTW, NBW, EPI_QKV>(a, blocks, st); break;
+    case EPI_SWIGLU: launch_one<T, MTW, NBW, EPI_SWIGLU>(a, blocks, st); break;
+    case EPI_RELU: launch_one<T, MTW, NBW, EPI_RELU>(a, blocks, st); break;
+    default: launch_one<T, MTW, NBW, EPI_LOGITS>(a, blocks, st); break;
+  }
+}
+
+template <class T, int MTW>
+static void launch_nb_tile(const GemmArgs &a, int NBW, int epi, int blocks, hipStream_t st) {
+  if (NBW == 2) launch_epi_tile<T, MTW, 2>(a, epi, blocks, st);
+  else if (NBW == 3) launch_epi_tile<T, MTW, 3>(a, epi, blocks, st);
+  else launch_epi_tile<T, MTW, 4>(a, epi, blocks, st);
+}
+
+template <class T>
+static void launch_tile_t(GemmArgs a, int epi, hipStream_t st) {
+  // rows per workgroup: 64 * MTW.  Fewest passes, then the smallest tile that covers them.
+  const int passes = (a.M + 255) / 256;
+  const int rows = (a.M + passes - 1) / passes;
+  const int MTW = rows <= 128 ? 2 : rows <= 192 ? 3 : 4;
+  a.passes = (a.M + 64 * MTW - 1) / (64 * MTW);
+  // strips per workgroup 2*NBW: one workgroup occupies a CU, so the launch takes ceil(workgroups / CUs)
+  // rounds of a duration that grows with NBW; fewest round-units wins, ties go to the larger tile
+  // (fewer LDS bytes per MFMA)
+  static int n_cu = 0;
+  if (!n_cu) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
+    if (n_cu <= 0) n_cu = 256;
+  }
+  int NBW = 4, best = 1 << 30;
+  for (int nb = 4; nb >= 2; --nb) {
+    const int wgs = ((a.NT + 2 * nb - 1) / (2 * nb)) * a.passes;
+    const int cost = ((wgs + n_cu - 1) / n_cu) * nb;
+    if (cost < best) { best = cost; NBW = nb; }
+  }
+  a.groups = (a.NT + 2 * NBW - 1) / (2 * NBW);
+  const int blocks = a.passes == 1 ? a.groups : ((a.groups + 7) / 8) * 8 * a.passes;
+  if (MTW == 2) launch_nb_tile<T, 2>(a, NBW, epi, blocks, st);
+  else if (MTW == 3) launch_nb_tile<T, 3>(a, NBW, epi, blocks, st);
+  else launch_nb_tile<T, 4>(a, NBW, epi, blocks, st);
+}
+
+void launch_gemm_tile(int dtype, GemmArgs a, int epi, hipStream_t st) {
+  if (dtype == SPEC_DTYPE_BF16) launch_tile_t<bf16_t>(a, epi, st);
+  else launch_tile_t<f16_t>(a, epi, st);
+}
+
+}  // namespace spec

@@ -46,6 +46,7 @@ void launch_pack_bias(int dtype, int mode, const PackedDims &p, int d, int hd, c
                       const void *s2, float *dst, hipStream_t st);
 void launch_rope_table(int L, int hd, float theta, float2 *tab, hipStream_t st);
 void launch_gemm_mfma(int dtype, const GemmArgs &a, int epi, hipStream_t st);
+void launch_gemm_tile(int dtype, GemmArgs a, int epi, hipStream_t st);  // more than 64 rows, wide outputs
 void launch_argmax_partials(const float *pv, const int32_t *pi, int M, int NT, int V, int q, int out_stride,
                             int32_t *out, hipStream_t st);
 

@@ -1,0 +1,122 @@
+// Shared by the matrix-core GEMM kernels: operand types, the one MFMA instruction, and the
+// tile epilogues (the layer's element-wise work on finished fp32 tiles).
+#pragma once
+#include "spec_internal.h"
+#include "device_utils.h"
+#include "mfma_gemm.h"
+
+// No implicit fusing of multiplies and adds (see kernels_gemm_mfma.hip).
+#pragma clang fp contract(off)
+
+namespace spec {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_v;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_v;
+typedef __attribute__((ext_vector_type(4))) float f32x4_v;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_v;
+
+template <class T> struct Mfma16;
+template <> struct Mfma16<bf16_t> {
+  static __device__ __forceinline__ f32x4_v run(u32x4_v a, u32x4_v b, f32x4_v c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_v, a), __builtin_bit_cast(bf16x8_v, b), c,
+                                                   0, 0, 0);
+  }
+};
+template <> struct Mfma16<f16_t> {
+  static __device__ __forceinline__ f32x4_v run(u32x4_v a, u32x4_v b, f32x4_v c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_v, a), __builtin_bit_cast(f16x8_v, b), c,
+                                                  0, 0, 0);
+  }
+};
+
+// ------------------------------------------------------------------------- epilogues
+// One finished 16x16 tile: this lane holds stored rows n .. n+3 (n = 16*nt + 4g) of
+// activation row m.  The element-wise work of the layer happens here, on fp32 sums.
+template <class T, int EPI>
+__device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int nt, int m, int g) {
+  if (nt >= a.NT) return;
+  const int n = nt * 16 + 4 * g;
+  if (a.bias) {
+    const float4 b4 = *(const float4 *)(a.bias + n);
+    v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
+  }
+  const bool live = m < a.M;
+
+  if (EPI == EPI_RESIDUAL) {
+    if (live && n < a.N) {
+      float4 *p = (float4 *)(a.h + (size_t)m * a.N + n);
+      float4 o = *p;
+      o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
+      *p = o;
+    }
+  } else if (EPI == EPI_QKV) {
+    if (live && n < a.N) {
+      const int region = n / a.d, cc = n % a.d, hh = cc / a.hd, e = cc % a.hd;
+      const int pos = a.row_pos[m], b = m / a.q_rows;
+      if (region < 2) {
+        float r0 = v[0], r1 = v[1], r2 = v[2], r3 = v[3];
+        if (a.rope && pos >= 0) {
+          const float2 cs0 = a.rope[(size_t)pos * (a.hd >> 1) + (e >> 1)];
+          const float2 cs1 = a.rope[(size_t)pos * (a.hd >> 1) + (e >> 1) + 1];
+          r0 = v[0] * cs0.x - v[1] * cs0.y; r1 = v[1] * cs0.x + v[0] * cs0.y;
+          r2 = v[2] * cs1.x - v[3] * cs1.y; r3 = v[3] * cs1.x + v[2] * cs1.y;
+        }
+        T o4[4];
+        Conv<T>::st(o4, 0, r0); Conv<T>::st(o4, 1, r1); Conv<T>::st(o4, 2, r2); Conv<T>::st(o4, 3, r3);
+        if (region == 0) {
+          *(uint2 *)((T *)a.q + (size_t)m * a.d + cc) = *(const uint2 *)o4;
+        } else if (pos >= 0) {
+          *(uint2 *)((T *)a.kc + kv_k_index(a.L_pad, a.H, a.hd, b, hh, pos, e)) = *(const uint2 *)o4;
+        }
+      } else if (pos >= 0) {
+        T *vc = (T *)a.vc;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) Conv<T>::st(vc, kv_v_index(a.L_pad, a.H, a.hd, b, hh, pos, e + i), v[i]);
+      }
+    }
+  } else if (EPI == EPI_SWIGLU) {
+    const int j = n >> 1;  // stored rows n..n+3 = gate_j, up_j, gate_{j+1}, up_{j+1}
+    if (live && j < a.f) {
+      const float r0 = v[0] / (1.0f + __expf(-v[0])) * v[1], r1 = v[2] / (1.0f + __expf(-v[2])) * v[3];
+      T o2[2], l2[2];
+      Conv<T>::st(o2, 0, r0); Conv<T>::st(o2, 1, r1);
+      Conv<T>::st(l2, 0, r0 - Conv<T>::round(r0)); Conv<T>::st(l2, 1, r1 - Conv<T>::round(r1));
+      const size_t at = xpack_index(m, j, a.f >> 5);
+      *(uint32_t *)((T *)a.act + at) = *(const uint32_t *)o2;
+      *(uint32_t *)((T *)a.act2 + at) = *(const uint32_t *)l2;
+    }
+  } else if (EPI == EPI_RELU) {
+    if (live && n < a.N) {
+      T o4[4], l4[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float r = v[i] > 0.f ? v[i] : 0.f;
+        Conv<T>::st(o4, i, r);
+        Conv<T>::st(l4, i, r - Conv<T>::round(r));
+      }
+      const size_t at = xpack_index(m, n, a.N >> 5);
+      *(uint2 *)((T *)a.act + at) = *(const uint2 *)o4;
+      *(uint2 *)((T *)a.act2 + at) = *(const uint2 *)l4;
+    }
+  } else {  // EPI_LOGITS: optional dump, per-strip arg-max partial (lowest index wins ties)
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (n + i < a.N) {
+        if (live && a.logits) a.logits[(size_t)m * a.N + n + i] = v[i];
+        argmax_combine(bv, bi, v[i], n + i);
+      }
+    for (int o = 16; o <= 32; o <<= 1) {
+      float ov = __shfl_xor(bv, o, 64);
+      int oi = __shfl_xor(bi, o, 64);
+      argmax_combine(bv, bi, ov, oi);
+    }
+    if (live && g == 0) {
+      a.part_val[(size_t)m * a.NT + nt] = bv;
+      a.part_idx[(size_t)m * a.NT + nt] = bi;
+    }
+  }
+}
+
+}  // namespace spec
