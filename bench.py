@@ -40,10 +40,11 @@ def gemm_cost(M, N, K, extra_bytes):
 
 def class_costs(desc, M, kv_positions, q):
     d, f, V, H = desc["d_model"], desc["d_ffn"], desc["vocab"], desc["n_heads"]
+    kf = 2 if desc["ffn_kind"] == 0 else 1   # SwiGLU streams gate and up, ReLU one matrix
     return {
         "gemm_qkv": gemm_cost(M, 3 * d, d, 2 * M * 3 * d),
         "gemm_o": gemm_cost(M, d, d, 8 * M * d),
-        "gemm_ffn_in": gemm_cost(M, 2 * f, d, 2 * M * f),
+        "gemm_ffn_in": gemm_cost(M, kf * f, d, 2 * M * f),
         "gemm_ffn_out": gemm_cost(M, d, f, 8 * M * d),
         "gemm_head": gemm_cost(M, V, d, 8 * M * ((V + 15) // 16)),
         # K and V rows of every attended position once, queries in, output out
@@ -77,7 +78,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     dtype, seed, tdesc, ddesc = si.CONFIGS[args.workload]
-    P, N, s_max, alpha = 128, 128, 8, 0.7
+    # prompt length, tokens per sequence in the profiling stage, longest speculation, acceptance probability
+    P, N, s_max, alpha = {"llama7b_bf16": (128, 128, 8, 0.7), "opt13b_fp16": (256, 128, 8, 0.8),
+                          "llama33b_bf16": (2048, 256, 6, 0.6)}.get(args.workload, (128, 128, 8, 0.7))
     B_list = sorted(int(b) for b in args.b_list.split(","))
     B_max = max(B_list + [args.batch])
     K, W = args.steps, args.warmup
@@ -191,9 +194,10 @@ def main():
     line = {
         "metric": "accepted tokens/s at adaptive s", "value": value, "unit": "tokens/s", "n_gpus": 1,
         "steps": K, "warmup": W, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s: 7B-shape target + 2-layer draft (BASELINE configs[2]), B=%d, prompt %d, "
-                               "acceptance prob %.1f, s=adaptive" % (args.workload, nB, P, alpha),
+        "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": "%s: %d-layer d=%d target + %d-layer d=%d draft (BASELINE configs), B=%d, prompt %d, "
+                               "acceptance prob %.1f, s=adaptive" % (args.workload, tdesc["n_layers"], tdesc["d_model"],
+                                                                       ddesc["n_layers"], ddesc["d_model"], nB, P, alpha),
                    "batch": nB, "s_star": s_star, "rows_per_verify": M, "accepted_hist": hist,
                    "tokens_per_round_per_seq": tokens / K / nB},
         "roofline": roof,
@@ -213,10 +217,10 @@ def verify_grid(ctx, torch, prompts, desc, P, B_list, s_list=(0, 1, 2, 4, 8), it
     byte once, the attended K/V rows once, the appended K/V rows; 2 flops per weight per row plus
     the attention products."""
     d, f, V, nl = desc["d_model"], desc["d_ffn"], desc["vocab"], desc["n_layers"]
-    w_layer = 4 * d * d + 3 * d * f
+    w_layer = 4 * d * d + (3 if desc["ffn_kind"] == 0 else 2) * d * f
     out = {}
     for nB in B_list:
-        for s in s_list:
+        for s in [x for x in s_list if x <= ctx.s_max]:
             M = nB * (s + 1)
             ctx.spec_reset_noprefill(prompts[:nB])      # cache content is whatever earlier runs left: timing only
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
