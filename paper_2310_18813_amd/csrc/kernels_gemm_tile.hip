@@ -9,22 +9,30 @@
 //   Per 32-k step the workgroup needs 2*NBW weight fragments and 2 * 4*MTW activation
 //   fragments (high and low parts) of 1 KB each.  Weights and activations are both stored in
 //   fragment order in global memory, so a fragment is one 16-byte load per lane, issued two
-//   steps ahead, parked in registers and written to the LDS stage the MFMAs are not reading; the
+//   steps ahead, parked in registers and written to the LDS stage that is not being read; the
 //   waves then read their fragments back with one 16-byte LDS load per lane, conflict-free.
 //
 // Results are bit-identical to the streaming kernel: the same instruction, every k-slice a
 // chain of MFMAs from zero in ascending k (high part, then low part, per step), the slices
 // added in order, the same epilogue code.
 #include "mfma_tiles.h"
+#include <cstdio>
+#include <cstdlib>
 
 namespace spec {
 
 #pragma clang fp contract(off)
 
-// Two LDS stages of fragments; global loads run two steps ahead of the MFMAs through a pair of
-// register sets (global -> VGPR -> LDS).  The direct global->LDS path was measured at about
+// Two LDS stages of fragments; global loads run three steps ahead of the LDS writes through
+// three register sets (global -> VGPR -> LDS).  The direct global->LDS path was measured at about
 // 18 bytes per clock and CU on this part, a third of what the ordinary load path sustains, so
 // it is not used here.
+//
+// The eight waves work as two groups of four (one wave of each group per SIMD) half a step
+// apart: while one group issues the MFMAs of its step, the other does its LDS traffic (fragment
+// reads for its next MFMA phase, the hand-over of prefetched global data into the other stage),
+// and at the next barrier they swap.  The matrix pipe and the LDS pipe of a SIMD are then busy
+// at the same time although every wave runs its phases strictly in order.
 template <class T, int MTW, int NBW, int EPI>
 __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -33,7 +41,8 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   constexpr int STAGE = FRAGS * 1024;
   constexpr int LPW = (FRAGS + 7) / 8;  // fragments each wave fetches per step
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int wn = w & 1, wm = w >> 1;
+  const int grp = w >> 2;               // phase group; waves w and w + 4 share a SIMD
+  const int wn = w & 1, wm = ((w >> 1) & 1) | (grp << 1);
   const int c = lane & 15, g = lane >> 4;
   int G, pass;
   if (a.passes == 1) { G = blockIdx.x; pass = 0; }
@@ -76,41 +85,63 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
       tot[nb][mt] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
     }
 
-  u32x4_v rA[LPW], rB[LPW];  // step kt+1 and step kt+2 on their way
+  u32x4_v r0[LPW], r1[LPW], r2[LPW];  // three steps on their way from global memory
   auto fetch = [&](u32x4_v (&r)[LPW], int kt) {
 #pragma unroll
     for (int i = 0; i < LPW; ++i) r[i] = src[i][(size_t)min(kt, a.KT - 1) * 64];
   };
+
   auto stash = [&](const u32x4_v (&r)[LPW], int stage) {
 #pragma unroll
     for (int i = 0; i < LPW; ++i)
       if (dst[i] >= 0) *(u32x4_v *)(smem + stage * STAGE + dst[i]) = r[i];
   };
+  // A bare barrier, not __syncthreads(): the fence of the latter would wait for the global loads in
+  // flight.  Ordered by hand: before it, this wave's LDS reads have returned and its LDS writes are
+  // done; nothing may be scheduled across it, so that the phases stay phases.
+  auto phase_end = [&]() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" ::: "memory");
+  };
 
   const int kt_per = a.KT / a.KS;
   int in_slice = 0, slice = 0;
-  // prologue: step 0 into LDS stage 0, steps 1 and 2 into the register sets
-  fetch(rA, 0);
-  fetch(rB, 1);
-  stash(rA, 0);
-  fetch(rA, 2);
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-  // invariant at the top of step kt: LDS stage kt&1 holds step kt; (kt even ? rB : rA) holds step kt+1
-  // (possibly still in flight), the other set step kt+2 (in flight).
-  // The loop is unrolled by two so that each register set has one fixed role per half: the compiler's
-  // own wait-count bookkeeping then stays exact and it adds no waits of its own for the younger group.
-  auto compute = [&](int stage) {
-    const unsigned char *sb = smem + stage * STAGE + lane * 16;
-    u32x4_v wf[NBW], xh[MTW], xl[MTW];
-#pragma unroll
-    for (int nb = 0; nb < NBW; ++nb) wf[nb] = *(const u32x4_v *)(sb + (wn * NBW + nb) * 1024);
-#pragma unroll
-    for (int mt = 0; mt < MTW; ++mt) {
-      xh[mt] = *(const u32x4_v *)(sb + (NBG + 2 * (wm * MTW + mt)) * 1024);
-      xl[mt] = *(const u32x4_v *)(sb + (NBG + 2 * (wm * MTW + mt) + 1) * 1024);
-    }
+  // prologue: step 0 into LDS stage 0, steps 1, 2 and 3 into the register sets
+  fetch(r0, 0);
+  fetch(r1, 1);
+  fetch(r2, 2);
+  stash(r0, 0);
+  fetch(r0, 3);
+  phase_end();
+  if (grp) phase_end();  // the second group runs half a step behind the first
+
+  u32x4_v wf[NBW], xh[MTW], xl[MTW];
+  // LDS phase of step kt: this wave's fragments of step kt out of stage kt&1; step kt+1, prefetched three
+  // steps ago, into the other stage (its last readers finished before the previous barrier: the own
+  // group a whole step ago, the other group in the phase just ended); that register set then fetches
+  // step kt+4.  The register sets rotate with period three: the loop below is unrolled by three so that
+  // each set has a fixed role per copy and the compiler's wait-count bookkeeping stays exact.
+#define SPEC_TILE_STEP(rset, kt_)                                                         \
+  {                                                                                       \
+    const int stage_ = (kt_) & 1;                                                         \
+    const unsigned char *sb = smem + stage_ * STAGE + lane * 16;                          \
+    _Pragma("unroll") for (int nb = 0; nb < NBW; ++nb)                                    \
+        wf[nb] = *(const u32x4_v *)(sb + (wn * NBW + nb) * 1024);                         \
+    _Pragma("unroll") for (int mt = 0; mt < MTW; ++mt) {                                  \
+      xh[mt] = *(const u32x4_v *)(sb + (NBG + 2 * (wm * MTW + mt)) * 1024);               \
+      xl[mt] = *(const u32x4_v *)(sb + (NBG + 2 * (wm * MTW + mt) + 1) * 1024);           \
+    }                                                                                     \
+    stash(rset, stage_ ^ 1);                                                              \
+    fetch(rset, (kt_) + 4);                                                               \
+    phase_end();                                                                          \
+    compute();                                                                            \
+    phase_end();                                                                          \
+  }
+  auto compute = [&]() {
+    __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
@@ -118,6 +149,7 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
         cur[nb][mt] = Mfma16<T>::run(wf[nb], xh[mt], cur[nb][mt]);
         cur[nb][mt] = Mfma16<T>::run(wf[nb], xl[mt], cur[nb][mt]);
       }
+    __builtin_amdgcn_s_setprio(0);
     if (++in_slice == kt_per) {  // slice finished: add it to the running total, in slice order
 #pragma unroll
       for (int nb = 0; nb < NBW; ++nb)
@@ -134,30 +166,16 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
       ++slice;
     }
   };
-  // Step kt+1 goes from its register set into the other LDS stage (nobody reads that stage during this
-  // step: its last readers passed the previous barrier), then that set fetches step kt+3.  The compiler
-  // waits for each register right before its LDS write (loads complete in order, the younger group of
-  // step kt+2 stays in flight).
-  // A bare barrier, not __syncthreads(): the fence of the latter would wait for the loads in flight;
-  // ordered by hand: this wave's LDS reads returned (the MFMAs consumed them), its LDS writes are done.
-#define SPEC_TILE_HANDOVER(rset, kt_, stage_)                              \
-  stash(rset, (stage_) ^ 1);                                               \
-  fetch(rset, (kt_) + 3);                                                  \
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                      \
-  __builtin_amdgcn_s_barrier();                                            \
-  asm volatile("" ::: "memory");
   int kt = 0;
-  for (; kt + 1 < a.KT; kt += 2) {
-    compute(0);
-    SPEC_TILE_HANDOVER(rB, kt, 0)
-    compute(1);
-    SPEC_TILE_HANDOVER(rA, kt + 1, 1)
+  for (; kt + 2 < a.KT; kt += 3) {
+    SPEC_TILE_STEP(r1, kt)
+    SPEC_TILE_STEP(r2, kt + 1)
+    SPEC_TILE_STEP(r0, kt + 2)
   }
-  if (kt < a.KT) {
-    compute(0);
-    SPEC_TILE_HANDOVER(rB, kt, 0)
-  }
-#undef SPEC_TILE_HANDOVER
+  if (kt < a.KT) SPEC_TILE_STEP(r1, kt)
+  if (kt + 1 < a.KT) SPEC_TILE_STEP(r2, kt + 1)
+#undef SPEC_TILE_STEP
+  if (!grp) phase_end();  // every wave passes the same number of barriers
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the over-fetched tail before the epilogue
 
 #pragma unroll
@@ -196,16 +214,35 @@ static void launch_nb_tile(const GemmArgs &a, int NBW, int epi, int blocks, hipS
   else launch_epi_tile<T, MTW, 4>(a, epi, blocks, st);
 }
 
+// Wave tile (MTW 16-row tiles x NBW strips) for M rows and NT strips.  One workgroup occupies a CU, so
+// a launch takes ceil(workgroups / CUs) rounds of KT steps; a step lasts two phases, each as long as the
+// slower of one group's MFMAs (16 clocks each) and the other group's LDS traffic (8 clocks per 1 KB
+// fragment read or written).  SPEC_GEMM_TILE="mtw,nbw" in the environment overrides the choice (tuning aid).
+static void choose_tile(int M, int NT, int n_cu, int &MTW, int &NBW) {
+  static int force_mt = -1, force_nb = 0;
+  if (force_mt < 0) {
+    force_mt = 0;
+    const char *e = getenv("SPEC_GEMM_TILE");
+    int mt = 0, nb = 0;
+    if (e && sscanf(e, "%d,%d", &mt, &nb) == 2 && mt >= 2 && mt <= 4 && nb >= 2 && nb <= 4) { force_mt = mt; force_nb = nb; }
+  }
+  if (force_mt > 0) { MTW = force_mt; NBW = force_nb; return; }
+  long best = -1;
+  for (int mt = 2; mt <= 4; ++mt)
+    for (int nb = 2; nb <= 4; ++nb) {
+      const int passes = (M + 64 * mt - 1) / (64 * mt);
+      const int wgs = passes * ((NT + 2 * nb - 1) / (2 * nb));
+      const int rounds = (wgs + n_cu - 1) / n_cu;
+      const int frags = 2 * nb + 8 * mt;
+      const int mfma = 2 * mt * nb * 16;
+      const int lds = 4 * (2 * mt + nb + (frags + 7) / 8) * 8;
+      const long cost = (long)rounds * (2 * (mfma > lds ? mfma : lds) + 100);
+      if (best < 0 || cost < best || (cost == best && mt * nb > MTW * NBW)) { best = cost; MTW = mt; NBW = nb; }
+    }
+}
+
 template <class T>
 static void launch_tile_t(GemmArgs a, int epi, hipStream_t st) {
-  // rows per workgroup: 64 * MTW.  Fewest passes, then the smallest tile that covers them.
-  const int passes = (a.M + 255) / 256;
-  const int rows = (a.M + passes - 1) / passes;
-  const int MTW = rows <= 128 ? 2 : rows <= 192 ? 3 : 4;
-  a.passes = (a.M + 64 * MTW - 1) / (64 * MTW);
-  // strips per workgroup 2*NBW: one workgroup occupies a CU, so the launch takes ceil(workgroups / CUs)
-  // rounds of a duration that grows with NBW; fewest round-units wins, ties go to the larger tile
-  // (fewer LDS bytes per MFMA)
   static int n_cu = 0;
   if (!n_cu) {
     int dev = 0;
@@ -213,12 +250,9 @@ static void launch_tile_t(GemmArgs a, int epi, hipStream_t st) {
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
     if (n_cu <= 0) n_cu = 256;
   }
-  int NBW = 4, best = 1 << 30;
-  for (int nb = 4; nb >= 2; --nb) {
-    const int wgs = ((a.NT + 2 * nb - 1) / (2 * nb)) * a.passes;
-    const int cost = ((wgs + n_cu - 1) / n_cu) * nb;
-    if (cost < best) { best = cost; NBW = nb; }
-  }
+  int MTW = 2, NBW = 2;
+  choose_tile(a.M, a.NT, n_cu, MTW, NBW);
+  a.passes = (a.M + 64 * MTW - 1) / (64 * MTW);
   a.groups = (a.NT + 2 * NBW - 1) / (2 * NBW);
   const int blocks = a.passes == 1 ? a.groups : ((a.groups + 7) / 8) * 8 * a.passes;
   if (MTW == 2) launch_nb_tile<T, 2>(a, NBW, epi, blocks, st);
