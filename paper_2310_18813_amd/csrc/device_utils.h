@@ -34,6 +34,17 @@ template <> struct Conv<f16_t> {
   static __device__ __forceinline__ float round(float f) { return (float)(f16_t)f; }
 };
 
+// Operand type of the matrix-core GEMMs, for bf16 and fp16 models alike: fp16 has three more
+// significand bits than bf16, and an fp32 activation rounded once to fp16 carries the layer as
+// accurately as a bf16 high part plus a bf16 low part at half the matrix work.  Weights of bf16
+// models are held as fp16 times a power of two per matrix (exact, see the packing kernel);
+// activations beyond the fp16 range saturate.
+typedef f16_t op_t;
+__device__ __forceinline__ op_t to_op(float f) {
+  f = f > 65504.f ? 65504.f : (f < -65504.f ? -65504.f : f);  // NaN passes through
+  return (op_t)f;
+}
+
 // Activations that feed a matrix-core GEMM are stored in the order the B operand is loaded:
 // 16-row x 32-k tiles of 1 KB, tile (m/16, k/32) at ((m/16) * KT + k/32), inside a tile lane
 // 16*((k%32)/8) + m%16 owns 8 consecutive k.  Element index of X[m][k] for a row length of 32*KT:

@@ -3,6 +3,7 @@
 #include "spec_internal.h"
 #include "mfma_gemm.h"
 #include <algorithm>
+#include <vector>
 
 namespace spec {
 
@@ -38,7 +39,8 @@ size_t fast_packed_bytes(const spec_model_desc &D, int dtype, int L_max) {
                      al256f((size_t)f.qkv.N_pad * 4) + al256f((size_t)f.o.N_pad * 4) + al256f((size_t)f.w13.N_pad * 4) +
                      al256f((size_t)f.w2.N_pad * 4);
   size_t top = al256f((size_t)D.vocab * d * e) + al256f((size_t)D.max_pos * d * e) + 2 * al256f(d * e) +
-               al256f(f.head.bytes(e)) + al256f((size_t)L_max * (d / D.n_heads / 2) * sizeof(float2));
+               al256f(f.head.bytes(e)) + al256f((size_t)L_max * (d / D.n_heads / 2) * sizeof(float2)) +
+               al256f((4 * (size_t)D.n_layers + 1) * sizeof(uint32_t));
   return top + per_layer * (size_t)D.n_layers;
 }
 
@@ -54,7 +56,7 @@ static const void *takef(const void *src, size_t bytes, void *&cursor, hipStream
   return dst;
 }
 
-void fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&cursor, hipStream_t st) {
+bool fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&cursor, hipStream_t st) {
   const spec_model_desc &D = m.desc;
   const int dt = c->run.dtype;
   const size_t e = dtype_bytes(dt), d = D.d_model;
@@ -67,8 +69,20 @@ void fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&curso
   m.pos_emb = D.pos_kind == SPEC_POS_LEARNED ? takef(w->d_pos_emb, (size_t)D.max_pos * d * e, cursor, st) : nullptr;
   m.final_norm_w = takef(w->d_final_norm_w, d * e, cursor, st);
   m.final_norm_b = ln ? takef(w->d_final_norm_b, d * e, cursor, st) : nullptr;
+  // bf16 sources: largest magnitude per matrix -> the power of two its fp16 copy is scaled by
+  // (word 4l + {0,1,2,3}: qkv, o, gate-up / fc1, down / fc2 of layer l; the last word: LM head)
+  const size_t n_amax = 4 * (size_t)D.n_layers + 1;
+  uint32_t *amax = (uint32_t *)bumpf(cursor, n_amax * sizeof(uint32_t));
+  generic_zero(amax, n_amax * sizeof(uint32_t), st);
+  const bool scaled = dt == SPEC_DTYPE_BF16;
+  auto amax_of = [&](size_t word, const void *src, size_t n) -> const uint32_t * {
+    if (!scaled) return nullptr;
+    launch_absmax(dt, src, n, amax + word, st);
+    return amax + word;
+  };
   void *head = bumpf(cursor, f.head.bytes(e));
-  launch_pack_weight(dt, 0, f.head, (int)d, hd, w->d_lm_head, nullptr, nullptr, head, st);
+  launch_pack_weight(dt, 0, f.head, (int)d, hd, w->d_lm_head, nullptr, nullptr, head,
+                     amax_of(n_amax - 1, w->d_lm_head, (size_t)D.vocab * d), st);
   m.lm_head = head;
   m.rope = nullptr;
   if (D.pos_kind == SPEC_POS_ROPE) {
@@ -84,18 +98,27 @@ void fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&curso
     L.ffn_norm_w = takef(T[SPEC_T_FFN_NORM_W], d * e, cursor, st);
     L.ffn_norm_b = ln ? takef(T[SPEC_T_FFN_NORM_B], d * e, cursor, st) : nullptr;
     void *p;
+    const size_t a0 = 4 * (size_t)l, ff = D.d_ffn;
     p = bumpf(cursor, f.qkv.bytes(e));
-    launch_pack_weight(dt, 1, f.qkv, (int)d, hd, T[SPEC_T_WQ], T[SPEC_T_WK], T[SPEC_T_WV], p, st);
+    amax_of(a0, T[SPEC_T_WQ], d * d);
+    amax_of(a0, T[SPEC_T_WK], d * d);
+    launch_pack_weight(dt, 1, f.qkv, (int)d, hd, T[SPEC_T_WQ], T[SPEC_T_WK], T[SPEC_T_WV], p,
+                       amax_of(a0, T[SPEC_T_WV], d * d), st);
     L.wqkv = p;
     p = bumpf(cursor, f.o.bytes(e));
-    launch_pack_weight(dt, 0, f.o, (int)d, hd, T[SPEC_T_WO], nullptr, nullptr, p, st);
+    launch_pack_weight(dt, 0, f.o, (int)d, hd, T[SPEC_T_WO], nullptr, nullptr, p, amax_of(a0 + 1, T[SPEC_T_WO], d * d), st);
     L.wo = p;
     p = bumpf(cursor, f.w13.bytes(e));
-    if (swi) launch_pack_weight(dt, 2, f.w13, (int)d, hd, T[SPEC_T_W1], T[SPEC_T_W3], nullptr, p, st);
-    else launch_pack_weight(dt, 0, f.w13, (int)d, hd, T[SPEC_T_W1], nullptr, nullptr, p, st);
+    if (swi) {
+      amax_of(a0 + 2, T[SPEC_T_W1], ff * d);
+      launch_pack_weight(dt, 2, f.w13, (int)d, hd, T[SPEC_T_W1], T[SPEC_T_W3], nullptr, p,
+                         amax_of(a0 + 2, T[SPEC_T_W3], ff * d), st);
+    } else {
+      launch_pack_weight(dt, 0, f.w13, (int)d, hd, T[SPEC_T_W1], nullptr, nullptr, p, amax_of(a0 + 2, T[SPEC_T_W1], ff * d), st);
+    }
     L.w13 = p;
     p = bumpf(cursor, f.w2.bytes(e));
-    launch_pack_weight(dt, 0, f.w2, (int)d, hd, T[SPEC_T_W2], nullptr, nullptr, p, st);
+    launch_pack_weight(dt, 0, f.w2, (int)d, hd, T[SPEC_T_W2], nullptr, nullptr, p, amax_of(a0 + 3, T[SPEC_T_W2], d * ff), st);
     L.w2 = p;
     L.bqkv = L.bo = L.b13 = L.b2 = nullptr;
     if (hb) {
@@ -115,12 +138,27 @@ void fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&curso
       }
     }
   }
+  // the GEMM epilogues undo the scaling: 1 / scale per matrix, from the same words the packing read
+  std::vector<uint32_t> h_amax(n_amax, 0u);
+  if (scaled) {
+    if (hipMemcpyAsync(h_amax.data(), amax, n_amax * sizeof(uint32_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+      return false;
+  }
+  for (int l = 0; l < D.n_layers; ++l) {
+    LayerW &L = m.layers[l];
+    L.s_qkv = 1.0f / weight_scale(h_amax[4 * l]);
+    L.s_o = 1.0f / weight_scale(h_amax[4 * l + 1]);
+    L.s_13 = 1.0f / weight_scale(h_amax[4 * l + 2]);
+    L.s_2 = 1.0f / weight_scale(h_amax[4 * l + 3]);
+  }
+  m.s_head = 1.0f / weight_scale(h_amax[n_amax - 1]);
+  return true;
 }
 
-static GemmArgs base_args(const PackedDims &p, const void *W, const void *bias, const void *X, const void *X2,
-                          int M) {
+static GemmArgs base_args(const PackedDims &p, const void *W, float inv_scale, const void *bias, const void *X, int M) {
   GemmArgs a{};
-  a.W = W; a.bias = (const float *)bias; a.X = X; a.X2 = X2;
+  a.W = W; a.bias = (const float *)bias; a.X = X; a.out_scale = inv_scale;
   a.M = M; a.N = p.N; a.NT = p.NT; a.KT = p.KT; a.KS = p.KS; a.K_pad = p.K_pad;
   return a;
 }
@@ -137,10 +175,10 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int m
   void *vc = (char *)m.vcache + (size_t)layer * m.kv_area_elems * esz;
 
   const bool tgt = &m == &c->tgt;  // only the target model's kernels are timed one by one
-  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, nullptr, st, ws.x_lo); }
+  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, nullptr, st); }
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_QKV : -1);
-    GemmArgs a = base_args(m.p_qkv, L.wqkv, L.bqkv, ws.x, ws.x_lo, M);
+    GemmArgs a = base_args(m.p_qkv, L.wqkv, L.s_qkv, L.bqkv, ws.x, M);
     a.q = ws.q; a.kc = kc; a.vc = vc; a.row_pos = ws.row_pos; a.rope = m.rope;
     a.q_rows = q_rows; a.d = d; a.hd = m.hd; a.H = D.n_heads; a.L_pad = m.L_pad;
     launch_gemm_mfma(dt, a, EPI_QKV, st);
@@ -148,7 +186,7 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int m
   {
     KScope k(c, tgt ? SPEC_KCLASS_ATTENTION : -1);
     AttnArgs t{};
-    t.q = ws.q; t.kc = kc; t.vc = vc; t.row_pos = ws.row_pos; t.out = ws.attn; t.out2 = ws.attn_lo;
+    t.q = ws.q; t.kc = kc; t.vc = vc; t.row_pos = ws.row_pos; t.out = ws.attn;
     t.part_acc = ws.attn_part; t.part_ml = ws.attn_ml;
     t.B = B; t.q_rows = q_rows; t.H = D.n_heads; t.hd = m.hd; t.L_pad = m.L_pad;
     t.shape = c->attn_shape;
@@ -157,20 +195,20 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int m
   }
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_O : -1);
-    GemmArgs a = base_args(m.p_o, L.wo, L.bo, ws.attn, ws.attn_lo, M);
+    GemmArgs a = base_args(m.p_o, L.wo, L.s_o, L.bo, ws.attn, M);
     a.h = ws.h;
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
   }
-  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, nullptr, st, ws.x_lo); }
+  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, nullptr, st); }
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_FFN_IN : -1);
-    GemmArgs a = base_args(m.p_13, L.w13, L.b13, ws.x, ws.x_lo, M);
-    a.act = ws.act; a.act2 = ws.act_lo; a.f = D.d_ffn;
+    GemmArgs a = base_args(m.p_13, L.w13, L.s_13, L.b13, ws.x, M);
+    a.act = ws.act; a.f = D.d_ffn;
     launch_gemm_mfma(dt, a, D.ffn_kind == SPEC_FFN_SWIGLU ? EPI_SWIGLU : EPI_RELU, st);
   }
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_FFN_OUT : -1);
-    GemmArgs a = base_args(m.p_2, L.w2, L.b2, ws.act, ws.act_lo, M);
+    GemmArgs a = base_args(m.p_2, L.w2, L.s_2, L.b2, ws.act, M);
     a.h = ws.h;
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
   }
@@ -180,8 +218,8 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int m
 void fast_head(spec_ctx *c, const Model &m, int Mh, float *logits_or_null, int q, int arg_stride, int32_t *arg_out,
                hipStream_t st) {
   const bool tgt = &m == &c->tgt;
-  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, c->ws.head_rows, st, c->ws.x_lo); }
-  GemmArgs a = base_args(m.p_head, m.lm_head, nullptr, c->ws.x, c->ws.x_lo, Mh);
+  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, c->ws.head_rows, st); }
+  GemmArgs a = base_args(m.p_head, m.lm_head, m.s_head, nullptr, c->ws.x, Mh);
   a.logits = logits_or_null;
   a.part_val = c->ws.head_part;
   a.part_idx = c->ws.head_part_idx;

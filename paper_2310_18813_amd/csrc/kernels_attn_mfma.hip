@@ -228,8 +228,8 @@ __global__ void k_attn_merge(AttnArgs a) {
   const int d = a.H * HD;
   const int pos = a.row_pos[m];
   const size_t at = xpack_index(m, hh * HD + e, d >> 5);
-  T *out = (T *)a.out + at, *out2 = (T *)a.out2 + at;
-  if (pos < 0) { Conv<T>::st(out, 0, 0.f); Conv<T>::st(out2, 0, 0.f); return; }
+  op_t *out = (op_t *)a.out + at;
+  if (pos < 0) { *out = (op_t)0.f; return; }
   const int nc = pos / ATTN_CHUNK + 1;
   const size_t slot0 = ((size_t)m * a.H + hh) * a.NC;
   const float scale = rsqrtf((float)HD) * LOG2E;  // score scale in base-2 exponent units
@@ -242,8 +242,7 @@ __global__ void k_attn_merge(AttnArgs a) {
     mr = mn;
   }
   const float res = ar * (1.0f / lr);
-  Conv<T>::st(out, 0, res);
-  Conv<T>::st(out2, 0, res - Conv<T>::round(res));
+  *out = to_op(res);
 }
 
 // Launch shape 2: one wave per (sequence, head) walks all chunks, merging in registers.
@@ -292,16 +291,11 @@ __global__ __launch_bounds__(256) void k_attn_seq(AttnArgs a) {
     const float inv = (w.pos_j >= 0) ? 1.0f / lr : 0.f;
 #pragma unroll
     for (int ht = 0; ht < HT; ++ht) {
-      T o4[4], l4[4];
+      op_t o4[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float res = w.pos_j >= 0 ? ar[ht][i] * inv : 0.f;
-        Conv<T>::st(o4, i, res);
-        Conv<T>::st(l4, i, res - Conv<T>::round(res));
-      }
+      for (int i = 0; i < 4; ++i) o4[i] = to_op(w.pos_j >= 0 ? ar[ht][i] * inv : 0.f);
       const size_t at = xpack_index(m, hh * HD + ht * 16 + 4 * w.g, d >> 5);
-      *(uint2 *)((T *)a.out + at) = *(const uint2 *)o4;
-      *(uint2 *)((T *)a.out2 + at) = *(const uint2 *)l4;
+      *(uint2 *)((op_t *)a.out + at) = *(const uint2 *)o4;
     }
   }
 }

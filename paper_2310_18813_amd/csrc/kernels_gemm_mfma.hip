@@ -1,10 +1,13 @@
-// Weight-streaming GEMMs on the matrix cores (16-bit storage, fp32 accumulate) with the
+// Weight-streaming GEMMs on the matrix cores (fp16 operands, fp32 accumulate) with the
 // layer's element-wise work fused into the epilogue.
 //
 //   Y^T[n][m] = sum_k W[n][k] * X[m][k]        W: weights [N][K], X: activations [M][K]
 //
-// One instruction, v_mfma_f32_16x16x32 (bf16 or f16), everywhere: the weight tile is the A
-// operand (16 output features x 32 k), the activation tile the B operand (16 rows x 32 k).
+// One instruction, v_mfma_f32_16x16x32_f16, everywhere: the weight tile is the A operand
+// (16 output features x 32 k), the activation tile the B operand (16 rows x 32 k).  bf16
+// models run on it too: their weights become fp16 times a power of two per matrix (exact
+// for all but vanishing elements), their activations are rounded from fp32 to fp16, which
+// keeps three more bits than bf16 would.
 //
 // Packed weights.  Each 16x32 tile is stored as the 1 KB a wave loads with one 16-byte load
 // per lane: lane L = 16*g + r holds W[n0 + r][k0 + 8g .. k0 + 8g + 7].  Tiles of one
@@ -22,6 +25,7 @@
 #include "device_utils.h"
 #include "mfma_gemm.h"
 #include "mfma_tiles.h"
+#include <algorithm>
 #include <type_traits>
 
 // No implicit fusing of multiplies and adds: which product a compiler folds into an FMA can
@@ -32,13 +36,36 @@
 namespace spec {
 
 // ------------------------------------------------------------------------- packing
+// Largest magnitude of a tensor as an fp32 bit pattern (atomic max over non-negative floats
+// ordered as integers).
+template <class T>
+__global__ void k_absmax(const T *__restrict__ s, size_t n, uint32_t *__restrict__ out) {
+  float m = 0.f;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+    const float v = fabsf(Conv<T>::ld(s, i));
+    if (v < INFINITY) m = fmaxf(m, v);
+  }
+  m = wave_max(m);
+  if ((threadIdx.x & 63) == 0) atomicMax(out, __float_as_uint(m));
+}
+void launch_absmax(int dtype, const void *src, size_t n, uint32_t *d_amax_bits, hipStream_t st) {
+  if (!src || n == 0) return;
+  const unsigned blocks = (unsigned)std::min<size_t>((n + 255) / 256, 2048);
+  if (dtype == SPEC_DTYPE_BF16)
+    hipLaunchKernelGGL(k_absmax<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t *)src, n, d_amax_bits);
+  else
+    hipLaunchKernelGGL(k_absmax<f16_t>, dim3(blocks), dim3(256), 0, st, (const f16_t *)src, n, d_amax_bits);
+}
+
 // mode 0: rows of one matrix in natural order
 // mode 1: q | k | v stacked; inside every head the q and k rows are pair-interleaved
 //         (stored row 2i <- canonical i, 2i+1 <- i + hd/2) so a rotary pair is lane-local
 // mode 2: gate / up interleaved: stored rows 4p.. = gate[2p], up[2p], gate[2p+1], up[2p+1]
+// Elements are written as fp16(weight * scale), scale the matrix's power of two (1 without amax_bits).
 template <class T>
 __global__ void k_pack_weight(int mode, int N, int K, int N_pad, int K_pad, int d, int hd, const T *__restrict__ s0,
-                              const T *__restrict__ s1, const T *__restrict__ s2, T *__restrict__ dst) {
+                              const T *__restrict__ s1, const T *__restrict__ s2, op_t *__restrict__ dst,
+                              const uint32_t *__restrict__ amax_bits) {
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // one thread per 8 packed elements
   const int KT = K_pad / 32;
   const size_t total = (size_t)(N_pad / 16) * KT * 64;
@@ -63,14 +90,12 @@ __global__ void k_pack_weight(int mode, int N, int K, int N_pad, int K_pad, int 
       row = 2 * p + (q >> 1);
     }
   }
-  T out[8];
+  const float scale = amax_bits ? weight_scale(*amax_bits) : 1.0f;
+  op_t out[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    T z;
-    Conv<T>::st(&z, 0, 0.f);
-    out[i] = (src && k0 + i < K) ? src[(size_t)row * K + k0 + i] : z;
-  }
-  T *o = dst + idx * 8;
+  for (int i = 0; i < 8; ++i)
+    out[i] = (src && k0 + i < K) ? (op_t)(Conv<T>::ld(src, (size_t)row * K + k0 + i) * scale) : (op_t)0.f;
+  op_t *o = dst + idx * 8;
 #pragma unroll
   for (int i = 0; i < 8; ++i) o[i] = out[i];
 }
@@ -108,15 +133,15 @@ PackedDims packed_dims(int N, int K) {
 }
 
 void launch_pack_weight(int dtype, int mode, const PackedDims &p, int d, int hd, const void *s0, const void *s1,
-                        const void *s2, void *dst, hipStream_t st) {
+                        const void *s2, void *dst, const uint32_t *d_amax_bits, hipStream_t st) {
   size_t total = (size_t)p.NT * p.KT * 64;
   unsigned blocks = (unsigned)((total + 255) / 256);
   if (dtype == SPEC_DTYPE_BF16)
     hipLaunchKernelGGL(k_pack_weight<bf16_t>, dim3(blocks), dim3(256), 0, st, mode, p.N, p.K, p.N_pad, p.K_pad, d, hd,
-                       (const bf16_t *)s0, (const bf16_t *)s1, (const bf16_t *)s2, (bf16_t *)dst);
+                       (const bf16_t *)s0, (const bf16_t *)s1, (const bf16_t *)s2, (op_t *)dst, d_amax_bits);
   else
     hipLaunchKernelGGL(k_pack_weight<f16_t>, dim3(blocks), dim3(256), 0, st, mode, p.N, p.K, p.N_pad, p.K_pad, d, hd,
-                       (const f16_t *)s0, (const f16_t *)s1, (const f16_t *)s2, (f16_t *)dst);
+                       (const f16_t *)s0, (const f16_t *)s1, (const f16_t *)s2, (op_t *)dst, d_amax_bits);
 }
 
 void launch_pack_bias(int dtype, int mode, const PackedDims &p, int d, int hd, const void *s0, const void *s1,
@@ -189,12 +214,6 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
     xlive[mt] = m_base + mt * 16 + c < a.M;
   }
   const u32x4_v zero4 = (u32x4_v){0u, 0u, 0u, 0u};
-  // Activation rows come as a high and a low 16-bit part (x = hi + lo, fragment order both),
-  // each multiplied with the weight tile in turn: the products then carry the fp32 activations to
-  // about 2^-16 relative instead of the 2^-8 of one 16-bit word, which is what keeps logits within
-  // the parity tolerance.  Weights are exact 16-bit values, so they need no such treatment.
-  constexpr bool SPLIT = true;
-  const ptrdiff_t x2off = SPLIT ? ((const u32x4_v *)a.X2 - (const u32x4_v *)a.X) : 0;
 
   f32x4_v acc[NB][MT];
 #pragma unroll
@@ -205,43 +224,31 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
   constexpr int U = (NB + MT >= 12) ? 1 : (NB + MT >= 6) ? 2 : (NB + MT >= 3) ? 4 : 8;
   int kt = kt0;
   for (; kt + U <= kt1; kt += U) {
-    u32x4_v wf[U][NB], xf[U][MT], xl[U][SPLIT ? MT : 1];
+    u32x4_v wf[U][NB], xf[U][MT];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) wf[u][nb] = __builtin_nontemporal_load(Wp[nb] + (size_t)(kt + u) * 64);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        xf[u][mt] = xlive[mt] ? Xp[mt][(size_t)(kt + u) * 64] : zero4;
-        if (SPLIT) xl[u][mt] = xlive[mt] ? Xp[mt][(size_t)(kt + u) * 64 + x2off] : zero4;
-      }
+      for (int mt = 0; mt < MT; ++mt) xf[u][mt] = xlive[mt] ? Xp[mt][(size_t)(kt + u) * 64] : zero4;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          acc[nb][mt] = Mfma16<T>::run(wf[u][nb], xf[u][mt], acc[nb][mt]);
-          if (SPLIT) acc[nb][mt] = Mfma16<T>::run(wf[u][nb], xl[u][mt], acc[nb][mt]);
-        }
+        for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = Mfma16::run(wf[u][nb], xf[u][mt], acc[nb][mt]);
   }
   for (; kt < kt1; ++kt) {
-    u32x4_v wf[NB], xf[MT], xl[SPLIT ? MT : 1];
+    u32x4_v wf[NB], xf[MT];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) wf[nb] = __builtin_nontemporal_load(Wp[nb] + (size_t)kt * 64);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      xf[mt] = xlive[mt] ? Xp[mt][(size_t)kt * 64] : zero4;
-      if (SPLIT) xl[mt] = xlive[mt] ? Xp[mt][(size_t)kt * 64 + x2off] : zero4;
-    }
+    for (int mt = 0; mt < MT; ++mt) xf[mt] = xlive[mt] ? Xp[mt][(size_t)kt * 64] : zero4;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        acc[nb][mt] = Mfma16<T>::run(wf[nb], xf[mt], acc[nb][mt]);
-        if (SPLIT) acc[nb][mt] = Mfma16<T>::run(wf[nb], xl[mt], acc[nb][mt]);
-      }
+      for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = Mfma16::run(wf[nb], xf[mt], acc[nb][mt]);
   }
 
   constexpr int TILES = NB * MT;

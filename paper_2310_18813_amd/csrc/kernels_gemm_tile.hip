@@ -6,15 +6,14 @@
 //
 //   workgroup = 8 waves = 2 (strip halves) x 4 (row quarters); wave tile = NBW strips x MTW
 //   16-row tiles; workgroup tile = 2*NBW strips x 4*MTW row tiles.
-//   Per 32-k step the workgroup needs 2*NBW weight fragments and 2 * 4*MTW activation
-//   fragments (high and low parts) of 1 KB each.  Weights and activations are both stored in
+//   Per 32-k step the workgroup needs 2*NBW weight fragments and 4*MTW activation
+//   fragments of 1 KB each.  Weights and activations are both stored in
 //   fragment order in global memory, so a fragment is one 16-byte load per lane, issued two
 //   steps ahead, parked in registers and written to the LDS stage that is not being read; the
 //   waves then read their fragments back with one 16-byte LDS load per lane, conflict-free.
 //
 // Results are bit-identical to the streaming kernel: the same instruction, every k-slice a
-// chain of MFMAs from zero in ascending k (high part, then low part, per step), the slices
-// added in order, the same epilogue code.
+// chain of MFMAs from zero in ascending k, the slices added in order, the same epilogue code.
 #include "mfma_tiles.h"
 #include <cstdio>
 #include <cstdlib>
@@ -37,7 +36,7 @@ template <class T, int MTW, int NBW, int EPI>
 __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int NBG = 2 * NBW, MTG = 4 * MTW;
-  constexpr int FRAGS = NBG + 2 * MTG;  // 1 KB fragments per stage
+  constexpr int FRAGS = NBG + MTG;  // 1 KB fragments per stage
   constexpr int STAGE = FRAGS * 1024;
   constexpr int LPW = (FRAGS + 7) / 8;  // fragments each wave fetches per step
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -56,7 +55,7 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   const int mtile0 = pass * MTG;
   const int m_tiles = (a.M + 15) >> 4;
 
-  // fragment f of a stage: f < NBG weight strip nt0 + f; else activation tile (f - NBG) / 2, part (f - NBG) % 2.
+  // fragment f of a stage: f < NBG weight strip nt0 + f; else activation tile f - NBG.
   // Wave w fetches fragments w, w + 8, ...; every wave issues exactly LPW loads per step (a wave with
   // nothing left re-reads its last fragment and drops it) so that one vmcnt value fits all waves.
   const u32x4_v *src[LPW];
@@ -70,9 +69,8 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
       const int nt = min(nt0 + fc, a.NT - 1);
       src[i] = (const u32x4_v *)a.W + (size_t)nt * a.KT * 64 + lane;
     } else {
-      const int idx = fc - NBG;
-      const int tile = min(mtile0 + (idx >> 1), m_tiles - 1);
-      src[i] = (const u32x4_v *)((idx & 1) ? a.X2 : a.X) + (size_t)tile * a.KT * 64 + lane;
+      const int tile = min(mtile0 + fc - NBG, m_tiles - 1);
+      src[i] = (const u32x4_v *)a.X + (size_t)tile * a.KT * 64 + lane;
     }
   }
 
@@ -118,7 +116,7 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   phase_end();
   if (grp) phase_end();  // the second group runs half a step behind the first
 
-  u32x4_v wf[NBW], xh[MTW], xl[MTW];
+  u32x4_v wf[NBW], xf[MTW];
   // LDS phase of step kt: this wave's fragments of step kt out of stage kt&1; step kt+1, prefetched three
   // steps ago, into the other stage (its last readers finished before the previous barrier: the own
   // group a whole step ago, the other group in the phase just ended); that register set then fetches
@@ -130,10 +128,8 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
     const unsigned char *sb = smem + stage_ * STAGE + lane * 16;                          \
     _Pragma("unroll") for (int nb = 0; nb < NBW; ++nb)                                    \
         wf[nb] = *(const u32x4_v *)(sb + (wn * NBW + nb) * 1024);                         \
-    _Pragma("unroll") for (int mt = 0; mt < MTW; ++mt) {                                  \
-      xh[mt] = *(const u32x4_v *)(sb + (NBG + 2 * (wm * MTW + mt)) * 1024);               \
-      xl[mt] = *(const u32x4_v *)(sb + (NBG + 2 * (wm * MTW + mt) + 1) * 1024);           \
-    }                                                                                     \
+    _Pragma("unroll") for (int mt = 0; mt < MTW; ++mt)                                    \
+        xf[mt] = *(const u32x4_v *)(sb + (NBG + wm * MTW + mt) * 1024);                   \
     stash(rset, stage_ ^ 1);                                                              \
     fetch(rset, (kt_) + 4);                                                               \
     phase_end();                                                                          \
@@ -145,10 +141,7 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
-      for (int mt = 0; mt < MTW; ++mt) {
-        cur[nb][mt] = Mfma16<T>::run(wf[nb], xh[mt], cur[nb][mt]);
-        cur[nb][mt] = Mfma16<T>::run(wf[nb], xl[mt], cur[nb][mt]);
-      }
+      for (int mt = 0; mt < MTW; ++mt) cur[nb][mt] = Mfma16::run(wf[nb], xf[mt], cur[nb][mt]);
     __builtin_amdgcn_s_setprio(0);
     if (++in_slice == kt_per) {  // slice finished: add it to the running total, in slice order
 #pragma unroll
@@ -187,7 +180,7 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
 
 template <class T, int MTW, int NBW, int EPI>
 static void launch_one(const GemmArgs &a, int blocks, hipStream_t st) {
-  constexpr size_t lds = 2 * (size_t)(2 * NBW + 8 * MTW) * 1024;
+  constexpr size_t lds = 2 * (size_t)(2 * NBW + 4 * MTW) * 1024;
   static bool attr_set = false;  // the kernel may use more than the default 64 KB of LDS
   if (!attr_set) {
     (void)hipFuncSetAttribute((const void *)k_gemm_tile<T, MTW, NBW, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -233,9 +226,9 @@ static void choose_tile(int M, int NT, int n_cu, int &MTW, int &NBW) {
       const int passes = (M + 64 * mt - 1) / (64 * mt);
       const int wgs = passes * ((NT + 2 * nb - 1) / (2 * nb));
       const int rounds = (wgs + n_cu - 1) / n_cu;
-      const int frags = 2 * nb + 8 * mt;
-      const int mfma = 2 * mt * nb * 16;
-      const int lds = 4 * (2 * mt + nb + (frags + 7) / 8) * 8;
+      const int frags = 2 * nb + 4 * mt;
+      const int mfma = mt * nb * 16;
+      const int lds = 4 * (mt + nb + 2 * ((frags + 7) / 8)) * 8;  // writes run at half the rate of reads
       const long cost = (long)rounds * (2 * (mfma > lds ? mfma : lds) + 100);
       if (best < 0 || cost < best || (cost == best && mt * nb > MTW * NBW)) { best = cost; MTW = mt; NBW = nb; }
     }

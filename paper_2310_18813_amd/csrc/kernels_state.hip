@@ -81,8 +81,8 @@ constexpr int NORM_MAX_V4 = 8;  // d <= 8192
 template <class T>
 __global__ __launch_bounds__(256) void k_norm(int kind, int d, float eps, const float *__restrict__ h,
                                               const T *__restrict__ gain, const T *__restrict__ bias,
-                                              const int32_t *__restrict__ gather, T *__restrict__ x,
-                                              int pack_kt, T *__restrict__ x_lo) {
+                                              const int32_t *__restrict__ gather, void *__restrict__ x,
+                                              int pack_kt) {
   __shared__ float sh[4];
   const int r = blockIdx.x;
   const float4 *hr = (const float4 *)(h + (size_t)(gather ? gather[r] : r) * d);
@@ -128,23 +128,21 @@ __global__ __launch_bounds__(256) void k_norm(int kind, int d, float eps, const 
       for (int k = 0; k < 4; ++k) {
         float o = (e[k] - mean) * inv * Conv<T>::ld(gain, 4 * c + k);
         if (kind != SPEC_NORM_RMS) o += Conv<T>::ld(bias, 4 * c + k);
-        // pack_kt > 0: the consumer is a matrix-core GEMM, rows are stored in fragment order
-        const size_t at = pack_kt > 0 ? xpack_index(r, 4 * c + k, pack_kt) : (size_t)r * d + 4 * c + k;
-        Conv<T>::st(x, at, o);
-        // optional second 16-bit word: what the first one lost (o = hi + lo up to 2^-16 relative)
-        if (x_lo) Conv<T>::st(x_lo, at, o - Conv<T>::round(o));
+        // pack_kt > 0: the consumer is a matrix-core GEMM: fp16 operands, rows stored in fragment order
+        if (pack_kt > 0) ((op_t *)x)[xpack_index(r, 4 * c + k, pack_kt)] = to_op(o);
+        else Conv<T>::st((T *)x, (size_t)r * d + 4 * c + k, o);
       }
     }
   }
 }
 
 void launch_norm(const spec_ctx *c, const Model &m, const float *h, const void *gain, const void *bias, void *x,
-                 int M, const int32_t *row_gather, hipStream_t st, void *x_lo) {
+                 int M, const int32_t *row_gather, hipStream_t st) {
   if (M <= 0) return;
   const int pack_kt = m.fast ? m.desc.d_model / 32 : 0;
   SPEC_DISPATCH_DTYPE(c->run.dtype, T,
     hipLaunchKernelGGL(k_norm<T>, dim3(M), dim3(256), 0, st, m.desc.norm_kind, m.desc.d_model, m.desc.norm_eps, h,
-                       (const T *)gain, (const T *)bias, row_gather, (T *)x, pack_kt, (T *)x_lo));
+                       (const T *)gain, (const T *)bias, row_gather, x, pack_kt));
 }
 
 // -------------------------------------------------------------------------

@@ -23,8 +23,8 @@ struct GemmArgs {
   // operands
   const void *W;      // packed tiles
   const float *bias;  // [N_pad] in stored-row order, or null
-  const void *X;      // activations in fragment order (xpack_index), ceil(M/16) x KT tiles
-  const void *X2;     // low 16-bit parts of the same rows (same layout): x = X + X2
+  const void *X;      // fp16 activations in fragment order (xpack_index), ceil(M/16) x KT tiles
+  float out_scale;    // 1 / (power of two the packed weights were multiplied by)
   int M, N, NT, KT, KS, K_pad;
   int passes, groups;  // filled by the launcher
   // epilogue targets (those the chosen epilogue uses)
@@ -33,15 +33,25 @@ struct GemmArgs {
   const int32_t *row_pos;    // EPI_QKV: absolute position per row, -1 = dead row
   const float2 *rope;        // EPI_QKV: (cos, sin) table [L][hd/2] or null
   int q_rows, d, hd, H, L_pad;
-  void *act, *act2;          // EPI_SWIGLU / EPI_RELU: high / low parts, fragment order, row length f (resp. N)
+  void *act;                 // EPI_SWIGLU / EPI_RELU: fp16, fragment order, row length f (resp. N)
   int f;
   float *logits;             // EPI_LOGITS: optional [M][N] fp32
   float *part_val;           // EPI_LOGITS: [M][NT]
   int32_t *part_idx;
 };
 
+// Packed weights are fp16 = weight * 2^k, k per matrix so that the largest magnitude lands in
+// [2^13, 2^14): every bf16 value within 2^-31 of the largest is then an exact fp16 number (smaller
+// ones round to a multiple of 2^-24 / 2^k).  amax_bits holds the fp32 bit pattern of that largest
+// magnitude (0 = no scaling, fp16 sources).
+__host__ __device__ inline float weight_scale(uint32_t amax_bits) {
+  const int e = (int)((amax_bits >> 23) & 0xffu) - 127;  // floor(log2(amax))
+  if (amax_bits == 0 || e < -90 || e > 90) return 1.0f;
+  return __builtin_bit_cast(float, (uint32_t)(13 - e + 127) << 23);
+}
+void launch_absmax(int dtype, const void *src, size_t n, uint32_t *d_amax_bits, hipStream_t st);
 void launch_pack_weight(int dtype, int mode, const PackedDims &p, int d, int hd, const void *s0, const void *s1,
-                        const void *s2, void *dst, hipStream_t st);
+                        const void *s2, void *dst, const uint32_t *d_amax_bits, hipStream_t st);
 void launch_pack_bias(int dtype, int mode, const PackedDims &p, int d, int hd, const void *s0, const void *s1,
                       const void *s2, float *dst, hipStream_t st);
 void launch_rope_table(int L, int hd, float theta, float2 *tab, hipStream_t st);
@@ -54,7 +64,7 @@ struct AttnArgs {
   const void *q;            // [M][d] model dtype, pair-interleaved heads
   const void *kc, *vc;      // this layer's cache areas
   const int32_t *row_pos;   // [M]
-  void *out, *out2;         // [M][d] high / low 16-bit parts, canonical element order, fragment layout
+  void *out;                // [M][d] fp16, canonical element order, fragment layout
   float *part_acc;          // [M][H][NC][hd] un-normalised partial outputs
   float *part_ml;           // [M][H][NC][2] running max (raw score units) and sum
   int shape;                // 0 auto, 1 split + merge, 2 one wave per (sequence, head)

@@ -15,14 +15,8 @@ typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_v;
 typedef __attribute__((ext_vector_type(4))) float f32x4_v;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_v;
 
-template <class T> struct Mfma16;
-template <> struct Mfma16<bf16_t> {
-  static __device__ __forceinline__ f32x4_v run(u32x4_v a, u32x4_v b, f32x4_v c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_v, a), __builtin_bit_cast(bf16x8_v, b), c,
-                                                   0, 0, 0);
-  }
-};
-template <> struct Mfma16<f16_t> {
+// The one instruction: D(16x16 fp32) += A(16x32 fp16) * B(32x16 fp16).
+struct Mfma16 {
   static __device__ __forceinline__ f32x4_v run(u32x4_v a, u32x4_v b, f32x4_v c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_v, a), __builtin_bit_cast(f16x8_v, b), c,
                                                   0, 0, 0);
@@ -36,6 +30,7 @@ template <class T, int EPI>
 __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int nt, int m, int g) {
   if (nt >= a.NT) return;
   const int n = nt * 16 + 4 * g;
+  v[0] *= a.out_scale; v[1] *= a.out_scale; v[2] *= a.out_scale; v[3] *= a.out_scale;  // exact: a power of two
   if (a.bias) {
     const float4 b4 = *(const float4 *)(a.bias + n);
     v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
@@ -78,25 +73,17 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int 
     const int j = n >> 1;  // stored rows n..n+3 = gate_j, up_j, gate_{j+1}, up_{j+1}
     if (live && j < a.f) {
       const float r0 = v[0] / (1.0f + __expf(-v[0])) * v[1], r1 = v[2] / (1.0f + __expf(-v[2])) * v[3];
-      T o2[2], l2[2];
-      Conv<T>::st(o2, 0, r0); Conv<T>::st(o2, 1, r1);
-      Conv<T>::st(l2, 0, r0 - Conv<T>::round(r0)); Conv<T>::st(l2, 1, r1 - Conv<T>::round(r1));
+      op_t o2[2] = {to_op(r0), to_op(r1)};
       const size_t at = xpack_index(m, j, a.f >> 5);
-      *(uint32_t *)((T *)a.act + at) = *(const uint32_t *)o2;
-      *(uint32_t *)((T *)a.act2 + at) = *(const uint32_t *)l2;
+      *(uint32_t *)((op_t *)a.act + at) = *(const uint32_t *)o2;
     }
   } else if (EPI == EPI_RELU) {
     if (live && n < a.N) {
-      T o4[4], l4[4];
+      op_t o4[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float r = v[i] > 0.f ? v[i] : 0.f;
-        Conv<T>::st(o4, i, r);
-        Conv<T>::st(l4, i, r - Conv<T>::round(r));
-      }
+      for (int i = 0; i < 4; ++i) o4[i] = to_op(v[i] > 0.f ? v[i] : 0.f);
       const size_t at = xpack_index(m, n, a.N >> 5);
-      *(uint2 *)((T *)a.act + at) = *(const uint2 *)o4;
-      *(uint2 *)((T *)a.act2 + at) = *(const uint2 *)l4;
+      *(uint2 *)((op_t *)a.act + at) = *(const uint2 *)o4;
     }
   } else {  // EPI_LOGITS: optional dump, per-strip arg-max partial (lowest index wins ties)
     float bv = -INFINITY;

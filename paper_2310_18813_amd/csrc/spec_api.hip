@@ -104,7 +104,7 @@ static Sizes compute_sizes(const spec_model_desc *tgt, const spec_model_desc *dr
     wide = std::max(wide, std::max<size_t>(3 * (size_t)drf->d_model, kfd * drf->d_ffn));
   }
   const size_t Mp = (M + 15) / 16 * 16;  // fragment-order activation buffers hold whole 16-row tiles
-  z.act = al256(M * d * 4) + 5 * al256(Mp * d * e) + 2 * al256(Mp * f * e) + al256(M * wide * 4) + al256(M * V * 4) +
+  z.act = al256(M * d * 4) + 3 * al256(Mp * d * e) + al256(Mp * f * e) + al256(M * wide * 4) + al256(M * V * 4) +
           4 * al256(M * 4);
   // matrix-core path: split-KV attention partials and per-strip arg-max partials
   const size_t NC = (L + ATTN_CHUNK - 1) / ATTN_CHUNK, NTh = (V + 15) / 16;
@@ -172,7 +172,7 @@ static int setup_model(spec_ctx *c, Model &m, const spec_model_desc *d, const sp
   m.layers.resize(d->n_layers);
   void *cursor = p;
   if (m.fast) {
-    fast_setup_model(c, m, w, cursor, c->stream);
+    if (!fast_setup_model(c, m, w, cursor, c->stream)) return fail(c, SPEC_ERR_HIP, "spec_init: weight packing failed");
   } else {
     generic_repack_top(c, m, w, cursor, c->stream);
     for (int l = 0; l < d->n_layers; ++l) generic_repack_layer(c, m, l, w, cursor, c->stream);
@@ -245,9 +245,6 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
   W.q = carve(p, Mp * d * e);
   W.attn = carve(p, Mp * d * e);
   W.act = carve(p, Mp * f * e);
-  W.x_lo = carve(p, Mp * d * e);
-  W.attn_lo = carve(p, Mp * d * e);
-  W.act_lo = carve(p, Mp * f * e);
   W.y32 = (float *)carve(p, M * wide * 4);
   W.logits = (float *)carve(p, M * V * 4);
   W.row_tok = (int32_t *)carve(p, M * 4);

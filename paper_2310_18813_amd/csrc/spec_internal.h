@@ -43,6 +43,7 @@ struct LayerW {
   const void *wo, *bo;      // [d][d]
   const void *w13, *b13;    // SwiGLU: [2f][d] gate/up rows; ReLU: [f][d]
   const void *w2, *b2;      // [d][f]
+  float s_qkv = 1.f, s_o = 1.f, s_13 = 1.f, s_2 = 1.f;  // MFMA path: 1 / scale of the packed fp16 weights
 };
 
 struct Model {
@@ -54,6 +55,7 @@ struct Model {
              *lm_head = nullptr;
   std::vector<LayerW> layers;
   PackedDims p_qkv{}, p_o{}, p_13{}, p_2{}, p_head{};  // MFMA path: packed shapes
+  float s_head = 1.f;                                  // MFMA path: 1 / scale of the packed LM head
   const float2 *rope = nullptr;                        // MFMA path: (cos, sin) table [L_max][hd/2]
   void *kcache = nullptr, *vcache = nullptr;  // [n_layers] x area
   size_t kv_area_elems = 0;                   // elements per layer per K (or V) area
@@ -71,8 +73,7 @@ enum PassKind {
 struct Workspace {
   // activations (shared by both models; sized for the larger)
   float *h = nullptr;       // [M_max][d]   fp32 residual stream
-  void *x = nullptr;        // [M_max][d]   normed rows, model dtype
-  void *x_lo = nullptr, *attn_lo = nullptr, *act_lo = nullptr;  // MFMA path: low 16-bit parts of x / attn / act
+  void *x = nullptr;        // [M_max][d]   normed rows, model dtype (MFMA path: fp16 operands, as attn and act)
   void *q = nullptr;        // [M_max][d]   queries, model dtype, pair-interleaved per head
   void *attn = nullptr;     // [M_max][d]   attention output, model dtype
   void *act = nullptr;      // [M_max][f]   FFN activation, model dtype
@@ -165,7 +166,7 @@ struct PassArgs {
 
 void launch_assemble_embed(const spec_ctx *c, const Model &m, const PassArgs &pa, hipStream_t st);
 void launch_norm(const spec_ctx *c, const Model &m, const float *h, const void *gain, const void *bias, void *x,
-                 int M, const int32_t *row_gather, hipStream_t st, void *x_lo = nullptr);
+                 int M, const int32_t *row_gather, hipStream_t st);
 void launch_argmax_rows(const float *logits, int M, int V, int q, int out_stride, int32_t *out, hipStream_t st);
 void launch_accept(spec_ctx *c, int s, hipStream_t st);
 void launch_fill_proposals(spec_ctx *c, int s, hipStream_t st);
@@ -190,7 +191,7 @@ size_t dtype_bytes(int dtype);
 // matrix-core path (16-bit dtypes)
 bool fast_supported(const spec_model_desc &D, int dtype);
 size_t fast_packed_bytes(const spec_model_desc &D, int dtype, int L_max);
-void fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&cursor, hipStream_t st);
+bool fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&cursor, hipStream_t st);  // false: HIP error
 void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int max_pos, hipStream_t st);
 void fast_head(spec_ctx *c, const Model &m, int Mh, float *logits_or_null, int q, int arg_stride, int32_t *arg_out,
                hipStream_t st);
