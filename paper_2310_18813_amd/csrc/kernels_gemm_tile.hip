@@ -22,16 +22,12 @@ namespace spec {
 
 #pragma clang fp contract(off)
 
-// Two LDS stages of fragments; global loads run three steps ahead of the LDS writes through
-// three register sets (global -> VGPR -> LDS).  The direct global->LDS path was measured at about
-// 18 bytes per clock and CU on this part, a third of what the ordinary load path sustains, so
-// it is not used here.
-//
-// The eight waves work as two groups of four (one wave of each group per SIMD) half a step
-// apart: while one group issues the MFMAs of its step, the other does its LDS traffic (fragment
-// reads for its next MFMA phase, the hand-over of prefetched global data into the other stage),
-// and at the next barrier they swap.  The matrix pipe and the LDS pipe of a SIMD are then busy
-// at the same time although every wave runs its phases strictly in order.
+// Three LDS stages of fragments.  Global loads run three steps ahead of the LDS writes through
+// three register sets (global -> VGPR -> LDS; the direct global->LDS path was measured at about
+// 18 bytes per clock and CU on this part, a third of what the ordinary load path sustains).
+// The waves read their fragments of step k+1 into a second set of fragment registers before they
+// issue the MFMAs of step k, so the LDS pipe, the global loads and the matrix pipe of a SIMD work at
+// the same time, with one barrier per step.
 template <class T, int MTW, int NBW, int EPI>
 __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -40,8 +36,7 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   constexpr int STAGE = FRAGS * 1024;
   constexpr int LPW = (FRAGS + 7) / 8;  // fragments each wave fetches per step
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int grp = w >> 2;               // phase group; waves w and w + 4 share a SIMD
-  const int wn = w & 1, wm = ((w >> 1) & 1) | (grp << 1);
+  const int wn = w & 1, wm = w >> 1;
   const int c = lane & 15, g = lane >> 4;
   int G, pass;
   if (a.passes == 1) { G = blockIdx.x; pass = 0; }
@@ -56,15 +51,16 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   const int m_tiles = (a.M + 15) >> 4;
 
   // fragment f of a stage: f < NBG weight strip nt0 + f; else activation tile f - NBG.
-  // Wave w fetches fragments w, w + 8, ...; every wave issues exactly LPW loads per step (a wave with
-  // nothing left re-reads its last fragment and drops it) so that one vmcnt value fits all waves.
+  // Wave w fetches fragments w, w + 8, ...; every wave issues exactly LPW loads and LDS writes per step (a
+  // wave with nothing left repeats the last fragment: the same bytes to the same place) so that the step is
+  // branch-free and one wait count fits all waves.
   const u32x4_v *src[LPW];
   int dst[LPW];
 #pragma unroll
   for (int i = 0; i < LPW; ++i) {
     const int f = w + 8 * i;
-    dst[i] = f < FRAGS ? f * 1024 + lane * 16 : -1;
     const int fc = min(f, FRAGS - 1);
+    dst[i] = fc * 1024 + lane * 16;
     if (fc < NBG) {
       const int nt = min(nt0 + fc, a.NT - 1);
       src[i] = (const u32x4_v *)a.W + (size_t)nt * a.KT * 64 + lane;
@@ -88,61 +84,37 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
 #pragma unroll
     for (int i = 0; i < LPW; ++i) r[i] = src[i][(size_t)min(kt, a.KT - 1) * 64];
   };
-
   auto stash = [&](const u32x4_v (&r)[LPW], int stage) {
 #pragma unroll
-    for (int i = 0; i < LPW; ++i)
-      if (dst[i] >= 0) *(u32x4_v *)(smem + stage * STAGE + dst[i]) = r[i];
+    for (int i = 0; i < LPW; ++i) *(u32x4_v *)(smem + stage * STAGE + dst[i]) = r[i];
+  };
+  struct Frags { u32x4_v wf[NBW], xf[MTW]; };
+  auto read_frags = [&](Frags &f, int stage) {
+    const unsigned char *sb = smem + stage * STAGE + lane * 16;
+#pragma unroll
+    for (int nb = 0; nb < NBW; ++nb) f.wf[nb] = *(const u32x4_v *)(sb + (wn * NBW + nb) * 1024);
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt) f.xf[mt] = *(const u32x4_v *)(sb + (NBG + wm * MTW + mt) * 1024);
   };
   // A bare barrier, not __syncthreads(): the fence of the latter would wait for the global loads in
-  // flight.  Ordered by hand: before it, this wave's LDS reads have returned and its LDS writes are
-  // done; nothing may be scheduled across it, so that the phases stay phases.
-  auto phase_end = [&]() {
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
+  // flight.  Ordered by hand: before it this wave's LDS writes are done; the NBW + MTW fragment reads
+  // issued after them may still be on their way (LDS operations of a wave complete in order).
+  auto step_end = [&]() {
+    static_assert(NBW + MTW <= 15, "wait count field");
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(NBW + MTW) : "memory");
     __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
     asm volatile("" ::: "memory");
   };
 
   const int kt_per = a.KT / a.KS;
   int in_slice = 0, slice = 0;
-  // prologue: step 0 into LDS stage 0, steps 1, 2 and 3 into the register sets
-  fetch(r0, 0);
-  fetch(r1, 1);
-  fetch(r2, 2);
-  stash(r0, 0);
-  fetch(r0, 3);
-  phase_end();
-  if (grp) phase_end();  // the second group runs half a step behind the first
-
-  u32x4_v wf[NBW], xf[MTW];
-  // LDS phase of step kt: this wave's fragments of step kt out of stage kt&1; step kt+1, prefetched three
-  // steps ago, into the other stage (its last readers finished before the previous barrier: the own
-  // group a whole step ago, the other group in the phase just ended); that register set then fetches
-  // step kt+4.  The register sets rotate with period three: the loop below is unrolled by three so that
-  // each set has a fixed role per copy and the compiler's wait-count bookkeeping stays exact.
-#define SPEC_TILE_STEP(rset, kt_)                                                         \
-  {                                                                                       \
-    const int stage_ = (kt_) & 1;                                                         \
-    const unsigned char *sb = smem + stage_ * STAGE + lane * 16;                          \
-    _Pragma("unroll") for (int nb = 0; nb < NBW; ++nb)                                    \
-        wf[nb] = *(const u32x4_v *)(sb + (wn * NBW + nb) * 1024);                         \
-    _Pragma("unroll") for (int mt = 0; mt < MTW; ++mt)                                    \
-        xf[mt] = *(const u32x4_v *)(sb + (NBG + wm * MTW + mt) * 1024);                   \
-    stash(rset, stage_ ^ 1);                                                              \
-    fetch(rset, (kt_) + 4);                                                               \
-    phase_end();                                                                          \
-    compute();                                                                            \
-    phase_end();                                                                          \
-  }
-  auto compute = [&]() {
-    __builtin_amdgcn_s_setprio(1);
+  auto mfmas = [&](const Frags &f) {
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
-      for (int mt = 0; mt < MTW; ++mt) cur[nb][mt] = Mfma16::run(wf[nb], xf[mt], cur[nb][mt]);
-    __builtin_amdgcn_s_setprio(0);
+      for (int mt = 0; mt < MTW; ++mt) cur[nb][mt] = Mfma16::run(f.wf[nb], f.xf[mt], cur[nb][mt]);
+  };
+  auto slice_end = [&]() {
     if (++in_slice == kt_per) {  // slice finished: add it to the running total, in slice order
 #pragma unroll
       for (int nb = 0; nb < NBW; ++nb)
@@ -159,16 +131,69 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
       ++slice;
     }
   };
-  int kt = 0;
-  for (; kt + 2 < a.KT; kt += 3) {
-    SPEC_TILE_STEP(r1, kt)
-    SPEC_TILE_STEP(r2, kt + 1)
-    SPEC_TILE_STEP(r0, kt + 2)
+
+  // prologue: steps 0 and 1 into LDS stages 0 and 1, steps 2, 3, 4 into the register sets, fragments of step 0
+  Frags f0, f1;
+  fetch(r0, 0);
+  fetch(r1, 1);
+  fetch(r2, 2);
+  stash(r0, 0);
+  fetch(r0, 3);
+  stash(r1, 1);
+  fetch(r1, 4);
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  read_frags(f0, 0);
+  // Step j lives in LDS stage j % 3.  Invariant at the top of step kt: stages kt % 3 and (kt+1) % 3 hold
+  // steps kt and kt+1; every wave's reads of stage (kt+2) % 3 (step kt-1) have returned (their MFMAs were
+  // issued before the last barrier); the fragment set of parity kt&1 holds step kt or is on its way; the
+  // register set of the step holds step kt+2 (possibly still in flight).  Fragment sets alternate, register
+  // sets and stages rotate with period three: the loop is unrolled by six so that each has a fixed role
+  // per copy and the compiler's wait-count bookkeeping stays exact.
+  // The instruction order inside a step is pinned: the LDS queue of the CU is short, and a wave that
+  // issues its LDS traffic in one burst waits for queue slots before it reaches its MFMAs.  Spread between
+  // the MFMAs (writes first, then reads: the wait before the barrier counts on that order) the LDS and
+  // global-memory instructions find their slots while the matrix pipe works.
+  auto interleave = [&]() {
+    constexpr int NM = NBW * MTW, NO = 2 * LPW + NBW + MTW;  // MFMAs; other instructions: writes, loads, reads
+#pragma unroll
+    for (int i = 0, o = 0; i < NM; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+      // others due after MFMA i: spread evenly, in program order (writes, global loads, reads)
+      const int due = ((i + 1) * NO) / NM;
+      for (; o < due; ++o) {
+        if (o < LPW) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);            // LDS write
+        else if (o < 2 * LPW) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // global load
+        else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                    // LDS read
+      }
+    }
+  };
+#define SPEC_TILE_STEP(fcur, fnext, rset, kt_, i_)                               \
+  {                                                                              \
+    stash(rset, ((i_) + 2) % 3);                                                 \
+    fetch(rset, (kt_) + 5);                                                      \
+    read_frags(fnext, ((i_) + 1) % 3);                                           \
+    mfmas(fcur);                                                                 \
+    interleave();                                                                \
+    slice_end();                                                                 \
+    step_end();                                                                  \
   }
-  if (kt < a.KT) SPEC_TILE_STEP(r1, kt)
-  if (kt + 1 < a.KT) SPEC_TILE_STEP(r2, kt + 1)
+  int kt = 0;
+  for (; kt + 5 < a.KT; kt += 6) {
+    SPEC_TILE_STEP(f0, f1, r2, kt, 0)
+    SPEC_TILE_STEP(f1, f0, r0, kt + 1, 1)
+    SPEC_TILE_STEP(f0, f1, r1, kt + 2, 2)
+    SPEC_TILE_STEP(f1, f0, r2, kt + 3, 3)
+    SPEC_TILE_STEP(f0, f1, r0, kt + 4, 4)
+    SPEC_TILE_STEP(f1, f0, r1, kt + 5, 5)
+  }
+  if (kt < a.KT) SPEC_TILE_STEP(f0, f1, r2, kt, 0)
+  if (kt + 1 < a.KT) SPEC_TILE_STEP(f1, f0, r0, kt + 1, 1)
+  if (kt + 2 < a.KT) SPEC_TILE_STEP(f0, f1, r1, kt + 2, 2)
+  if (kt + 3 < a.KT) SPEC_TILE_STEP(f1, f0, r2, kt + 3, 3)
+  if (kt + 4 < a.KT) SPEC_TILE_STEP(f0, f1, r0, kt + 4, 4)
 #undef SPEC_TILE_STEP
-  if (!grp) phase_end();  // every wave passes the same number of barriers
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the over-fetched tail before the epilogue
 
 #pragma unroll
@@ -180,7 +205,7 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
 
 template <class T, int MTW, int NBW, int EPI>
 static void launch_one(const GemmArgs &a, int blocks, hipStream_t st) {
-  constexpr size_t lds = 2 * (size_t)(2 * NBW + 4 * MTW) * 1024;
+  constexpr size_t lds = 3 * (size_t)(2 * NBW + 4 * MTW) * 1024;
   static bool attr_set = false;  // the kernel may use more than the default 64 KB of LDS
   if (!attr_set) {
     (void)hipFuncSetAttribute((const void *)k_gemm_tile<T, MTW, NBW, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -208,9 +233,10 @@ static void launch_nb_tile(const GemmArgs &a, int NBW, int epi, int blocks, hipS
 }
 
 // Wave tile (MTW 16-row tiles x NBW strips) for M rows and NT strips.  One workgroup occupies a CU, so
-// a launch takes ceil(workgroups / CUs) rounds of KT steps; a step lasts two phases, each as long as the
-// slower of one group's MFMAs (16 clocks each) and the other group's LDS traffic (8 clocks per 1 KB
-// fragment read or written).  SPEC_GEMM_TILE="mtw,nbw" in the environment overrides the choice (tuning aid).
+// a launch takes ceil(workgroups / CUs) rounds of KT steps.  Measured on MI355X a step costs about
+// 150 + 45 * MTW * NBW + 40 * (MTW + NBW) clocks (two waves per SIMD at 16 clocks per MFMA are 32 of the
+// 45; the last term is the LDS traffic).  SPEC_GEMM_TILE="mtw,nbw" in the environment overrides the
+// choice (tuning aid).
 static void choose_tile(int M, int NT, int n_cu, int &MTW, int &NBW) {
   static int force_mt = -1, force_nb = 0;
   if (force_mt < 0) {
@@ -226,10 +252,7 @@ static void choose_tile(int M, int NT, int n_cu, int &MTW, int &NBW) {
       const int passes = (M + 64 * mt - 1) / (64 * mt);
       const int wgs = passes * ((NT + 2 * nb - 1) / (2 * nb));
       const int rounds = (wgs + n_cu - 1) / n_cu;
-      const int frags = 2 * nb + 4 * mt;
-      const int mfma = mt * nb * 16;
-      const int lds = 4 * (mt + nb + 2 * ((frags + 7) / 8)) * 8;  // writes run at half the rate of reads
-      const long cost = (long)rounds * (2 * (mfma > lds ? mfma : lds) + 100);
+      const long cost = (long)rounds * (150 + 45 * mt * nb + 40 * (mt + nb));
       if (best < 0 || cost < best || (cost == best && mt * nb > MTW * NBW)) { best = cost; MTW = mt; NBW = nb; }
     }
 }
