@@ -196,7 +196,7 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int m
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_O : -1);
     GemmArgs a = base_args(m.p_o, L.wo, L.s_o, L.bo, ws.attn, M);
-    a.h = ws.h;
+    a.h = ws.h; a.part = ws.gemm_part; a.part_rows = (M + 15) / 16 * 16;
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
   }
   { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, nullptr, st); }
@@ -209,7 +209,7 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int m
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_FFN_OUT : -1);
     GemmArgs a = base_args(m.p_2, L.w2, L.s_2, L.b2, ws.act, M);
-    a.h = ws.h;
+    a.h = ws.h; a.part = ws.gemm_part; a.part_rows = (M + 15) / 16 * 16;
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
   }
 }

@@ -298,8 +298,11 @@ static void launch_epi(const GemmArgs &a, int epi, dim3 grid, dim3 block, size_t
 template <class T>
 static void launch_gemm_t(GemmArgs a, int epi, hipStream_t st) {
   if (a.M <= 0) return;
-  // wide outputs with more than 64 rows: the LDS-tiled kernel (same bits, weights fetched once per 256 rows)
-  if (a.M > 64 && epi != EPI_RESIDUAL && a.NT >= 64) {
+  // more than 64 rows: the LDS-tiled kernel (same bits, weights fetched once per up to 256 rows); the narrow
+  // residual GEMMs run it one k-slice per workgroup when the context has the scratch for the slices
+  // (worth the second kernel from about 32 steps per slice, or from 5 row passes of the streaming kernel)
+  const bool split_ok = a.part && a.KS > 1 && (a.N & 3) == 0 && (a.KT / a.KS >= 32 || a.M > 256);
+  if (a.M > 64 && a.NT >= 64 && (epi != EPI_RESIDUAL || split_ok)) {
     launch_gemm_tile(std::is_same<T, bf16_t>::value ? SPEC_DTYPE_BF16 : SPEC_DTYPE_F16, a, epi, st);
     return;
   }

@@ -38,14 +38,21 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int wn = w & 1, wm = w >> 1;
   const int c = lane & 15, g = lane >> 4;
-  int G, pass;
-  if (a.passes == 1) { G = blockIdx.x; pass = 0; }
+  constexpr bool PARTIAL = EPI == EPI_PARTIAL;
+  int G, pass, slice_id = 0;
+  if (!PARTIAL && a.passes == 1) { G = blockIdx.x; pass = 0; }
   else {  // all passes of a strip group on one XCD (see the streaming kernel)
-    const int id = blockIdx.x, rest = id >> 3;
+    const int id = blockIdx.x;
+    int rest = id >> 3;
     pass = rest % a.passes;
-    G = (rest / a.passes) * 8 + (id & 7);
+    rest /= a.passes;
+    if (PARTIAL) { slice_id = rest % a.KS; rest /= a.KS; }  // one k-slice per workgroup
+    G = rest * 8 + (id & 7);
   }
   if (G >= a.groups) return;
+  const int kt_per = a.KT / a.KS;
+  const int KTL = PARTIAL ? kt_per : a.KT;          // steps of this workgroup
+  const int kt_lo = PARTIAL ? slice_id * kt_per : 0;  // first k-tile
   const int nt0 = G * NBG;
   const int mtile0 = pass * MTG;
   const int m_tiles = (a.M + 15) >> 4;
@@ -82,7 +89,7 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   u32x4_v r0[LPW], r1[LPW], r2[LPW];  // three steps on their way from global memory
   auto fetch = [&](u32x4_v (&r)[LPW], int kt) {
 #pragma unroll
-    for (int i = 0; i < LPW; ++i) r[i] = src[i][(size_t)min(kt, a.KT - 1) * 64];
+    for (int i = 0; i < LPW; ++i) r[i] = src[i][(size_t)(kt_lo + min(kt, KTL - 1)) * 64];
   };
   auto stash = [&](const u32x4_v (&r)[LPW], int stage) {
 #pragma unroll
@@ -106,7 +113,6 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
     asm volatile("" ::: "memory");
   };
 
-  const int kt_per = a.KT / a.KS;
   int in_slice = 0, slice = 0;
   auto mfmas = [&](const Frags &f) {
 #pragma unroll
@@ -180,7 +186,7 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
     step_end();                                                                  \
   }
   int kt = 0;
-  for (; kt + 5 < a.KT; kt += 6) {
+  for (; kt + 5 < KTL; kt += 6) {
     SPEC_TILE_STEP(f0, f1, r2, kt, 0)
     SPEC_TILE_STEP(f1, f0, r0, kt + 1, 1)
     SPEC_TILE_STEP(f0, f1, r1, kt + 2, 2)
@@ -188,20 +194,47 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
     SPEC_TILE_STEP(f0, f1, r0, kt + 4, 4)
     SPEC_TILE_STEP(f1, f0, r1, kt + 5, 5)
   }
-  if (kt < a.KT) SPEC_TILE_STEP(f0, f1, r2, kt, 0)
-  if (kt + 1 < a.KT) SPEC_TILE_STEP(f1, f0, r0, kt + 1, 1)
-  if (kt + 2 < a.KT) SPEC_TILE_STEP(f0, f1, r1, kt + 2, 2)
-  if (kt + 3 < a.KT) SPEC_TILE_STEP(f1, f0, r2, kt + 3, 3)
-  if (kt + 4 < a.KT) SPEC_TILE_STEP(f0, f1, r0, kt + 4, 4)
+  if (kt < KTL) SPEC_TILE_STEP(f0, f1, r2, kt, 0)
+  if (kt + 1 < KTL) SPEC_TILE_STEP(f1, f0, r0, kt + 1, 1)
+  if (kt + 2 < KTL) SPEC_TILE_STEP(f0, f1, r1, kt + 2, 2)
+  if (kt + 3 < KTL) SPEC_TILE_STEP(f1, f0, r2, kt + 3, 3)
+  if (kt + 4 < KTL) SPEC_TILE_STEP(f0, f1, r0, kt + 4, 4)
 #undef SPEC_TILE_STEP
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the over-fetched tail before the epilogue
 
 #pragma unroll
   for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
-    for (int mt = 0; mt < MTW; ++mt)
-      tile_epilogue<T, EPI>(a, tot[nb][mt], nt0 + wn * NBW + nb, (mtile0 + wm * MTW + mt) * 16 + c, g);
+    for (int mt = 0; mt < MTW; ++mt) {
+      const int nt = nt0 + wn * NBW + nb, m = (mtile0 + wm * MTW + mt) * 16 + c;
+      if (PARTIAL) {  // the slice's chain as it is; k_partial_reduce adds the slices in order
+        const int n = nt * 16 + 4 * g;
+        if (nt < a.NT && m < a.M && n < a.N)
+          *(f32x4_v *)(a.part + ((size_t)slice_id * a.part_rows + m) * a.N + n) = tot[nb][mt];
+      } else {
+        tile_epilogue<T, EPI == EPI_PARTIAL ? EPI_RESIDUAL : EPI>(a, tot[nb][mt], nt, m, g);
+      }
+    }
 }
+
+// Second half of a split residual GEMM: out = ((P_0 + P_1) + ...) + P_{KS-1}, then the same epilogue as
+// everywhere (scale, bias, h += out).  One thread per four consecutive outputs of a row.
+template <class T>
+__global__ __launch_bounds__(256) void k_partial_reduce(GemmArgs a) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const int n4 = a.N >> 2;
+  if (idx >= (size_t)a.M * n4) return;
+  const int m = (int)(idx / n4), n = (int)(idx % n4) * 4;
+  const float *p = a.part + (size_t)m * a.N + n;
+  const size_t stride = (size_t)a.part_rows * a.N;
+  f32x4_v v = *(const f32x4_v *)p;
+  for (int s = 1; s < a.KS; ++s) {
+    const f32x4_v q = *(const f32x4_v *)(p + s * stride);
+    v[0] += q[0]; v[1] += q[1]; v[2] += q[2]; v[3] += q[3];
+  }
+  tile_epilogue<T, EPI_RESIDUAL>(a, v, n >> 4, m, (n & 15) >> 2);
+}
+
 
 template <class T, int MTW, int NBW, int EPI>
 static void launch_one(const GemmArgs &a, int blocks, hipStream_t st) {
@@ -221,6 +254,7 @@ static void launch_epi_tile(const GemmArgs &a, int epi, int blocks, hipStream_t 
     case EPI_QKV: launch_one<T, MTW, NBW, EPI_QKV>(a, blocks, st); break;
     case EPI_SWIGLU: launch_one<T, MTW, NBW, EPI_SWIGLU>(a, blocks, st); break;
     case EPI_RELU: launch_one<T, MTW, NBW, EPI_RELU>(a, blocks, st); break;
+    case EPI_PARTIAL: launch_one<T, MTW, NBW, EPI_PARTIAL>(a, blocks, st); break;
     default: launch_one<T, MTW, NBW, EPI_LOGITS>(a, blocks, st); break;
   }
 }
@@ -237,7 +271,7 @@ static void launch_nb_tile(const GemmArgs &a, int NBW, int epi, int blocks, hipS
 // 150 + 45 * MTW * NBW + 40 * (MTW + NBW) clocks (two waves per SIMD at 16 clocks per MFMA are 32 of the
 // 45; the last term is the LDS traffic).  SPEC_GEMM_TILE="mtw,nbw" in the environment overrides the
 // choice (tuning aid).
-static void choose_tile(int M, int NT, int n_cu, int &MTW, int &NBW) {
+static void choose_tile(int M, int NT, int n_cu, int steps, int wg_mult, int &MTW, int &NBW) {
   static int force_mt = -1, force_nb = 0;
   if (force_mt < 0) {
     force_mt = 0;
@@ -250,9 +284,10 @@ static void choose_tile(int M, int NT, int n_cu, int &MTW, int &NBW) {
   for (int mt = 2; mt <= 4; ++mt)
     for (int nb = 2; nb <= 4; ++nb) {
       const int passes = (M + 64 * mt - 1) / (64 * mt);
-      const int wgs = passes * ((NT + 2 * nb - 1) / (2 * nb));
+      const int wgs = passes * ((NT + 2 * nb - 1) / (2 * nb)) * wg_mult;
       const int rounds = (wgs + n_cu - 1) / n_cu;
-      const long cost = (long)rounds * (150 + 45 * mt * nb + 40 * (mt + nb));
+      // per round: the steps, plus filling the pipeline and the epilogue (about 2 us)
+      const long cost = (long)rounds * ((long)steps * (150 + 45 * mt * nb + 40 * (mt + nb)) + 5000);
       if (best < 0 || cost < best || (cost == best && mt * nb > MTW * NBW)) { best = cost; MTW = mt; NBW = nb; }
     }
 }
@@ -267,13 +302,20 @@ static void launch_tile_t(GemmArgs a, int epi, hipStream_t st) {
     if (n_cu <= 0) n_cu = 256;
   }
   int MTW = 2, NBW = 2;
-  choose_tile(a.M, a.NT, n_cu, MTW, NBW);
+  const bool split = epi == EPI_RESIDUAL;  // narrow outputs: one k-slice per workgroup, slices added by a second kernel
+  if (split) epi = EPI_PARTIAL;
+  choose_tile(a.M, a.NT, n_cu, split ? a.KT / a.KS : a.KT, split ? a.KS : 1, MTW, NBW);
   a.passes = (a.M + 64 * MTW - 1) / (64 * MTW);
   a.groups = (a.NT + 2 * NBW - 1) / (2 * NBW);
-  const int blocks = a.passes == 1 ? a.groups : ((a.groups + 7) / 8) * 8 * a.passes;
+  const int blocks = split ? ((a.groups + 7) / 8) * 8 * a.passes * a.KS
+                           : a.passes == 1 ? a.groups : ((a.groups + 7) / 8) * 8 * a.passes;
   if (MTW == 2) launch_nb_tile<T, 2>(a, NBW, epi, blocks, st);
   else if (MTW == 3) launch_nb_tile<T, 3>(a, NBW, epi, blocks, st);
   else launch_nb_tile<T, 4>(a, NBW, epi, blocks, st);
+  if (split) {
+    const size_t total = (size_t)a.M * (a.N >> 2);
+    hipLaunchKernelGGL(k_partial_reduce<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a);
+  }
 }
 
 void launch_gemm_tile(int dtype, GemmArgs a, int epi, hipStream_t st) {

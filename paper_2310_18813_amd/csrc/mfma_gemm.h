@@ -10,7 +10,8 @@ enum GemmEpilogue {
   EPI_QKV = 1,       // rotary on q,k; q -> buffer, k,v -> cache at the row's position
   EPI_SWIGLU = 2,    // act[m][j] = silu(gate_j) * up_j
   EPI_RELU = 3,      // act[m][n] = max(y, 0)
-  EPI_LOGITS = 4     // per-strip arg-max partials (+ optional fp32 logits dump)
+  EPI_LOGITS = 4,    // per-strip arg-max partials (+ optional fp32 logits dump)
+  EPI_PARTIAL = 5    // tiled kernel only: raw fp32 sums of one k-slice -> part[slice][m][n]
 };
 
 struct PackedDims {
@@ -29,6 +30,8 @@ struct GemmArgs {
   int passes, groups;  // filled by the launcher
   // epilogue targets (those the chosen epilogue uses)
   float *h;                  // EPI_RESIDUAL: [M][N] fp32
+  float *part;               // EPI_RESIDUAL with more than 64 rows: scratch [KS][part_rows][N] fp32, or null
+  int part_rows;             // M rounded up to 16
   void *q, *kc, *vc;         // EPI_QKV
   const int32_t *row_pos;    // EPI_QKV: absolute position per row, -1 = dead row
   const float2 *rope;        // EPI_QKV: (cos, sin) table [L][hd/2] or null

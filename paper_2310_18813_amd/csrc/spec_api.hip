@@ -109,6 +109,7 @@ static Sizes compute_sizes(const spec_model_desc *tgt, const spec_model_desc *dr
   // matrix-core path: split-KV attention partials and per-strip arg-max partials
   const size_t NC = (L + ATTN_CHUNK - 1) / ATTN_CHUNK, NTh = (V + 15) / 16;
   z.act += al256(M * d * NC * 4) + al256(M * (d / 64 + 1) * NC * 2 * 4) + 2 * al256(M * NTh * 4);
+  if (M > 64) z.act += al256(8 * Mp * d * 4);  // k-slice sums of the split residual GEMMs
   z.tgt_w = packed_bytes(*tgt, run->dtype, run->L_max);
   z.kv_area_tgt = B * (size_t)tgt->d_model * z.L_pad;
   z.tgt_kv = 2 * al256((size_t)tgt->n_layers * z.kv_area_tgt * e);
@@ -258,6 +259,7 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
     W.attn_ml = (float *)carve(p, M * (d / 64 + 1) * NC * 2 * 4);
     W.head_part = (float *)carve(p, M * NTh * 4);
     W.head_part_idx = (int32_t *)carve(p, M * NTh * 4);
+    W.gemm_part = M > 64 ? (float *)carve(p, 8 * Mp * d * 4) : nullptr;
   }
 
   rc = setup_model(c, c->tgt, tgt, tgt_w, p, z.tgt_w, z.kv_area_tgt, z.tgt_kv, z.L_pad);

@@ -80,6 +80,7 @@ struct Workspace {
   float *y32 = nullptr;     // [M_max][max(3d, 2f)] fp32 GEMM output (generic path)
   float *logits = nullptr;  // [M_max][vocab] fp32 (generic path / debug)
   float *attn_part = nullptr, *attn_ml = nullptr;  // split-KV partials (MFMA path)
+  float *gemm_part = nullptr;                      // k-slice sums of the split residual GEMMs (M_max > 64)
   float *head_part = nullptr;                      // per-strip arg-max partials (MFMA path)
   int32_t *head_part_idx = nullptr;
   int32_t *row_tok = nullptr, *row_pos = nullptr, *row_seq = nullptr;  // [M_max]
