@@ -64,6 +64,10 @@ bool fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&curso
   FastDims f = fast_dims(D);
   m.p_qkv = f.qkv; m.p_o = f.o; m.p_13 = f.w13; m.p_2 = f.w2; m.p_head = f.head;
   const bool ln = D.norm_kind == SPEC_NORM_LAYER, hb = D.has_bias != 0, swi = D.ffn_kind == SPEC_FFN_SWIGLU;
+  // RMS norm: y = W (g * h / rms) = (W diag(g)) h / rms, so the gain goes into the packed weights and the
+  // division into the GEMM's epilogue; the layer then needs no norm kernel.  (Layer norm subtracts the mean
+  // first, which does not commute with the rounding of h to fp16 as harmlessly: it keeps its kernel.)
+  m.fold_norm = !ln;
 
   m.tok_emb = takef(w->d_tok_emb, (size_t)D.vocab * d * e, cursor, st);
   m.pos_emb = D.pos_kind == SPEC_POS_LEARNED ? takef(w->d_pos_emb, (size_t)D.max_pos * d * e, cursor, st) : nullptr;
@@ -75,13 +79,14 @@ bool fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&curso
   uint32_t *amax = (uint32_t *)bumpf(cursor, n_amax * sizeof(uint32_t));
   generic_zero(amax, n_amax * sizeof(uint32_t), st);
   const bool scaled = dt == SPEC_DTYPE_BF16;
-  auto amax_of = [&](size_t word, const void *src, size_t n) -> const uint32_t * {
-    if (!scaled) return nullptr;
-    launch_absmax(dt, src, n, amax + word, st);
+  // with a folded gain the products need the scaling whatever the dtype (fp16 * fp16 may leave the range)
+  auto amax_of = [&](size_t word, const void *src, size_t n, const void *gain = nullptr) -> const uint32_t * {
+    if (!scaled && !gain) return nullptr;
+    launch_absmax(dt, src, n, (int)d, gain, amax + word, st);
     return amax + word;
   };
   void *head = bumpf(cursor, f.head.bytes(e));
-  launch_pack_weight(dt, 0, f.head, (int)d, hd, w->d_lm_head, nullptr, nullptr, head,
+  launch_pack_weight(dt, 0, f.head, (int)d, hd, w->d_lm_head, nullptr, nullptr, nullptr, head,
                      amax_of(n_amax - 1, w->d_lm_head, (size_t)D.vocab * d), st);
   m.lm_head = head;
   m.rope = nullptr;
@@ -99,26 +104,28 @@ bool fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&curso
     L.ffn_norm_b = ln ? takef(T[SPEC_T_FFN_NORM_B], d * e, cursor, st) : nullptr;
     void *p;
     const size_t a0 = 4 * (size_t)l, ff = D.d_ffn;
+    const void *g1 = m.fold_norm ? L.attn_norm_w : nullptr, *g2 = m.fold_norm ? L.ffn_norm_w : nullptr;
     p = bumpf(cursor, f.qkv.bytes(e));
-    amax_of(a0, T[SPEC_T_WQ], d * d);
-    amax_of(a0, T[SPEC_T_WK], d * d);
-    launch_pack_weight(dt, 1, f.qkv, (int)d, hd, T[SPEC_T_WQ], T[SPEC_T_WK], T[SPEC_T_WV], p,
-                       amax_of(a0, T[SPEC_T_WV], d * d), st);
+    amax_of(a0, T[SPEC_T_WQ], d * d, g1);
+    amax_of(a0, T[SPEC_T_WK], d * d, g1);
+    launch_pack_weight(dt, 1, f.qkv, (int)d, hd, T[SPEC_T_WQ], T[SPEC_T_WK], T[SPEC_T_WV], g1, p,
+                       amax_of(a0, T[SPEC_T_WV], d * d, g1), st);
     L.wqkv = p;
     p = bumpf(cursor, f.o.bytes(e));
-    launch_pack_weight(dt, 0, f.o, (int)d, hd, T[SPEC_T_WO], nullptr, nullptr, p, amax_of(a0 + 1, T[SPEC_T_WO], d * d), st);
+    launch_pack_weight(dt, 0, f.o, (int)d, hd, T[SPEC_T_WO], nullptr, nullptr, nullptr, p, amax_of(a0 + 1, T[SPEC_T_WO], d * d), st);
     L.wo = p;
     p = bumpf(cursor, f.w13.bytes(e));
     if (swi) {
-      amax_of(a0 + 2, T[SPEC_T_W1], ff * d);
-      launch_pack_weight(dt, 2, f.w13, (int)d, hd, T[SPEC_T_W1], T[SPEC_T_W3], nullptr, p,
-                         amax_of(a0 + 2, T[SPEC_T_W3], ff * d), st);
+      amax_of(a0 + 2, T[SPEC_T_W1], ff * d, g2);
+      launch_pack_weight(dt, 2, f.w13, (int)d, hd, T[SPEC_T_W1], T[SPEC_T_W3], nullptr, g2, p,
+                         amax_of(a0 + 2, T[SPEC_T_W3], ff * d, g2), st);
     } else {
-      launch_pack_weight(dt, 0, f.w13, (int)d, hd, T[SPEC_T_W1], nullptr, nullptr, p, amax_of(a0 + 2, T[SPEC_T_W1], ff * d), st);
+      launch_pack_weight(dt, 0, f.w13, (int)d, hd, T[SPEC_T_W1], nullptr, nullptr, g2, p,
+                         amax_of(a0 + 2, T[SPEC_T_W1], ff * d, g2), st);
     }
     L.w13 = p;
     p = bumpf(cursor, f.w2.bytes(e));
-    launch_pack_weight(dt, 0, f.w2, (int)d, hd, T[SPEC_T_W2], nullptr, nullptr, p, amax_of(a0 + 3, T[SPEC_T_W2], d * ff), st);
+    launch_pack_weight(dt, 0, f.w2, (int)d, hd, T[SPEC_T_W2], nullptr, nullptr, nullptr, p, amax_of(a0 + 3, T[SPEC_T_W2], d * ff), st);
     L.w2 = p;
     L.bqkv = L.bo = L.b13 = L.b2 = nullptr;
     if (hb) {
@@ -140,7 +147,7 @@ bool fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&curso
   }
   // the GEMM epilogues undo the scaling: 1 / scale per matrix, from the same words the packing read
   std::vector<uint32_t> h_amax(n_amax, 0u);
-  if (scaled) {
+  if (scaled || m.fold_norm) {
     if (hipMemcpyAsync(h_amax.data(), amax, n_amax * sizeof(uint32_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
         hipStreamSynchronize(st) != hipSuccess)
       return false;
@@ -175,10 +182,29 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int m
   void *vc = (char *)m.vcache + (size_t)layer * m.kv_area_elems * esz;
 
   const bool tgt = &m == &c->tgt;  // only the target model's kernels are timed one by one
-  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, nullptr, st); }
+  const bool fold = m.fold_norm;  // then ws.x holds fp16(h) and ws.part_ss the sums of squares, left by the producer of h
+  // up to 16 rows the consumer adds the strip sums up itself, behind its weight stream; beyond, or when a
+  // row has too many strips for its registers, a small kernel does it once per row.  Same function, same bits.
+  const bool inv_kernel = fold && (M > 16 || d / 16 > ROW_INV_INLINE_MAX_NT || m.p_qkv.KS != 8);
+  auto consume_norm = [&](GemmArgs &a) {
+    if (!fold) return;
+    a.ss_in = ws.part_ss; a.ss_nt = d / 16; a.ss_d = d; a.ss_eps = D.norm_eps;
+    if (inv_kernel) a.rinv_in = ws.row_inv;
+  };
+  auto row_inv_now = [&]() {
+    if (!inv_kernel) return;
+    KScope k(c, tgt ? SPEC_KCLASS_NORM : -1);
+    launch_row_inv(ws.part_ss, M, d / 16, d, D.norm_eps, ws.row_inv, st);
+  };
+  auto produce_norm = [&](GemmArgs &a) {
+    if (fold) { a.ss_out = ws.part_ss; a.x_out = ws.x; }
+  };
+  if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, nullptr, st); }
+  else row_inv_now();
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_QKV : -1);
     GemmArgs a = base_args(m.p_qkv, L.wqkv, L.s_qkv, L.bqkv, ws.x, M);
+    consume_norm(a);
     a.q = ws.q; a.kc = kc; a.vc = vc; a.row_pos = ws.row_pos; a.rope = m.rope;
     a.q_rows = q_rows; a.d = d; a.hd = m.hd; a.H = D.n_heads; a.L_pad = m.L_pad;
     launch_gemm_mfma(dt, a, EPI_QKV, st);
@@ -197,12 +223,15 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int m
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_O : -1);
     GemmArgs a = base_args(m.p_o, L.wo, L.s_o, L.bo, ws.attn, M);
     a.h = ws.h; a.part = ws.gemm_part; a.part_rows = (M + 15) / 16 * 16;
+    produce_norm(a);
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
   }
-  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, nullptr, st); }
+  if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, nullptr, st); }
+  else row_inv_now();
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_FFN_IN : -1);
     GemmArgs a = base_args(m.p_13, L.w13, L.s_13, L.b13, ws.x, M);
+    consume_norm(a);
     a.act = ws.act; a.f = D.d_ffn;
     launch_gemm_mfma(dt, a, D.ffn_kind == SPEC_FFN_SWIGLU ? EPI_SWIGLU : EPI_RELU, st);
   }
@@ -210,6 +239,7 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int m
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_FFN_OUT : -1);
     GemmArgs a = base_args(m.p_2, L.w2, L.s_2, L.b2, ws.act, M);
     a.h = ws.h; a.part = ws.gemm_part; a.part_rows = (M + 15) / 16 * 16;
+    produce_norm(a);
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
   }
 }

@@ -39,33 +39,36 @@ namespace spec {
 // Largest magnitude of a tensor as an fp32 bit pattern (atomic max over non-negative floats
 // ordered as integers).
 template <class T>
-__global__ void k_absmax(const T *__restrict__ s, size_t n, uint32_t *__restrict__ out) {
+__global__ void k_absmax(const T *__restrict__ s, size_t n, int K, const T *__restrict__ gain, uint32_t *__restrict__ out) {
   float m = 0.f;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
-    const float v = fabsf(Conv<T>::ld(s, i));
+    float v = fabsf(Conv<T>::ld(s, i));
+    if (gain) v *= fabsf(Conv<T>::ld(gain, i % (size_t)K));
     if (v < INFINITY) m = fmaxf(m, v);
   }
   m = wave_max(m);
   if ((threadIdx.x & 63) == 0) atomicMax(out, __float_as_uint(m));
 }
-void launch_absmax(int dtype, const void *src, size_t n, uint32_t *d_amax_bits, hipStream_t st) {
+void launch_absmax(int dtype, const void *src, size_t n, int K, const void *gain, uint32_t *d_amax_bits, hipStream_t st) {
   if (!src || n == 0) return;
   const unsigned blocks = (unsigned)std::min<size_t>((n + 255) / 256, 2048);
   if (dtype == SPEC_DTYPE_BF16)
-    hipLaunchKernelGGL(k_absmax<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t *)src, n, d_amax_bits);
+    hipLaunchKernelGGL(k_absmax<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t *)src, n, K, (const bf16_t *)gain, d_amax_bits);
   else
-    hipLaunchKernelGGL(k_absmax<f16_t>, dim3(blocks), dim3(256), 0, st, (const f16_t *)src, n, d_amax_bits);
+    hipLaunchKernelGGL(k_absmax<f16_t>, dim3(blocks), dim3(256), 0, st, (const f16_t *)src, n, K, (const f16_t *)gain, d_amax_bits);
 }
 
 // mode 0: rows of one matrix in natural order
 // mode 1: q | k | v stacked; inside every head the q and k rows are pair-interleaved
 //         (stored row 2i <- canonical i, 2i+1 <- i + hd/2) so a rotary pair is lane-local
 // mode 2: gate / up interleaved: stored rows 4p.. = gate[2p], up[2p], gate[2p+1], up[2p+1]
-// Elements are written as fp16(weight * scale), scale the matrix's power of two (1 without amax_bits).
+// Elements are written as fp16(weight * gain[k] * scale): gain the folded norm gain of column k (1 without
+// gain), scale the matrix's power of two (1 without amax_bits).  The product of two 16-bit values is exact
+// in fp32, the scaling too: one rounding per element.
 template <class T>
 __global__ void k_pack_weight(int mode, int N, int K, int N_pad, int K_pad, int d, int hd, const T *__restrict__ s0,
-                              const T *__restrict__ s1, const T *__restrict__ s2, op_t *__restrict__ dst,
-                              const uint32_t *__restrict__ amax_bits) {
+                              const T *__restrict__ s1, const T *__restrict__ s2, const T *__restrict__ gain,
+                              op_t *__restrict__ dst, const uint32_t *__restrict__ amax_bits) {
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // one thread per 8 packed elements
   const int KT = K_pad / 32;
   const size_t total = (size_t)(N_pad / 16) * KT * 64;
@@ -94,7 +97,9 @@ __global__ void k_pack_weight(int mode, int N, int K, int N_pad, int K_pad, int 
   op_t out[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i)
-    out[i] = (src && k0 + i < K) ? (op_t)(Conv<T>::ld(src, (size_t)row * K + k0 + i) * scale) : (op_t)0.f;
+    out[i] = (src && k0 + i < K)
+                 ? (op_t)(Conv<T>::ld(src, (size_t)row * K + k0 + i) * (gain ? Conv<T>::ld(gain, k0 + i) : 1.0f) * scale)
+                 : (op_t)0.f;
   op_t *o = dst + idx * 8;
 #pragma unroll
   for (int i = 0; i < 8; ++i) o[i] = out[i];
@@ -133,15 +138,15 @@ PackedDims packed_dims(int N, int K) {
 }
 
 void launch_pack_weight(int dtype, int mode, const PackedDims &p, int d, int hd, const void *s0, const void *s1,
-                        const void *s2, void *dst, const uint32_t *d_amax_bits, hipStream_t st) {
+                        const void *s2, const void *gain, void *dst, const uint32_t *d_amax_bits, hipStream_t st) {
   size_t total = (size_t)p.NT * p.KT * 64;
   unsigned blocks = (unsigned)((total + 255) / 256);
   if (dtype == SPEC_DTYPE_BF16)
     hipLaunchKernelGGL(k_pack_weight<bf16_t>, dim3(blocks), dim3(256), 0, st, mode, p.N, p.K, p.N_pad, p.K_pad, d, hd,
-                       (const bf16_t *)s0, (const bf16_t *)s1, (const bf16_t *)s2, (op_t *)dst, d_amax_bits);
+                       (const bf16_t *)s0, (const bf16_t *)s1, (const bf16_t *)s2, (const bf16_t *)gain, (op_t *)dst, d_amax_bits);
   else
     hipLaunchKernelGGL(k_pack_weight<f16_t>, dim3(blocks), dim3(256), 0, st, mode, p.N, p.K, p.N_pad, p.K_pad, d, hd,
-                       (const f16_t *)s0, (const f16_t *)s1, (const f16_t *)s2, (op_t *)dst, d_amax_bits);
+                       (const f16_t *)s0, (const f16_t *)s1, (const f16_t *)s2, (const f16_t *)gain, (op_t *)dst, d_amax_bits);
 }
 
 void launch_pack_bias(int dtype, int mode, const PackedDims &p, int d, int hd, const void *s0, const void *s1,
@@ -221,6 +226,31 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
 
+  // Folded norm without a k_row_inv launch (8 waves): wave w owns rows w, w + 8, ... of the pass.  Their
+  // strip sums are fetched now and added up after the k loop, so the round trip hides behind the weight
+  // stream.
+  constexpr bool INLINE_INV = MT == 1 && EPI != EPI_RESIDUAL;
+  constexpr int INV_LD = ROW_INV_INLINE_LOADS, INV_ROWS = 2;
+  float pre[INLINE_INV ? INV_ROWS : 1][INLINE_INV ? INV_LD : 1];
+  const bool inline_inv = INLINE_INV && a.ss_in && !a.rinv_in;
+  float rv[MT];  // 1 / rms of this lane's rows when k_row_inv left them: fetched now, used in the epilogue
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int m = m_base + mt * 16 + c;
+    rv[mt] = (EPI != EPI_RESIDUAL && a.ss_in && a.rinv_in && m < a.M) ? a.rinv_in[m] : 1.0f;
+  }
+  if (INLINE_INV && inline_inv) {
+#pragma unroll
+    for (int r = 0; r < INV_ROWS; ++r) {
+      const int m = m_base + w + 8 * r;
+#pragma unroll
+      for (int i = 0; i < INV_LD; ++i) {
+        const int idx = lane + 64 * i;
+        pre[r][i] = (m < a.M && idx < a.ss_nt) ? a.ss_in[(size_t)m * a.ss_nt + idx] : 0.f;
+      }
+    }
+  }
+
   constexpr int U = (NB + MT >= 12) ? 1 : (NB + MT >= 6) ? 2 : (NB + MT >= 3) ? 4 : 8;
   int kt = kt0;
   for (; kt + U <= kt1; kt += U) {
@@ -252,10 +282,28 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
   }
 
   constexpr int TILES = NB * MT;
+  // folded norm: 1 / rms of the pass's rows, one wave per row
+  __shared__ float rinv_s[16];
+  if (INLINE_INV && inline_inv) {
+#pragma unroll
+    for (int r = 0; r < INV_ROWS; ++r) {
+      float s = 0.f;   // ascending strips, as row_inv_rms adds them (absent strips add zeros at the end)
+#pragma unroll
+      for (int i = 0; i < INV_LD; ++i) s += pre[r][i];
+      const float v = row_inv_finish(s, a.ss_d, a.ss_eps);
+      if (lane == 0) rinv_s[w + 8 * r] = v;
+    }
+    __syncthreads();
+  }
+  auto rinv_of = [&](int mt) {
+    if (EPI == EPI_RESIDUAL || !a.ss_in) return 1.0f;
+    if (a.rinv_in) return rv[mt];
+    return INLINE_INV ? rinv_s[c] : 1.0f;
+  };
   if (KS == 1) {
 #pragma unroll
     for (int t = 0; t < TILES; ++t)
-      tile_epilogue<T, EPI>(a, acc[t / MT][t % MT], nt0 + t / MT, m_base + (t % MT) * 16 + c, g);
+      tile_epilogue<T, EPI>(a, acc[t / MT][t % MT], nt0 + t / MT, m_base + (t % MT) * 16 + c, g, rinv_of(t % MT));
     return;
   }
   constexpr int ROUNDS = (TILES + 7) / 8;
@@ -279,7 +327,7 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
         f32x4_v p = *(const f32x4_v *)&red[((size_t)(s * SLOTS + slot) * 64 + lane) * 4];
         v[0] += p[0]; v[1] += p[1]; v[2] += p[2]; v[3] += p[3];
       }
-      tile_epilogue<T, EPI>(a, v, nt0 + t / MT, m_base + (t % MT) * 16 + c, g);
+      tile_epilogue<T, EPI>(a, v, nt0 + t / MT, m_base + (t % MT) * 16 + c, g, rinv_of(t % MT));
     }
   }
 }

@@ -86,6 +86,15 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
       tot[nb][mt] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
     }
 
+  // folded norm: 1 / rms of this lane's rows (from k_row_inv), fetched now, used in the epilogue
+  const bool folded = !PARTIAL && EPI != EPI_RESIDUAL && a.rinv_in;
+  float rv[MTW];
+#pragma unroll
+  for (int mt = 0; mt < MTW; ++mt) {
+    const int m = (mtile0 + wm * MTW + mt) * 16 + c;
+    rv[mt] = (folded && m < a.M) ? a.rinv_in[m] : 1.0f;
+  }
+
   u32x4_v r0[LPW], r1[LPW], r2[LPW];  // three steps on their way from global memory
   auto fetch = [&](u32x4_v (&r)[LPW], int kt) {
 #pragma unroll
@@ -202,6 +211,7 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
 #undef SPEC_TILE_STEP
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the over-fetched tail before the epilogue
 
+
 #pragma unroll
   for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
@@ -212,7 +222,8 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
         if (nt < a.NT && m < a.M && n < a.N)
           *(f32x4_v *)(a.part + ((size_t)slice_id * a.part_rows + m) * a.N + n) = tot[nb][mt];
       } else {
-        tile_epilogue<T, EPI == EPI_PARTIAL ? EPI_RESIDUAL : EPI>(a, tot[nb][mt], nt, m, g);
+        tile_epilogue<T, EPI == EPI_PARTIAL ? EPI_RESIDUAL : EPI>(a, tot[nb][mt], nt, m, g,
+                                                                 rv[mt]);
       }
     }
 }
@@ -232,9 +243,22 @@ __global__ __launch_bounds__(256) void k_partial_reduce(GemmArgs a) {
     const f32x4_v q = *(const f32x4_v *)(p + s * stride);
     v[0] += q[0]; v[1] += q[1]; v[2] += q[2]; v[3] += q[3];
   }
-  tile_epilogue<T, EPI_RESIDUAL>(a, v, n >> 4, m, (n & 15) >> 2);
+  tile_epilogue<T, EPI_RESIDUAL, 1>(a, v, n >> 4, m, (n & 15) >> 2);
 }
 
+
+// 1 / rms of every row from the strip sums (folded norm, more than 16 rows): one wave per row.
+__global__ __launch_bounds__(256) void k_row_inv(const float *__restrict__ ss, int M, int nt, int d, float eps,
+                                                 float *__restrict__ rinv) {
+  const int m = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (m >= M) return;
+  const float v = row_inv_rms(ss + (size_t)m * nt, nt, d, eps, lane);
+  if (lane == 0) rinv[m] = v;
+}
+void launch_row_inv(const float *ss, int M, int nt, int d, float eps, float *rinv, hipStream_t st) {
+  if (M <= 0) return;
+  hipLaunchKernelGGL(k_row_inv, dim3((M + 3) / 4), dim3(256), 0, st, ss, M, nt, d, eps, rinv);
+}
 
 template <class T, int MTW, int NBW, int EPI>
 static void launch_one(const GemmArgs &a, int blocks, hipStream_t st) {

@@ -136,6 +136,33 @@ __global__ __launch_bounds__(256) void k_norm(int kind, int d, float eps, const 
   }
 }
 
+// Folded-norm models, in front of the first layer: the fp16 copy of the embedded rows in fragment order and
+// their per-strip sums of squares, exactly as the residual epilogues leave them behind every later GEMM
+// (four consecutive elements per thread, chain of fused multiply-adds, the strip's four groups added as
+// (g0 + g1) + (g2 + g3)).
+__global__ __launch_bounds__(256) void k_row_prep(int d, const float *__restrict__ h, op_t *__restrict__ x,
+                                                  float *__restrict__ ss) {
+  const int r = blockIdx.x, nv = d >> 2;
+  const float4 *hr = (const float4 *)(h + (size_t)r * d);
+  for (int c0 = 0; c0 < nv; c0 += 256) {   // nv is a multiple of 4: a group of four threads is in or out together
+    const int c = c0 + threadIdx.x;
+    if (c < nv) {
+      const float4 o = hr[c];
+      op_t o4[4] = {to_op(o.x), to_op(o.y), to_op(o.z), to_op(o.w)};
+      *(uint2 *)(x + xpack_index(r, 4 * c, d >> 5)) = *(const uint2 *)o4;
+      float p = o.x * o.x;
+      p = fmaf(o.y, o.y, p); p = fmaf(o.z, o.z, p); p = fmaf(o.w, o.w, p);
+      p += __shfl_xor(p, 1, 64);
+      p += __shfl_xor(p, 2, 64);
+      if ((c & 3) == 0) ss[(size_t)r * (d >> 4) + (c >> 2)] = p;
+    }
+  }
+}
+void launch_row_prep(const spec_ctx *c, const Model &m, int M, hipStream_t st) {
+  if (M <= 0) return;
+  hipLaunchKernelGGL(k_row_prep, dim3(M), dim3(256), 0, st, m.desc.d_model, c->ws.h, (op_t *)c->ws.x, c->ws.part_ss);
+}
+
 void launch_norm(const spec_ctx *c, const Model &m, const float *h, const void *gain, const void *bias, void *x,
                  int M, const int32_t *row_gather, hipStream_t st) {
   if (M <= 0) return;

@@ -23,14 +23,30 @@ struct Mfma16 {
   }
 };
 
+// 1 / rms of a row of h from its per-strip partial sums of squares; called by a whole wave per row
+// (lanes take strips lane, lane + 64, ... in ascending order, then the fixed butterfly), so every kernel
+// that needs the value computes the same bits.
+__device__ __forceinline__ float row_inv_finish(float s, int d, float eps) {
+  s = wave_sum(s);
+  return 1.0f / sqrtf(s / (float)d + eps);
+}
+__device__ __forceinline__ float row_inv_rms(const float *__restrict__ ss, int nt, int d, float eps, int lane) {
+  float s = 0.f;
+  for (int i = lane; i < nt; i += 64) s += ss[i];
+  return row_inv_finish(s, d, eps);
+}
+
 // ------------------------------------------------------------------------- epilogues
 // One finished 16x16 tile: this lane holds stored rows n .. n+3 (n = 16*nt + 4g) of
 // activation row m.  The element-wise work of the layer happens here, on fp32 sums.
-template <class T, int EPI>
-__device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int nt, int m, int g) {
+// rinv: 1 / rms of row m when the norm in front of this GEMM is folded into it, else 1.  GS: lane distance
+// between the four lanes that hold one strip of a row (16 in the GEMM kernels, 1 in the reduction kernel).
+template <class T, int EPI, int GS = 16>
+__device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int nt, int m, int g, float rinv = 1.0f) {
   if (nt >= a.NT) return;
   const int n = nt * 16 + 4 * g;
   v[0] *= a.out_scale; v[1] *= a.out_scale; v[2] *= a.out_scale; v[3] *= a.out_scale;  // exact: a power of two
+  if (EPI != EPI_RESIDUAL) { v[0] *= rinv; v[1] *= rinv; v[2] *= rinv; v[3] *= rinv; }
   if (a.bias) {
     const float4 b4 = *(const float4 *)(a.bias + n);
     v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
@@ -38,11 +54,23 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int 
   const bool live = m < a.M;
 
   if (EPI == EPI_RESIDUAL) {
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
     if (live && n < a.N) {
       float4 *p = (float4 *)(a.h + (size_t)m * a.N + n);
-      float4 o = *p;
+      o = *p;
       o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
       *p = o;
+      if (a.x_out) {  // the next GEMM's activations: the updated row, rounded to fp16
+        op_t o4[4] = {to_op(o.x), to_op(o.y), to_op(o.z), to_op(o.w)};
+        *(uint2 *)((op_t *)a.x_out + xpack_index(m, n, a.N >> 5)) = *(const uint2 *)o4;
+      }
+    }
+    if (a.ss_out) {  // sum of squares of the strip's 16 elements of the row, in a fixed order
+      float p = o.x * o.x;
+      p = fmaf(o.y, o.y, p); p = fmaf(o.z, o.z, p); p = fmaf(o.w, o.w, p);
+      p += __shfl_xor(p, GS, 64);
+      p += __shfl_xor(p, 2 * GS, 64);
+      if (live && g == 0) a.ss_out[(size_t)m * a.NT + nt] = p;
     }
   } else if (EPI == EPI_QKV) {
     if (live && n < a.N) {

@@ -51,6 +51,7 @@ struct Model {
   spec_model_desc desc{};
   int hd = 0, L_pad = 0;
   bool fast = false;  // MFMA kernels (16-bit dtypes with supported shapes) or generic kernels
+  bool fold_norm = false;  // MFMA path, RMS norm: the layer norms live inside the GEMMs around them
   const void *tok_emb = nullptr, *pos_emb = nullptr, *final_norm_w = nullptr, *final_norm_b = nullptr,
              *lm_head = nullptr;
   std::vector<LayerW> layers;
@@ -80,6 +81,8 @@ struct Workspace {
   float *y32 = nullptr;     // [M_max][max(3d, 2f)] fp32 GEMM output (generic path)
   float *logits = nullptr;  // [M_max][vocab] fp32 (generic path / debug)
   float *attn_part = nullptr, *attn_ml = nullptr;  // split-KV partials (MFMA path)
+  float *part_ss = nullptr;                        // [M_max][d/16] per-strip sums of squares of h (folded norm)
+  float *row_inv = nullptr;                        // [M_max] 1 / rms of the rows of h (folded norm, more than 16 rows)
   float *gemm_part = nullptr;                      // k-slice sums of the split residual GEMMs (M_max > 64)
   float *head_part = nullptr;                      // per-strip arg-max partials (MFMA path)
   int32_t *head_part_idx = nullptr;
@@ -168,6 +171,7 @@ struct PassArgs {
 void launch_assemble_embed(const spec_ctx *c, const Model &m, const PassArgs &pa, hipStream_t st);
 void launch_norm(const spec_ctx *c, const Model &m, const float *h, const void *gain, const void *bias, void *x,
                  int M, const int32_t *row_gather, hipStream_t st);
+void launch_row_prep(const spec_ctx *c, const Model &m, int M, hipStream_t st);
 void launch_argmax_rows(const float *logits, int M, int V, int q, int out_stride, int32_t *out, hipStream_t st);
 void launch_accept(spec_ctx *c, int s, hipStream_t st);
 void launch_fill_proposals(spec_ctx *c, int s, hipStream_t st);
