@@ -23,7 +23,7 @@ MFMA_BF16_PEAK = 2.5e15  # flop/s dense bf16, MI355X published
 
 # HBM bytes per launch from the committed rocprofv3 counter passes (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00,
 # calibrated on a copy of known size in the same run): {(kernel class, rows M): bytes}.  Other cells: null.
-PMC_TRAFFIC = {("gemm_ffn_in", 1): 181.4e6 + 0.09e6, ("gemm_ffn_in", 256): 431.4e6 + 11.3e6}
+PMC_TRAFFIC = {("gemm_ffn_in", 1): 181.0e6 + 0.04e6, ("gemm_ffn_in", 256): 197.4e6 + 5.6e6}
 
 
 def to_device(w, dev):
