@@ -50,6 +50,11 @@ enum {
   SPEC_ERR_HIP = 6          /* a HIP runtime call failed                              */
 };
 
+/* Storage type of the weights handed in and of the KV cache.  Arithmetic: fp32 runs on plain fp32 ALU
+   kernels; the 16-bit types run their GEMMs on the matrix cores with fp16 operands and fp32 sums (bf16
+   weights are held as fp16 times a power of two per matrix, which is exact for all but vanishing
+   elements; activations are rounded from fp32 to fp16 and saturate at +-65504), attention on the
+   matrix cores in the storage type; residual stream, norms and softmax in fp32.                       */
 enum { SPEC_DTYPE_F32 = 0, SPEC_DTYPE_BF16 = 1, SPEC_DTYPE_F16 = 2 };
 enum { SPEC_FFN_SWIGLU = 0, SPEC_FFN_RELU = 1 };
 enum { SPEC_NORM_RMS = 0, SPEC_NORM_LAYER = 1 };
