@@ -350,7 +350,10 @@ static void launch_gemm_t(GemmArgs a, int epi, hipStream_t st) {
   // residual GEMMs run it one k-slice per workgroup when the context has the scratch for the slices
   // (worth the second kernel from about 32 steps per slice, or from 5 row passes of the streaming kernel)
   const bool split_ok = a.part && a.KS > 1 && (a.N & 3) == 0 && (a.KT / a.KS >= 32 || a.M > 256);
-  if (a.M > 64 && a.NT >= 64 && (epi != EPI_RESIDUAL || split_ok)) {
+  // the widest outputs (gate-up, LM head) already gain from 33 rows on: the streaming kernel's waves each fetch
+  // their own copy of the activations, the tiled kernel shares them through LDS
+  const int tile_min_m = a.NT >= 1024 ? 33 : 65;
+  if (a.M >= tile_min_m && a.NT >= 64 && (epi != EPI_RESIDUAL || (split_ok && a.M > 64))) {
     launch_gemm_tile(std::is_same<T, bf16_t>::value ? SPEC_DTYPE_BF16 : SPEC_DTYPE_F16, a, epi, st);
     return;
   }

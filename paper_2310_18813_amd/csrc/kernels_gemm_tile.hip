@@ -301,11 +301,11 @@ static void choose_tile(int M, int NT, int n_cu, int steps, int wg_mult, int &MT
     force_mt = 0;
     const char *e = getenv("SPEC_GEMM_TILE");
     int mt = 0, nb = 0;
-    if (e && sscanf(e, "%d,%d", &mt, &nb) == 2 && mt >= 2 && mt <= 4 && nb >= 2 && nb <= 4) { force_mt = mt; force_nb = nb; }
+    if (e && sscanf(e, "%d,%d", &mt, &nb) == 2 && mt >= 1 && mt <= 4 && nb >= 2 && nb <= 4) { force_mt = mt; force_nb = nb; }
   }
   if (force_mt > 0) { MTW = force_mt; NBW = force_nb; return; }
   long best = -1;
-  for (int mt = 2; mt <= 4; ++mt)
+  for (int mt = 1; mt <= 4; ++mt)
     for (int nb = 2; nb <= 4; ++nb) {
       const int passes = (M + 64 * mt - 1) / (64 * mt);
       const int wgs = passes * ((NT + 2 * nb - 1) / (2 * nb)) * wg_mult;
@@ -333,7 +333,8 @@ static void launch_tile_t(GemmArgs a, int epi, hipStream_t st) {
   a.groups = (a.NT + 2 * NBW - 1) / (2 * NBW);
   const int blocks = split ? ((a.groups + 7) / 8) * 8 * a.passes * a.KS
                            : a.passes == 1 ? a.groups : ((a.groups + 7) / 8) * 8 * a.passes;
-  if (MTW == 2) launch_nb_tile<T, 2>(a, NBW, epi, blocks, st);
+  if (MTW == 1) launch_nb_tile<T, 1>(a, NBW, epi, blocks, st);
+  else if (MTW == 2) launch_nb_tile<T, 2>(a, NBW, epi, blocks, st);
   else if (MTW == 3) launch_nb_tile<T, 3>(a, NBW, epi, blocks, st);
   else launch_nb_tile<T, 4>(a, NBW, epi, blocks, st);
   if (split) {

@@ -12,7 +12,7 @@ from helpers import LOGIT_TOL, top2_margin
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 KV_LEN = 512
-CELLS = [(1, 0), (2, 4), (8, 8), (33, 1), (64, 8)]   # M = 1, 10, 72, 66, 576
+CELLS = [(1, 0), (2, 4), (16, 2), (8, 8), (33, 1), (64, 8)]   # M = 1, 10, 48, 72, 66, 576
 
 
 @pytest.fixture(scope="module")
@@ -97,7 +97,7 @@ def test_rows_are_bit_identical_across_batch_and_speculation_length(world):
     this is what makes speculative output equal non-speculative output token for token."""
     wd = world
     base, _, _, _ = gpu_cell(wd, 1, 0)          # M = 1, split-KV attention
-    for nB, s in [(1, 8), (3, 2), (16, 1), (32, 0), (64, 0), (64, 8)]:
+    for nB, s in [(1, 8), (3, 2), (16, 1), (12, 3), (32, 0), (64, 0), (64, 8)]:   # M = 9 .. 576: every GEMM kernel and tile shape
         lg, _, _, _ = gpu_cell(wd, nB, s)
         assert torch.equal(lg[0, 0], base[0, 0]), (nB, s)
     a8, _, _, _ = gpu_cell(wd, 8, 8)
