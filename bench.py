@@ -186,6 +186,7 @@ def main():
         curve[str(b)] = entry
 
     vgrid = None if args.no_grid else verify_grid(ctx, torch, prompts, tdesc, P, B_list)
+    model = None if vgrid is None else model_fit_object(ctx, prompts, B_list, vgrid, alpha, lut)
 
     cpu = None
     if host_w is not None:
@@ -206,6 +207,7 @@ def main():
         "lut": {str(b): s for b, s in zip(B_list, lut)},
         "curve": curve,
         "verify_grid": vgrid,
+        "model": model,
         "setup_s": round(t_setup, 1),
     }
     print(json.dumps(line))
@@ -238,6 +240,35 @@ def verify_grid(ctx, torch, prompts, desc, P, B_list, s_list=(0, 1, 2, 4, 8), it
             out["%d,%d" % (nB, s)] = {"us": round(us, 1), "hbm_frac": round(nbytes / HBM_PEAK / (us * 1e-6), 3),
                                       "mfma_frac": round(flops / MFMA_BF16_PEAK / (us * 1e-6), 3)}
     return out
+
+
+def model_fit_object(ctx, prompts, B_list, vgrid, alpha, lut):
+    """The runtime model of Sec. 3.2 fitted to this run: t_L(B, s) ~ alpha_B s + beta from the verify grid, one
+    draft step t_S(B, 1) from the draft passes of a few rounds, l(s) from the workload's acceptance probability
+    (Eq. 6 under independence) fitted by c s^gamma (Eq. 5); the root of Eq. 11 next to the measured arg-min and
+    the profiled table."""
+    from paper_2310_18813_amd import model_fit as mf
+    s_list = sorted({int(k.split(",")[1]) for k in vgrid})
+    t_L = [[vgrid["%d,%d" % (b, s)]["us"] for s in s_list] for b in B_list]
+    t_S = []
+    for b in B_list:
+        ctx.spec_reset_noprefill(prompts[:b])
+        ctx.spec_round(2, 1)
+        ctx.spec_kernel_timing(True)
+        ctx.spec_read_kernel_timing()
+        ctx.spec_round(2, 3)
+        cnt, ms = ctx.spec_read_kernel_timing()["draft_pass"]
+        ctx.spec_kernel_timing(False)
+        t_S.append(ms * 1000.0 / max(cnt, 1))
+    l_of_s = [mf.l_iid(alpha, s) for s in range(max(s_list) + 1)]
+    res = mf.explain(B_list, s_list, t_L, t_S, l_of_s)
+    for row, ts, s_lut in zip(res["rows"], t_S, lut):
+        row["t_S_us"] = round(ts, 1)
+        row["s_lut"] = int(s_lut)
+        for k in ("alpha_b", "alpha_b_with_draft", "beta", "s_opt_model"):
+            row[k] = round(row[k], 2)
+    res["c"], res["gamma"] = round(res["c"], 3), round(res["gamma"], 3)
+    return res
 
 
 def cpu_baseline(si, tdesc, ddesc, host_w, ctx, dtype, seed):
