@@ -1,16 +1,20 @@
-// GEMM for more than 64 activation rows and wide outputs (QKV, gate-up / fc1, LM head).
+// GEMM for more than 64 activation rows (gate-up / fc1 and the LM head: from 33 rows on).
 //
 // The streaming kernel covers 64 rows per pass and re-streams the weights for every pass.
 // Here one workgroup holds up to 256 rows of a group of weight strips, so a weight byte is
-// fetched once per 256 rows, and both operands reach the waves through LDS:
+// fetched once per up to 256 rows, and both operands reach the waves through LDS:
 //
 //   workgroup = 8 waves = 2 (strip halves) x 4 (row quarters); wave tile = NBW strips x MTW
 //   16-row tiles; workgroup tile = 2*NBW strips x 4*MTW row tiles.
 //   Per 32-k step the workgroup needs 2*NBW weight fragments and 4*MTW activation
-//   fragments of 1 KB each.  Weights and activations are both stored in
-//   fragment order in global memory, so a fragment is one 16-byte load per lane, issued two
-//   steps ahead, parked in registers and written to the LDS stage that is not being read; the
-//   waves then read their fragments back with one 16-byte LDS load per lane, conflict-free.
+//   fragments of 1 KB each.  Weights and activations are both stored in fragment order in
+//   global memory, so a fragment is one 16-byte load per lane, issued three steps ahead, parked
+//   in registers and written to the LDS stage nobody reads; the waves then read their fragments
+//   back with one 16-byte LDS load per lane, conflict-free.
+//
+// Wide outputs (QKV, gate-up / fc1, LM head) walk all of k in one workgroup.  Narrow outputs (the
+// residual GEMMs, N = d_model) would leave most CUs idle that way: there each workgroup takes
+// one k-slice of its tile (EPI_PARTIAL) and k_partial_reduce adds the slices in slice order.
 //
 // Results are bit-identical to the streaming kernel: the same instruction, every k-slice a
 // chain of MFMAs from zero in ascending k, the slices added in order, the same epilogue code.
