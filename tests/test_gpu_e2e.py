@@ -22,6 +22,9 @@ CASES = {
     # fp16 OPT shape: LayerNorm, biases, ReLU, learned positions
     "small_fp16_opt": dict(dtype="fp16", seed=78, B=2, P=5, N=18, s=5, alpha=0.6,
                            tgt=si.opt_desc(2, 256, 4, 384, 777, 64), drf=si.opt_desc(1, 128, 2, 192, 777, 64)),
+    # fp16 LLaMA shape: the RMS norm folded into fp16 weights (gain * weight needs the per-matrix scaling too)
+    "small_fp16_llama": dict(dtype="fp16", seed=81, B=2, P=7, N=16, s=4, alpha=0.7,
+                             tgt=si.llama_desc(2, 256, 4, 448, 900, 64), drf=si.llama_desc(1, 128, 2, 160, 900, 64)),
     # wider bf16 model: 8 k-slices, two row passes (M = 96), two strips per workgroup in the LM head
     "medium_bf16": dict(dtype="bf16", seed=79, B=24, P=12, N=12, s=3, alpha=0.7,
                         tgt=si.llama_desc(1, 512, 4, 1536, 20000, 64), drf=si.llama_desc(1, 256, 4, 512, 20000, 64)),
