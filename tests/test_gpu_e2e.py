@@ -207,6 +207,39 @@ def test_draft_model_proposals(orc, B, name):
     assert out == base
 
 
+def test_maximum_speculation_length_and_exact_capacity(orc, B):
+    """The largest s the library takes (15: 16 rows per sequence in one pass), a workspace sized to the last
+    position (L_max = P + gen_max + s_max exactly), every slot of the batch used, rounds that overshoot
+    gen_max: output is still the plain greedy output, for perfect, useless and mixed proposals."""
+    c = CASES["small_bf16"]
+    ot, od, gt, gd = build_pair(orc, c["tgt"], c["drf"], c["dtype"], c["seed"], DEV, random_norms=True)
+    nB, P, N, s_max = 3, 9, 21, 15
+    L_max = P + N + s_max
+    ctx = B.Context(c["tgt"], gt, c["drf"], gd, c["dtype"], nB, s_max, L_max, N, B.PROPOSALS_EXTERNAL, DEV)
+    prompts = si.make_prompts(nB, P, c["tgt"]["vocab"], c["seed"])
+    ctx.spec_reset(prompts)
+    ctx.spec_round(0, N)
+    base, _ = ctx.spec_read_output()
+    assert all(len(x) == N for x in base)
+    truth = np.zeros((nB, L_max), dtype=np.int32)
+    for b in range(nB):
+        truth[b, P:P + N] = base[b]
+    for alpha in (1.0, 0.0, 0.8):
+        table = (truth + 1) % c["tgt"]["vocab"] if alpha == 0.0 else si.make_proposal_table(truth, alpha, c["tgt"]["vocab"], 9)
+        ctx.spec_set_proposal_table(table)
+        ctx.spec_rewind()
+        ctx.spec_round(s_max, N)                    # far more rounds than needed: finished sequences stay frozen
+        out, hist = ctx.spec_read_output()
+        assert out == base, alpha
+        n, _, _, _ = ctx.spec_read_state()
+        assert list(n) == [P + N] * nB
+        if alpha == 1.0:                            # 16 tokens in the first round, the remaining 5 in the second
+            assert hist[s_max] >= nB
+    with pytest.raises(B.SpecError):
+        ctx.spec_round(s_max + 1, 1)
+    ctx.close()
+
+
 def test_kv_import_export_roundtrip(orc, B):
     c, ot, od, ctx, prompts, L_max = setup_case(orc, B, "small_bf16")
     d = c["tgt"]["d_model"]
