@@ -196,7 +196,7 @@ def main():
         "metric": "accepted tokens/s at adaptive s", "value": value, "unit": "tokens/s", "n_gpus": 1,
         "steps": K, "warmup": W, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": dtype, "data": "synthetic",
-        "config": {"workload": "%s: %d-layer d=%d target + %d-layer d=%d draft (BASELINE configs), B=%d, prompt %d, "
+        "config": {"workload": "%s: %d-layer d=%d target + %d-layer d=%d draft, random init, B=%d, prompt %d, "
                                "acceptance prob %.1f, s=adaptive" % (args.workload, tdesc["n_layers"], tdesc["d_model"],
                                                                        ddesc["n_layers"], ddesc["d_model"], nB, P, alpha),
                    "batch": nB, "s_star": s_star, "rows_per_verify": M, "accepted_hist": hist,

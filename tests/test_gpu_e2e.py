@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 CASES = {
-    # BASELINE config 1: fp32 pair, B=1, s=4, P=16, N=32, replacement probability 0.3
+    # the smallest named configuration: fp32 pair, B=1, s=4, P=16, N=32, replacement probability 0.3
     "tiny_fp32": dict(dtype="fp32", seed=1000, B=1, P=16, N=32, s=4, alpha=0.7,
                       tgt=si.CONFIGS["tiny_fp32"][2], drf=si.CONFIGS["tiny_fp32"][3]),
     # bf16 LLaMA shape, head_dim 64 and 128 mixed between target and draft, ragged vocab
