@@ -123,14 +123,24 @@ def test_llama7b_every_layer_matches_oracle_at_full_depth():
     tdesc = dict(tdesc, max_pos=L_max)
     d, V, nl = tdesc["d_model"], tdesc["vocab"], tdesc["n_layers"]
     w = si.make_weights(tdesc, dtype, seed, device=DEV, tag="tgt.")
-    ctx = B.Context(tdesc, w, None, None, dtype, nB, s, L_max, 8, B.PROPOSALS_EXTERNAL, DEV)
-    prompts = si.make_prompts(nB, P, V, seed)
-    props = si.make_prompts(nB, s, V, seed + 9)
+    B_big = 64                                  # the batch size the benchmark times
+    ctx = B.Context(tdesc, w, None, None, dtype, B_big, s, L_max, 8, B.PROPOSALS_EXTERNAL, DEV)
+    prompts_big = si.make_prompts(B_big, P, V, seed)
+    props_big = si.make_prompts(B_big, s, V, seed + 9)
+    prompts, props = prompts_big[:nB], props_big[:nB]
     ctx.spec_reset(prompts)
     ctx.spec_set_proposals(torch.tensor(props))
     dump = ctx.spec_set_hidden_dump(True)
     lg = ctx.spec_verify_step(s, want_logits=True).cpu().numpy()
     ctx.spec_set_hidden_dump(False)
+    # the same two sequences inside the benchmark's launch configuration (64 sequences, 320 rows: tiled and split
+    # GEMMs, one wave per (sequence, head) attention): their logits must be the very same bits, which carries the
+    # layer-by-layer comparison below over to that configuration
+    ctx.spec_reset(prompts_big)
+    ctx.spec_set_proposals(torch.tensor(props_big))
+    lg_big = ctx.spec_verify_step(s, want_logits=True)
+    assert torch.equal(lg_big[:nB].cpu(), torch.from_numpy(lg)), "rows depend on the batch they run in"
+    del lg_big
     q, M = s + 1, nB * (s + 1)
     hidden = dump[:(nl + 1) * M * d].view(nl + 1, M, d).cpu().numpy().astype(np.float64)
     tol = LOGIT_TOL["bf16"]
