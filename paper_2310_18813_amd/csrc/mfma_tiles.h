@@ -74,8 +74,17 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int 
     }
   } else if (EPI == EPI_QKV) {
     if (live && n < a.N) {
-      const int region = n / a.d, cc = n % a.d, hh = cc / a.hd, e = cc % a.hd;
-      const int pos = a.row_pos[m], b = m / a.q_rows;
+      // No per-lane integer division (it would be most of this epilogue).  A strip of 16 stored rows lies
+      // inside one head of one of q, k, v (d and hd are multiples of 16), and the strip number is the same for
+      // the whole wave: its place is scalar arithmetic.  The row's sequence m / q_rows comes from a float
+      // product, made exact by one step either way.
+      const int base = __builtin_amdgcn_readfirstlane(nt) * 16;
+      const int region = base / a.d, cc0 = base - region * a.d, hh = cc0 / a.hd;
+      const int cc = cc0 + 4 * g, e = cc - hh * a.hd;
+      const int pos = a.row_pos[m];
+      int b = (int)(((float)m + 0.5f) * (1.0f / (float)a.q_rows));
+      b += ((b + 1) * a.q_rows <= m) ? 1 : 0;
+      b -= (b * a.q_rows > m) ? 1 : 0;
       if (region < 2) {
         float r0 = v[0], r1 = v[1], r2 = v[2], r3 = v[3];
         if (a.rope && pos >= 0) {
