@@ -27,8 +27,9 @@ namespace spec {
 #pragma clang fp contract(off)
 
 // Three LDS stages of fragments.  Global loads run three steps ahead of the LDS writes through
-// three register sets (global -> VGPR -> LDS; the direct global->LDS path was measured at about
-// 18 bytes per clock and CU on this part, a third of what the ordinary load path sustains).
+// three register sets (global -> VGPR -> LDS; direct global->LDS loads into deeper rings of stages run at
+// the same rate on this part and were measured no faster for this loop: the operand stream itself, weights
+// from HBM mixed with activations from L2 through one CU's vector L1, is what bounds it).
 // The waves read their fragments of step k+1 into a second set of fragment registers before they
 // issue the MFMAs of step k, so the LDS pipe, the global loads and the matrix pipe of a SIMD work at
 // the same time, with one barrier per step.
