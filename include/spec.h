@@ -143,6 +143,15 @@ int spec_reset(spec_ctx *ctx, int32_t B, const int32_t *d_prompt, int32_t P);
    given cache.                                                                        */
 int spec_reset_noprefill(spec_ctx *ctx, int32_t B, const int32_t *d_prompt, int32_t P);
 
+/* Continuous batching (beyond the paper, which decodes fixed batches): batch slot b, 0 <= b < B, starts
+   over with the P prompt tokens d_prompt[0..P-1] (int32, device; P as given to the last spec_reset).  The
+   slot's emitted tokens are dropped (read them with spec_read_output first), its prompt is run through both
+   models in a single-sequence pass, and from the next round on it decodes beside the others, whose state and
+   results do not change.  Not allowed between a round's first draft or verify step and its
+   spec_accept_commit (SPEC_ERR_STATE).  With an external proposal table the caller updates row b of the
+   table it owns.  Counters and the accepted-length histogram keep running for the whole batch.           */
+int spec_admit(spec_ctx *ctx, int32_t b, const int32_t *d_prompt);
+
 /* Back to the state right after the last reset (lengths, counters, emitted tokens);
    cached prompt KV is kept.                                                           */
 int spec_rewind(spec_ctx *ctx);

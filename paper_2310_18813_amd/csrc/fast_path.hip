@@ -172,14 +172,16 @@ static GemmArgs base_args(const PackedDims &p, const void *W, float inv_scale, c
 
 // One pre-norm decoder layer over the M rows of the pass; max_pos is an upper bound of the
 // largest row position (sizes the attention grid; chunks past a sequence's end exit at once).
-void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int max_pos, hipStream_t st) {
+void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b0, int max_pos, hipStream_t st) {
   const spec_model_desc &D = m.desc;
   const int dt = c->run.dtype, M = B * q_rows, d = D.d_model;
   const LayerW &L = m.layers[layer];
   Workspace &ws = c->ws;
   const size_t esz = dtype_bytes(dt);
-  void *kc = (char *)m.kcache + (size_t)layer * m.kv_area_elems * esz;
-  void *vc = (char *)m.vcache + (size_t)layer * m.kv_area_elems * esz;
+  // the layer's cache area, from batch slot b0 on (a sequence owns H * L_pad * hd elements of each)
+  const size_t slot0 = (size_t)b0 * D.n_heads * m.L_pad * m.hd;
+  void *kc = (char *)m.kcache + ((size_t)layer * m.kv_area_elems + slot0) * esz;
+  void *vc = (char *)m.vcache + ((size_t)layer * m.kv_area_elems + slot0) * esz;
 
   const bool tgt = &m == &c->tgt;  // only the target model's kernels are timed one by one
   const bool fold = m.fold_norm;  // then ws.x holds fp16(h) and ws.part_ss the sums of squares, left by the producer of h

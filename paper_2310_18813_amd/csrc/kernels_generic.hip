@@ -283,14 +283,15 @@ void generic_repack_layer(spec_ctx *c, Model &m, int layer, const spec_weights *
 // -------------------------------------------------------------------------
 // One decoder layer over the M rows of the pass (pre-norm residual block).
 template <class T>
-static void generic_layer_t(spec_ctx *c, const Model &m, int layer, int M, int q_rows, hipStream_t st) {
+static void generic_layer_t(spec_ctx *c, const Model &m, int layer, int M, int q_rows, int b0, hipStream_t st) {
   const spec_model_desc &D = m.desc;
   const int d = D.d_model, f = D.d_ffn, H = D.n_heads, hd = m.hd;
   const LayerW &L = m.layers[layer];
   Workspace &ws = c->ws;
   const size_t esz = sizeof(T);
-  T *kc = (T *)((char *)m.kcache + (size_t)layer * m.kv_area_elems * esz);
-  T *vc = (T *)((char *)m.vcache + (size_t)layer * m.kv_area_elems * esz);
+  const size_t slot0 = (size_t)b0 * H * m.L_pad * hd;  // the pass starts at batch slot b0
+  T *kc = (T *)((char *)m.kcache + ((size_t)layer * m.kv_area_elems + slot0) * esz);
+  T *vc = (T *)((char *)m.vcache + ((size_t)layer * m.kv_area_elems + slot0) * esz);
 
   launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, nullptr, st);
   gemm_generic<T>(M, 3 * d, d, ws.x, L.wqkv, L.bqkv, ws.y32, 3 * d, 0, st);
@@ -309,8 +310,8 @@ static void generic_layer_t(spec_ctx *c, const Model &m, int layer, int M, int q
   gemm_generic<T>(M, d, f, ws.act, L.w2, L.b2, ws.h, d, 1, st);
 }
 
-void generic_layer(spec_ctx *c, const Model &m, int layer, int M, int q_rows, hipStream_t st) {
-  SPEC_DISPATCH_DTYPE(c->run.dtype, T, generic_layer_t<T>(c, m, layer, M, q_rows, st));
+void generic_layer(spec_ctx *c, const Model &m, int layer, int M, int q_rows, int b0, hipStream_t st) {
+  SPEC_DISPATCH_DTYPE(c->run.dtype, T, generic_layer_t<T>(c, m, layer, M, q_rows, b0, st));
 }
 
 // Final norm over the rows that need logits, then the LM head into fp32 logits [Mh][vocab].

@@ -57,8 +57,9 @@ void launch_assemble_embed(const spec_ctx *c, const Model &m, const PassArgs &pa
   SPEC_DISPATCH_DTYPE(c->run.dtype, T,
     hipLaunchKernelGGL(k_assemble_embed<T>, dim3(M), dim3(256), 0, st, (int)pa.kind, pa.q, pa.j, pa.P,
                        c->run.s_max, c->run.L_max, m.desc.vocab, m.desc.d_model,
-                       (int)(m.desc.pos_kind == SPEC_POS_LEARNED), c->st.seq, c->st.n, c->drf.kv_len, c->st.t,
-                       (const T *)m.tok_emb, (const T *)m.pos_emb, c->ws.row_tok, c->ws.row_pos, c->ws.h));
+                       (int)(m.desc.pos_kind == SPEC_POS_LEARNED), c->st.seq + (size_t)pa.b0 * c->run.L_max,
+                       c->st.n + pa.b0, c->drf.kv_len ? c->drf.kv_len + pa.b0 : nullptr,
+                       c->st.t + (size_t)pa.b0 * c->run.s_max, (const T *)m.tok_emb, (const T *)m.pos_emb, c->ws.row_tok, c->ws.row_pos, c->ws.h));
 }
 
 // -------------------------------------------------------------------------
@@ -298,6 +299,19 @@ __global__ void k_state_reset(int B, int P, int L_max, int s_max, const int32_t 
   if (i < B) { n[i] = P; l_last[i] = 0; if (kv_draft) kv_draft[i] = P - 1; }
   if (i <= s_max) hist[i] = 0ull;
   if (i < 2) counters[i] = 0ull;
+}
+// One batch slot back to "prompt just given": its tokens, length, draft-cache length.  Counters and the
+// accepted-length histogram belong to the whole batch and are left alone.
+__global__ void k_state_admit(int P, const int32_t *__restrict__ prompt, int32_t *__restrict__ seq_b,
+                              int32_t *__restrict__ n_b, int32_t *__restrict__ kv_draft_b, int32_t *__restrict__ l_last_b) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < P) seq_b[i] = prompt[i];
+  if (i == 0) { *n_b = P; *l_last_b = 0; if (kv_draft_b) *kv_draft_b = P - 1; }
+}
+void launch_state_admit(spec_ctx *c, int b, const int32_t *d_prompt, hipStream_t st) {
+  hipLaunchKernelGGL(k_state_admit, dim3((c->P + 255) / 256), dim3(256), 0, st, c->P, d_prompt,
+                     c->st.seq + (size_t)b * c->run.L_max, c->st.n + b, c->drf.kv_len ? c->drf.kv_len + b : nullptr,
+                     c->st.l_last + b);
 }
 void launch_state_reset(spec_ctx *c, const int32_t *d_prompt, hipStream_t st) {
   int work = c->B * c->P;

@@ -348,8 +348,8 @@ static int forward_pass(spec_ctx *c, Model &m, const PassArgs &pa, HeadMode head
   if (dump) generic_copy(c->ws.h, dump, hbytes, st);
   if (m.fast && m.fold_norm) { KScope k(c, &m == &c->tgt ? SPEC_KCLASS_NORM : -1); launch_row_prep(c, m, M, st); }
   for (int l = 0; l < m.desc.n_layers; ++l) {
-    if (m.fast) fast_layer(c, m, l, pa.B, pa.q, max_pos, st);
-    else generic_layer(c, m, l, M, pa.q, st);
+    if (m.fast) fast_layer(c, m, l, pa.B, pa.q, pa.b0, max_pos, st);
+    else generic_layer(c, m, l, M, pa.q, pa.b0, st);
     if (dump) generic_copy(c->ws.h, (char *)dump + (size_t)(l + 1) * hbytes, hbytes, st);
   }
   if (head != HEAD_NONE) {
@@ -408,6 +408,29 @@ extern "C" int spec_reset(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32
 }
 extern "C" int spec_reset_noprefill(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32_t P) {
   return do_reset(c, B, d_prompt, P, false, "spec_reset_noprefill");
+}
+
+// Continuous batching: one slot of the running batch starts over with a new prompt of the batch's prompt
+// length; the other sequences keep their state.  The slot's prompt runs through both models in a pass of
+// its own (B = 1 at batch slot b), so its cost is that of a single-sequence prefill.
+extern "C" int spec_admit(spec_ctx *c, int32_t b, const int32_t *d_prompt) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_admit: ctx is null");
+  if (!c->active) return fail(c, SPEC_ERR_STATE, "spec_admit: no batch; call spec_reset first");
+  if (!d_prompt) return fail(c, SPEC_ERR_INVALID_ARG, "spec_admit: prompt is null");
+  if (b < 0 || b >= c->B) return fail(c, SPEC_ERR_INVALID_ARG, "spec_admit: slot %d outside 0..B-1=%d", b, c->B - 1);
+  if (c->draft_j != 0 || c->verified_s >= 0)
+    return fail(c, SPEC_ERR_STATE, "spec_admit: a round is in progress; finish it with spec_accept_commit first");
+  const int P = c->P;
+  launch_state_admit(c, b, d_prompt, c->stream);
+  const int chunk = std::max(1, std::min(Q_LIMIT, c->M_max));
+  for (int base = 0; base < P - 1; base += chunk) {
+    PassArgs pa{PASS_PREFILL, 1, std::min(chunk, P - 1 - base), base, P, c->run.s_max, c->run.L_max, b};
+    int rc = forward_pass(c, c->tgt, pa, HEAD_NONE, nullptr, nullptr, 0, base + chunk - 1);
+    if (!rc && c->drf.present) rc = forward_pass(c, c->drf, pa, HEAD_NONE, nullptr, nullptr, 0, base + chunk - 1);
+    if (rc) return rc;
+  }
+  HIPCHK(c, hipGetLastError());
+  return SPEC_OK;
 }
 
 extern "C" int spec_rewind(spec_ctx *c) {

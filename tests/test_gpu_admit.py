@@ -1,0 +1,143 @@
+"""Continuous batching through the C ABI (spec_admit): a slot of the running batch starts over with a new
+prompt while the other sequences go on.  Greedy speculative decoding must still emit, for every prompt,
+exactly the target's own greedy continuation (Sec. 2, Alg. 1: the output does not depend on the proposals),
+whatever was admitted when; checked against the same library decoding each prompt without speculation, and
+for the fp32 configuration against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from helpers import build_pair
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+CASES = {
+    "tiny_fp32": dict(dtype="fp32", seed=1000, B=3, P=16, N=20, s=4, alpha=0.7,
+                      tgt=si.CONFIGS["tiny_fp32"][2], drf=si.CONFIGS["tiny_fp32"][3]),
+    "small_bf16": dict(dtype="bf16", seed=77, B=4, P=21, N=24, s=3, alpha=0.7,
+                       tgt=si.llama_desc(2, 256, 2, 416, 1000, 128), drf=si.llama_desc(1, 128, 2, 160, 1000, 128)),
+    "small_fp16_opt": dict(dtype="fp16", seed=78, B=3, P=5, N=18, s=5, alpha=0.6,
+                           tgt=si.opt_desc(2, 256, 4, 384, 777, 64), drf=si.opt_desc(1, 128, 2, 192, 777, 64)),
+}
+EXTRA = 3  # prompts admitted later
+
+
+@pytest.fixture(scope="module")
+def orc():
+    from oracle import oracle as om
+    return om.Oracle("f64")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2310_18813_amd import binding
+    return binding
+
+
+def greedy_reference(ctx, prompts, nB, N):
+    """The library's own non-speculative decode of every prompt, nB at a time."""
+    out = []
+    for lo in range(0, len(prompts), nB):
+        part = prompts[lo:lo + nB]
+        ctx.spec_reset(part)
+        ctx.spec_round(0, N)
+        toks, _ = ctx.spec_read_output()
+        assert all(len(toks[b]) == N for b in range(len(part)))
+        out.extend(np.array(toks[b]) for b in range(len(part)))
+    return out
+
+
+@pytest.mark.parametrize("mode", ["table", "draft"])
+@pytest.mark.parametrize("name", list(CASES))
+def test_admitted_sequences_decode_as_if_alone(orc, B, name, mode):
+    c = CASES[name]
+    nB, P, N, s = c["B"], c["P"], c["N"], c["s"]
+    ot, od, gt, gd = build_pair(orc, c["tgt"], c["drf"], c["dtype"], c["seed"], DEV)
+    L_max = P + N + s + 3
+    pmode = B.PROPOSALS_EXTERNAL if mode == "table" else B.PROPOSALS_DRAFT
+    ctx = B.Context(c["tgt"], gt, c["drf"], gd, c["dtype"], nB, s, L_max, N, pmode, DEV)
+    prompts = si.make_prompts(nB + EXTRA, P, c["tgt"]["vocab"], c["seed"])
+    if mode == "table":
+        ctx.spec_set_proposal_table(np.zeros((nB, L_max), dtype=np.int32))  # unused at s = 0
+    ref = greedy_reference(ctx, prompts, nB, N)
+    if name == "tiny_fp32":  # fp32: the library's greedy decode is the oracle's, token for token
+        for i, p in enumerate(prompts):
+            assert np.array_equal(ref[i], ot.greedy(p, N)), i
+
+    # which prompt sits in which slot, and the proposals that go with it (its greedy continuation with
+    # a share of the tokens replaced)
+    owner = list(range(nB))
+
+    def set_table():
+        if mode != "table":
+            return
+        truth = np.zeros((nB, L_max), dtype=np.int32)
+        for b in range(nB):
+            truth[b, P:P + N] = ref[owner[b]]
+        ctx.spec_set_proposal_table(si.make_proposal_table(truth, c["alpha"], c["tgt"]["vocab"], c["seed"] + 5))
+
+    def admit(b, i):
+        owner[b] = i
+        ctx.spec_admit(b, prompts[i])
+        set_table()
+
+    def check(slots):
+        toks, _ = ctx.spec_read_output()
+        for b in slots:
+            assert len(toks[b]) == N, (b, len(toks[b]))
+            assert np.array_equal(np.array(toks[b]), ref[owner[b]]), (name, mode, b, owner[b])
+
+    def prompt_kv(slot):
+        """Cached keys and values of a slot's prompt, first and last layer of both models."""
+        out = []
+        for which, desc in ((B.MODEL_TARGET, c["tgt"]), (B.MODEL_DRAFT, c["drf"])):
+            for layer in sorted({0, desc["n_layers"] - 1}):
+                K, V = ctx.spec_kv_export(which, layer, nB, P - 1)
+                out += [K[slot].clone(), V[slot].clone()]
+        return out
+
+    # what a plain reset leaves in slot 1 for the prompt that will be admitted there
+    first = [prompts[b] for b in range(nB)]
+    first[1] = prompts[nB]
+    ctx.spec_reset(np.stack(first))
+    kv_reset = prompt_kv(1)
+
+    set_table()
+    ctx.spec_reset(prompts[:nB])
+    ctx.spec_round(s, 2)
+    admit(1, nB)                  # a sequence in mid-flight is replaced
+    # the single-sequence prefill leaves the same bits in both caches as the batch prefill does
+    for got, want in zip(prompt_kv(1), kv_reset):
+        assert torch.equal(got, want)
+    ctx.spec_round(s, 3)
+    admit(0, nB + 1)              # and another, a few rounds later
+    ctx.spec_round(s, N)          # more rounds than anyone needs: finished sequences stay as they are
+    check(range(nB))
+    n_before, _, _, _ = ctx.spec_read_state()
+    admit(nB - 1, nB + 2)         # a finished sequence leaves, a new one takes its slot
+    ctx.spec_round(s, N)
+    check(range(nB))
+    n_after, _, _, _ = ctx.spec_read_state()
+    assert list(n_after) == list(n_before)
+    ctx.close()
+
+
+def test_admit_is_refused_where_it_cannot_work(orc, B):
+    c = CASES["tiny_fp32"]
+    nB, P, N, s = c["B"], c["P"], c["N"], c["s"]
+    ot, od, gt, gd = build_pair(orc, c["tgt"], c["drf"], c["dtype"], c["seed"], DEV)
+    ctx = B.Context(c["tgt"], gt, c["drf"], gd, c["dtype"], nB, s, P + N + s + 3, N, B.PROPOSALS_DRAFT, DEV)
+    prompts = si.make_prompts(nB, P, c["tgt"]["vocab"], c["seed"])
+    with pytest.raises(B.SpecError):
+        ctx.spec_admit(0, prompts[0])          # no batch yet
+    ctx.spec_reset(prompts)
+    for bad in (-1, nB):
+        with pytest.raises(B.SpecError):
+            ctx.spec_admit(bad, prompts[0])    # slot out of range
+    ctx.spec_draft_step(1)
+    with pytest.raises(B.SpecError):
+        ctx.spec_admit(0, prompts[0])          # inside a round
+    ctx.close()
