@@ -346,14 +346,14 @@ static void launch_epi(const GemmArgs &a, int epi, dim3 grid, dim3 block, size_t
 template <class T>
 static void launch_gemm_t(GemmArgs a, int epi, hipStream_t st) {
   if (a.M <= 0) return;
-  // more than 64 rows: the LDS-tiled kernel (same bits, weights fetched once per up to 256 rows); the narrow
-  // residual GEMMs run it one k-slice per workgroup when the context has the scratch for the slices
-  // (worth the second kernel from about 32 steps per slice, or from 5 row passes of the streaming kernel)
+  // Wide outputs go to the LDS-tiled kernel (same bits, weights fetched once per up to 256 rows) from 65 rows
+  // on, the widest (gate-up, LM head) already from 33: the streaming kernel's waves each fetch their own copy
+  // of the activations, the tiled kernel shares them through LDS.  The narrow residual GEMMs run it one k-slice
+  // per workgroup when the context has the scratch for the slices: worth the second kernel from 33 rows on
+  // when a slice has at least 32 steps (down projection), and from 5 row passes of the streaming kernel.
   const bool split_ok = a.part && a.KS > 1 && (a.N & 3) == 0 && (a.KT / a.KS >= 32 || a.M > 256);
-  // the widest outputs (gate-up, LM head) already gain from 33 rows on: the streaming kernel's waves each fetch
-  // their own copy of the activations, the tiled kernel shares them through LDS
   const int tile_min_m = a.NT >= 1024 ? 33 : 65;
-  if (a.M >= tile_min_m && a.NT >= 64 && (epi != EPI_RESIDUAL || (split_ok && a.M > 64))) {
+  if (a.NT >= 64 && (epi != EPI_RESIDUAL ? a.M >= tile_min_m : (split_ok && a.M >= 33))) {
     launch_gemm_tile(std::is_same<T, bf16_t>::value ? SPEC_DTYPE_BF16 : SPEC_DTYPE_F16, a, epi, st);
     return;
   }
@@ -362,9 +362,9 @@ static void launch_gemm_t(GemmArgs a, int epi, hipStream_t st) {
   const int MT = a.M <= 16 ? 1 : a.M <= 32 ? 2 : 4;
   a.passes = (a.M + MT * 16 - 1) / (MT * 16);
   // as many strips per workgroup as row tiles (activation traffic = weight traffic), while the
-  // launch still has at least one workgroup per CU
+  // launch still has workgroups for 160 of the 256 CUs (measured: fewer, fuller workgroups win down to there)
   int NB = 1;
-  while (NB < MT && (a.NT / (NB * 2)) * a.passes >= 256) NB *= 2;
+  while (NB < MT && (a.NT / (NB * 2)) * a.passes >= 160) NB *= 2;
   // eight strips halve the activation traffic again; worth it once enough workgroups remain
   if (MT == 4 && NB == 4 && (a.NT / 8) * a.passes >= 160) NB = 8;
   a.groups = (a.NT + NB - 1) / NB;
