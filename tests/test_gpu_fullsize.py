@@ -1,13 +1,14 @@
 """GPU parity at the full width of the single-layer verify micro-benchmark (d=4096, 32 heads x
 128, SwiGLU 11008, vocab 32000, bf16, 512 cached positions per sequence), in the launch
-configurations the benchmark times.  The oracle recomputes sampled sequences one by one;
-properties that hold at any size cover the rest."""
+configurations the benchmark times, and at the width of the 13B OPT shape (fp16, d=5120, 40 heads,
+ReLU 20480, LayerNorm, biases, learned positions, ragged vocabulary 50272).  The oracle recomputes
+sampled sequences one by one; properties that hold at any size cover the rest."""
 import numpy as np
 import pytest
 import torch
 
 import synth_inputs as si
-from helpers import LOGIT_TOL, top2_margin
+from helpers import LOGIT_TOL, ORC_WDTYPE, top2_margin
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -15,18 +16,26 @@ KV_LEN = 512
 CELLS = [(1, 0), (2, 4), (16, 2), (8, 8), (33, 1), (64, 8)]   # M = 1, 10, 48, 72, 66, 576
 
 
-@pytest.fixture(scope="module")
-def world():
+WIDTHS = {
+    "llama_bf16": lambda: si.CONFIGS["layer_bf16"][:3],
+    "opt_fp16": lambda: ("fp16", 1003, si.opt_desc(1, 5120, 40, 20480, 50272, 1024)),
+}
+# significant bits of the cache dtype: half an ulp of a stored K/V value is |value| / 2^bits
+STORE_BITS = {"bf16": 8, "fp16": 11}
+
+
+@pytest.fixture(scope="module", params=list(WIDTHS))
+def world(request):
     from oracle import oracle as om
     from paper_2310_18813_amd import binding as B
     orc = om.Oracle("f64")
-    dtype, seed, tdesc, _ = si.CONFIGS["layer_bf16"]
+    dtype, seed, tdesc = WIDTHS[request.param]()
     B_max, s_max = 64, 8
     L_max = KV_LEN + 1 + s_max + 8
     tdesc = dict(tdesc, max_pos=L_max)
     w = si.make_weights(tdesc, dtype, seed, device=DEV, emb_std=1.0, tag="tgt.")
     wn = si.weights_to_numpy(w)
-    ot = orc.model(tdesc, wn, 1)
+    ot = orc.model(tdesc, wn, ORC_WDTYPE[dtype])
     ctx = B.Context(tdesc, w, None, None, dtype, B_max, s_max, L_max, 4, B.PROPOSALS_EXTERNAL, DEV)
     del w
     K, V = si.make_kv(B_max, tdesc["d_model"], KV_LEN, dtype, seed, DEV)
@@ -35,7 +44,8 @@ def world():
     Vh = V.float().cpu().numpy()
     prompts = si.make_prompts(B_max, KV_LEN + 1, tdesc["vocab"], seed)
     props = si.make_prompts(B_max, s_max, tdesc["vocab"], seed + 5)
-    return dict(B=B, orc=orc, ot=ot, ctx=ctx, tdesc=tdesc, Kh=Kh, Vh=Vh, prompts=prompts, props=props, L_max=L_max)
+    return dict(B=B, orc=orc, ot=ot, ctx=ctx, tdesc=tdesc, Kh=Kh, Vh=Vh, prompts=prompts, props=props, L_max=L_max,
+                dtype=dtype)
 
 
 def gpu_cell(wd, nB, s):
@@ -51,7 +61,7 @@ def gpu_cell(wd, nB, s):
 
 def test_sampled_rows_match_oracle_at_full_width(world):
     wd = world
-    B, ot, tol = wd["B"], wd["ot"], LOGIT_TOL["bf16"]
+    B, ot, tol = wd["B"], wd["ot"], LOGIT_TOL[wd["dtype"]]
     worst = 0.0
     for nB, s in CELLS:
         logits, n, l, a = gpu_cell(wd, nB, s)
@@ -78,14 +88,15 @@ def test_sampled_rows_match_oracle_at_full_width(world):
             for i in range(s + 1):
                 if marg[i] > 2 * tol:
                     assert a[b][i] == int(o[i].argmax())
-            # the K/V rows appended by this pass.  Stored in bf16 (8 significant bits): half an ulp is at
-            # most 2^-8 |value|; the bf16 rounding of the 4096 normalised inputs adds about 2.2e-3 (one
-            # sigma: 2^-8/sqrt(3) relative per input, weights of sigma 0.02); 2e-2 absolute, the logit
-            # tolerance, covers the maximum over all elements with margin
+            # the K/V rows appended by this pass.  Stored in the cache dtype: half an ulp is at most
+            # 2^-bits |value| (8 significant bits in bf16, 11 in fp16); the rounding of the normalised inputs
+            # to 16 bits adds about 2.2e-3 in bf16 (one sigma: 2^-8/sqrt(3) relative per input, 4096 weights of
+            # sigma 0.02); the logit tolerance of the dtype as the absolute part covers the maximum over all
+            # elements with margin
             for name, got, ref in (("K", Kx, cache.k(0)), ("V", Vx, cache.v(0))):
                 g = got[b, KV_LEN:].float().cpu().numpy()
                 r = ref[KV_LEN:KV_LEN + s + 1]
-                bound = np.abs(r) / 256.0 + 2e-2
+                bound = np.abs(r) / float(2 ** STORE_BITS[wd["dtype"]]) + tol
                 ratio = np.abs(g - r) / bound
                 w = np.unravel_index(ratio.argmax(), ratio.shape)
                 assert ratio.max() <= 1.0, (name, nB, s, b, w, float(g[w]), float(r[w]), float(ratio.max()))
