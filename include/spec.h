@@ -152,6 +152,15 @@ int spec_reset_noprefill(spec_ctx *ctx, int32_t B, const int32_t *d_prompt, int3
    table it owns.  Counters and the accepted-length histogram keep running for the whole batch.           */
 int spec_admit(spec_ctx *ctx, int32_t b, const int32_t *d_prompt);
 
+/* A speculation length per sequence (beyond the paper, whose rounds use one s for the whole batch):
+   d_s[b] (int32, device, B entries, the caller's memory, read by every round until replaced) caps the
+   proposals of sequence b.  A round called with s then verifies min(s, d_s[b]) proposals for sequence b:
+   its rows for further proposals are dead (no cache write, no attention, logits ignored) and its draft
+   steps beyond the cap are skipped the same way; the pass still has B * (s + 1) rows.  Negative entries count
+   as 0.  NULL (the default) removes the caps.  spec_profile_and_choose_s ignores them.  Not allowed inside a
+   round (SPEC_ERR_STATE).  Emitted tokens do not depend on the caps (Sec. 2).                            */
+int spec_set_seq_s(spec_ctx *ctx, const int32_t *d_s_or_null);
+
 /* Back to the state right after the last reset (lengths, counters, emitted tokens);
    cached prompt KV is kept.                                                           */
 int spec_rewind(spec_ctx *ctx);

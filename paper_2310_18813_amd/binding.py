@@ -25,8 +25,8 @@ DTYPE_CODE = {"fp32": DTYPE_F32, "bf16": DTYPE_BF16, "fp16": DTYPE_F16}
 TORCH_DTYPE = {DTYPE_F32: torch.float32, DTYPE_BF16: torch.bfloat16, DTYPE_F16: torch.float16}
 
 EXPORTS = ["spec_last_error", "spec_workspace_bytes", "spec_init", "spec_destroy", "spec_reset",
-           "spec_reset_noprefill", "spec_admit", "spec_rewind", "spec_set_proposal_table", "spec_set_proposals",
-           "spec_draft_step", "spec_verify_step", "spec_accept_commit", "spec_round",
+           "spec_reset_noprefill", "spec_admit", "spec_set_seq_s", "spec_rewind", "spec_set_proposal_table",
+           "spec_set_proposals", "spec_draft_step", "spec_verify_step", "spec_accept_commit", "spec_round",
            "spec_profile_and_choose_s", "spec_set_lut", "spec_choose_s", "spec_read_output",
            "spec_read_state", "spec_kv_import", "spec_kv_export", "spec_kernel_timing",
            "spec_read_kernel_timing", "spec_set_hidden_dump", "spec_set_attention_shape"]
@@ -61,6 +61,7 @@ lib.spec_reset.argtypes = [_vp, _i32, _vp, _i32]
 lib.spec_reset_noprefill.argtypes = [_vp, _i32, _vp, _i32]
 lib.spec_rewind.argtypes = [_vp]
 lib.spec_admit.argtypes = [_vp, _i32, _vp]
+lib.spec_set_seq_s.argtypes = [_vp, _vp]
 lib.spec_set_proposal_table.argtypes = [_vp, _vp]
 lib.spec_set_proposals.argtypes = [_vp, _vp, _i32]
 lib.spec_draft_step.argtypes = [_vp, _i32]
@@ -186,6 +187,16 @@ class Context:
         assert p.dim() == 1
         self._admit_prompt = p  # stays alive until the stream has consumed it
         _check(lib.spec_admit(self.h, int(b), _dp(p)), self.h)
+
+    def spec_set_seq_s(self, caps):
+        if caps is None:
+            self._seq_s = None
+            _check(lib.spec_set_seq_s(self.h, None), self.h)
+            return
+        t = torch.as_tensor(caps, dtype=torch.int32).to(self.device).contiguous()
+        assert t.dim() == 1 and t.shape[0] >= self.B
+        self._seq_s = t  # must outlive its use
+        _check(lib.spec_set_seq_s(self.h, _dp(t)), self.h)
 
     def spec_rewind(self):
         _check(lib.spec_rewind(self.h), self.h)

@@ -20,20 +20,27 @@ template <class T>
 __global__ void k_assemble_embed(int kind, int q, int j, int P, int s_max, int L_max, int vocab, int d,
                                  int learned_pos, const int32_t *__restrict__ seq, const int32_t *__restrict__ n,
                                  const int32_t *__restrict__ kv_draft, const int32_t *__restrict__ t,
+                                 const int32_t *__restrict__ seq_s,
                                  const T *__restrict__ tok_emb, const T *__restrict__ pos_emb,
                                  int32_t *__restrict__ row_tok, int32_t *__restrict__ row_pos, float *__restrict__ h) {
   const int m = blockIdx.x, b = m / q, i = m % q;
   int tok = 0, pos = -1;
   const int nb = n[b];
+  // a sequence with its own cap s_b on the speculation length: its rows for proposals beyond s_b are dead
+  const int sb = seq_s ? max(0, seq_s[b]) : s_max;
   if (kind == PASS_VERIFY) {
-    pos = nb - 1 + i;
-    tok = (i == 0) ? seq[(size_t)b * L_max + nb - 1] : t[(size_t)b * s_max + i - 1];
+    if (i <= sb) {
+      pos = nb - 1 + i;
+      tok = (i == 0) ? seq[(size_t)b * L_max + nb - 1] : t[(size_t)b * s_max + i - 1];
+    }
   } else if (kind == PASS_DRAFT_FIRST) {
     int p = nb - q + i;
     if (p >= 0 && p >= kv_draft[b]) { pos = p; tok = seq[(size_t)b * L_max + p]; }
-  } else if (kind == PASS_DRAFT_NEXT) {
-    pos = nb + j - 2;
-    tok = t[(size_t)b * s_max + j - 2];
+  } else if (kind == PASS_DRAFT_NEXT) {  // draft step j >= 2 yields t_j: wanted only up to s_b
+    if (j <= sb) {
+      pos = nb + j - 2;
+      tok = t[(size_t)b * s_max + j - 2];
+    }
   } else {  // PASS_PREFILL: j is the base position
     int p = j + i;
     if (p < P - 1) { pos = p; tok = seq[(size_t)b * L_max + p]; }
@@ -59,7 +66,8 @@ void launch_assemble_embed(const spec_ctx *c, const Model &m, const PassArgs &pa
                        c->run.s_max, c->run.L_max, m.desc.vocab, m.desc.d_model,
                        (int)(m.desc.pos_kind == SPEC_POS_LEARNED), c->st.seq + (size_t)pa.b0 * c->run.L_max,
                        c->st.n + pa.b0, c->drf.kv_len ? c->drf.kv_len + pa.b0 : nullptr,
-                       c->st.t + (size_t)pa.b0 * c->run.s_max, (const T *)m.tok_emb, (const T *)m.pos_emb, c->ws.row_tok, c->ws.row_pos, c->ws.h));
+                       c->st.t + (size_t)pa.b0 * c->run.s_max, c->seq_s ? c->seq_s + pa.b0 : nullptr,
+                       (const T *)m.tok_emb, (const T *)m.pos_emb, c->ws.row_tok, c->ws.row_pos, c->ws.h));
 }
 
 // -------------------------------------------------------------------------
@@ -256,6 +264,7 @@ void launch_copy_proposals(spec_ctx *c, const int32_t *d_tok, int s, hipStream_t
 // the last survivor is appended.  Rollback is by length only: the K/V rows written for
 // rejected positions stay in the cache and are overwritten by the next round.
 __global__ void k_accept(int B, int s, int s_max, int L_max, int P, int gen_max, int draft_steps,
+                         const int32_t *__restrict__ seq_s,
                          const int32_t *__restrict__ t, const int32_t *__restrict__ a, int32_t *__restrict__ seq,
                          int32_t *__restrict__ n, int32_t *__restrict__ kv_draft, int32_t *__restrict__ l_last,
                          unsigned long long *__restrict__ hist, unsigned long long *__restrict__ counters) {
@@ -266,8 +275,12 @@ __global__ void k_accept(int B, int s, int s_max, int L_max, int P, int gen_max,
   const int gen = n_old - P;
   const int32_t *tb = t + (size_t)b * s_max;
   const int32_t *ab = a + (size_t)b * (s_max + 1);
+  // with a cap per sequence only the first min(s, s_b) proposals were verified, and the draft ran
+  // max(1, min(draft_steps, s_b)) live steps for this sequence
+  const int sb = seq_s ? min(s, max(0, seq_s[b])) : s;
+  if (seq_s && draft_steps > 0) draft_steps = max(1, min(draft_steps, sb));
   int l = 0;
-  while (l < s && tb[l] == ab[l]) ++l;
+  while (l < sb && tb[l] == ab[l]) ++l;
   int take = min(l + 1, gen_max - gen);
   if (take < 0) take = 0;
   for (int i = 0; i < take; ++i) seq[(size_t)b * L_max + n_old + i] = (i < l) ? tb[i] : ab[l];
@@ -285,7 +298,7 @@ __global__ void k_accept(int B, int s, int s_max, int L_max, int P, int gen_max,
 }
 void launch_accept(spec_ctx *c, int s, hipStream_t st) {
   hipLaunchKernelGGL(k_accept, dim3((c->B + 63) / 64), dim3(64), 0, st, c->B, s, c->run.s_max, c->run.L_max, c->P,
-                     c->run.gen_max, c->draft_j, c->st.t, c->st.a, c->st.seq, c->st.n, c->drf.kv_len, c->st.l_last,
+                     c->run.gen_max, c->draft_j, c->seq_s, c->st.t, c->st.a, c->st.seq, c->st.n, c->drf.kv_len, c->st.l_last,
                      c->st.hist, c->st.counters);
 }
 

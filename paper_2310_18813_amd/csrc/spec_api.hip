@@ -295,6 +295,15 @@ extern "C" int spec_set_hidden_dump(spec_ctx *c, float *d_hidden) {
   return SPEC_OK;
 }
 
+// Per-sequence cap on the speculation length (beyond the paper, whose rounds use one s for the batch).
+extern "C" int spec_set_seq_s(spec_ctx *c, const int32_t *d_s_or_null) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_set_seq_s: ctx is null");
+  if (c->draft_j != 0 || c->verified_s >= 0)
+    return fail(c, SPEC_ERR_STATE, "spec_set_seq_s: a round is in progress; finish it with spec_accept_commit first");
+  c->seq_s = d_s_or_null;
+  return SPEC_OK;
+}
+
 extern "C" int spec_set_attention_shape(spec_ctx *c, int32_t shape) {
   if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_set_attention_shape: ctx is null");
   if (shape < 0 || shape > 2) return fail(c, SPEC_ERR_INVALID_ARG, "spec_set_attention_shape: shape must be 0, 1 or 2");
@@ -633,6 +642,11 @@ extern "C" int spec_profile_and_choose_s(spec_ctx *c, const int32_t *h_batch_siz
   const int nS = s_max_profile + 1;
   std::vector<double> grid((size_t)n_b * nS);
   std::vector<int32_t> lut(n_b);
+  struct CapsOff {  // the profiling stage times uniform rounds: per-sequence caps are set aside until it returns
+    spec_ctx *c; const int32_t *saved;
+    explicit CapsOff(spec_ctx *ctx) : c(ctx), saved(ctx->seq_s) { c->seq_s = nullptr; }
+    ~CapsOff() { c->seq_s = saved; }
+  } caps_off(c);
   for (int bi = 0; bi < n_b; ++bi) {
     const int B = h_batch_sizes[bi];
     // rows of d_prompt have stride P: the first B rows are the batch

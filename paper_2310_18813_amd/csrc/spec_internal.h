@@ -120,6 +120,7 @@ struct spec_ctx {
   int verified_s = -1;    // s of the verify step waiting for accept_commit, or -1
   bool proposals_ready = false;
   const int32_t *prop_table = nullptr;
+  const int32_t *seq_s = nullptr;  // [B] per-sequence cap of the speculation length (caller's device memory), or null
   float *hidden_dump = nullptr;
   int attn_shape = 0;
   std::vector<int32_t> lut_B, lut_s;
