@@ -3,7 +3,8 @@
 intervals, a server that merges whatever waits in its queue into one batch (at most `max_batch` requests) and
 decodes it with batched speculative decoding, four policies for the speculation length (none, fixed 2, fixed 4,
 adaptive = the profiled look-up table).  Latency of a request = finish time of its batch - its arrival time, so
-waiting in the queue counts.
+waiting in the queue counts.  Beside the paper's server a continuous-batching one (`serve_continuous`, on
+spec_admit): requests join the running batch between rounds and leave when they are done.
 
 The queue is simulated on the host on a virtual clock; the service time of a batch of B requests at speculation
 length s is what the library needs on the GPU to generate N tokens for B synthetic prompts (measured once per
@@ -74,6 +75,44 @@ def serve(arrivals, service_time, choose_s, max_batch=16):
     return lat, batches
 
 
+def serve_continuous(arrivals, n_tokens, slots, round_time, admit_time, tokens_per_round, choose_s):
+    """Continuous batching (beyond the paper's server, which decodes whole batches): the server owns `slots`
+    sequence slots and decodes them round after round; a request that waits takes a free slot as soon as the
+    current round ends (spec_admit: the server is busy for admit_time per admission, one after the other), and
+    leaves when its n_tokens are out.  A round with speculation length s = choose_s(occupied) lasts
+    round_time(s) whatever the number of occupied slots (the pass always has slots * (s + 1) rows) and gives
+    every occupied slot tokens_per_round(s) tokens (a callable: 1 + the accepted length of that sequence's
+    round).  Returns (latencies per request, list of (start, occupied, s) per round)."""
+    arrivals = np.asarray(arrivals, dtype=np.float64)
+    n = len(arrivals)
+    lat = np.zeros(n)
+    left = [0] * slots      # tokens still owed to the request in the slot
+    who = [-1] * slots      # request index, -1 = free
+    rounds = []
+    t, nxt, done = 0.0, 0, 0
+    while done < n:
+        for k in range(slots):  # admissions, oldest request first
+            if who[k] < 0 and nxt < n and arrivals[nxt] <= t:
+                who[k], left[k] = nxt, int(n_tokens)
+                nxt += 1
+                t += float(admit_time)
+        occupied = sum(1 for w in who if w >= 0)
+        if occupied == 0:
+            t = max(t, arrivals[nxt])  # idle until the next request
+            continue
+        s = int(choose_s(occupied))
+        rounds.append((t, occupied, s))
+        t += float(round_time(s))
+        for k in range(slots):
+            if who[k] >= 0:
+                left[k] -= int(tokens_per_round(s))
+                if left[k] <= 0:
+                    lat[who[k]] = t - arrivals[who[k]]
+                    who[k] = -1
+                    done += 1
+    return lat, rounds
+
+
 def lut_policy(profiled_B, lut):
     """The look-up of Sec. 4: exact hit, else the smaller entry of the two nearest profiled sizes; ends clamp."""
     pb, lt = list(profiled_B), list(lut)
@@ -107,6 +146,39 @@ def measure_service_table(ctx, prompts, n_tokens, batch_sizes, s_values, check_e
                     break
             table[(B, s)] = time.perf_counter() - t0
     return table
+
+
+def measure_continuous(ctx, prompts, n_tokens, s_values, n_admit=4):
+    """What the continuous-batching server needs, measured through the C ABI with all slots of the batch busy:
+    seconds per round and the distribution of tokens per round and sequence (1 + accepted length) for every s,
+    and the seconds one spec_admit takes."""
+    import time
+    import torch
+    B = prompts.shape[0]
+    round_s, gain = {}, {}
+    for s in s_values:
+        rounds = max(1, n_tokens // (s + 1))   # nobody can finish within these
+        ctx.spec_reset(prompts)
+        ctx.spec_round(s, 1)
+        ctx.spec_rewind()
+        ctx.spec_read_state()
+        t0 = time.perf_counter()
+        ctx.spec_round(s, rounds)
+        ctx.spec_read_state()                  # synchronises
+        round_s[s] = (time.perf_counter() - t0) / rounds
+        _, hist = ctx.spec_read_output()
+        h = np.array(hist[:s + 1], dtype=np.float64)
+        gain[s] = (np.arange(1, s + 2), h / h.sum())
+    ctx.spec_reset(prompts)
+    ctx.spec_round(0, 1)
+    ctx.spec_read_state()
+    t0 = time.perf_counter()
+    for i in range(n_admit):
+        ctx.spec_admit(i % B, prompts[(i + 1) % B])
+    ctx.spec_read_state()
+    torch.cuda.synchronize()
+    admit_s = (time.perf_counter() - t0) / n_admit
+    return round_s, gain, admit_s
 
 
 def main():
@@ -162,6 +234,26 @@ def main():
             row["adaptive_vs_s0"] = round(row["s=0"]["mean_latency_s"] / row["adaptive"]["mean_latency_s"], 3)
             row["adaptive_vs_best_fixed"] = round(min(row["s=2"]["mean_latency_s"], row["s=4"]["mean_latency_s"]) /
                                                   row["adaptive"]["mean_latency_s"], 3)
+            print(json.dumps(row), flush=True)
+    # continuous batching on the same arrivals: all slots decode every round, waiting requests take free slots
+    round_s, gain, admit_s = measure_continuous(ctx, prompts, N, sorted({0, 2, 4, adaptive(mb)}))
+    print(json.dumps({"continuous": {"slots": mb, "admit_s": round(admit_s, 4),
+                                     "round_s": {str(k): round(v, 5) for k, v in round_s.items()},
+                                     "mean_tokens_per_round": {str(k): round(float((g[0] * g[1]).sum()), 3)
+                                                               for k, g in gain.items()}}}), flush=True)
+    cont = {"s=0": 0, "s=2": 2, "s=4": 4, "adaptive": adaptive(mb)}
+    for cv in [float(x) for x in args.cvs.split(",")]:
+        for rel in [float(x) for x in args.intervals.split(",")]:
+            arr = gamma_arrivals(args.requests, rel * unit, cv, seed=int(1000 * cv) + int(100 * rel))
+            row = {"cv": cv, "interval_units": rel, "server": "continuous"}
+            for name, sv in cont.items():
+                draws = iter(np.random.default_rng(17).choice(gain[sv][0], p=gain[sv][1], size=args.requests * N + 64))
+                lat, _ = serve_continuous(arr, N, mb, lambda s_: round_s[s_], admit_s,
+                                          lambda s_: next(draws), lambda occ, sv=sv: sv)
+                row[name] = round(float(lat.mean()), 4)
+            lat_static, _ = serve(arr, lambda b, s_: table[(b, s_)], adaptive, mb)
+            row["static_adaptive"] = round(float(lat_static.mean()), 4)
+            row["continuous_vs_static"] = round(row["static_adaptive"] / row["adaptive"], 3)
             print(json.dumps(row), flush=True)
     # timeline: intense and sparse traffic alternate every 50 mean-service units, CV = 1
     arr = alternating_arrivals(300 * unit * 5, [0.4 * unit, 2.0 * unit], 50 * unit * 5, 1.0, seed=7)

@@ -93,3 +93,88 @@ def test_adaptive_wins_when_it_is_faster_for_every_batch_and_load_is_light():
     arr = np.arange(50) * 10.0
     means = {s: ts.serve(arr, service, lambda b, s=s: s)[0].mean() for s in (0, 2, 4)}
     assert means[4] < means[2] < means[0]
+
+
+def brute_force_continuous(arrivals, n_tokens, slots, dt_round, dt_admit, gain, tick):
+    """Time-stepped continuous-batching server with constant round time and token gain: a state machine that
+    looks at the clock every tick (all event times are multiples of the tick)."""
+    n = len(arrivals)
+    lat = np.zeros(n)
+    who, left = [-1] * slots, [0] * slots
+    nxt = done = 0
+    busy_until, mode = 0.0, "idle"
+    for k in range(10 ** 7):
+        if done == n:
+            return lat
+        t = k * tick
+        if t < busy_until - 1e-9:
+            continue
+        if mode == "round":  # the round that was running ends now
+            for i in range(slots):
+                if who[i] >= 0:
+                    left[i] -= gain
+                    if left[i] <= 0:
+                        lat[who[i]] = busy_until - arrivals[who[i]]
+                        who[i] = -1
+                        done += 1
+        mode = "idle"
+        free = [i for i in range(slots) if who[i] < 0]
+        if free and nxt < n and arrivals[nxt] <= t + 1e-9:
+            who[free[0]], left[free[0]] = nxt, n_tokens
+            nxt += 1
+            busy_until, mode = t + dt_admit, "admitting"
+        elif any(w >= 0 for w in who):
+            busy_until, mode = t + dt_round, "round"
+    raise AssertionError("the time-stepped server did not finish")
+
+
+def test_continuous_server_hand_worked():
+    # one slot, rounds of 1 s giving 2 tokens, requests of 4 tokens, admission 0.5 s:
+    # request 0 arrives at 0: admitted 0..0.5, rounds end at 1.5 and 2.5 -> latency 2.5
+    # request 1 arrives at 0.2, waits for the slot: admitted 2.5..3.0, rounds end at 4.0 and 5.0 -> latency 4.8
+    lat, rounds = ts.serve_continuous([0.0, 0.2], 4, 1, lambda s: 1.0, 0.5, lambda s: 2, lambda occ: 3)
+    assert lat == pytest.approx([2.5, 4.8])
+    assert [r[0] for r in rounds] == pytest.approx([0.5, 1.5, 3.0, 4.0])
+    assert all(occ == 1 and s == 3 for _, occ, s in rounds)
+    # two slots: the second request joins after the round in progress when it arrived
+    # t=0: admit r0 (0.5); round 0.5..1.5 (r0: 2 left); r1 arrived at 0.7 -> admitted 1.5..2.0; round 2.0..3.0
+    # finishes r0 (latency 3.0), r1 has 2 left; round 3.0..4.0 finishes r1 (latency 3.3)
+    lat, rounds = ts.serve_continuous([0.0, 0.7], 4, 2, lambda s: 1.0, 0.5, lambda s: 2, lambda occ: 0)
+    assert lat == pytest.approx([3.0, 3.3])
+    assert [occ for _, occ, _ in rounds] == [1, 2, 1]
+    # a request that arrives while another is being admitted is admitted right after it, before the first round
+    lat, rounds = ts.serve_continuous([0.0, 0.2], 4, 2, lambda s: 1.0, 0.5, lambda s: 2, lambda occ: 0)
+    assert lat == pytest.approx([3.0, 2.8])
+    assert [occ for _, occ, _ in rounds] == [2, 2]
+    # idle gaps: the server waits for the next arrival
+    lat, rounds = ts.serve_continuous([0.0, 10.0], 2, 2, lambda s: 1.0, 0.0, lambda s: 2, lambda occ: 0)
+    assert lat == pytest.approx([1.0, 1.0])
+    lat, rounds = ts.serve_continuous([], 2, 2, lambda s: 1.0, 0.0, lambda s: 2, lambda occ: 0)
+    assert len(lat) == 0 and rounds == []
+
+
+def test_continuous_server_matches_time_stepped_one():
+    # every time is a multiple of 1/64 s, so sums of them are exact and "arrived by now" has no rounding to argue about
+    rng = np.random.default_rng(11)
+    tick = 1.0 / 64
+    for trial in range(6):
+        arr = np.cumsum(rng.geometric(0.05, size=40)) * tick
+        lat, _ = ts.serve_continuous(arr, 6, 3, lambda s: 16 * tick, 4 * tick, lambda s: 2, lambda occ: 2)
+        ref = brute_force_continuous(arr, 6, 3, 16 * tick, 4 * tick, 2, tick=tick)
+        assert np.array_equal(lat, ref), trial
+
+
+def test_continuous_server_conservation_and_policy():
+    arr = ts.gamma_arrivals(300, 0.2, 2.0, seed=4)
+    seen = []
+
+    def policy(occ):
+        seen.append(occ)
+        return 4 if occ <= 2 else 1
+    gains = iter(np.random.default_rng(0).integers(1, 4, size=10 ** 6))
+    lat, rounds = ts.serve_continuous(arr, 16, 4, lambda s: 0.05 + 0.01 * s, 0.02, lambda s: int(next(gains)), policy)
+    assert (lat > 0).all() and len(lat) == 300
+    assert max(seen) <= 4 and min(seen) >= 1
+    assert all(s == (4 if occ <= 2 else 1) for _, occ, s in rounds)
+    # nobody finishes faster than the rounds it needs at the largest gain
+    assert lat.min() >= np.ceil(16 / 3) * 0.05 - 1e-9
