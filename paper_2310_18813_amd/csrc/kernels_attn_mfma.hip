@@ -207,8 +207,9 @@ __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a) {
   const T *qrow = (const T *)a.q + (size_t)w.m_row * d + (size_t)hh * HD;
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) qf[kk] = *(const u32x4_v *)(qrow + kk * 32 + 8 * w.g);
-  const T *kbase = (const T *)a.kc + (size_t)bh * a.L_pad * HD;
-  const T *vbase = (const T *)a.vc + (size_t)bh * (a.L_pad / KV_VBLOCK) * HD * KV_VBLOCK;
+  const size_t cbh = a.kv_one_seq ? (size_t)hh : (size_t)bh;  // whose cache: this group's own sequence, or the one sequence of the pass
+  const T *kbase = (const T *)a.kc + cbh * a.L_pad * HD;
+  const T *vbase = (const T *)a.vc + cbh * (a.L_pad / KV_VBLOCK) * HD * KV_VBLOCK;
   float m_run, l_run;
   f32x4_v acc[HT];
   chunk_partial<T, HD>(kbase, vbase, qf, k0, kend, w.j, w.g, w.pos_j, scale, m_run, l_run, acc);
@@ -260,8 +261,9 @@ __global__ __launch_bounds__(256) void k_attn_seq(AttnArgs a) {
   const T *qrow = (const T *)a.q + (size_t)w.m_row * d + (size_t)hh * HD;
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) qf[kk] = *(const u32x4_v *)(qrow + kk * 32 + 8 * w.g);
-  const T *kbase = (const T *)a.kc + (size_t)bh * a.L_pad * HD;
-  const T *vbase = (const T *)a.vc + (size_t)bh * (a.L_pad / KV_VBLOCK) * HD * KV_VBLOCK;
+  const size_t cbh = a.kv_one_seq ? (size_t)hh : (size_t)bh;  // whose cache: this group's own sequence, or the one sequence of the pass
+  const T *kbase = (const T *)a.kc + cbh * a.L_pad * HD;
+  const T *vbase = (const T *)a.vc + cbh * (a.L_pad / KV_VBLOCK) * HD * KV_VBLOCK;
   float mr = NEG_BIG, lr = 0.f;
   f32x4_v ar[HT];
 #pragma unroll

@@ -357,8 +357,8 @@ static int forward_pass(spec_ctx *c, Model &m, const PassArgs &pa, HeadMode head
   if (dump) generic_copy(c->ws.h, dump, hbytes, st);
   if (m.fast && m.fold_norm) { KScope k(c, &m == &c->tgt ? SPEC_KCLASS_NORM : -1); launch_row_prep(c, m, M, st); }
   for (int l = 0; l < m.desc.n_layers; ++l) {
-    if (m.fast) fast_layer(c, m, l, pa.B, pa.q, pa.b0, max_pos, st);
-    else generic_layer(c, m, l, M, pa.q, pa.b0, st);
+    if (m.fast) fast_layer(c, m, l, pa.B, pa.q, pa.b0, pa.one_seq, max_pos, st);
+    else generic_layer(c, m, l, M, pa.q, pa.b0, pa.one_seq, st);
     if (dump) generic_copy(c->ws.h, (char *)dump + (size_t)(l + 1) * hbytes, hbytes, st);
   }
   if (head != HEAD_NONE) {
@@ -431,11 +431,16 @@ extern "C" int spec_admit(spec_ctx *c, int32_t b, const int32_t *d_prompt) {
     return fail(c, SPEC_ERR_STATE, "spec_admit: a round is in progress; finish it with spec_accept_commit first");
   const int P = c->P;
   launch_state_admit(c, b, d_prompt, c->stream);
-  const int chunk = std::max(1, std::min(Q_LIMIT, c->M_max));
-  for (int base = 0; base < P - 1; base += chunk) {
-    PassArgs pa{PASS_PREFILL, 1, std::min(chunk, P - 1 - base), base, P, c->run.s_max, c->run.L_max, b};
-    int rc = forward_pass(c, c->tgt, pa, HEAD_NONE, nullptr, nullptr, 0, base + chunk - 1);
-    if (!rc && c->drf.present) rc = forward_pass(c, c->drf, pa, HEAD_NONE, nullptr, nullptr, 0, base + chunk - 1);
+  // The prompt goes through in passes of up to M_max rows, all of this one sequence: groups of Q_LIMIT rows
+  // (the attention query tile) at consecutive positions that share the slot's cache, so a prompt of up to
+  // M_max tokens costs one pass over the weights.
+  const int cap = c->M_max >= Q_LIMIT ? c->M_max / Q_LIMIT * Q_LIMIT : c->M_max;
+  for (int base = 0; base < P - 1; base += cap) {
+    const int rows = std::min(cap, P - 1 - base);
+    const int q = std::min(rows, Q_LIMIT), groups = (rows + q - 1) / q;
+    PassArgs pa{PASS_PREFILL, groups, q, base, P, c->run.s_max, c->run.L_max, b, true};
+    int rc = forward_pass(c, c->tgt, pa, HEAD_NONE, nullptr, nullptr, 0, base + rows - 1);
+    if (!rc && c->drf.present) rc = forward_pass(c, c->drf, pa, HEAD_NONE, nullptr, nullptr, 0, base + rows - 1);
     if (rc) return rc;
   }
   HIPCHK(c, hipGetLastError());

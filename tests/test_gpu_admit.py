@@ -19,6 +19,10 @@ CASES = {
                       tgt=si.CONFIGS["tiny_fp32"][2], drf=si.CONFIGS["tiny_fp32"][3]),
     "small_bf16": dict(dtype="bf16", seed=77, B=4, P=21, N=24, s=3, alpha=0.7,
                        tgt=si.llama_desc(2, 256, 2, 416, 1000, 128), drf=si.llama_desc(1, 128, 2, 160, 1000, 128)),
+    # a prompt longer than the pass has rows: two groups of 16 rows of the one sequence in the first pass
+    # (they share the slot's cache), a ragged second pass
+    "small_bf16_long": dict(dtype="bf16", seed=83, B=4, P=43, N=14, s=7, alpha=0.7,
+                            tgt=si.llama_desc(2, 256, 4, 416, 1000, 128), drf=si.llama_desc(1, 128, 2, 160, 1000, 128)),
     "small_fp16_opt": dict(dtype="fp16", seed=78, B=3, P=5, N=18, s=5, alpha=0.6,
                            tgt=si.opt_desc(2, 256, 4, 384, 777, 64), drf=si.opt_desc(1, 128, 2, 192, 777, 64)),
 }
