@@ -172,7 +172,7 @@ static GemmArgs base_args(const PackedDims &p, const void *W, float inv_scale, c
 
 // One pre-norm decoder layer over the M rows of the pass; max_pos is an upper bound of the
 // largest row position (sizes the attention grid; chunks past a sequence's end exit at once).
-void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b0, bool one_seq, int max_pos, hipStream_t st) {
+void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b0, int seq_groups, int max_pos, hipStream_t st) {
   const spec_model_desc &D = m.desc;
   const int dt = c->run.dtype, M = B * q_rows, d = D.d_model;
   const LayerW &L = m.layers[layer];
@@ -208,7 +208,7 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
     GemmArgs a = base_args(m.p_qkv, L.wqkv, L.s_qkv, L.bqkv, ws.x, M);
     consume_norm(a);
     a.q = ws.q; a.kc = kc; a.vc = vc; a.row_pos = ws.row_pos; a.rope = m.rope;
-    a.q_rows = q_rows; a.d = d; a.hd = m.hd; a.H = D.n_heads; a.L_pad = m.L_pad; a.kv_one_seq = one_seq;
+    a.q_rows = q_rows; a.d = d; a.hd = m.hd; a.H = D.n_heads; a.L_pad = m.L_pad; a.seq_groups = seq_groups;
     launch_gemm_mfma(dt, a, EPI_QKV, st);
   }
   {
@@ -217,7 +217,7 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
     t.q = ws.q; t.kc = kc; t.vc = vc; t.row_pos = ws.row_pos; t.out = ws.attn;
     t.part_acc = ws.attn_part; t.part_ml = ws.attn_ml;
     t.B = B; t.q_rows = q_rows; t.H = D.n_heads; t.hd = m.hd; t.L_pad = m.L_pad;
-    t.kv_one_seq = one_seq;
+    t.seq_groups = seq_groups;
     t.shape = c->attn_shape;
     t.NC = std::min(c->NC_max, max_pos / ATTN_CHUNK + 1);
     launch_attention_mfma(dt, t, st);

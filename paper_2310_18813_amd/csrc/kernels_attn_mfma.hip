@@ -207,7 +207,7 @@ __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a) {
   const T *qrow = (const T *)a.q + (size_t)w.m_row * d + (size_t)hh * HD;
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) qf[kk] = *(const u32x4_v *)(qrow + kk * 32 + 8 * w.g);
-  const size_t cbh = a.kv_one_seq ? (size_t)hh : (size_t)bh;  // whose cache: this group's own sequence, or the one sequence of the pass
+  const size_t cbh = a.seq_groups > 1 ? (size_t)(b / a.seq_groups) * a.H + hh : (size_t)bh;  // whose cache: the group's sequence
   const T *kbase = (const T *)a.kc + cbh * a.L_pad * HD;
   const T *vbase = (const T *)a.vc + cbh * (a.L_pad / KV_VBLOCK) * HD * KV_VBLOCK;
   float m_run, l_run;
@@ -261,7 +261,7 @@ __global__ __launch_bounds__(256) void k_attn_seq(AttnArgs a) {
   const T *qrow = (const T *)a.q + (size_t)w.m_row * d + (size_t)hh * HD;
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) qf[kk] = *(const u32x4_v *)(qrow + kk * 32 + 8 * w.g);
-  const size_t cbh = a.kv_one_seq ? (size_t)hh : (size_t)bh;  // whose cache: this group's own sequence, or the one sequence of the pass
+  const size_t cbh = a.seq_groups > 1 ? (size_t)(b / a.seq_groups) * a.H + hh : (size_t)bh;  // whose cache: the group's sequence
   const T *kbase = (const T *)a.kc + cbh * a.L_pad * HD;
   const T *vbase = (const T *)a.vc + cbh * (a.L_pad / KV_VBLOCK) * HD * KV_VBLOCK;
   float mr = NEG_BIG, lr = 0.f;

@@ -112,10 +112,10 @@ static void gemm_generic(int M, int N, int K, const void *x, const void *W, cons
 // the append of this pass's K/V rows at their absolute positions.  One block per
 // (row, head); thread i handles pair (i, i + hd/2) and two value elements.
 template <class T>
-__global__ void k_rope_append(int q_rows, int one_seq, int H, int hd, int L_pad, int rope, float theta,
+__global__ void k_rope_append(int q_rows, int seq_groups, int H, int hd, int L_pad, int rope, float theta,
                               const float *__restrict__ y /*[M][3d]*/, const int32_t *__restrict__ row_pos,
                               T *__restrict__ qout, T *__restrict__ kc, T *__restrict__ vc) {
-  const int m = blockIdx.x, hh = blockIdx.y, b = one_seq ? 0 : m / q_rows;
+  const int m = blockIdx.x, hh = blockIdx.y, b = m / q_rows / seq_groups;  // the row group's sequence
   const int d = H * hd, half = hd >> 1;
   const int pos = row_pos[m];
   const float *yq = y + (size_t)m * 3 * d + (size_t)hh * hd;
@@ -149,11 +149,11 @@ __global__ void k_rope_append(int q_rows, int one_seq, int H, int hd, int L_pad,
 // order per lane followed by a fixed butterfly, so the result depends on (sequence,
 // position) only.
 template <class T>
-__global__ void k_attn_generic(int q_rows, int one_seq, int H, int hd, int L_pad, const T *__restrict__ qin,
+__global__ void k_attn_generic(int q_rows, int seq_groups, int H, int hd, int L_pad, const T *__restrict__ qin,
                                const int32_t *__restrict__ row_pos, const T *__restrict__ kc,
                                const T *__restrict__ vc, T *__restrict__ out) {
   extern __shared__ float sc[];  // [pos+1] scores, then [64][hd] is not needed: values reduced via shuffles
-  const int m = blockIdx.x, hh = blockIdx.y, b = one_seq ? 0 : m / q_rows, lane = threadIdx.x;
+  const int m = blockIdx.x, hh = blockIdx.y, b = m / q_rows / seq_groups, lane = threadIdx.x;
   const int d = H * hd;
   const int pos = row_pos[m];
   T *orow = out + (size_t)m * d + (size_t)hh * hd;
@@ -283,7 +283,7 @@ void generic_repack_layer(spec_ctx *c, Model &m, int layer, const spec_weights *
 // -------------------------------------------------------------------------
 // One decoder layer over the M rows of the pass (pre-norm residual block).
 template <class T>
-static void generic_layer_t(spec_ctx *c, const Model &m, int layer, int M, int q_rows, int b0, bool one_seq, hipStream_t st) {
+static void generic_layer_t(spec_ctx *c, const Model &m, int layer, int M, int q_rows, int b0, int seq_groups, hipStream_t st) {
   const spec_model_desc &D = m.desc;
   const int d = D.d_model, f = D.d_ffn, H = D.n_heads, hd = m.hd;
   const LayerW &L = m.layers[layer];
@@ -295,9 +295,9 @@ static void generic_layer_t(spec_ctx *c, const Model &m, int layer, int M, int q
 
   launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, nullptr, st);
   gemm_generic<T>(M, 3 * d, d, ws.x, L.wqkv, L.bqkv, ws.y32, 3 * d, 0, st);
-  hipLaunchKernelGGL(k_rope_append<T>, dim3(M, H), dim3(64), 0, st, q_rows, (int)one_seq, H, hd, m.L_pad,
+  hipLaunchKernelGGL(k_rope_append<T>, dim3(M, H), dim3(64), 0, st, q_rows, seq_groups, H, hd, m.L_pad,
                      (int)(D.pos_kind == SPEC_POS_ROPE), D.rope_theta, ws.y32, ws.row_pos, (T *)ws.q, kc, vc);
-  hipLaunchKernelGGL(k_attn_generic<T>, dim3(M, H), dim3(64), (size_t)m.L_pad * sizeof(float), st, q_rows, (int)one_seq, H, hd,
+  hipLaunchKernelGGL(k_attn_generic<T>, dim3(M, H), dim3(64), (size_t)m.L_pad * sizeof(float), st, q_rows, seq_groups, H, hd,
                      m.L_pad, (const T *)ws.q, ws.row_pos, kc, vc, (T *)ws.attn);
   gemm_generic<T>(M, d, d, ws.attn, L.wo, L.bo, ws.h, d, 1, st);
 
@@ -310,8 +310,8 @@ static void generic_layer_t(spec_ctx *c, const Model &m, int layer, int M, int q
   gemm_generic<T>(M, d, f, ws.act, L.w2, L.b2, ws.h, d, 1, st);
 }
 
-void generic_layer(spec_ctx *c, const Model &m, int layer, int M, int q_rows, int b0, bool one_seq, hipStream_t st) {
-  SPEC_DISPATCH_DTYPE(c->run.dtype, T, generic_layer_t<T>(c, m, layer, M, q_rows, b0, one_seq, st));
+void generic_layer(spec_ctx *c, const Model &m, int layer, int M, int q_rows, int b0, int seq_groups, hipStream_t st) {
+  SPEC_DISPATCH_DTYPE(c->run.dtype, T, generic_layer_t<T>(c, m, layer, M, q_rows, b0, seq_groups, st));
 }
 
 // Final norm over the rows that need logits, then the LM head into fp32 logits [Mh][vocab].

@@ -18,13 +18,15 @@ namespace spec {
 // Verification rows follow Alg. 1's call LLM(S, t_1..t_s): pending token, then proposals.
 template <class T>
 __global__ void k_assemble_embed(int kind, int q, int j, int P, int s_max, int L_max, int vocab, int d,
-                                 int learned_pos, int one_seq, const int32_t *__restrict__ seq, const int32_t *__restrict__ n,
+                                 int learned_pos, int seq_groups, const int32_t *__restrict__ seq, const int32_t *__restrict__ n,
                                  const int32_t *__restrict__ kv_draft, const int32_t *__restrict__ t,
                                  const int32_t *__restrict__ seq_s,
                                  const T *__restrict__ tok_emb, const T *__restrict__ pos_emb,
                                  int32_t *__restrict__ row_tok, int32_t *__restrict__ row_pos, float *__restrict__ h) {
-  // one_seq (prefill of a single sequence): every row belongs to the sequence the pointers start at
-  const int m = blockIdx.x, b = one_seq ? 0 : m / q, i = one_seq ? m : m % q;
+  // prefill with several row groups per sequence: group = m / q, sequence = group / seq_groups, and the row's
+  // offset from the pass's base position counts the sequence's earlier groups
+  const int m = blockIdx.x, grp = m / q;
+  const int b = grp / seq_groups, i = (grp % seq_groups) * q + m % q;
   int tok = 0, pos = -1;
   const int nb = n[b];
   // a sequence with its own cap s_b on the speculation length: its rows for proposals beyond s_b are dead
@@ -65,7 +67,7 @@ void launch_assemble_embed(const spec_ctx *c, const Model &m, const PassArgs &pa
   SPEC_DISPATCH_DTYPE(c->run.dtype, T,
     hipLaunchKernelGGL(k_assemble_embed<T>, dim3(M), dim3(256), 0, st, (int)pa.kind, pa.q, pa.j, pa.P,
                        c->run.s_max, c->run.L_max, m.desc.vocab, m.desc.d_model,
-                       (int)(m.desc.pos_kind == SPEC_POS_LEARNED), (int)pa.one_seq,
+                       (int)(m.desc.pos_kind == SPEC_POS_LEARNED), pa.seq_groups,
                        c->st.seq + (size_t)pa.b0 * c->run.L_max,
                        c->st.n + pa.b0, c->drf.kv_len ? c->drf.kv_len + pa.b0 : nullptr,
                        c->st.t + (size_t)pa.b0 * c->run.s_max, c->seq_s ? c->seq_s + pa.b0 : nullptr,

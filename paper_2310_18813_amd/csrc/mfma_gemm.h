@@ -46,7 +46,7 @@ struct GemmArgs {
   const int32_t *row_pos;    // EPI_QKV: absolute position per row, -1 = dead row
   const float2 *rope;        // EPI_QKV: (cos, sin) table [L][hd/2] or null
   int q_rows, d, hd, H, L_pad;
-  int kv_one_seq;            // EPI_QKV: all rows belong to the sequence the cache pointers start at
+  int seq_groups;            // EPI_QKV: consecutive groups of q_rows rows per sequence (0 or 1: one)
   void *act;                 // EPI_SWIGLU / EPI_RELU: fp16, fragment order, row length f (resp. N)
   int f;
   float *logits;             // EPI_LOGITS: optional [M][N] fp32
@@ -90,7 +90,7 @@ struct AttnArgs {
   float *part_ml;           // [M][H][NC][2] running max (raw score units) and sum
   int shape;                // 0 auto, 1 split + merge, 2 one wave per (sequence, head)
   int B, q_rows, H, hd, L_pad, NC;  // NC = chunks launched (upper bound over the batch)
-  int kv_one_seq;           // all B groups of q_rows rows read the cache of the sequence the pointers start at
+  int seq_groups;           // consecutive groups of q_rows rows that belong to one sequence and share its cache (0 or 1: one)
 };
 constexpr int ATTN_CHUNK = 256;  // keys per split; boundaries at multiples of this position
 constexpr int ATTN_SEQ_MIN_PAIRS = 1024;  // (sequence, head) pairs from which one wave walks all chunks

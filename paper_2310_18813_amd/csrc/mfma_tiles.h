@@ -85,7 +85,7 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int 
       int b = (int)(((float)m + 0.5f) * (1.0f / (float)a.q_rows));
       b += ((b + 1) * a.q_rows <= m) ? 1 : 0;
       b -= (b * a.q_rows > m) ? 1 : 0;
-      if (a.kv_one_seq) b = 0;
+      if (a.seq_groups > 1) b /= a.seq_groups;  // prefill passes only
       if (region < 2) {
         float r0 = v[0], r1 = v[1], r2 = v[2], r3 = v[3];
         if (a.rope && pos >= 0) {

@@ -357,8 +357,8 @@ static int forward_pass(spec_ctx *c, Model &m, const PassArgs &pa, HeadMode head
   if (dump) generic_copy(c->ws.h, dump, hbytes, st);
   if (m.fast && m.fold_norm) { KScope k(c, &m == &c->tgt ? SPEC_KCLASS_NORM : -1); launch_row_prep(c, m, M, st); }
   for (int l = 0; l < m.desc.n_layers; ++l) {
-    if (m.fast) fast_layer(c, m, l, pa.B, pa.q, pa.b0, pa.one_seq, max_pos, st);
-    else generic_layer(c, m, l, M, pa.q, pa.b0, pa.one_seq, st);
+    if (m.fast) fast_layer(c, m, l, pa.B, pa.q, pa.b0, pa.seq_groups, max_pos, st);
+    else generic_layer(c, m, l, M, pa.q, pa.b0, pa.seq_groups, st);
     if (dump) generic_copy(c->ws.h, (char *)dump + (size_t)(l + 1) * hbytes, hbytes, st);
   }
   if (head != HEAD_NONE) {
@@ -374,6 +374,26 @@ static int forward_pass(spec_ctx *c, Model &m, const PassArgs &pa, HeadMode head
     }
   }
   HIPCHK(c, hipGetLastError());
+  return SPEC_OK;
+}
+
+// ------------------------------------------------------------------ prefill
+// The first P-1 prompt tokens of the sequences at slots b0 .. b0+B-1 through both models, in passes of up to
+// M_max rows.  A sequence's share of a pass is cut into groups of Q_LIMIT rows (the attention query tile) at
+// consecutive positions; all groups of a sequence read and write that sequence's cache, so few sequences with
+// long prompts need few passes over the weights (one sequence, M_max >= P-1: a single pass).
+static int prefill(spec_ctx *c, int b0, int B) {
+  const int P = c->P, per = std::max(1, c->M_max / B);
+  const int q = std::min(Q_LIMIT, per), g = std::max(1, per / q);
+  for (int base = 0; base < P - 1; base += g * q) {
+    const int left = P - 1 - base;
+    const int gp = std::min(g, (left + q - 1) / q);          // groups per sequence that still hold positions
+    PassArgs pa{PASS_PREFILL, B * gp, q, base, P, c->run.s_max, c->run.L_max, b0, gp};
+    const int max_pos = base + std::min(left, gp * q) - 1;
+    int rc = forward_pass(c, c->tgt, pa, HEAD_NONE, nullptr, nullptr, 0, max_pos);
+    if (!rc && c->drf.present) rc = forward_pass(c, c->drf, pa, HEAD_NONE, nullptr, nullptr, 0, max_pos);
+    if (rc) return rc;
+  }
   return SPEC_OK;
 }
 
@@ -400,13 +420,8 @@ static int do_reset(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32_t P, 
   c->proposals_ready = false;
   launch_state_reset(c, d_prompt, c->stream);
   if (prefill) {
-    const int chunk = std::max(1, std::min(Q_LIMIT, c->M_max / B));
-    for (int base = 0; base < P - 1; base += chunk) {
-      PassArgs pa{PASS_PREFILL, B, std::min(chunk, P - 1 - base), base, P, c->run.s_max, c->run.L_max};
-      int rc = forward_pass(c, c->tgt, pa, HEAD_NONE, nullptr, nullptr, 0, base + chunk - 1);
-      if (!rc && c->drf.present) rc = forward_pass(c, c->drf, pa, HEAD_NONE, nullptr, nullptr, 0, base + chunk - 1);
-      if (rc) return rc;
-    }
+    int rc = ::prefill(c, 0, B);
+    if (rc) return rc;
   }
   HIPCHK(c, hipGetLastError());
   return SPEC_OK;
@@ -431,18 +446,8 @@ extern "C" int spec_admit(spec_ctx *c, int32_t b, const int32_t *d_prompt) {
     return fail(c, SPEC_ERR_STATE, "spec_admit: a round is in progress; finish it with spec_accept_commit first");
   const int P = c->P;
   launch_state_admit(c, b, d_prompt, c->stream);
-  // The prompt goes through in passes of up to M_max rows, all of this one sequence: groups of Q_LIMIT rows
-  // (the attention query tile) at consecutive positions that share the slot's cache, so a prompt of up to
-  // M_max tokens costs one pass over the weights.
-  const int cap = c->M_max >= Q_LIMIT ? c->M_max / Q_LIMIT * Q_LIMIT : c->M_max;
-  for (int base = 0; base < P - 1; base += cap) {
-    const int rows = std::min(cap, P - 1 - base);
-    const int q = std::min(rows, Q_LIMIT), groups = (rows + q - 1) / q;
-    PassArgs pa{PASS_PREFILL, groups, q, base, P, c->run.s_max, c->run.L_max, b, true};
-    int rc = forward_pass(c, c->tgt, pa, HEAD_NONE, nullptr, nullptr, 0, base + rows - 1);
-    if (!rc && c->drf.present) rc = forward_pass(c, c->drf, pa, HEAD_NONE, nullptr, nullptr, 0, base + rows - 1);
-    if (rc) return rc;
-  }
+  int rc = prefill(c, b, 1);
+  if (rc) return rc;
   HIPCHK(c, hipGetLastError());
   return SPEC_OK;
 }

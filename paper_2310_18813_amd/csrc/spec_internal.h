@@ -168,7 +168,8 @@ struct PassArgs {
   int P;         // prompt length (PASS_PREFILL)
   int s_max, L_max;
   int b0 = 0;    // first batch slot of the pass: its rows are the sequences b0 .. b0 + B - 1
-  bool one_seq = false;  // PASS_PREFILL: all B*q rows belong to the sequence at slot b0, row m at position base + m
+  int seq_groups = 1;  // PASS_PREFILL: this many consecutive groups of q rows belong to one sequence (B counts groups):
+                       // group g of a sequence holds positions base + g*q .. and all its groups share the sequence's cache
 };
 
 void launch_assemble_embed(const spec_ctx *c, const Model &m, const PassArgs &pa, hipStream_t st);
@@ -189,7 +190,7 @@ void launch_head_rows(spec_ctx *c, int B, int q, bool last_only, hipStream_t st)
 // generic kernels (any dtype, any shape)
 void generic_repack_top(spec_ctx *c, Model &m, const spec_weights *w, void *&cursor, hipStream_t st);
 void generic_repack_layer(spec_ctx *c, Model &m, int layer, const spec_weights *w, void *&cursor, hipStream_t st);
-void generic_layer(spec_ctx *c, const Model &m, int layer, int M, int q_rows, int b0, bool one_seq, hipStream_t st);
+void generic_layer(spec_ctx *c, const Model &m, int layer, int M, int q_rows, int b0, int seq_groups, hipStream_t st);
 void generic_head(spec_ctx *c, const Model &m, int Mh, float *logits, hipStream_t st);
 size_t generic_packed_bytes(const spec_model_desc &d, int dtype);
 void generic_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
@@ -201,7 +202,7 @@ size_t dtype_bytes(int dtype);
 bool fast_supported(const spec_model_desc &D, int dtype);
 size_t fast_packed_bytes(const spec_model_desc &D, int dtype, int L_max);
 bool fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&cursor, hipStream_t st);  // false: HIP error
-void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b0, bool one_seq, int max_pos, hipStream_t st);
+void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b0, int seq_groups, int max_pos, hipStream_t st);
 void fast_head(spec_ctx *c, const Model &m, int Mh, float *logits_or_null, int q, int arg_stride, int32_t *arg_out,
                hipStream_t st);
 
