@@ -164,6 +164,10 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": dbytes / dur / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
+    # the same against what a pure load stream and back-to-back MFMA issue reach on this GPU (spec_measure_peaks)
+    hbm_meas, mfma_meas = B.spec_measure_peaks("cuda:0", 1 << 30)
+    roof["peak_measured"] = hbm_meas if roof["bound"] == "hbm" else mfma_meas
+    roof["frac_of_measured"] = roof["achieved"] / roof["peak_measured"]
     roof["traffic"] = PMC_TRAFFIC.get((dom, M))
     roof["kernel"] = dom
     roof["avg_us"] = per_class[dom]["avg_us"]
@@ -202,6 +206,7 @@ def main():
                    "batch": nB, "s_star": s_star, "rows_per_verify": M, "accepted_hist": hist,
                    "tokens_per_round_per_seq": tokens / K / nB},
         "roofline": roof,
+        "measured_peaks": {"hbm_stream_GBs": round(hbm_meas, 1), "mfma_f16_TFLOPs": round(mfma_meas, 1)},
         "cpu_baseline": cpu,
         "kernels": per_class,
         "lut": {str(b): s for b, s in zip(B_list, lut)},

@@ -245,6 +245,14 @@ int spec_kv_export(spec_ctx *ctx, int32_t which_model, int32_t layer, int32_t B,
    off.  The buffer is the caller's and must hold (n_layers + 1) * B_max * 16 * d_model floats. */
 int spec_set_hidden_dump(spec_ctx *ctx, float *d_hidden);
 
+/* Measurement aid: what this GPU delivers, for roofline fractions against measured as well as nominal peaks.
+   Streams d_buf (device, 16-byte aligned, `bytes` long; at least 64 KB per compute unit, a few hundred MB
+   to be beyond every cache) once per repetition with plain 16-byte loads, and issues the GEMM kernels' MFMA
+   instruction (f32 += f16 x f16, 16x16x32) back to back on every SIMD; the best of two timed repetitions of
+   each goes to *h_hbm_gbs (GB/s) and *h_mfma_tflops (TFLOP/s).  The buffer is only read.  Runs on hip_stream
+   and waits for it.  Needs no context.  SPEC_ERR_CAPACITY if the buffer is too small.                       */
+int spec_measure_peaks(void *hip_stream, void *d_buf, size_t bytes, double *h_hbm_gbs, double *h_mfma_tflops);
+
 /* Test aid: pin the launch shape of the 16-bit verify attention.  0 = chosen from the batch size
    (default), 1 = one wave per (sequence, head, chunk) plus a merge kernel, 2 = one wave per
    (sequence, head).  Results must not depend on it.                                          */

@@ -29,7 +29,7 @@ EXPORTS = ["spec_last_error", "spec_workspace_bytes", "spec_init", "spec_destroy
            "spec_set_proposals", "spec_draft_step", "spec_verify_step", "spec_accept_commit", "spec_round",
            "spec_profile_and_choose_s", "spec_set_lut", "spec_choose_s", "spec_read_output",
            "spec_read_state", "spec_kv_import", "spec_kv_export", "spec_kernel_timing",
-           "spec_read_kernel_timing", "spec_set_hidden_dump", "spec_set_attention_shape"]
+           "spec_read_kernel_timing", "spec_set_hidden_dump", "spec_set_attention_shape", "spec_measure_peaks"]
 KCLASS_NAMES = ["gemm_qkv", "gemm_o", "gemm_ffn_in", "gemm_ffn_out", "gemm_head", "attention", "norm", "other",
                 "draft_pass"]
 
@@ -79,6 +79,7 @@ lib.spec_set_hidden_dump.argtypes = [_vp, _vp]
 lib.spec_set_attention_shape.argtypes = [_vp, _i32]
 lib.spec_kernel_timing.argtypes = [_vp, _i32]
 lib.spec_read_kernel_timing.argtypes = [_vp, _i64p, C.POINTER(C.c_double)]
+lib.spec_measure_peaks.argtypes = [_vp, _vp, C.c_size_t, C.POINTER(C.c_double), C.POINTER(C.c_double)]
 
 
 class SpecError(RuntimeError):
@@ -116,6 +117,17 @@ def make_weights(w):
     s = Weights(_dp(w["tok_emb"]), _dp(w.get("pos_emb")), _dp(w["final_norm_w"]), _dp(w.get("final_norm_b")),
                 _dp(w["lm_head"]), C.cast(arr, C.POINTER(C.c_void_p)))
     return s, arr
+
+
+def spec_measure_peaks(device="cuda:0", nbytes=1 << 30):
+    """-> (HBM stream GB/s, MFMA f16 TFLOP/s) measured on the device, over a scratch tensor of nbytes."""
+    dev = torch.device(device)
+    buf = torch.arange(nbytes // 8, dtype=torch.int64, device=dev).mul_(0x9E3779B97F4A7C15 - (1 << 64))  # not all zeros
+    g, t = C.c_double(0.0), C.c_double(0.0)
+    with torch.cuda.device(dev):
+        st = torch.cuda.current_stream(dev)
+        _check(lib.spec_measure_peaks(C.c_void_p(st.cuda_stream), _dp(buf), buf.numel() * 8, C.byref(g), C.byref(t)))
+    return g.value, t.value
 
 
 def spec_workspace_bytes(tgt_desc, drf_desc, run):
