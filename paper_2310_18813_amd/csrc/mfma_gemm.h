@@ -93,6 +93,7 @@ struct AttnArgs {
   int seq_groups;           // consecutive groups of q_rows rows that belong to one sequence and share its cache (0 or 1: one)
 };
 constexpr int ATTN_CHUNK = 256;  // keys per split; boundaries at multiples of this position
+constexpr int ATTN_STREAM_MIN_WAVES = 1024;  // (sequence, head, chunk) waves from which the split kernel loads non-temporally
 constexpr int ATTN_SEQ_MIN_PAIRS = 1024;  // (sequence, head) pairs from which one wave walks all chunks
 void launch_attention_mfma(int dtype, const AttnArgs &a, hipStream_t st);
 
