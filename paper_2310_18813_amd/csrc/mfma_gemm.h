@@ -94,7 +94,7 @@ struct AttnArgs {
 };
 constexpr int ATTN_CHUNK = 256;  // keys per split; boundaries at multiples of this position
 constexpr int ATTN_STREAM_MIN_WAVES = 1024;  // (sequence, head, chunk) waves from which the split kernel loads non-temporally
-constexpr int ATTN_SEQ_MIN_PAIRS = 1024;  // (sequence, head) pairs from which one wave walks all chunks
+constexpr int ATTN_SEQ_MIN_PAIRS = 768;   // (sequence, head) pairs from which one wave walks all chunks (measured: 24 sequences x 32 heads 55 -> 45 us)
 void launch_attention_mfma(int dtype, const AttnArgs &a, hipStream_t st);
 
 }  // namespace spec
