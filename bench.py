@@ -182,8 +182,9 @@ def main():
     curve = {}
     for i, b in enumerate([] if args.no_curve else B_list):
         s_b = ctx.spec_choose_s(b)
-        tk, tt, _ = run_timed(b, s_b, max(4, N // (s_b + 1) // 2), 1)
-        entry = {"s_star": s_b, "tokens_per_s": tk / tt}
+        tk, tt, hb = run_timed(b, s_b, max(4, N // (s_b + 1) // 2), 1)
+        entry = {"s_star": s_b, "tokens_per_s": tk / tt,
+                 "mean_accepted": round(sum(l * c for l, c in enumerate(hb)) / max(1, sum(hb)), 3)}
         if grid is not None:
             entry["us_per_token_by_s"] = [round(x, 2) for x in grid[i]]
             entry["best_fixed_s"] = int(np.argmin(grid[i]))
