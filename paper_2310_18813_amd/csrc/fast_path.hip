@@ -201,8 +201,8 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
   auto produce_norm = [&](GemmArgs &a) {
     if (fold) { a.ss_out = ws.part_ss; a.x_out = ws.x; }
   };
-  if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, nullptr, st); }
-  else row_inv_now();
+  if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, 0, st); }
+  else if (layer > 0) row_inv_now();  // in front of layer 0 the embedding kernel has left 1 / rms of every row
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_QKV : -1);
     GemmArgs a = base_args(m.p_qkv, L.wqkv, L.s_qkv, L.bqkv, ws.x, M);
@@ -229,7 +229,7 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
     produce_norm(a);
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
   }
-  if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, nullptr, st); }
+  if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, 0, st); }
   else row_inv_now();
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_FFN_IN : -1);
@@ -248,10 +248,10 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
 }
 
 // Final norm over the rows that need a token, LM head with the arg-max fused in.
-void fast_head(spec_ctx *c, const Model &m, int Mh, float *logits_or_null, int q, int arg_stride, int32_t *arg_out,
+void fast_head(spec_ctx *c, const Model &m, int Mh, int last_of_q, float *logits_or_null, int q, int arg_stride, int32_t *arg_out,
                hipStream_t st) {
   const bool tgt = &m == &c->tgt;
-  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, c->ws.head_rows, st); }
+  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, last_of_q, st); }
   GemmArgs a = base_args(m.p_head, m.lm_head, m.s_head, nullptr, c->ws.x, Mh);
   a.logits = logits_or_null;
   a.part_val = c->ws.head_part;

@@ -293,7 +293,7 @@ static void generic_layer_t(spec_ctx *c, const Model &m, int layer, int M, int q
   T *kc = (T *)((char *)m.kcache + ((size_t)layer * m.kv_area_elems + slot0) * esz);
   T *vc = (T *)((char *)m.vcache + ((size_t)layer * m.kv_area_elems + slot0) * esz);
 
-  launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, nullptr, st);
+  launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, 0, st);
   gemm_generic<T>(M, 3 * d, d, ws.x, L.wqkv, L.bqkv, ws.y32, 3 * d, 0, st);
   hipLaunchKernelGGL(k_rope_append<T>, dim3(M, H), dim3(64), 0, st, q_rows, seq_groups, H, hd, m.L_pad,
                      (int)(D.pos_kind == SPEC_POS_ROPE), D.rope_theta, ws.y32, ws.row_pos, (T *)ws.q, kc, vc);
@@ -301,7 +301,7 @@ static void generic_layer_t(spec_ctx *c, const Model &m, int layer, int M, int q
                      m.L_pad, (const T *)ws.q, ws.row_pos, kc, vc, (T *)ws.attn);
   gemm_generic<T>(M, d, d, ws.attn, L.wo, L.bo, ws.h, d, 1, st);
 
-  launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, nullptr, st);
+  launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, 0, st);
   const bool swi = D.ffn_kind == SPEC_FFN_SWIGLU;
   gemm_generic<T>(M, swi ? 2 * f : f, d, ws.x, L.w13, L.b13, ws.y32, swi ? 2 * f : f, 0, st);
   size_t tot = (size_t)M * f;
@@ -315,8 +315,8 @@ void generic_layer(spec_ctx *c, const Model &m, int layer, int M, int q_rows, in
 }
 
 // Final norm over the rows that need logits, then the LM head into fp32 logits [Mh][vocab].
-void generic_head(spec_ctx *c, const Model &m, int Mh, float *logits, hipStream_t st) {
-  launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, c->ws.head_rows, st);
+void generic_head(spec_ctx *c, const Model &m, int Mh, int last_of_q, float *logits, hipStream_t st) {
+  launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, last_of_q, st);
   SPEC_DISPATCH_DTYPE(c->run.dtype, T,
     gemm_generic<T>(Mh, m.desc.vocab, m.desc.d_model, c->ws.x, m.lm_head, nullptr, logits, m.desc.vocab, 0, st));
 }

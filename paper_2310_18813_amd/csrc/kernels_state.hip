@@ -2,6 +2,7 @@
 // norms, arg-max, acceptance/commit, proposal handling, reset/rewind, KV import/export.
 #include "spec_internal.h"
 #include "device_utils.h"
+#include "mfma_tiles.h"
 
 // No implicit fusing of multiplies and adds: which product a compiler folds into an FMA can
 // differ between two instantiations of the same source, and results here must be bit-identical
@@ -16,13 +17,19 @@ namespace spec {
 // no attention, logits ignored), then gathers the embedding (plus the learned position
 // row for OPT-shape models) into the fp32 residual stream.
 // Verification rows follow Alg. 1's call LLM(S, t_1..t_s): pending token, then proposals.
-template <class T>
-__global__ void k_assemble_embed(int kind, int q, int j, int P, int s_max, int L_max, int vocab, int d,
+// PREP (models whose RMS norm is folded into the GEMMs): the kernel also leaves what the first layer's QKV GEMM
+// consumes — the fp16 copy of the row in fragment order, its per-strip sums of squares exactly as the residual
+// epilogues leave them behind every later GEMM (four consecutive elements per thread, chain of fused
+// multiply-adds, the strip's four groups added as (g0 + g1) + (g2 + g3)), and 1 / rms of the row as k_row_inv
+// computes it in front of the later layers.
+template <class T, bool PREP>
+__global__ __launch_bounds__(256) void k_assemble_embed(int kind, int q, int j, int P, int s_max, int L_max, int vocab, int d,
                                  int learned_pos, int seq_groups, const int32_t *__restrict__ seq, const int32_t *__restrict__ n,
                                  const int32_t *__restrict__ kv_draft, const int32_t *__restrict__ t,
                                  const int32_t *__restrict__ seq_s,
                                  const T *__restrict__ tok_emb, const T *__restrict__ pos_emb,
-                                 int32_t *__restrict__ row_tok, int32_t *__restrict__ row_pos, float *__restrict__ h) {
+                                 int32_t *__restrict__ row_tok, int32_t *__restrict__ row_pos, float *__restrict__ h,
+                                 op_t *__restrict__ x, float *__restrict__ ss, float *__restrict__ rinv, float eps) {
   // prefill with several row groups per sequence: group = m / q, sequence = group / seq_groups, and the row's
   // offset from the pass's base position counts the sequence's earlier groups
   const int m = blockIdx.x, grp = m / q;
@@ -52,26 +59,54 @@ __global__ void k_assemble_embed(int kind, int q, int j, int P, int s_max, int L
   tok = min(max(tok, 0), vocab - 1);
   if (threadIdx.x == 0) { row_tok[m] = tok; row_pos[m] = pos; }
   float *hr = h + (size_t)m * d;
-  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+  auto value = [&](int c) {
     float e = 0.f;
     if (pos >= 0) {
       e = Conv<T>::ld(tok_emb, (size_t)tok * d + c);
       if (learned_pos) e += Conv<T>::ld(pos_emb, (size_t)pos * d + c);
     }
-    hr[c] = e;
+    return e;
+  };
+  if (!PREP) {
+    for (int c = threadIdx.x; c < d; c += blockDim.x) hr[c] = value(c);
+    return;
+  }
+  // four consecutive elements per thread; d is a multiple of 32, so a group of four threads (one strip of 16)
+  // is in or out of the loop together
+  const int nv = d >> 2, nt = d >> 4;
+  for (int c0 = 0; c0 < nv; c0 += 256) {
+    const int c = c0 + threadIdx.x;
+    if (c < nv) {
+      const float4 o = make_float4(value(4 * c), value(4 * c + 1), value(4 * c + 2), value(4 * c + 3));
+      *(float4 *)(hr + 4 * c) = o;
+      op_t o4[4] = {to_op(o.x), to_op(o.y), to_op(o.z), to_op(o.w)};
+      *(uint2 *)(x + xpack_index(m, 4 * c, d >> 5)) = *(const uint2 *)o4;
+      float p = o.x * o.x;
+      p = fmaf(o.y, o.y, p); p = fmaf(o.z, o.z, p); p = fmaf(o.w, o.w, p);
+      p += __shfl_xor(p, 1, 64);
+      p += __shfl_xor(p, 2, 64);
+      if ((c & 3) == 0) ss[(size_t)m * nt + (c >> 2)] = p;
+    }
+  }
+  __syncthreads();  // the strip sums of the row are written (and visible to this workgroup)
+  if (threadIdx.x < 64) {
+    const float v = row_inv_rms(ss + (size_t)m * nt, nt, d, eps, threadIdx.x);
+    if (threadIdx.x == 0) rinv[m] = v;
   }
 }
 
 void launch_assemble_embed(const spec_ctx *c, const Model &m, const PassArgs &pa, hipStream_t st) {
   const int M = pa.B * pa.q;
+  const bool prep = m.fast && m.fold_norm;
   SPEC_DISPATCH_DTYPE(c->run.dtype, T,
-    hipLaunchKernelGGL(k_assemble_embed<T>, dim3(M), dim3(256), 0, st, (int)pa.kind, pa.q, pa.j, pa.P,
+    hipLaunchKernelGGL((prep ? k_assemble_embed<T, true> : k_assemble_embed<T, false>), dim3(M), dim3(256), 0, st, (int)pa.kind, pa.q, pa.j, pa.P,
                        c->run.s_max, c->run.L_max, m.desc.vocab, m.desc.d_model,
                        (int)(m.desc.pos_kind == SPEC_POS_LEARNED), pa.seq_groups,
                        c->st.seq + (size_t)pa.b0 * c->run.L_max,
                        c->st.n + pa.b0, c->drf.kv_len ? c->drf.kv_len + pa.b0 : nullptr,
                        c->st.t + (size_t)pa.b0 * c->run.s_max, c->seq_s ? c->seq_s + pa.b0 : nullptr,
-                       (const T *)m.tok_emb, (const T *)m.pos_emb, c->ws.row_tok, c->ws.row_pos, c->ws.h));
+                       (const T *)m.tok_emb, (const T *)m.pos_emb, c->ws.row_tok, c->ws.row_pos, c->ws.h,
+                       (op_t *)c->ws.x, c->ws.part_ss, c->ws.row_inv, m.desc.norm_eps));
 }
 
 // -------------------------------------------------------------------------
@@ -94,11 +129,12 @@ constexpr int NORM_MAX_V4 = 8;  // d <= 8192
 template <class T>
 __global__ __launch_bounds__(256) void k_norm(int kind, int d, float eps, const float *__restrict__ h,
                                               const T *__restrict__ gain, const T *__restrict__ bias,
-                                              const int32_t *__restrict__ gather, void *__restrict__ x,
+                                              int last_of_q, void *__restrict__ x,
                                               int pack_kt) {
   __shared__ float sh[4];
   const int r = blockIdx.x;
-  const float4 *hr = (const float4 *)(h + (size_t)(gather ? gather[r] : r) * d);
+  // last_of_q > 0: output row r is the last of input rows r * q .. r * q + q - 1 (the rows that need a token)
+  const float4 *hr = (const float4 *)(h + (size_t)(last_of_q > 0 ? r * last_of_q + last_of_q - 1 : r) * d);
   const int nv = d >> 2;
   float4 v[NORM_MAX_V4];
 #pragma unroll
@@ -149,40 +185,13 @@ __global__ __launch_bounds__(256) void k_norm(int kind, int d, float eps, const 
   }
 }
 
-// Folded-norm models, in front of the first layer: the fp16 copy of the embedded rows in fragment order and
-// their per-strip sums of squares, exactly as the residual epilogues leave them behind every later GEMM
-// (four consecutive elements per thread, chain of fused multiply-adds, the strip's four groups added as
-// (g0 + g1) + (g2 + g3)).
-__global__ __launch_bounds__(256) void k_row_prep(int d, const float *__restrict__ h, op_t *__restrict__ x,
-                                                  float *__restrict__ ss) {
-  const int r = blockIdx.x, nv = d >> 2;
-  const float4 *hr = (const float4 *)(h + (size_t)r * d);
-  for (int c0 = 0; c0 < nv; c0 += 256) {   // nv is a multiple of 4: a group of four threads is in or out together
-    const int c = c0 + threadIdx.x;
-    if (c < nv) {
-      const float4 o = hr[c];
-      op_t o4[4] = {to_op(o.x), to_op(o.y), to_op(o.z), to_op(o.w)};
-      *(uint2 *)(x + xpack_index(r, 4 * c, d >> 5)) = *(const uint2 *)o4;
-      float p = o.x * o.x;
-      p = fmaf(o.y, o.y, p); p = fmaf(o.z, o.z, p); p = fmaf(o.w, o.w, p);
-      p += __shfl_xor(p, 1, 64);
-      p += __shfl_xor(p, 2, 64);
-      if ((c & 3) == 0) ss[(size_t)r * (d >> 4) + (c >> 2)] = p;
-    }
-  }
-}
-void launch_row_prep(const spec_ctx *c, const Model &m, int M, hipStream_t st) {
-  if (M <= 0) return;
-  hipLaunchKernelGGL(k_row_prep, dim3(M), dim3(256), 0, st, m.desc.d_model, c->ws.h, (op_t *)c->ws.x, c->ws.part_ss);
-}
-
 void launch_norm(const spec_ctx *c, const Model &m, const float *h, const void *gain, const void *bias, void *x,
-                 int M, const int32_t *row_gather, hipStream_t st) {
+                 int M, int last_of_q, hipStream_t st) {
   if (M <= 0) return;
   const int pack_kt = m.fast ? m.desc.d_model / 32 : 0;
   SPEC_DISPATCH_DTYPE(c->run.dtype, T,
     hipLaunchKernelGGL(k_norm<T>, dim3(M), dim3(256), 0, st, m.desc.norm_kind, m.desc.d_model, m.desc.norm_eps, h,
-                       (const T *)gain, (const T *)bias, row_gather, x, pack_kt));
+                       (const T *)gain, (const T *)bias, last_of_q, x, pack_kt));
 }
 
 // -------------------------------------------------------------------------
@@ -213,18 +222,6 @@ void launch_argmax_rows(const float *logits, int M, int V, int q, int out_stride
 }
 
 // -------------------------------------------------------------------------
-// head_rows: which rows of the pass need logits (all of them for verification, the last
-// row of every sequence for a draft step).
-__global__ void k_head_rows(int B, int q, int last_only, int32_t *__restrict__ rows) {
-  int r = blockIdx.x * blockDim.x + threadIdx.x;
-  int Mh = last_only ? B : B * q;
-  if (r < Mh) rows[r] = last_only ? r * q + q - 1 : r;
-}
-void launch_head_rows(spec_ctx *c, int B, int q, bool last_only, hipStream_t st) {
-  int Mh = last_only ? B : B * q;
-  hipLaunchKernelGGL(k_head_rows, dim3((Mh + 255) / 256), dim3(256), 0, st, B, q, (int)last_only, c->ws.head_rows);
-}
-
 // -------------------------------------------------------------------------
 // Draft step epilogue: in draft-proposal mode the draft's greedy token becomes t_j.
 __global__ void k_store_draft_token(int B, int j, int s_max, int write, const int32_t *__restrict__ arg,

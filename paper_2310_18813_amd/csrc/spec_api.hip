@@ -355,7 +355,6 @@ static int forward_pass(spec_ctx *c, Model &m, const PassArgs &pa, HeadMode head
   float *dump = (&m == &c->tgt) ? c->hidden_dump : nullptr;
   const size_t hbytes = (size_t)M * m.desc.d_model * sizeof(float);
   if (dump) generic_copy(c->ws.h, dump, hbytes, st);
-  if (m.fast && m.fold_norm) { KScope k(c, &m == &c->tgt ? SPEC_KCLASS_NORM : -1); launch_row_prep(c, m, M, st); }
   for (int l = 0; l < m.desc.n_layers; ++l) {
     if (m.fast) fast_layer(c, m, l, pa.B, pa.q, pa.b0, pa.seq_groups, max_pos, st);
     else generic_layer(c, m, l, M, pa.q, pa.b0, pa.seq_groups, st);
@@ -364,12 +363,12 @@ static int forward_pass(spec_ctx *c, Model &m, const PassArgs &pa, HeadMode head
   if (head != HEAD_NONE) {
     const bool last = head == HEAD_LAST;
     const int Mh = last ? pa.B : M;
-    launch_head_rows(c, pa.B, pa.q, last, st);
+    const int last_of_q = last ? pa.q : 0;  // the final norm gathers the rows that need a token
     if (m.fast) {
-      fast_head(c, m, Mh, logits_out, last ? 1 : pa.q, arg_stride, arg_out, st);
+      fast_head(c, m, Mh, last_of_q, logits_out, last ? 1 : pa.q, arg_stride, arg_out, st);
     } else {
       float *lg = logits_out ? logits_out : c->ws.logits;
-      generic_head(c, m, Mh, lg, st);
+      generic_head(c, m, Mh, last_of_q, lg, st);
       launch_argmax_rows(lg, Mh, m.desc.vocab, last ? 1 : pa.q, arg_stride, arg_out, st);
     }
   }
@@ -527,7 +526,7 @@ extern "C" int spec_draft_step(spec_ctx *c, int32_t j) {
     rc = forward_pass(c, c->drf, pa, HEAD_LAST, nullptr, c->st.draft_arg, 1, c->n_ub + j - 2);
   }
   if (rc) return rc;
-  launch_store_draft_token(c, j, !ext, c->stream);
+  if (!ext) launch_store_draft_token(c, j, true, c->stream);  // external proposals: nothing to store
   c->draft_j = j;
   HIPCHK(c, hipGetLastError());
   return SPEC_OK;

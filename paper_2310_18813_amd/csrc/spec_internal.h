@@ -174,8 +174,7 @@ struct PassArgs {
 
 void launch_assemble_embed(const spec_ctx *c, const Model &m, const PassArgs &pa, hipStream_t st);
 void launch_norm(const spec_ctx *c, const Model &m, const float *h, const void *gain, const void *bias, void *x,
-                 int M, const int32_t *row_gather, hipStream_t st);
-void launch_row_prep(const spec_ctx *c, const Model &m, int M, hipStream_t st);
+                 int M, int last_of_q, hipStream_t st);
 void launch_argmax_rows(const float *logits, int M, int V, int q, int out_stride, int32_t *out, hipStream_t st);
 void launch_accept(spec_ctx *c, int s, hipStream_t st);
 void launch_fill_proposals(spec_ctx *c, int s, hipStream_t st);
@@ -185,13 +184,12 @@ void launch_state_reset(spec_ctx *c, const int32_t *d_prompt_or_null, hipStream_
 void launch_state_admit(spec_ctx *c, int b, const int32_t *d_prompt, hipStream_t st);
 void launch_kv_convert(spec_ctx *c, const Model &m, int layer, int B, int len, void *k, void *v, bool import_,
                        hipStream_t st);
-void launch_head_rows(spec_ctx *c, int B, int q, bool last_only, hipStream_t st);
 
 // generic kernels (any dtype, any shape)
 void generic_repack_top(spec_ctx *c, Model &m, const spec_weights *w, void *&cursor, hipStream_t st);
 void generic_repack_layer(spec_ctx *c, Model &m, int layer, const spec_weights *w, void *&cursor, hipStream_t st);
 void generic_layer(spec_ctx *c, const Model &m, int layer, int M, int q_rows, int b0, int seq_groups, hipStream_t st);
-void generic_head(spec_ctx *c, const Model &m, int Mh, float *logits, hipStream_t st);
+void generic_head(spec_ctx *c, const Model &m, int Mh, int last_of_q, float *logits, hipStream_t st);
 size_t generic_packed_bytes(const spec_model_desc &d, int dtype);
 void generic_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
 void generic_zero(void *dst, size_t bytes, hipStream_t st);
@@ -203,7 +201,7 @@ bool fast_supported(const spec_model_desc &D, int dtype);
 size_t fast_packed_bytes(const spec_model_desc &D, int dtype, int L_max);
 bool fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&cursor, hipStream_t st);  // false: HIP error
 void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b0, int seq_groups, int max_pos, hipStream_t st);
-void fast_head(spec_ctx *c, const Model &m, int Mh, float *logits_or_null, int q, int arg_stride, int32_t *arg_out,
-               hipStream_t st);
+void fast_head(spec_ctx *c, const Model &m, int Mh, int last_of_q, float *logits_or_null, int q, int arg_stride,
+               int32_t *arg_out, hipStream_t st);
 
 }  // namespace spec
