@@ -1,0 +1,147 @@
+"""The adaptive choice of the speculation length through the C ABI (Sec. 4): the profiling stage
+(spec_profile_and_choose_s) and the look-up of the execution stage (spec_choose_s, spec_set_lut).
+
+Timings cannot be compared with a CPU oracle, so the checks are: the table the library returns is the
+oracle's arg-min rule applied to the grid the library measured; proposals that are always right make the
+longest profiled length win and the per-token latency fall with s as 1 / (s + 1) would have it; the look-up
+for every batch size is the oracle's nearest-profiled-size rule; and profiling leaves a context that decodes
+the target's greedy continuation."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from helpers import build_pair, truth_table
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+TGT = si.llama_desc(2, 256, 2, 416, 1000, 128)
+DRF = si.llama_desc(1, 128, 2, 160, 1000, 128)
+SEED, P, N, S_MAX, B_MAX = 321, 9, 24, 4, 6
+SIZES = [1, 2, 4, 6]
+
+
+@pytest.fixture(scope="module")
+def orc():
+    from oracle import oracle as om
+    return om.Oracle("f64")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2310_18813_amd import binding
+    return binding
+
+
+def oracle_rule_holds(orc, lut, grid):
+    """The returned table against the oracle's rule on the returned grid.  The library decides on the
+    un-rounded timings and hands the grid back as fp32, so a tie exactly at the 1 % margin may fall either
+    way: both sides of the margin are accepted."""
+    g = np.asarray(grid, dtype=np.float64)
+    lo, hi = orc.lut_build(g, 0.01 - 1e-5), orc.lut_build(g, 0.01 + 1e-5)
+    for i, s in enumerate(lut):
+        assert s in (int(lo[i]), int(hi[i])), (i, s, lo[i], hi[i], g[i])
+
+
+def greedy(ctx, prompts, nB, n):
+    ctx.spec_reset(prompts[:nB])
+    ctx.spec_round(0, n)
+    toks, _ = ctx.spec_read_output()
+    return np.array(toks)
+
+
+def test_profiled_table_with_a_proposal_table(orc, B):
+    ot, od, gt, gd = build_pair(orc, TGT, None, "bf16", SEED, DEV)
+    L_max = P + N + S_MAX + 3
+    ctx = B.Context(TGT, gt, None, None, "bf16", B_MAX, S_MAX, L_max, N, B.PROPOSALS_EXTERNAL, DEV)
+    prompts = si.make_prompts(B_MAX, P, TGT["vocab"], SEED)
+    with pytest.raises(B.SpecError):       # no table yet
+        ctx.spec_profile_and_choose_s(SIZES, S_MAX, prompts, N)
+    ctx.spec_set_proposal_table(np.zeros((B_MAX, L_max), dtype=np.int32))
+    ref = greedy(ctx, prompts, B_MAX, N)
+    truth = truth_table(ref, P, L_max)
+
+    # proposals that are always right: every round emits s + 1 tokens per sequence
+    ctx.spec_set_proposal_table(truth)
+    lut, grid = ctx.spec_profile_and_choose_s(SIZES, S_MAX, prompts, N)
+    g = np.array(grid)
+    assert g.shape == (len(SIZES), S_MAX + 1) and np.all(np.isfinite(g)) and np.all(g > 0)
+    oracle_rule_holds(orc, lut, grid)
+    assert lut == [S_MAX] * len(SIZES), (lut, grid)
+    # a round of s + 1 tokens costs more than a round of one token and less than s + 1 of them
+    for i in range(len(SIZES)):
+        for s in range(1, S_MAX + 1):
+            assert g[i, 0] / (s + 1) * 0.7 < g[i, s] < g[i, 0], (i, s, g[i])
+
+    # the execution stage: every batch size against the oracle's rule
+    for nB in range(1, B_MAX + 5):
+        assert ctx.spec_choose_s(nB) == orc.lut_lookup(SIZES, lut, nB)
+
+    # the context is left rewound on the last profiled batch and decodes the greedy continuation
+    assert ctx.B == SIZES[-1]
+    ctx.spec_round(lut[-1], N)
+    toks, hist = ctx.spec_read_output()
+    assert np.array_equal(np.array(toks), ref[:SIZES[-1]])
+    assert sum(hist[:S_MAX]) <= SIZES[-1]   # all-right proposals: only a sequence's last round can stop early
+
+    # proposals that are always wrong: every round emits one token; only the rule can be checked
+    ctx.spec_set_proposal_table((truth + 1) % TGT["vocab"])
+    lut_w, grid_w = ctx.spec_profile_and_choose_s(SIZES[:2], 2, prompts, 8)
+    oracle_rule_holds(orc, lut_w, grid_w)
+    gw = np.array(grid_w)
+    assert np.all(gw[:, 1:] > 0.8 * gw[:, :1])    # no speed-up from proposals that are never accepted
+    for nB in range(1, B_MAX + 1):
+        assert ctx.spec_choose_s(nB) == orc.lut_lookup(SIZES[:2], lut_w, nB)
+    ctx.close()
+
+
+def test_profiled_table_with_the_draft_model(orc, B):
+    ot, od, gt, gd = build_pair(orc, TGT, DRF, "bf16", SEED, DEV)
+    L_max = P + N + S_MAX + 3
+    ctx = B.Context(TGT, gt, DRF, gd, "bf16", B_MAX, S_MAX, L_max, N, B.PROPOSALS_DRAFT, DEV)
+    prompts = si.make_prompts(B_MAX, P, TGT["vocab"], SEED)
+    ref = greedy(ctx, prompts, B_MAX, N)
+    ctx.spec_set_seq_s([0] * B_MAX)        # caps are set aside while profiling and back afterwards
+    sizes = [2, 5]
+    lut, grid = ctx.spec_profile_and_choose_s(sizes, 3, prompts, 12)
+    oracle_rule_holds(orc, lut, grid)
+    g = np.array(grid)
+    assert np.all(np.isfinite(g)) and np.all(g > 0)
+    for nB in range(1, B_MAX + 3):
+        assert ctx.spec_choose_s(nB) == orc.lut_lookup(sizes, lut, nB)
+    ctx.spec_round(3, 2)
+    _, hist = ctx.spec_read_output()
+    assert sum(hist[1:]) == 0              # the caps (all zero) are in force again
+    ctx.spec_set_seq_s(None)
+    ctx.spec_reset(prompts[:5])
+    ctx.spec_round(lut[-1], N)
+    toks, _ = ctx.spec_read_output()
+    assert np.array_equal(np.array(toks), ref[:5])
+    ctx.close()
+
+
+def test_installed_table_and_argument_checks(orc, B):
+    ot, od, gt, gd = build_pair(orc, TGT, None, "bf16", SEED, DEV)
+    ctx = B.Context(TGT, gt, None, None, "bf16", B_MAX, S_MAX, 48, 8, B.PROPOSALS_EXTERNAL, DEV)
+    with pytest.raises(B.SpecError):
+        ctx.spec_choose_s(1)               # no table yet
+    sizes, lut = [1, 2, 4, 8, 16, 32], [4, 4, 3, 1, 2, 0]
+    ctx.spec_set_lut(sizes, lut)
+    for nB in range(1, 70):
+        assert ctx.spec_choose_s(nB) == orc.lut_lookup(sizes, lut, nB), nB
+    ctx.spec_set_lut([3], [2])
+    assert [ctx.spec_choose_s(nB) for nB in (1, 3, 64)] == [2, 2, 2]
+    for bad_sizes, bad_lut in (([2, 2], [0, 0]), ([4, 2], [0, 0]), ([0, 1], [0, 0]), ([1, 2], [0, S_MAX + 1]),
+                               ([1, 2], [-1, 0])):
+        with pytest.raises(B.SpecError):
+            ctx.spec_set_lut(bad_sizes, bad_lut)
+    assert ctx.spec_choose_s(5) == 2       # a refused table leaves the installed one in place
+    with pytest.raises(B.SpecError):
+        ctx.spec_choose_s(0)
+    prompts = si.make_prompts(B_MAX, 5, TGT["vocab"], SEED)
+    ctx.spec_set_proposal_table(np.zeros((B_MAX, 48), dtype=np.int32))
+    for args in (([1, 2], S_MAX + 1, prompts, 8), ([1, B_MAX + 1], 1, prompts, 8), ([1, 2], 1, prompts, 9),
+                 ([2, 1], 1, prompts, 8), ([1, 2], 1, prompts, 0)):
+        with pytest.raises((B.SpecError, AssertionError)):
+            ctx.spec_profile_and_choose_s(*args)
+    ctx.close()
