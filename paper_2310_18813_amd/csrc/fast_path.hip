@@ -184,25 +184,15 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
   void *vc = (char *)m.vcache + ((size_t)layer * m.kv_area_elems + slot0) * esz;
 
   const bool tgt = &m == &c->tgt;  // only the target model's kernels are timed one by one
-  const bool fold = m.fold_norm;  // then ws.x holds fp16(h) and ws.part_ss the sums of squares, left by the producer of h
-  // up to 16 rows the consumer adds the strip sums up itself, behind its weight stream; beyond, or when a
-  // row has too many strips for its registers, a small kernel does it once per row.  Same function, same bits.
-  const bool inv_kernel = fold && (M > 16 || d / 16 > ROW_INV_INLINE_MAX_NT || m.p_qkv.KS != 8);
+  const bool fold = m.fold_norm;  // then ws.x holds fp16(h), left by the producer of h, and the consumer takes 1 / rms from it
   auto consume_norm = [&](GemmArgs &a) {
     if (!fold) return;
-    a.ss_in = ws.part_ss; a.ss_nt = d / 16; a.ss_d = d; a.ss_eps = D.norm_eps;
-    if (inv_kernel) a.rinv_in = ws.row_inv;
-  };
-  auto row_inv_now = [&]() {
-    if (!inv_kernel) return;
-    KScope k(c, tgt ? SPEC_KCLASS_NORM : -1);
-    launch_row_inv(ws.part_ss, M, d / 16, d, D.norm_eps, ws.row_inv, st);
+    a.fold_x = 1; a.ss_d = d; a.ss_eps = D.norm_eps; a.rinv_ws = ws.row_inv;
   };
   auto produce_norm = [&](GemmArgs &a) {
-    if (fold) { a.ss_out = ws.part_ss; a.x_out = ws.x; }
+    if (fold) a.x_out = ws.x;
   };
   if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, 0, st); }
-  else if (layer > 0) row_inv_now();  // in front of layer 0 the embedding kernel has left 1 / rms of every row
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_QKV : -1);
     GemmArgs a = base_args(m.p_qkv, L.wqkv, L.s_qkv, L.bqkv, ws.x, M);
@@ -230,7 +220,6 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
   }
   if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, 0, st); }
-  else row_inv_now();
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_FFN_IN : -1);
     GemmArgs a = base_args(m.p_13, L.w13, L.s_13, L.b13, ws.x, M);

@@ -226,31 +226,11 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
 
-  // Folded norm without a k_row_inv launch (8 waves): wave w owns rows w, w + 8, ... of the pass.  Their
-  // strip sums are fetched now and added up after the k loop, so the round trip hides behind the weight
-  // stream.
-  constexpr bool INLINE_INV = MT == 1 && EPI != EPI_RESIDUAL;
-  constexpr int INV_LD = ROW_INV_INLINE_LOADS, INV_ROWS = 2;
-  float pre[INLINE_INV ? INV_ROWS : 1][INLINE_INV ? INV_LD : 1];
-  const bool inline_inv = INLINE_INV && a.ss_in && !a.rinv_in;
-  float rv[MT];  // 1 / rms of this lane's rows when k_row_inv left them: fetched now, used in the epilogue
+  constexpr bool FOLDX = EPI == EPI_QKV || EPI == EPI_SWIGLU;  // the GEMMs behind an RMS norm
+  const bool foldx = FOLDX && a.fold_x;
+  float ssq[MT];  // this lane's part of the sum of squares of its rows over the wave's k-slice
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    const int m = m_base + mt * 16 + c;
-    rv[mt] = (EPI != EPI_RESIDUAL && a.ss_in && a.rinv_in && m < a.M) ? a.rinv_in[m] : 1.0f;
-  }
-  if (INLINE_INV && inline_inv) {
-#pragma unroll
-    for (int r = 0; r < INV_ROWS; ++r) {
-      const int m = m_base + w + 8 * r;
-#pragma unroll
-      for (int i = 0; i < INV_LD; ++i) {
-        const int idx = lane + 64 * i;
-        pre[r][i] = (m < a.M && idx < a.ss_nt) ? a.ss_in[(size_t)m * a.ss_nt + idx] : 0.f;
-      }
-    }
-  }
-
+  for (int mt = 0; mt < MT; ++mt) ssq[mt] = 0.f;
   constexpr int U = (NB + MT >= 12) ? 1 : (NB + MT >= 6) ? 2 : (NB + MT >= 3) ? 4 : 8;
   int kt = kt0;
   for (; kt + U <= kt1; kt += U) {
@@ -268,6 +248,12 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
       for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = Mfma16::run(wf[u][nb], xf[u][mt], acc[nb][mt]);
+    if (foldx) {
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) ssq[mt] = frag_ssq(xf[u][mt], ssq[mt]);
+    }
   }
   for (; kt < kt1; ++kt) {
     u32x4_v wf[NB], xf[MT];
@@ -279,27 +265,32 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = Mfma16::run(wf[nb], xf[mt], acc[nb][mt]);
+    if (foldx) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) ssq[mt] = frag_ssq(xf[mt], ssq[mt]);
+    }
   }
 
   constexpr int TILES = NB * MT;
-  // folded norm: 1 / rms of the pass's rows, one wave per row
-  __shared__ float rinv_s[16];
-  if (INLINE_INV && inline_inv) {
+  // folded norm from the operand fragments: the waves' slice sums meet in LDS and are added in slice order
+  __shared__ float ssq_s[FOLDX ? 8 : 1][FOLDX ? MT * 64 : 1];
+  float rinv_x[MT];
+  if (foldx) {
+    if (KS > 1) {
 #pragma unroll
-    for (int r = 0; r < INV_ROWS; ++r) {
-      float s = 0.f;   // ascending strips, as row_inv_rms adds them (absent strips add zeros at the end)
+      for (int mt = 0; mt < MT; ++mt) ssq_s[w][mt * 64 + lane] = ssq[mt];
+      __syncthreads();
 #pragma unroll
-      for (int i = 0; i < INV_LD; ++i) s += pre[r][i];
-      const float v = row_inv_finish(s, a.ss_d, a.ss_eps);
-      if (lane == 0) rinv_s[w + 8 * r] = v;
+      for (int mt = 0; mt < MT; ++mt) {
+        float t = ssq_s[0][mt * 64 + lane];
+        for (int s = 1; s < KS; ++s) t += ssq_s[s][mt * 64 + lane];
+        ssq[mt] = t;
+      }
     }
-    __syncthreads();
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) rinv_x[mt] = row_inv_from_lane_ssq(ssq[mt], a.ss_d, a.ss_eps);
   }
-  auto rinv_of = [&](int mt) {
-    if (EPI == EPI_RESIDUAL || !a.ss_in) return 1.0f;
-    if (a.rinv_in) return rv[mt];
-    return INLINE_INV ? rinv_s[c] : 1.0f;
-  };
+  auto rinv_of = [&](int mt) { return foldx ? rinv_x[mt] : 1.0f; };
   if (KS == 1) {
 #pragma unroll
     for (int t = 0; t < TILES; ++t)

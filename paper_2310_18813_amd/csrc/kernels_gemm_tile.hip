@@ -91,13 +91,18 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
       tot[nb][mt] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
     }
 
-  // folded norm: 1 / rms of this lane's rows (from k_row_inv), fetched now, used in the epilogue
-  const bool folded = !PARTIAL && EPI != EPI_RESIDUAL && a.rinv_in;
-  float rv[MTW];
+  // Folded norm.  With one row tile per wave the sum of squares comes from the operand fragments inside the
+  // loop (frag_ssq: per lane, one chain per k-slice, slices added in order), where it costs nothing; with larger
+  // wave tiles the loop has no issue slots to spare (measured: +10 %) and k_row_inv_x has left 1 / rms per row.
+  constexpr bool FOLD_EPI = EPI == EPI_QKV || EPI == EPI_SWIGLU;
+  constexpr bool INLOOP = FOLD_EPI && MTW == 1;
+  const bool inloop = INLOOP && a.fold_x;
+  float ssq_cur = 0.f, ssq_tot = 0.f;
+  float rv[MTW];  // 1 / rms of this lane's rows
 #pragma unroll
   for (int mt = 0; mt < MTW; ++mt) {
     const int m = (mtile0 + wm * MTW + mt) * 16 + c;
-    rv[mt] = (folded && m < a.M) ? a.rinv_in[m] : 1.0f;
+    rv[mt] = (FOLD_EPI && !INLOOP && a.fold_x && m < a.M) ? a.rinv_ws[m] : 1.0f;
   }
 
   u32x4_v r0[LPW], r1[LPW], r2[LPW];  // three steps on their way from global memory
@@ -133,6 +138,7 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
     for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
       for (int mt = 0; mt < MTW; ++mt) cur[nb][mt] = Mfma16::run(f.wf[nb], f.xf[mt], cur[nb][mt]);
+    if (inloop) ssq_cur = frag_ssq(f.xf[0], ssq_cur);
   };
   auto slice_end = [&]() {
     if (++in_slice == kt_per) {  // slice finished: add it to the running total, in slice order
@@ -147,6 +153,10 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
           }
           cur[nb][mt] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
         }
+      if (inloop) {
+        ssq_tot = slice == 0 ? ssq_cur : ssq_tot + ssq_cur;
+        ssq_cur = 0.f;
+      }
       in_slice = 0;
       ++slice;
     }
@@ -215,7 +225,7 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   if (kt + 4 < KTL) SPEC_TILE_STEP(f0, f1, r0, kt + 4, 4)
 #undef SPEC_TILE_STEP
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the over-fetched tail before the epilogue
-
+  if (inloop) rv[0] = row_inv_from_lane_ssq(ssq_tot, a.ss_d, a.ss_eps);
 
 #pragma unroll
   for (int nb = 0; nb < NBW; ++nb)
@@ -248,21 +258,39 @@ __global__ __launch_bounds__(256) void k_partial_reduce(GemmArgs a) {
     const f32x4_v q = *(const f32x4_v *)(p + s * stride);
     v[0] += q[0]; v[1] += q[1]; v[2] += q[2]; v[3] += q[3];
   }
-  tile_epilogue<T, EPI_RESIDUAL, 1>(a, v, n >> 4, m, (n & 15) >> 2);
+  tile_epilogue<T, EPI_RESIDUAL>(a, v, n >> 4, m, (n & 15) >> 2);
 }
 
 
-// 1 / rms of every row from the strip sums (folded norm, more than 16 rows): one wave per row.
-__global__ __launch_bounds__(256) void k_row_inv(const float *__restrict__ ss, int M, int nt, int d, float eps,
-                                                 float *__restrict__ rinv) {
-  const int m = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (m >= M) return;
-  const float v = row_inv_rms(ss + (size_t)m * nt, nt, d, eps, lane);
-  if (lane == 0) rinv[m] = v;
-}
-void launch_row_inv(const float *ss, int M, int nt, int d, float eps, float *rinv, hipStream_t st) {
-  if (M <= 0) return;
-  hipLaunchKernelGGL(k_row_inv, dim3((M + 3) / 4), dim3(256), 0, st, ss, M, nt, d, eps, rinv);
+// 1 / rms of every row of the fp16 activations X, in exactly the order the GEMM kernels add the squares up
+// themselves (frag_ssq): one workgroup per 16-row tile, wave w walks k-slice w, the slice sums meet in LDS and are
+// added in slice order.  For the tiled kernel with more than one row tile per wave.
+__global__ __launch_bounds__(512) void k_row_inv_x(const void *__restrict__ X, int M, int KT, int KS, int d, float eps,
+                                                   float *__restrict__ rinv) {
+  __shared__ float ssq_s[8][64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, c = lane & 15, g = lane >> 4;
+  const int tile = blockIdx.x, kt_per = KT / KS;
+  const u32x4_v *xp = (const u32x4_v *)X + (size_t)tile * KT * 64 + lane;
+  float s = 0.f;
+  int kt = w * kt_per;
+  const int kt1 = kt + kt_per;
+  for (; kt + 8 <= kt1; kt += 8) {
+    u32x4_v xf[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) xf[u] = xp[(size_t)(kt + u) * 64];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s = frag_ssq(xf[u], s);
+  }
+  for (; kt < kt1; ++kt) s = frag_ssq(xp[(size_t)kt * 64], s);
+  if (KS > 1) {
+    ssq_s[w][lane] = s;
+    __syncthreads();
+    s = ssq_s[0][lane];
+    for (int i = 1; i < KS; ++i) s += ssq_s[i][lane];
+  }
+  const float v = row_inv_from_lane_ssq(s, d, eps);
+  const int m = tile * 16 + c;
+  if (w == 0 && g == 0 && m < M) rinv[m] = v;
 }
 
 template <class T, int MTW, int NBW, int EPI>
@@ -338,6 +366,8 @@ static void launch_tile_t(GemmArgs a, int epi, hipStream_t st) {
   a.groups = (a.NT + 2 * NBW - 1) / (2 * NBW);
   const int blocks = split ? ((a.groups + 7) / 8) * 8 * a.passes * a.KS
                            : a.passes == 1 ? a.groups : ((a.groups + 7) / 8) * 8 * a.passes;
+  if (a.fold_x && MTW > 1 && (epi == EPI_QKV || epi == EPI_SWIGLU))
+    hipLaunchKernelGGL(k_row_inv_x, dim3((a.M + 15) / 16), dim3(a.KS * 64), 0, st, a.X, a.M, a.KT, a.KS, a.ss_d, a.ss_eps, a.rinv_ws);
   if (MTW == 1) launch_nb_tile<T, 1>(a, NBW, epi, blocks, st);
   else if (MTW == 2) launch_nb_tile<T, 2>(a, NBW, epi, blocks, st);
   else if (MTW == 3) launch_nb_tile<T, 3>(a, NBW, epi, blocks, st);

@@ -18,10 +18,7 @@ namespace spec {
 // row for OPT-shape models) into the fp32 residual stream.
 // Verification rows follow Alg. 1's call LLM(S, t_1..t_s): pending token, then proposals.
 // PREP (models whose RMS norm is folded into the GEMMs): the kernel also leaves what the first layer's QKV GEMM
-// consumes — the fp16 copy of the row in fragment order, its per-strip sums of squares exactly as the residual
-// epilogues leave them behind every later GEMM (four consecutive elements per thread, chain of fused
-// multiply-adds, the strip's four groups added as (g0 + g1) + (g2 + g3)), and 1 / rms of the row as k_row_inv
-// computes it in front of the later layers.
+// consumes, the fp16 copy of the row in fragment order (the GEMM takes 1 / rms of the row from those values).
 template <class T, bool PREP>
 __global__ __launch_bounds__(256) void k_assemble_embed(int kind, int q, int j, int P, int s_max, int L_max, int vocab, int d,
                                  int learned_pos, int seq_groups, const int32_t *__restrict__ seq, const int32_t *__restrict__ n,
@@ -29,7 +26,7 @@ __global__ __launch_bounds__(256) void k_assemble_embed(int kind, int q, int j, 
                                  const int32_t *__restrict__ seq_s,
                                  const T *__restrict__ tok_emb, const T *__restrict__ pos_emb,
                                  int32_t *__restrict__ row_tok, int32_t *__restrict__ row_pos, float *__restrict__ h,
-                                 op_t *__restrict__ x, float *__restrict__ ss, float *__restrict__ rinv, float eps) {
+                                 op_t *__restrict__ x) {
   // prefill with several row groups per sequence: group = m / q, sequence = group / seq_groups, and the row's
   // offset from the pass's base position counts the sequence's earlier groups
   const int m = blockIdx.x, grp = m / q;
@@ -71,27 +68,12 @@ __global__ __launch_bounds__(256) void k_assemble_embed(int kind, int q, int j, 
     for (int c = threadIdx.x; c < d; c += blockDim.x) hr[c] = value(c);
     return;
   }
-  // four consecutive elements per thread; d is a multiple of 32, so a group of four threads (one strip of 16)
-  // is in or out of the loop together
-  const int nv = d >> 2, nt = d >> 4;
-  for (int c0 = 0; c0 < nv; c0 += 256) {
-    const int c = c0 + threadIdx.x;
-    if (c < nv) {
-      const float4 o = make_float4(value(4 * c), value(4 * c + 1), value(4 * c + 2), value(4 * c + 3));
-      *(float4 *)(hr + 4 * c) = o;
-      op_t o4[4] = {to_op(o.x), to_op(o.y), to_op(o.z), to_op(o.w)};
-      *(uint2 *)(x + xpack_index(m, 4 * c, d >> 5)) = *(const uint2 *)o4;
-      float p = o.x * o.x;
-      p = fmaf(o.y, o.y, p); p = fmaf(o.z, o.z, p); p = fmaf(o.w, o.w, p);
-      p += __shfl_xor(p, 1, 64);
-      p += __shfl_xor(p, 2, 64);
-      if ((c & 3) == 0) ss[(size_t)m * nt + (c >> 2)] = p;
-    }
-  }
-  __syncthreads();  // the strip sums of the row are written (and visible to this workgroup)
-  if (threadIdx.x < 64) {
-    const float v = row_inv_rms(ss + (size_t)m * nt, nt, d, eps, threadIdx.x);
-    if (threadIdx.x == 0) rinv[m] = v;
+  const int nv = d >> 2;  // four consecutive elements per thread
+  for (int c = threadIdx.x; c < nv; c += 256) {
+    const float4 o = make_float4(value(4 * c), value(4 * c + 1), value(4 * c + 2), value(4 * c + 3));
+    *(float4 *)(hr + 4 * c) = o;
+    op_t o4[4] = {to_op(o.x), to_op(o.y), to_op(o.z), to_op(o.w)};
+    *(uint2 *)(x + xpack_index(m, 4 * c, d >> 5)) = *(const uint2 *)o4;
   }
 }
 
@@ -106,7 +88,7 @@ void launch_assemble_embed(const spec_ctx *c, const Model &m, const PassArgs &pa
                        c->st.n + pa.b0, c->drf.kv_len ? c->drf.kv_len + pa.b0 : nullptr,
                        c->st.t + (size_t)pa.b0 * c->run.s_max, c->seq_s ? c->seq_s + pa.b0 : nullptr,
                        (const T *)m.tok_emb, (const T *)m.pos_emb, c->ws.row_tok, c->ws.row_pos, c->ws.h,
-                       (op_t *)c->ws.x, c->ws.part_ss, c->ws.row_inv, m.desc.norm_eps));
+                       (op_t *)c->ws.x));
 }
 
 // -------------------------------------------------------------------------

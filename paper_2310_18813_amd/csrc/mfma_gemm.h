@@ -30,15 +30,13 @@ struct GemmArgs {
   int passes, groups;  // filled by the launcher
   // epilogue targets (those the chosen epilogue uses)
   float *h;                  // EPI_RESIDUAL: [M][N] fp32
-  // RMS norm folded into the GEMMs around it (null = off): the gain sits in the packed weights of the
-  // consumer, whose activations are the fp16-rounded rows of h themselves; the consumer's epilogue
-  // multiplies by 1 / rms of the row, from the partial sums of squares the producer of h left per strip.
-  const float *rinv_in;      // consumer: [M] 1 / rms per row (k_row_inv ran), or null: computed here from ss_in
-                             //   (streaming kernel with up to 16 rows only)
-  const float *ss_in;        // consumer: [M][ss_nt] partial sums of squares of the rows of h
-  int ss_nt, ss_d;           // strips per row of h, its length
+  // RMS norm folded into the GEMMs around it: the gain sits in the packed weights of the consumer, whose
+  // activations are the fp16-rounded rows of h themselves, written by the producer of h; the consumer's
+  // epilogue multiplies by 1 / rms of the row, which it takes from the operand fragments it reads anyway.
+  int fold_x;                // consumer: norm folded in (row length ss_d, epsilon ss_eps)
+  int ss_d;
   float ss_eps;
-  float *ss_out;             // EPI_RESIDUAL producer: [M][NT] partial sums of squares of the updated rows
+  float *rinv_ws;            // consumer: [M] scratch for 1 / rms per row (tiled kernel with more than one row tile per wave)
   void *x_out;               // EPI_RESIDUAL producer: fp16 copy of the updated rows, fragment order
   float *part;               // EPI_RESIDUAL with more than 64 rows: scratch [KS][part_rows][N] fp32, or null
   int part_rows;             // M rounded up to 16
@@ -69,12 +67,6 @@ void launch_pack_weight(int dtype, int mode, const PackedDims &p, int d, int hd,
                         const void *s2, const void *gain, void *dst, const uint32_t *d_amax_bits, hipStream_t st);
 void launch_pack_bias(int dtype, int mode, const PackedDims &p, int d, int hd, const void *s0, const void *s1,
                       const void *s2, float *dst, hipStream_t st);
-void launch_row_inv(const float *ss, int M, int nt, int d, float eps, float *rinv, hipStream_t st);
-// Up to 16 rows the streaming kernel adds the strip sums up itself: each of its 8 waves keeps the sums of two
-// rows in registers during the k loop, 64 strips per register (with more rows per pass this was measured
-// slower than the separate kernel).  Registers per row, and the strips per row they cover:
-constexpr int ROW_INV_INLINE_LOADS = 8;
-constexpr int ROW_INV_INLINE_MAX_NT = 64 * ROW_INV_INLINE_LOADS;
 void launch_rope_table(int L, int hd, float theta, float2 *tab, hipStream_t st);
 void launch_gemm_mfma(int dtype, const GemmArgs &a, int epi, hipStream_t st);
 void launch_gemm_tile(int dtype, GemmArgs a, int epi, hipStream_t st);  // more than 64 rows, wide outputs

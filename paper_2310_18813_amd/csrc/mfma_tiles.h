@@ -23,25 +23,30 @@ struct Mfma16 {
   }
 };
 
-// 1 / rms of a row of h from its per-strip partial sums of squares; called by a whole wave per row
-// (lanes take strips lane, lane + 64, ... in ascending order, then the fixed butterfly), so every kernel
-// that needs the value computes the same bits.
-__device__ __forceinline__ float row_inv_finish(float s, int d, float eps) {
-  s = wave_sum(s);
-  return 1.0f / sqrtf(s / (float)d + eps);
+// Folded RMS norm, consumer side: the sum of squares of a row of activations is taken from the fp16 operand
+// fragments the GEMM reads anyway.  In the B operand lane (c, g) holds elements 8g .. 8g+7 of row c of a
+// 32-k step: a lane adds its eight squares (exact in fp32) to a running fp32 sum by fused multiply-adds in
+// ascending k, one chain per k-slice from zero; the slices are added in slice order per lane, then the four
+// lane groups of a row as (g0 + g1) + (g2 + g3).  Every GEMM kernel follows exactly this order, so the value
+// depends on the row alone.
+__device__ __forceinline__ float frag_ssq(u32x4_v x, float s) {
+  const f16x8_v h = __builtin_bit_cast(f16x8_v, x);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) s = fmaf((float)h[i], (float)h[i], s);
+  return s;
 }
-__device__ __forceinline__ float row_inv_rms(const float *__restrict__ ss, int nt, int d, float eps, int lane) {
-  float s = 0.f;
-  for (int i = lane; i < nt; i += 64) s += ss[i];
-  return row_inv_finish(s, d, eps);
+// per-lane slice-ordered sum -> 1 / rms of the lane's row (all four lanes of a row get the same bits)
+__device__ __forceinline__ float row_inv_from_lane_ssq(float t, int d, float eps) {
+  t += __shfl_xor(t, 16, 64);
+  t += __shfl_xor(t, 32, 64);
+  return 1.0f / sqrtf(t / (float)d + eps);
 }
 
 // ------------------------------------------------------------------------- epilogues
 // One finished 16x16 tile: this lane holds stored rows n .. n+3 (n = 16*nt + 4g) of
 // activation row m.  The element-wise work of the layer happens here, on fp32 sums.
-// rinv: 1 / rms of row m when the norm in front of this GEMM is folded into it, else 1.  GS: lane distance
-// between the four lanes that hold one strip of a row (16 in the GEMM kernels, 1 in the reduction kernel).
-template <class T, int EPI, int GS = 16>
+// rinv: 1 / rms of row m when the norm in front of this GEMM is folded into it, else 1.
+template <class T, int EPI>
 __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int nt, int m, int g, float rinv = 1.0f) {
   if (nt >= a.NT) return;
   const int n = nt * 16 + 4 * g;
@@ -64,13 +69,6 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int 
         op_t o4[4] = {to_op(o.x), to_op(o.y), to_op(o.z), to_op(o.w)};
         *(uint2 *)((op_t *)a.x_out + xpack_index(m, n, a.N >> 5)) = *(const uint2 *)o4;
       }
-    }
-    if (a.ss_out) {  // sum of squares of the strip's 16 elements of the row, in a fixed order
-      float p = o.x * o.x;
-      p = fmaf(o.y, o.y, p); p = fmaf(o.z, o.z, p); p = fmaf(o.w, o.w, p);
-      p += __shfl_xor(p, GS, 64);
-      p += __shfl_xor(p, 2 * GS, 64);
-      if (live && g == 0) a.ss_out[(size_t)m * a.NT + nt] = p;
     }
   } else if (EPI == EPI_QKV) {
     if (live && n < a.N) {

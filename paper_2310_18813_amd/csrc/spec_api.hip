@@ -105,12 +105,12 @@ static Sizes compute_sizes(const spec_model_desc *tgt, const spec_model_desc *dr
   }
   const size_t Mp = (M + 15) / 16 * 16;  // fragment-order activation buffers hold whole 16-row tiles
   z.act = al256(M * d * 4) + 3 * al256(Mp * d * e) + al256(Mp * f * e) + al256(M * wide * 4) + al256(M * V * 4) +
-          4 * al256(M * 4);
+          3 * al256(M * 4);
   // matrix-core path: split-KV attention partials and per-strip arg-max partials
   const size_t NC = (L + ATTN_CHUNK - 1) / ATTN_CHUNK, NTh = (V + 15) / 16;
   z.act += al256(M * d * NC * 4) + al256(M * (d / 64 + 1) * NC * 2 * 4) + 2 * al256(M * NTh * 4);
   if (M > 32) z.act += al256(8 * Mp * d * 4);  // k-slice sums of the split residual GEMMs
-  z.act += al256(M * (d / 16 + 1) * 4) + al256(M * 4);  // per-strip sums of squares, 1 / rms per row (folded norm)
+  z.act += al256(M * 4);  // 1 / rms per row (folded norm)
   z.tgt_w = packed_bytes(*tgt, run->dtype, run->L_max);
   z.kv_area_tgt = B * (size_t)tgt->d_model * z.L_pad;
   z.tgt_kv = 2 * al256((size_t)tgt->n_layers * z.kv_area_tgt * e);
@@ -252,7 +252,6 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
   W.row_tok = (int32_t *)carve(p, M * 4);
   W.row_pos = (int32_t *)carve(p, M * 4);
   W.row_seq = (int32_t *)carve(p, M * 4);
-  W.head_rows = (int32_t *)carve(p, M * 4);
   {
     const size_t NC = (L + ATTN_CHUNK - 1) / ATTN_CHUNK, NTh = (V + 15) / 16;
     c->NC_max = (int)NC;
@@ -261,7 +260,6 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
     W.head_part = (float *)carve(p, M * NTh * 4);
     W.head_part_idx = (int32_t *)carve(p, M * NTh * 4);
     W.gemm_part = M > 32 ? (float *)carve(p, 8 * Mp * d * 4) : nullptr;
-    W.part_ss = (float *)carve(p, M * (d / 16 + 1) * 4);
     W.row_inv = (float *)carve(p, M * 4);
   }
 

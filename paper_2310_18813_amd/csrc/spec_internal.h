@@ -81,13 +81,11 @@ struct Workspace {
   float *y32 = nullptr;     // [M_max][max(3d, 2f)] fp32 GEMM output (generic path)
   float *logits = nullptr;  // [M_max][vocab] fp32 (generic path / debug)
   float *attn_part = nullptr, *attn_ml = nullptr;  // split-KV partials (MFMA path)
-  float *part_ss = nullptr;                        // [M_max][d/16] per-strip sums of squares of h (folded norm)
-  float *row_inv = nullptr;                        // [M_max] 1 / rms of the rows of h (folded norm, more than 16 rows)
+  float *row_inv = nullptr;                        // [M_max] 1 / rms of the rows of h (folded norm, tiled GEMM with large wave tiles)
   float *gemm_part = nullptr;                      // k-slice sums of the split residual GEMMs (M_max > 32)
   float *head_part = nullptr;                      // per-strip arg-max partials (MFMA path)
   int32_t *head_part_idx = nullptr;
   int32_t *row_tok = nullptr, *row_pos = nullptr, *row_seq = nullptr;  // [M_max]
-  int32_t *head_rows = nullptr;                                        // [M_max] rows that need logits
 };
 
 struct State {
