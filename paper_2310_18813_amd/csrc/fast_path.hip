@@ -189,16 +189,23 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
     if (!fold) return;
     a.fold_x = 1; a.ss_d = d; a.ss_eps = D.norm_eps; a.rinv_ws = ws.row_inv;
   };
+  // the tiled kernel's larger wave tiles read 1 / rms per row from scratch: a small kernel fills it first
+  auto row_inv_first = [&](const GemmArgs &a, int epi) {
+    if (!fold || !gemm_wants_row_inv(a, epi)) return;
+    KScope k(c, tgt ? SPEC_KCLASS_NORM : -1);
+    launch_row_inv_x(a, st);
+  };
   auto produce_norm = [&](GemmArgs &a) {
     if (fold) a.x_out = ws.x;
   };
   if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, 0, st); }
   {
-    KScope k(c, tgt ? SPEC_KCLASS_GEMM_QKV : -1);
     GemmArgs a = base_args(m.p_qkv, L.wqkv, L.s_qkv, L.bqkv, ws.x, M);
     consume_norm(a);
     a.q = ws.q; a.kc = kc; a.vc = vc; a.row_pos = ws.row_pos; a.rope = m.rope;
     a.q_rows = q_rows; a.d = d; a.hd = m.hd; a.H = D.n_heads; a.L_pad = m.L_pad; a.seq_groups = seq_groups;
+    row_inv_first(a, EPI_QKV);
+    KScope k(c, tgt ? SPEC_KCLASS_GEMM_QKV : -1);
     launch_gemm_mfma(dt, a, EPI_QKV, st);
   }
   {
@@ -221,11 +228,13 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
   }
   if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, 0, st); }
   {
-    KScope k(c, tgt ? SPEC_KCLASS_GEMM_FFN_IN : -1);
     GemmArgs a = base_args(m.p_13, L.w13, L.s_13, L.b13, ws.x, M);
     consume_norm(a);
     a.act = ws.act; a.f = D.d_ffn;
-    launch_gemm_mfma(dt, a, D.ffn_kind == SPEC_FFN_SWIGLU ? EPI_SWIGLU : EPI_RELU, st);
+    const int epi = D.ffn_kind == SPEC_FFN_SWIGLU ? EPI_SWIGLU : EPI_RELU;
+    row_inv_first(a, epi);
+    KScope k(c, tgt ? SPEC_KCLASS_GEMM_FFN_IN : -1);
+    launch_gemm_mfma(dt, a, epi, st);
   }
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_FFN_OUT : -1);

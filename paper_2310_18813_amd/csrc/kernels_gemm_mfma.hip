@@ -334,17 +334,24 @@ static void launch_epi(const GemmArgs &a, int epi, dim3 grid, dim3 block, size_t
   }
 }
 
+// Wide outputs go to the LDS-tiled kernel (same bits, weights fetched once per up to 256 rows) from 65 rows
+// on, the widest (gate-up, LM head) already from 33: the streaming kernel's waves each fetch their own copy
+// of the activations, the tiled kernel shares them through LDS.  The narrow residual GEMMs run it one k-slice
+// per workgroup when the context has the scratch for the slices: worth the second kernel from 33 rows on
+// when a slice has at least 32 steps (down projection), and from 5 row passes of the streaming kernel.
+static bool goes_to_tile_kernel(const GemmArgs &a, int epi) {
+  const bool split_ok = a.part && a.KS > 1 && (a.N & 3) == 0 && (a.KT / a.KS >= 32 || a.M > 256);
+  const int tile_min_m = a.NT >= 1024 ? 33 : 65;
+  return a.NT >= 64 && (epi != EPI_RESIDUAL ? a.M >= tile_min_m : (split_ok && a.M >= 33));
+}
+bool gemm_wants_row_inv(const GemmArgs &a, int epi) {
+  return a.M > 0 && goes_to_tile_kernel(a, epi) && gemm_tile_wants_row_inv(a, epi);
+}
+
 template <class T>
 static void launch_gemm_t(GemmArgs a, int epi, hipStream_t st) {
   if (a.M <= 0) return;
-  // Wide outputs go to the LDS-tiled kernel (same bits, weights fetched once per up to 256 rows) from 65 rows
-  // on, the widest (gate-up, LM head) already from 33: the streaming kernel's waves each fetch their own copy
-  // of the activations, the tiled kernel shares them through LDS.  The narrow residual GEMMs run it one k-slice
-  // per workgroup when the context has the scratch for the slices: worth the second kernel from 33 rows on
-  // when a slice has at least 32 steps (down projection), and from 5 row passes of the streaming kernel.
-  const bool split_ok = a.part && a.KS > 1 && (a.N & 3) == 0 && (a.KT / a.KS >= 32 || a.M > 256);
-  const int tile_min_m = a.NT >= 1024 ? 33 : 65;
-  if (a.NT >= 64 && (epi != EPI_RESIDUAL ? a.M >= tile_min_m : (split_ok && a.M >= 33))) {
+  if (goes_to_tile_kernel(a, epi)) {
     launch_gemm_tile(std::is_same<T, bf16_t>::value ? SPEC_DTYPE_BF16 : SPEC_DTYPE_F16, a, epi, st);
     return;
   }

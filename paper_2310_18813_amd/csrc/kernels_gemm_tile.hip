@@ -349,8 +349,8 @@ static void choose_tile(int M, int NT, int n_cu, int steps, int wg_mult, int &MT
     }
 }
 
-template <class T>
-static void launch_tile_t(GemmArgs a, int epi, hipStream_t st) {
+// wave tile of the launch for these arguments (epi as given by the caller, EPI_RESIDUAL = split by k-slice)
+static void tile_for(const GemmArgs &a, int epi, int &MTW, int &NBW) {
   static int n_cu = 0;
   if (!n_cu) {
     int dev = 0;
@@ -358,16 +358,34 @@ static void launch_tile_t(GemmArgs a, int epi, hipStream_t st) {
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
     if (n_cu <= 0) n_cu = 256;
   }
-  int MTW = 2, NBW = 2;
+  const bool split = epi == EPI_RESIDUAL;
+  MTW = 2; NBW = 2;
+  choose_tile(a.M, a.NT, n_cu, split ? a.KT / a.KS : a.KT, split ? a.KS : 1, MTW, NBW);
+}
+
+// With more than one row tile per wave the kernel reads 1 / rms of its rows from a.rinv_ws: the caller runs
+// launch_row_inv_x first when this says so.
+bool gemm_tile_wants_row_inv(const GemmArgs &a, int epi) {
+  if (!a.fold_x || (epi != EPI_QKV && epi != EPI_SWIGLU)) return false;
+  int MTW, NBW;
+  tile_for(a, epi, MTW, NBW);
+  return MTW > 1;
+}
+void launch_row_inv_x(const GemmArgs &a, hipStream_t st) {
+  if (a.M <= 0) return;
+  hipLaunchKernelGGL(k_row_inv_x, dim3((a.M + 15) / 16), dim3(a.KS * 64), 0, st, a.X, a.M, a.KT, a.KS, a.ss_d, a.ss_eps, a.rinv_ws);
+}
+
+template <class T>
+static void launch_tile_t(GemmArgs a, int epi, hipStream_t st) {
+  int MTW, NBW;
+  tile_for(a, epi, MTW, NBW);
   const bool split = epi == EPI_RESIDUAL;  // narrow outputs: one k-slice per workgroup, slices added by a second kernel
   if (split) epi = EPI_PARTIAL;
-  choose_tile(a.M, a.NT, n_cu, split ? a.KT / a.KS : a.KT, split ? a.KS : 1, MTW, NBW);
   a.passes = (a.M + 64 * MTW - 1) / (64 * MTW);
   a.groups = (a.NT + 2 * NBW - 1) / (2 * NBW);
   const int blocks = split ? ((a.groups + 7) / 8) * 8 * a.passes * a.KS
                            : a.passes == 1 ? a.groups : ((a.groups + 7) / 8) * 8 * a.passes;
-  if (a.fold_x && MTW > 1 && (epi == EPI_QKV || epi == EPI_SWIGLU))
-    hipLaunchKernelGGL(k_row_inv_x, dim3((a.M + 15) / 16), dim3(a.KS * 64), 0, st, a.X, a.M, a.KT, a.KS, a.ss_d, a.ss_eps, a.rinv_ws);
   if (MTW == 1) launch_nb_tile<T, 1>(a, NBW, epi, blocks, st);
   else if (MTW == 2) launch_nb_tile<T, 2>(a, NBW, epi, blocks, st);
   else if (MTW == 3) launch_nb_tile<T, 3>(a, NBW, epi, blocks, st);

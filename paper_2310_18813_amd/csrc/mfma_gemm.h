@@ -70,6 +70,12 @@ void launch_pack_bias(int dtype, int mode, const PackedDims &p, int d, int hd, c
 void launch_rope_table(int L, int hd, float theta, float2 *tab, hipStream_t st);
 void launch_gemm_mfma(int dtype, const GemmArgs &a, int epi, hipStream_t st);
 void launch_gemm_tile(int dtype, GemmArgs a, int epi, hipStream_t st);  // more than 64 rows, wide outputs
+// Folded norm: true when the launch for these arguments reads 1 / rms of its rows from a.rinv_ws (tiled kernel
+// with more than one row tile per wave); launch_row_inv_x then has to run first.  Every other launch takes the
+// value from its own operand fragments.
+bool gemm_wants_row_inv(const GemmArgs &a, int epi);
+bool gemm_tile_wants_row_inv(const GemmArgs &a, int epi);
+void launch_row_inv_x(const GemmArgs &a, hipStream_t st);
 void launch_argmax_partials(const float *pv, const int32_t *pi, int M, int NT, int V, int q, int out_stride,
                             int32_t *out, hipStream_t st);
 
