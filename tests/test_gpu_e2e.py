@@ -25,6 +25,10 @@ CASES = {
     # fp16 LLaMA shape: the RMS norm folded into fp16 weights (gain * weight needs the per-matrix scaling too)
     "small_fp16_llama": dict(dtype="fp16", seed=81, B=2, P=7, N=16, s=4, alpha=0.7,
                              tgt=si.llama_desc(2, 256, 4, 448, 900, 64), drf=si.llama_desc(1, 128, 2, 160, 900, 64)),
+    # widths whose k dimension splits into two slices (d = 192: 6 steps of 32) and into one (f = 352: 11 steps),
+    # three heads, a single-head draft
+    "odd_slices_bf16": dict(dtype="bf16", seed=83, B=2, P=6, N=14, s=3, alpha=0.7,
+                            tgt=si.llama_desc(2, 192, 3, 352, 500, 64), drf=si.llama_desc(1, 64, 1, 96, 500, 64)),
     # wider bf16 model: 8 k-slices, two row passes (M = 96), two strips per workgroup in the LM head
     "medium_bf16": dict(dtype="bf16", seed=79, B=24, P=12, N=12, s=3, alpha=0.7,
                         tgt=si.llama_desc(1, 512, 4, 1536, 20000, 64), drf=si.llama_desc(1, 256, 4, 512, 20000, 64)),
