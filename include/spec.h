@@ -144,13 +144,15 @@ int spec_reset(spec_ctx *ctx, int32_t B, const int32_t *d_prompt, int32_t P);
 int spec_reset_noprefill(spec_ctx *ctx, int32_t B, const int32_t *d_prompt, int32_t P);
 
 /* Continuous batching (beyond the paper, which decodes fixed batches): batch slot b, 0 <= b < B, starts
-   over with the P prompt tokens d_prompt[0..P-1] (int32, device; P as given to the last spec_reset).  The
-   slot's emitted tokens are dropped (read them with spec_read_output first), its prompt is run through both
-   models in a single-sequence pass, and from the next round on it decodes beside the others, whose state and
-   results do not change.  Not allowed between a round's first draft or verify step and its
+   over with the P prompt tokens d_prompt[0..P-1] (int32, device).  P need not be the length given to
+   spec_reset: every slot keeps its own prompt length (P >= 1, P + gen_max + s_max <= L_max, and <= max_pos for
+   learned positions; SPEC_ERR_CAPACITY otherwise).  The slot's emitted tokens are dropped (read them with
+   spec_read_output first), its prompt is run through both models in a single-sequence pass, and from the next
+   round on it decodes beside the others, whose state and results do not change.  spec_rewind takes every slot
+   back to its own prompt.  Not allowed between a round's first draft or verify step and its
    spec_accept_commit (SPEC_ERR_STATE).  With an external proposal table the caller updates row b of the
    table it owns.  Counters and the accepted-length histogram keep running for the whole batch.           */
-int spec_admit(spec_ctx *ctx, int32_t b, const int32_t *d_prompt);
+int spec_admit(spec_ctx *ctx, int32_t b, const int32_t *d_prompt, int32_t P);
 
 /* A speculation length per sequence (beyond the paper, whose rounds use one s for the whole batch):
    d_s[b] (int32, device, B entries, the caller's memory, read by every round until replaced) caps the

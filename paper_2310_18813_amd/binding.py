@@ -60,7 +60,7 @@ lib.spec_destroy.argtypes = [_vp]
 lib.spec_reset.argtypes = [_vp, _i32, _vp, _i32]
 lib.spec_reset_noprefill.argtypes = [_vp, _i32, _vp, _i32]
 lib.spec_rewind.argtypes = [_vp]
-lib.spec_admit.argtypes = [_vp, _i32, _vp]
+lib.spec_admit.argtypes = [_vp, _i32, _vp, _i32]
 lib.spec_set_seq_s.argtypes = [_vp, _vp]
 lib.spec_set_proposal_table.argtypes = [_vp, _vp]
 lib.spec_set_proposals.argtypes = [_vp, _vp, _i32]
@@ -198,7 +198,7 @@ class Context:
         p = torch.as_tensor(prompt, dtype=torch.int32).to(self.device).contiguous()
         assert p.dim() == 1
         self._admit_prompt = p  # stays alive until the stream has consumed it
-        _check(lib.spec_admit(self.h, int(b), _dp(p)), self.h)
+        _check(lib.spec_admit(self.h, int(b), _dp(p), int(p.shape[0])), self.h)
 
     def spec_set_seq_s(self, caps):
         if caps is None:

@@ -246,7 +246,7 @@ void launch_copy_proposals(spec_ctx *c, const int32_t *d_tok, int s, hipStream_t
 // only while all earlier ones matched the target's greedy token; the target's token after
 // the last survivor is appended.  Rollback is by length only: the K/V rows written for
 // rejected positions stay in the cache and are overwritten by the next round.
-__global__ void k_accept(int B, int s, int s_max, int L_max, int P, int gen_max, int draft_steps,
+__global__ void k_accept(int B, int s, int s_max, int L_max, const int32_t *__restrict__ P_b, int gen_max, int draft_steps,
                          const int32_t *__restrict__ seq_s,
                          const int32_t *__restrict__ t, const int32_t *__restrict__ a, int32_t *__restrict__ seq,
                          int32_t *__restrict__ n, int32_t *__restrict__ kv_draft, int32_t *__restrict__ l_last,
@@ -255,7 +255,7 @@ __global__ void k_accept(int B, int s, int s_max, int L_max, int P, int gen_max,
   if (b == 0) atomicAdd(&counters[1], 1ull);
   if (b >= B) return;
   const int n_old = n[b];
-  const int gen = n_old - P;
+  const int gen = n_old - P_b[b];
   const int32_t *tb = t + (size_t)b * s_max;
   const int32_t *ab = a + (size_t)b * (s_max + 1);
   // with a cap per sequence only the first min(s, s_b) proposals were verified, and the draft ran
@@ -280,41 +280,50 @@ __global__ void k_accept(int B, int s, int s_max, int L_max, int P, int gen_max,
   }
 }
 void launch_accept(spec_ctx *c, int s, hipStream_t st) {
-  hipLaunchKernelGGL(k_accept, dim3((c->B + 63) / 64), dim3(64), 0, st, c->B, s, c->run.s_max, c->run.L_max, c->P,
+  hipLaunchKernelGGL(k_accept, dim3((c->B + 63) / 64), dim3(64), 0, st, c->B, s, c->run.s_max, c->run.L_max, c->st.P_b,
                      c->run.gen_max, c->draft_j, c->seq_s, c->st.t, c->st.a, c->st.seq, c->st.n, c->drf.kv_len, c->st.l_last,
                      c->st.hist, c->st.counters);
 }
 
 // -------------------------------------------------------------------------
+// With a prompt: a new batch, every sequence P tokens long.  Without: back to "prompts just given", every sequence
+// to its own prompt length (slots admitted later may differ from the batch's).
 __global__ void k_state_reset(int B, int P, int L_max, int s_max, const int32_t *__restrict__ prompt,
-                              int32_t *__restrict__ seq, int32_t *__restrict__ n, int32_t *__restrict__ kv_draft,
+                              int32_t *__restrict__ seq, int32_t *__restrict__ n, int32_t *__restrict__ P_b,
+                              int32_t *__restrict__ kv_draft,
                               int32_t *__restrict__ l_last, unsigned long long *__restrict__ hist,
                               unsigned long long *__restrict__ counters) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (prompt && i < B * P) seq[(size_t)(i / P) * L_max + i % P] = prompt[i];
-  if (i < B) { n[i] = P; l_last[i] = 0; if (kv_draft) kv_draft[i] = P - 1; }
+  if (i < B) {
+    const int Pi = prompt ? P : P_b[i];
+    P_b[i] = Pi;
+    n[i] = Pi; l_last[i] = 0;
+    if (kv_draft) kv_draft[i] = Pi - 1;
+  }
   if (i <= s_max) hist[i] = 0ull;
   if (i < 2) counters[i] = 0ull;
 }
 // One batch slot back to "prompt just given": its tokens, length, draft-cache length.  Counters and the
 // accepted-length histogram belong to the whole batch and are left alone.
 __global__ void k_state_admit(int P, const int32_t *__restrict__ prompt, int32_t *__restrict__ seq_b,
-                              int32_t *__restrict__ n_b, int32_t *__restrict__ kv_draft_b, int32_t *__restrict__ l_last_b) {
+                              int32_t *__restrict__ n_b, int32_t *__restrict__ P_b_b, int32_t *__restrict__ kv_draft_b,
+                              int32_t *__restrict__ l_last_b) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < P) seq_b[i] = prompt[i];
-  if (i == 0) { *n_b = P; *l_last_b = 0; if (kv_draft_b) *kv_draft_b = P - 1; }
+  if (i == 0) { *n_b = P; *P_b_b = P; *l_last_b = 0; if (kv_draft_b) *kv_draft_b = P - 1; }
 }
-void launch_state_admit(spec_ctx *c, int b, const int32_t *d_prompt, hipStream_t st) {
-  hipLaunchKernelGGL(k_state_admit, dim3((c->P + 255) / 256), dim3(256), 0, st, c->P, d_prompt,
-                     c->st.seq + (size_t)b * c->run.L_max, c->st.n + b, c->drf.kv_len ? c->drf.kv_len + b : nullptr,
-                     c->st.l_last + b);
+void launch_state_admit(spec_ctx *c, int b, const int32_t *d_prompt, int P, hipStream_t st) {
+  hipLaunchKernelGGL(k_state_admit, dim3((P + 255) / 256), dim3(256), 0, st, P, d_prompt,
+                     c->st.seq + (size_t)b * c->run.L_max, c->st.n + b, c->st.P_b + b,
+                     c->drf.kv_len ? c->drf.kv_len + b : nullptr, c->st.l_last + b);
 }
 void launch_state_reset(spec_ctx *c, const int32_t *d_prompt, hipStream_t st) {
   int work = c->B * c->P;
   if (work < c->run.s_max + 1) work = c->run.s_max + 1;
   if (work < 2) work = 2;
   hipLaunchKernelGGL(k_state_reset, dim3((work + 255) / 256), dim3(256), 0, st, c->B, c->P, c->run.L_max,
-                     c->run.s_max, d_prompt, c->st.seq, c->st.n, c->drf.kv_len, c->st.l_last, c->st.hist,
+                     c->run.s_max, d_prompt, c->st.seq, c->st.n, c->st.P_b, c->drf.kv_len, c->st.l_last, c->st.hist,
                      c->st.counters);
 }
 

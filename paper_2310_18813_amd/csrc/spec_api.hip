@@ -91,7 +91,7 @@ static Sizes compute_sizes(const spec_model_desc *tgt, const spec_model_desc *dr
   z.M_max = run->B_max * z.q_pass;
   z.L_pad = (run->L_max + KV_LPAD - 1) / KV_LPAD * KV_LPAD;
   const size_t B = run->B_max, L = run->L_max, s = run->s_max, M = z.M_max;
-  z.state = al256(B * L * 4) + 4 * al256(B * 4) + al256(B * std::max<size_t>(s, 1) * 4) + al256(B * (s + 1) * 4) +
+  z.state = al256(B * L * 4) + 5 * al256(B * 4) + al256(B * std::max<size_t>(s, 1) * 4) + al256(B * (s + 1) * 4) +
             al256((s + 1) * 8) + al256(16);
   size_t d = tgt->d_model, f = tgt->d_ffn, V = tgt->vocab;
   size_t kf = tgt->ffn_kind == SPEC_FFN_SWIGLU ? 2 : 1;
@@ -224,6 +224,7 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
   State &S = c->st;
   S.seq = (int32_t *)carve(p, B * L * 4);
   S.n = (int32_t *)carve(p, B * 4);
+  S.P_b = (int32_t *)carve(p, B * 4);
   S.l_last = (int32_t *)carve(p, B * 4);
   S.draft_arg = (int32_t *)carve(p, B * 4);
   c->drf.kv_len = (int32_t *)carve(p, B * 4);
@@ -379,8 +380,8 @@ static int forward_pass(spec_ctx *c, Model &m, const PassArgs &pa, HeadMode head
 // M_max rows.  A sequence's share of a pass is cut into groups of Q_LIMIT rows (the attention query tile) at
 // consecutive positions; all groups of a sequence read and write that sequence's cache, so few sequences with
 // long prompts need few passes over the weights (one sequence, M_max >= P-1: a single pass).
-static int prefill(spec_ctx *c, int b0, int B) {
-  const int P = c->P, per = std::max(1, c->M_max / B);
+static int prefill(spec_ctx *c, int b0, int B, int P) {
+  const int per = std::max(1, c->M_max / B);
   const int q = std::min(Q_LIMIT, per), g = std::max(1, per / q);
   for (int base = 0; base < P - 1; base += g * q) {
     const int left = P - 1 - base;
@@ -409,6 +410,7 @@ static int do_reset(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32_t P, 
                   m->desc.max_pos);
   c->B = B;
   c->P = P;
+  c->P_host.assign((size_t)B, P);
   c->n_ub = P;
   c->active = true;
   c->draft_j = 0;
@@ -417,7 +419,7 @@ static int do_reset(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32_t P, 
   c->proposals_ready = false;
   launch_state_reset(c, d_prompt, c->stream);
   if (prefill) {
-    int rc = ::prefill(c, 0, B);
+    int rc = ::prefill(c, 0, B, P);
     if (rc) return rc;
   }
   HIPCHK(c, hipGetLastError());
@@ -431,19 +433,28 @@ extern "C" int spec_reset_noprefill(spec_ctx *c, int32_t B, const int32_t *d_pro
   return do_reset(c, B, d_prompt, P, false, "spec_reset_noprefill");
 }
 
-// Continuous batching: one slot of the running batch starts over with a new prompt of the batch's prompt
-// length; the other sequences keep their state.  The slot's prompt runs through both models in a pass of
-// its own (B = 1 at batch slot b), so its cost is that of a single-sequence prefill.
-extern "C" int spec_admit(spec_ctx *c, int32_t b, const int32_t *d_prompt) {
+// Continuous batching: one slot of the running batch starts over with a new prompt (of any length that fits);
+// the other sequences keep their state.  The slot's prompt runs through both models in a pass of its own
+// (B = 1 at batch slot b), so its cost is that of a single-sequence prefill.
+extern "C" int spec_admit(spec_ctx *c, int32_t b, const int32_t *d_prompt, int32_t P) {
   if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_admit: ctx is null");
   if (!c->active) return fail(c, SPEC_ERR_STATE, "spec_admit: no batch; call spec_reset first");
   if (!d_prompt) return fail(c, SPEC_ERR_INVALID_ARG, "spec_admit: prompt is null");
   if (b < 0 || b >= c->B) return fail(c, SPEC_ERR_INVALID_ARG, "spec_admit: slot %d outside 0..B-1=%d", b, c->B - 1);
+  if (P < 1) return fail(c, SPEC_ERR_INVALID_ARG, "spec_admit: P must be at least 1");
+  if ((long long)P + c->run.gen_max + c->run.s_max > c->run.L_max)
+    return fail(c, SPEC_ERR_CAPACITY, "spec_admit: P + gen_max + s_max = %lld exceeds L_max = %d",
+                (long long)P + c->run.gen_max + c->run.s_max, c->run.L_max);
+  for (Model *m : {&c->tgt, &c->drf})
+    if (m->present && m->desc.pos_kind == SPEC_POS_LEARNED && P + c->run.gen_max + c->run.s_max > m->desc.max_pos)
+      return fail(c, SPEC_ERR_CAPACITY, "spec_admit: positions would exceed the learned position table (max_pos=%d)",
+                  m->desc.max_pos);
   if (c->draft_j != 0 || c->verified_s >= 0)
     return fail(c, SPEC_ERR_STATE, "spec_admit: a round is in progress; finish it with spec_accept_commit first");
-  const int P = c->P;
-  launch_state_admit(c, b, d_prompt, c->stream);
-  int rc = prefill(c, b, 1);
+  launch_state_admit(c, b, d_prompt, P, c->stream);
+  c->P_host[(size_t)b] = P;
+  c->n_ub = std::max(c->n_ub, (int)P);
+  int rc = prefill(c, b, 1, P);
   if (rc) return rc;
   HIPCHK(c, hipGetLastError());
   return SPEC_OK;
@@ -456,7 +467,7 @@ extern "C" int spec_rewind(spec_ctx *c) {
   c->draft_lag = 1;
   c->verified_s = -1;
   c->proposals_ready = false;
-  c->n_ub = c->P;
+  c->n_ub = *std::max_element(c->P_host.begin(), c->P_host.end());
   launch_state_reset(c, nullptr, c->stream);
   HIPCHK(c, hipGetLastError());
   return SPEC_OK;
@@ -556,7 +567,7 @@ extern "C" int spec_accept_commit(spec_ctx *c, int32_t s) {
   if (c->verified_s < 0) return fail(c, SPEC_ERR_STATE, "spec_accept_commit: no verify step to commit");
   if (s != c->verified_s) return fail(c, SPEC_ERR_STATE, "spec_accept_commit: verify step ran with s=%d, got s=%d", c->verified_s, s);
   { KScope k(c, SPEC_KCLASS_OTHER); launch_accept(c, s, c->stream); }
-  c->n_ub = std::min(c->n_ub + s + 1, c->P + c->run.gen_max);
+  c->n_ub = std::min(c->n_ub + s + 1, *std::max_element(c->P_host.begin(), c->P_host.end()) + c->run.gen_max);
   if (c->drf.present) c->draft_lag = c->draft_j > 0 ? 2 : std::min(c->draft_lag + 1, Q_LIMIT + 1);
   c->draft_j = 0;
   c->verified_s = -1;
@@ -702,10 +713,11 @@ extern "C" int spec_read_output(spec_ctx *c, int32_t *h_tokens, int32_t *h_len, 
   HIPCHK(c, hipMemcpy(n.data(), c->st.n, (size_t)c->B * 4, hipMemcpyDeviceToHost));
   const int G = c->run.gen_max;
   for (int b = 0; b < c->B; ++b) {
-    int len = std::max(0, std::min(n[b] - c->P, G));
+    const int Pb = c->P_host[(size_t)b];
+    int len = std::max(0, std::min(n[b] - Pb, G));
     h_len[b] = len;
     if (len)
-      HIPCHK(c, hipMemcpy(h_tokens + (size_t)b * G, c->st.seq + (size_t)b * c->run.L_max + c->P, (size_t)len * 4,
+      HIPCHK(c, hipMemcpy(h_tokens + (size_t)b * G, c->st.seq + (size_t)b * c->run.L_max + Pb, (size_t)len * 4,
                           hipMemcpyDeviceToHost));
   }
   if (h_hist) {

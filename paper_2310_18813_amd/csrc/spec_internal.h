@@ -91,6 +91,7 @@ struct Workspace {
 struct State {
   int32_t *seq = nullptr;     // [B_max][L_max] committed tokens (prompt + emitted)
   int32_t *n = nullptr;       // [B_max] committed length
+  int32_t *P_b = nullptr;     // [B_max] prompt length of the sequence in the slot (admissions may differ from the batch's)
   int32_t *t = nullptr;       // [B_max][s_max]   proposals of the round
   int32_t *a = nullptr;       // [B_max][s_max+1] target greedy tokens of the round
   int32_t *l_last = nullptr;  // [B_max]
@@ -111,7 +112,8 @@ struct spec_ctx {
   int NC_max = 1;         // attention chunks that cover L_max
   int n_ub = 0;           // host upper bound of every sequence's committed length
   // host-side bookkeeping
-  int B = 0, P = 0;
+  int B = 0, P = 0;       // current batch; P: prompt length given to the last reset
+  std::vector<int32_t> P_host;  // [B] prompt length per slot (host mirror of st.P_b)
   bool active = false;
   int draft_j = 0;        // draft steps done this round
   int draft_lag = 1;      // upper bound of n_b - kv_draft_b
@@ -179,7 +181,7 @@ void launch_fill_proposals(spec_ctx *c, int s, hipStream_t st);
 void launch_copy_proposals(spec_ctx *c, const int32_t *d_tok, int s, hipStream_t st);
 void launch_store_draft_token(spec_ctx *c, int j, bool write_proposal, hipStream_t st);
 void launch_state_reset(spec_ctx *c, const int32_t *d_prompt_or_null, hipStream_t st);
-void launch_state_admit(spec_ctx *c, int b, const int32_t *d_prompt, hipStream_t st);
+void launch_state_admit(spec_ctx *c, int b, const int32_t *d_prompt, int P, hipStream_t st);
 void launch_kv_convert(spec_ctx *c, const Model &m, int layer, int B, int len, void *k, void *v, bool import_,
                        hipStream_t st);
 

@@ -129,6 +129,108 @@ def test_admitted_sequences_decode_as_if_alone(orc, B, name, mode):
     ctx.close()
 
 
+RAGGED = {
+    # admitted prompts shorter and longer than the batch's; the longest needs two prefill passes of its own
+    "tiny_fp32": dict(lengths=[5, 23, 1]),
+    "small_bf16": dict(lengths=[9, 40, 21]),
+    "small_fp16_opt": dict(lengths=[12, 2, 7]),
+}
+
+
+@pytest.mark.parametrize("mode", ["table", "draft"])
+@pytest.mark.parametrize("name", list(RAGGED))
+def test_admitted_prompts_of_other_lengths(orc, B, name, mode):
+    """Every slot keeps its own prompt length: emitted tokens are the greedy continuation of that prompt
+    (the library decoding it alone, without speculation; the CPU oracle for fp32), the admitted prompt's
+    cache rows equal those of a reset with that prompt, and a rewind takes every slot back to its own prompt."""
+    c = CASES[name]
+    nB, P, N, s = c["B"], c["P"], c["N"], c["s"]
+    lengths = RAGGED[name]["lengths"]
+    ot, od, gt, gd = build_pair(orc, c["tgt"], c["drf"], c["dtype"], c["seed"], DEV)
+    L_max = max(P, max(lengths)) + N + s + 3
+    pmode = B.PROPOSALS_EXTERNAL if mode == "table" else B.PROPOSALS_DRAFT
+    ctx = B.Context(c["tgt"], gt, c["drf"], gd, c["dtype"], nB, s, L_max, N, pmode, DEV)
+    vocab = c["tgt"]["vocab"]
+    base = si.make_prompts(nB, P, vocab, c["seed"])
+    extra = [si.make_prompts(1, L, vocab, c["seed"] + 100 + i)[0] for i, L in enumerate(lengths)]
+    if mode == "table":
+        ctx.spec_set_proposal_table(np.zeros((nB, L_max), dtype=np.int32))
+    ref_base = greedy_reference(ctx, base, nB, N)
+    ref_extra, kv_extra = [], []
+    for p in extra:                      # each admitted prompt alone: its continuation and its cache rows
+        ctx.spec_reset(p[None, :])
+        kv = []
+        if len(p) > 1:
+            for which, desc in ((B.MODEL_TARGET, c["tgt"]), (B.MODEL_DRAFT, c["drf"])):
+                K, V = ctx.spec_kv_export(which, desc["n_layers"] - 1, 1, len(p) - 1)
+                kv += [K[0].clone(), V[0].clone()]
+        kv_extra.append(kv)
+        ctx.spec_round(0, N)
+        toks, _ = ctx.spec_read_output()
+        ref_extra.append(np.array(toks[0]))
+        if name == "tiny_fp32":
+            assert np.array_equal(ref_extra[-1], ot.greedy(p, N))
+
+    owner = [("base", b) for b in range(nB)]
+
+    def prompt_of(o):
+        return base[o[1]] if o[0] == "base" else extra[o[1]]
+
+    def ref_of(o):
+        return ref_base[o[1]] if o[0] == "base" else ref_extra[o[1]]
+
+    def set_table():
+        if mode != "table":
+            return
+        truth = np.zeros((nB, L_max), dtype=np.int32)
+        for b in range(nB):
+            Pb = len(prompt_of(owner[b]))
+            truth[b, Pb:Pb + N] = ref_of(owner[b])
+        ctx.spec_set_proposal_table(si.make_proposal_table(truth, c["alpha"], vocab, c["seed"] + 5))
+
+    def admit(b, i):
+        owner[b] = ("extra", i)
+        ctx.spec_admit(b, extra[i])
+        set_table()
+
+    def check():
+        toks, _ = ctx.spec_read_output()
+        n, _, _, _ = ctx.spec_read_state()
+        for b in range(nB):
+            assert np.array_equal(np.array(toks[b]), ref_of(owner[b])), (name, mode, b, owner[b])
+            assert n[b] == len(prompt_of(owner[b])) + N
+
+    set_table()
+    ctx.spec_reset(base)
+    ctx.spec_round(s, 2)
+    admit(0, 0)
+    admit(nB - 1, 1)
+    if len(extra[1]) > 1:                # same cache bits as the single-sequence reset left
+        got = []
+        for which, desc in ((B.MODEL_TARGET, c["tgt"]), (B.MODEL_DRAFT, c["drf"])):
+            K, V = ctx.spec_kv_export(which, desc["n_layers"] - 1, nB, len(extra[1]) - 1)
+            got += [K[nB - 1], V[nB - 1]]
+        for g, w in zip(got, kv_extra[1]):
+            assert torch.equal(g, w)
+    ctx.spec_round(s, 3)
+    admit(1, 2)
+    ctx.spec_round(s, N)
+    check()
+    # back to "prompts just given", each slot to its own prompt, and the same tokens again
+    ctx.spec_rewind()
+    n, _, _, _ = ctx.spec_read_state()
+    assert list(n) == [len(prompt_of(o)) for o in owner]
+    ctx.spec_round(s, N)
+    check()
+    # a new batch forgets the admitted lengths
+    ctx.spec_reset(base)
+    owner[:] = [("base", b) for b in range(nB)]
+    set_table()
+    ctx.spec_round(s, N)
+    check()
+    ctx.close()
+
+
 def test_admit_is_refused_where_it_cannot_work(orc, B):
     c = CASES["tiny_fp32"]
     nB, P, N, s = c["B"], c["P"], c["N"], c["s"]
@@ -141,6 +243,11 @@ def test_admit_is_refused_where_it_cannot_work(orc, B):
     for bad in (-1, nB):
         with pytest.raises(B.SpecError):
             ctx.spec_admit(bad, prompts[0])    # slot out of range
+    with pytest.raises(B.SpecError):           # P + gen_max + s_max would not fit into L_max
+        ctx.spec_admit(0, si.make_prompts(1, P + 4, c["tgt"]["vocab"], 5)[0])
+    with pytest.raises(B.SpecError):
+        ctx.spec_admit(0, np.zeros(0, dtype=np.int32))   # an empty prompt
+    ctx.spec_admit(0, si.make_prompts(1, P + 3, c["tgt"]["vocab"], 5)[0])   # the longest that fits
     ctx.spec_draft_step(1)
     with pytest.raises(B.SpecError):
         ctx.spec_admit(0, prompts[0])          # inside a round
