@@ -272,26 +272,29 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
   }
 
   constexpr int TILES = NB * MT;
-  // folded norm from the operand fragments: the waves' slice sums meet in LDS and are added in slice order
+  // folded norm from the operand fragments: the waves' slice sums meet in LDS (behind the same barrier as the
+  // first round of partial tiles) and are added in slice order
   __shared__ float ssq_s[FOLDX ? 8 : 1][FOLDX ? MT * 64 : 1];
   float rinv_x[MT];
-  if (foldx) {
-    if (KS > 1) {
+  if (foldx && KS > 1) {
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) ssq_s[w][mt * 64 + lane] = ssq[mt];
-      __syncthreads();
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        float t = ssq_s[0][mt * 64 + lane];
-        for (int s = 1; s < KS; ++s) t += ssq_s[s][mt * 64 + lane];
-        ssq[mt] = t;
-      }
-    }
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) rinv_x[mt] = row_inv_from_lane_ssq(ssq[mt], a.ss_d, a.ss_eps);
+    for (int mt = 0; mt < MT; ++mt) ssq_s[w][mt * 64 + lane] = ssq[mt];
   }
+  auto finish_rinv = [&]() {
+    if (!foldx) return;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      float t = ssq[mt];
+      if (KS > 1) {
+        t = ssq_s[0][mt * 64 + lane];
+        for (int s = 1; s < KS; ++s) t += ssq_s[s][mt * 64 + lane];
+      }
+      rinv_x[mt] = row_inv_from_lane_ssq(t, a.ss_d, a.ss_eps);
+    }
+  };
   auto rinv_of = [&](int mt) { return foldx ? rinv_x[mt] : 1.0f; };
   if (KS == 1) {
+    finish_rinv();
 #pragma unroll
     for (int t = 0; t < TILES; ++t)
       tile_epilogue<T, EPI>(a, acc[t / MT][t % MT], nt0 + t / MT, m_base + (t % MT) * 16 + c, g, rinv_of(t % MT));
@@ -308,6 +311,7 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
       if (t < TILES) *(f32x4_v *)&red[((size_t)(w * SLOTS + slot) * 64 + lane) * 4] = acc[t / MT][t % MT];
     }
     __syncthreads();
+    if (r == 0) finish_rinv();
 #pragma unroll
     for (int slot = 0; slot < 8; ++slot) {
       const int t = r * 8 + slot;
