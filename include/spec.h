@@ -138,6 +138,13 @@ int spec_destroy(spec_ctx *ctx);
    [0, vocab) (ids are clamped on the device, not checked).                           */
 int spec_reset(spec_ctx *ctx, int32_t B, const int32_t *d_prompt, int32_t P);
 
+/* As spec_reset for prompts of different lengths: row b of d_prompt ([B][P_stride], int32, device) holds the
+   h_len[b] prompt tokens of sequence b (h_len: host, B entries, 1 <= h_len[b] <= P_stride; the rest of a row
+   is ignored).  One batch prefill over the longest prompt, rows beyond a sequence's own prompt being dead
+   rows of the pass; the capacity rules of spec_reset apply to the longest prompt.  Every sequence emits up to
+   gen_max tokens after its own prompt.  Synchronises the stream once (the lengths go to the device).       */
+int spec_reset_ragged(spec_ctx *ctx, int32_t B, const int32_t *d_prompt, int32_t P_stride, const int32_t *h_len);
+
 /* As spec_reset but without touching the KV caches: the caller provides positions
    0..P-2 through spec_kv_import.  For micro-benchmarks and tests that start from a
    given cache.                                                                        */

@@ -25,7 +25,7 @@ DTYPE_CODE = {"fp32": DTYPE_F32, "bf16": DTYPE_BF16, "fp16": DTYPE_F16}
 TORCH_DTYPE = {DTYPE_F32: torch.float32, DTYPE_BF16: torch.bfloat16, DTYPE_F16: torch.float16}
 
 EXPORTS = ["spec_last_error", "spec_workspace_bytes", "spec_init", "spec_destroy", "spec_reset",
-           "spec_reset_noprefill", "spec_admit", "spec_set_seq_s", "spec_rewind", "spec_set_proposal_table",
+           "spec_reset_noprefill", "spec_reset_ragged", "spec_admit", "spec_set_seq_s", "spec_rewind", "spec_set_proposal_table",
            "spec_set_proposals", "spec_draft_step", "spec_verify_step", "spec_accept_commit", "spec_round",
            "spec_profile_and_choose_s", "spec_set_lut", "spec_choose_s", "spec_read_output",
            "spec_read_state", "spec_kv_import", "spec_kv_export", "spec_kernel_timing",
@@ -59,6 +59,7 @@ lib.spec_init.argtypes = [C.POINTER(ModelDesc), C.POINTER(Weights), C.POINTER(Mo
 lib.spec_destroy.argtypes = [_vp]
 lib.spec_reset.argtypes = [_vp, _i32, _vp, _i32]
 lib.spec_reset_noprefill.argtypes = [_vp, _i32, _vp, _i32]
+lib.spec_reset_ragged.argtypes = [_vp, _i32, _vp, _i32, _i32p]
 lib.spec_rewind.argtypes = [_vp]
 lib.spec_admit.argtypes = [_vp, _i32, _vp, _i32]
 lib.spec_set_seq_s.argtypes = [_vp, _vp]
@@ -187,6 +188,16 @@ class Context:
     def spec_reset(self, prompt):
         p = self._prompt(prompt)
         _check(lib.spec_reset(self.h, p.shape[0], _dp(p), p.shape[1]), self.h)
+        self.B = p.shape[0]
+
+    def spec_reset_ragged(self, prompts):
+        """prompts: a list of 1-d token arrays of different lengths."""
+        lens = [int(len(p)) for p in prompts]
+        rows = torch.zeros((len(prompts), max(lens)), dtype=torch.int32)
+        for b, p in enumerate(prompts):
+            rows[b, :lens[b]] = torch.as_tensor(p, dtype=torch.int32)
+        p = rows.to(self.device).contiguous()
+        _check(lib.spec_reset_ragged(self.h, p.shape[0], _dp(p), p.shape[1], (C.c_int32 * len(lens))(*lens)), self.h)
         self.B = p.shape[0]
 
     def spec_reset_noprefill(self, prompt):

@@ -23,7 +23,7 @@ template <class T, bool PREP>
 __global__ __launch_bounds__(256) void k_assemble_embed(int kind, int q, int j, int P, int s_max, int L_max, int vocab, int d,
                                  int learned_pos, int seq_groups, const int32_t *__restrict__ seq, const int32_t *__restrict__ n,
                                  const int32_t *__restrict__ kv_draft, const int32_t *__restrict__ t,
-                                 const int32_t *__restrict__ seq_s,
+                                 const int32_t *__restrict__ seq_s, const int32_t *__restrict__ P_b,
                                  const T *__restrict__ tok_emb, const T *__restrict__ pos_emb,
                                  int32_t *__restrict__ row_tok, int32_t *__restrict__ row_pos, float *__restrict__ h,
                                  op_t *__restrict__ x) {
@@ -50,7 +50,7 @@ __global__ __launch_bounds__(256) void k_assemble_embed(int kind, int q, int j, 
     }
   } else {  // PASS_PREFILL: j is the base position
     int p = j + i;
-    if (p < P - 1) { pos = p; tok = seq[(size_t)b * L_max + p]; }
+    if (p < P_b[b] - 1) { pos = p; tok = seq[(size_t)b * L_max + p]; }  // the sequence's own prompt length
   }
   if (pos >= L_max) pos = -1;  // cannot happen when the host checks hold; never write out of range
   tok = min(max(tok, 0), vocab - 1);
@@ -86,7 +86,7 @@ void launch_assemble_embed(const spec_ctx *c, const Model &m, const PassArgs &pa
                        (int)(m.desc.pos_kind == SPEC_POS_LEARNED), pa.seq_groups,
                        c->st.seq + (size_t)pa.b0 * c->run.L_max,
                        c->st.n + pa.b0, c->drf.kv_len ? c->drf.kv_len + pa.b0 : nullptr,
-                       c->st.t + (size_t)pa.b0 * c->run.s_max, c->seq_s ? c->seq_s + pa.b0 : nullptr,
+                       c->st.t + (size_t)pa.b0 * c->run.s_max, c->seq_s ? c->seq_s + pa.b0 : nullptr, c->st.P_b + pa.b0,
                        (const T *)m.tok_emb, (const T *)m.pos_emb, c->ws.row_tok, c->ws.row_pos, c->ws.h,
                        (op_t *)c->ws.x));
 }
@@ -286,17 +286,18 @@ void launch_accept(spec_ctx *c, int s, hipStream_t st) {
 }
 
 // -------------------------------------------------------------------------
-// With a prompt: a new batch, every sequence P tokens long.  Without: back to "prompts just given", every sequence
-// to its own prompt length (slots admitted later may differ from the batch's).
-__global__ void k_state_reset(int B, int P, int L_max, int s_max, const int32_t *__restrict__ prompt,
+// With a prompt: a new batch, every sequence P tokens long — or, ragged, prompt rows of stride P of which sequence
+// b uses the first P_b[b] (already on the device).  Without: back to "prompts just given", every sequence to its
+// own prompt length.
+__global__ void k_state_reset(int B, int P, int ragged, int L_max, int s_max, const int32_t *__restrict__ prompt,
                               int32_t *__restrict__ seq, int32_t *__restrict__ n, int32_t *__restrict__ P_b,
                               int32_t *__restrict__ kv_draft,
                               int32_t *__restrict__ l_last, unsigned long long *__restrict__ hist,
                               unsigned long long *__restrict__ counters) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (prompt && i < B * P) seq[(size_t)(i / P) * L_max + i % P] = prompt[i];
+  if (prompt && i < B * P && (!ragged || i % P < P_b[i / P])) seq[(size_t)(i / P) * L_max + i % P] = prompt[i];
   if (i < B) {
-    const int Pi = prompt ? P : P_b[i];
+    const int Pi = (prompt && !ragged) ? P : P_b[i];
     P_b[i] = Pi;
     n[i] = Pi; l_last[i] = 0;
     if (kv_draft) kv_draft[i] = Pi - 1;
@@ -318,11 +319,11 @@ void launch_state_admit(spec_ctx *c, int b, const int32_t *d_prompt, int P, hipS
                      c->st.seq + (size_t)b * c->run.L_max, c->st.n + b, c->st.P_b + b,
                      c->drf.kv_len ? c->drf.kv_len + b : nullptr, c->st.l_last + b);
 }
-void launch_state_reset(spec_ctx *c, const int32_t *d_prompt, hipStream_t st) {
-  int work = c->B * c->P;
+void launch_state_reset(spec_ctx *c, const int32_t *d_prompt, int P_stride, bool ragged, hipStream_t st) {
+  int work = c->B * P_stride;
   if (work < c->run.s_max + 1) work = c->run.s_max + 1;
   if (work < 2) work = 2;
-  hipLaunchKernelGGL(k_state_reset, dim3((work + 255) / 256), dim3(256), 0, st, c->B, c->P, c->run.L_max,
+  hipLaunchKernelGGL(k_state_reset, dim3((work + 255) / 256), dim3(256), 0, st, c->B, P_stride, (int)ragged, c->run.L_max,
                      c->run.s_max, d_prompt, c->st.seq, c->st.n, c->st.P_b, c->drf.kv_len, c->st.l_last, c->st.hist,
                      c->st.counters);
 }

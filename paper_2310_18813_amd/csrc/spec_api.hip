@@ -396,11 +396,23 @@ static int prefill(spec_ctx *c, int b0, int B, int P) {
 }
 
 // ------------------------------------------------------------------ reset
-static int do_reset(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32_t P, bool prefill, const char *who) {
+// h_len: null (every sequence P tokens long) or B prompt lengths in 1..P, P then being the row stride of d_prompt
+static int do_reset(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32_t P, const int32_t *h_len, bool prefill,
+                    const char *who) {
   if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "%s: ctx is null", who);
   if (!d_prompt) return fail(c, SPEC_ERR_INVALID_ARG, "%s: prompt is null", who);
   if (B < 1 || B > c->run.B_max) return fail(c, SPEC_ERR_CAPACITY, "%s: B=%d outside 1..B_max=%d", who, B, c->run.B_max);
   if (P < 1) return fail(c, SPEC_ERR_INVALID_ARG, "%s: P must be at least 1", who);
+  const int32_t stride = P;
+  if (h_len) {  // the longest prompt decides what has to fit
+    int32_t longest = 0;
+    for (int b = 0; b < B; ++b) {
+      if (h_len[b] < 1 || h_len[b] > stride)
+        return fail(c, SPEC_ERR_INVALID_ARG, "%s: length %d of sequence %d outside 1..%d", who, h_len[b], b, stride);
+      longest = std::max(longest, h_len[b]);
+    }
+    P = longest;
+  }
   if ((long long)P + c->run.gen_max + c->run.s_max > c->run.L_max)
     return fail(c, SPEC_ERR_CAPACITY, "%s: P + gen_max + s_max = %lld exceeds L_max = %d", who,
                 (long long)P + c->run.gen_max + c->run.s_max, c->run.L_max);
@@ -410,14 +422,19 @@ static int do_reset(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32_t P, 
                   m->desc.max_pos);
   c->B = B;
   c->P = P;
-  c->P_host.assign((size_t)B, P);
+  if (h_len) c->P_host.assign(h_len, h_len + B);
+  else c->P_host.assign((size_t)B, P);
   c->n_ub = P;
   c->active = true;
   c->draft_j = 0;
   c->draft_lag = 1;
   c->verified_s = -1;
   c->proposals_ready = false;
-  launch_state_reset(c, d_prompt, c->stream);
+  if (h_len) {  // in stream order, and done with the host buffer before anything can change it
+    HIPCHK(c, hipMemcpyAsync(c->st.P_b, c->P_host.data(), (size_t)B * 4, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+  }
+  launch_state_reset(c, d_prompt, stride, h_len != nullptr, c->stream);
   if (prefill) {
     int rc = ::prefill(c, 0, B, P);
     if (rc) return rc;
@@ -427,10 +444,14 @@ static int do_reset(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32_t P, 
 }
 
 extern "C" int spec_reset(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32_t P) {
-  return do_reset(c, B, d_prompt, P, true, "spec_reset");
+  return do_reset(c, B, d_prompt, P, nullptr, true, "spec_reset");
+}
+extern "C" int spec_reset_ragged(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32_t P_stride, const int32_t *h_len) {
+  if (c && !h_len) return fail(c, SPEC_ERR_INVALID_ARG, "spec_reset_ragged: lengths are null");
+  return do_reset(c, B, d_prompt, P_stride, h_len, true, "spec_reset_ragged");
 }
 extern "C" int spec_reset_noprefill(spec_ctx *c, int32_t B, const int32_t *d_prompt, int32_t P) {
-  return do_reset(c, B, d_prompt, P, false, "spec_reset_noprefill");
+  return do_reset(c, B, d_prompt, P, nullptr, false, "spec_reset_noprefill");
 }
 
 // Continuous batching: one slot of the running batch starts over with a new prompt (of any length that fits);
@@ -468,7 +489,7 @@ extern "C" int spec_rewind(spec_ctx *c) {
   c->verified_s = -1;
   c->proposals_ready = false;
   c->n_ub = *std::max_element(c->P_host.begin(), c->P_host.end());
-  launch_state_reset(c, nullptr, c->stream);
+  launch_state_reset(c, nullptr, 1, false, c->stream);
   HIPCHK(c, hipGetLastError());
   return SPEC_OK;
 }

@@ -180,7 +180,7 @@ void launch_accept(spec_ctx *c, int s, hipStream_t st);
 void launch_fill_proposals(spec_ctx *c, int s, hipStream_t st);
 void launch_copy_proposals(spec_ctx *c, const int32_t *d_tok, int s, hipStream_t st);
 void launch_store_draft_token(spec_ctx *c, int j, bool write_proposal, hipStream_t st);
-void launch_state_reset(spec_ctx *c, const int32_t *d_prompt_or_null, hipStream_t st);
+void launch_state_reset(spec_ctx *c, const int32_t *d_prompt, int P_stride, bool ragged, hipStream_t st);
 void launch_state_admit(spec_ctx *c, int b, const int32_t *d_prompt, int P, hipStream_t st);
 void launch_kv_convert(spec_ctx *c, const Model &m, int layer, int B, int len, void *k, void *v, bool import_,
                        hipStream_t st);

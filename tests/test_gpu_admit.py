@@ -231,6 +231,75 @@ def test_admitted_prompts_of_other_lengths(orc, B, name, mode):
     ctx.close()
 
 
+@pytest.mark.parametrize("mode", ["table", "draft"])
+@pytest.mark.parametrize("name", list(RAGGED))
+def test_batch_of_prompts_of_different_lengths(orc, B, name, mode):
+    """spec_reset_ragged: one batch prefill over prompts of different lengths.  Every sequence emits the greedy
+    continuation of its own prompt (the library decoding it alone; the CPU oracle for fp32) and its prompt's
+    cache rows carry the bits a reset with that prompt alone leaves."""
+    c = CASES[name]
+    N, s = c["N"], c["s"]
+    lengths = RAGGED[name]["lengths"] + [c["P"]]
+    nB = len(lengths)
+    ot, od, gt, gd = build_pair(orc, c["tgt"], c["drf"], c["dtype"], c["seed"], DEV)
+    L_max = max(lengths) + N + s + 3
+    pmode = B.PROPOSALS_EXTERNAL if mode == "table" else B.PROPOSALS_DRAFT
+    ctx = B.Context(c["tgt"], gt, c["drf"], gd, c["dtype"], nB, s, L_max, N, pmode, DEV)
+    vocab = c["tgt"]["vocab"]
+    prompts = [si.make_prompts(1, L, vocab, c["seed"] + 200 + i)[0] for i, L in enumerate(lengths)]
+    if mode == "table":
+        ctx.spec_set_proposal_table(np.zeros((nB, L_max), dtype=np.int32))
+    ref, kv_ref = [], []
+    last = {B.MODEL_TARGET: c["tgt"]["n_layers"] - 1, B.MODEL_DRAFT: c["drf"]["n_layers"] - 1}
+    for p in prompts:
+        ctx.spec_reset(p[None, :])
+        kv = []
+        if len(p) > 1:
+            for which in (B.MODEL_TARGET, B.MODEL_DRAFT):
+                K, V = ctx.spec_kv_export(which, last[which], 1, len(p) - 1)
+                kv += [K[0].clone(), V[0].clone()]
+        kv_ref.append(kv)
+        ctx.spec_round(0, N)
+        toks, _ = ctx.spec_read_output()
+        ref.append(np.array(toks[0]))
+        if name == "tiny_fp32":
+            assert np.array_equal(ref[-1], ot.greedy(p, N))
+    if mode == "table":
+        truth = np.zeros((nB, L_max), dtype=np.int32)
+        for b in range(nB):
+            truth[b, lengths[b]:lengths[b] + N] = ref[b]
+        ctx.spec_set_proposal_table(si.make_proposal_table(truth, c["alpha"], vocab, c["seed"] + 5))
+
+    ctx.spec_reset_ragged(prompts)
+    n, _, _, _ = ctx.spec_read_state()
+    assert list(n) == lengths
+    for b in range(nB):
+        if lengths[b] > 1:
+            got = []
+            for which in (B.MODEL_TARGET, B.MODEL_DRAFT):
+                K, V = ctx.spec_kv_export(which, last[which], nB, lengths[b] - 1)
+                got += [K[b], V[b]]
+            for g, w in zip(got, kv_ref[b]):
+                assert torch.equal(g, w), (name, mode, b)
+    for attempt in range(2):             # the second time after a rewind to the prompts
+        ctx.spec_round(s, N)
+        toks, _ = ctx.spec_read_output()
+        n, _, _, _ = ctx.spec_read_state()
+        for b in range(nB):
+            assert np.array_equal(np.array(toks[b]), ref[b]), (name, mode, attempt, b)
+            assert n[b] == lengths[b] + N
+        ctx.spec_rewind()
+        n, _, _, _ = ctx.spec_read_state()
+        assert list(n) == lengths
+    # refused: a length outside 1..stride
+    rows = torch.zeros((2, 4), dtype=torch.int32, device=DEV)
+    import ctypes as C
+    for bad in ([0, 4], [5, 1]):
+        rc = B.lib.spec_reset_ragged(ctx.h, 2, C.c_void_p(rows.data_ptr()), 4, (C.c_int32 * 2)(*bad))
+        assert rc == B.ERR_INVALID_ARG
+    ctx.close()
+
+
 def test_admit_is_refused_where_it_cannot_work(orc, B):
     c = CASES["tiny_fp32"]
     nB, P, N, s = c["B"], c["P"], c["N"], c["s"]
