@@ -170,6 +170,14 @@ int spec_admit(spec_ctx *ctx, int32_t b, const int32_t *d_prompt, int32_t P);
    round (SPEC_ERR_STATE).  Emitted tokens do not depend on the caps (Sec. 2).                            */
 int spec_set_seq_s(spec_ctx *ctx, const int32_t *d_s_or_null);
 
+/* End-of-sequence token (beyond the paper, whose sequences all run to a fixed length): once a sequence has
+   emitted eos_token it stops for good — the tokens the same round accepted behind it are dropped, its length no
+   longer moves, spec_read_output returns it up to and including the end token — until its slot is given a new
+   prompt (spec_admit) or the batch starts over (spec_reset*, spec_rewind).  -1 (the default) means none.  Takes
+   effect from the next spec_accept_commit; sequences already stopped stay stopped.  spec_profile_and_choose_s
+   ignores it.  Not allowed inside a round (SPEC_ERR_STATE).                                                 */
+int spec_set_eos(spec_ctx *ctx, int32_t eos_token);
+
 /* Back to the state right after the last reset (lengths, counters, emitted tokens);
    cached prompt KV is kept.                                                           */
 int spec_rewind(spec_ctx *ctx);

@@ -25,7 +25,7 @@ DTYPE_CODE = {"fp32": DTYPE_F32, "bf16": DTYPE_BF16, "fp16": DTYPE_F16}
 TORCH_DTYPE = {DTYPE_F32: torch.float32, DTYPE_BF16: torch.bfloat16, DTYPE_F16: torch.float16}
 
 EXPORTS = ["spec_last_error", "spec_workspace_bytes", "spec_init", "spec_destroy", "spec_reset",
-           "spec_reset_noprefill", "spec_reset_ragged", "spec_admit", "spec_set_seq_s", "spec_rewind", "spec_set_proposal_table",
+           "spec_reset_noprefill", "spec_reset_ragged", "spec_admit", "spec_set_seq_s", "spec_set_eos", "spec_rewind", "spec_set_proposal_table",
            "spec_set_proposals", "spec_draft_step", "spec_verify_step", "spec_accept_commit", "spec_round",
            "spec_profile_and_choose_s", "spec_set_lut", "spec_choose_s", "spec_read_output",
            "spec_read_state", "spec_kv_import", "spec_kv_export", "spec_kernel_timing",
@@ -63,6 +63,7 @@ lib.spec_reset_ragged.argtypes = [_vp, _i32, _vp, _i32, _i32p]
 lib.spec_rewind.argtypes = [_vp]
 lib.spec_admit.argtypes = [_vp, _i32, _vp, _i32]
 lib.spec_set_seq_s.argtypes = [_vp, _vp]
+lib.spec_set_eos.argtypes = [_vp, _i32]
 lib.spec_set_proposal_table.argtypes = [_vp, _vp]
 lib.spec_set_proposals.argtypes = [_vp, _vp, _i32]
 lib.spec_draft_step.argtypes = [_vp, _i32]
@@ -220,6 +221,9 @@ class Context:
         assert t.dim() == 1 and t.shape[0] >= self.B
         self._seq_s = t  # must outlive its use
         _check(lib.spec_set_seq_s(self.h, _dp(t)), self.h)
+
+    def spec_set_eos(self, eos_token):
+        _check(lib.spec_set_eos(self.h, -1 if eos_token is None else int(eos_token)), self.h)
 
     def spec_rewind(self):
         _check(lib.spec_rewind(self.h), self.h)

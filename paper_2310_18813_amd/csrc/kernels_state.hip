@@ -246,8 +246,10 @@ void launch_copy_proposals(spec_ctx *c, const int32_t *d_tok, int s, hipStream_t
 // only while all earlier ones matched the target's greedy token; the target's token after
 // the last survivor is appended.  Rollback is by length only: the K/V rows written for
 // rejected positions stay in the cache and are overwritten by the next round.
-__global__ void k_accept(int B, int s, int s_max, int L_max, const int32_t *__restrict__ P_b, int gen_max, int draft_steps,
-                         const int32_t *__restrict__ seq_s,
+// A sequence stops for good after gen_cap[b] emitted tokens: gen_max, or the count at which it emitted the end
+// token eos (the tokens a round accepted behind an end token are dropped with it).
+__global__ void k_accept(int B, int s, int s_max, int L_max, const int32_t *__restrict__ P_b, int32_t *__restrict__ gen_cap,
+                         int eos, int draft_steps, const int32_t *__restrict__ seq_s,
                          const int32_t *__restrict__ t, const int32_t *__restrict__ a, int32_t *__restrict__ seq,
                          int32_t *__restrict__ n, int32_t *__restrict__ kv_draft, int32_t *__restrict__ l_last,
                          unsigned long long *__restrict__ hist, unsigned long long *__restrict__ counters) {
@@ -264,9 +266,14 @@ __global__ void k_accept(int B, int s, int s_max, int L_max, const int32_t *__re
   if (seq_s && draft_steps > 0) draft_steps = max(1, min(draft_steps, sb));
   int l = 0;
   while (l < sb && tb[l] == ab[l]) ++l;
-  int take = min(l + 1, gen_max - gen);
+  const int cap = gen_cap[b];
+  int take = min(l + 1, cap - gen);
   if (take < 0) take = 0;
-  for (int i = 0; i < take; ++i) seq[(size_t)b * L_max + n_old + i] = (i < l) ? tb[i] : ab[l];
+  for (int i = 0; i < take; ++i) {
+    const int32_t tok = (i < l) ? tb[i] : ab[l];
+    seq[(size_t)b * L_max + n_old + i] = tok;
+    if (tok == eos) { take = i + 1; gen_cap[b] = gen + take; }
+  }
   const int n_new = n_old + take;
   n[b] = n_new;
   l_last[b] = l;
@@ -274,14 +281,14 @@ __global__ void k_accept(int B, int s, int s_max, int L_max, const int32_t *__re
     int kd = n_old + min(l, draft_steps - 1);
     kv_draft[b] = max(0, min(kd, n_new - 1));
   }
-  if (gen < gen_max) {
+  if (gen < cap) {
     atomicAdd(&hist[l], 1ull);
     atomicAdd(&counters[0], (unsigned long long)take);
   }
 }
 void launch_accept(spec_ctx *c, int s, hipStream_t st) {
   hipLaunchKernelGGL(k_accept, dim3((c->B + 63) / 64), dim3(64), 0, st, c->B, s, c->run.s_max, c->run.L_max, c->st.P_b,
-                     c->run.gen_max, c->draft_j, c->seq_s, c->st.t, c->st.a, c->st.seq, c->st.n, c->drf.kv_len, c->st.l_last,
+                     c->st.gen_cap, c->eos, c->draft_j, c->seq_s, c->st.t, c->st.a, c->st.seq, c->st.n, c->drf.kv_len, c->st.l_last,
                      c->st.hist, c->st.counters);
 }
 
@@ -289,8 +296,9 @@ void launch_accept(spec_ctx *c, int s, hipStream_t st) {
 // With a prompt: a new batch, every sequence P tokens long — or, ragged, prompt rows of stride P of which sequence
 // b uses the first P_b[b] (already on the device).  Without: back to "prompts just given", every sequence to its
 // own prompt length.
-__global__ void k_state_reset(int B, int P, int ragged, int L_max, int s_max, const int32_t *__restrict__ prompt,
+__global__ void k_state_reset(int B, int P, int ragged, int L_max, int s_max, int gen_max, const int32_t *__restrict__ prompt,
                               int32_t *__restrict__ seq, int32_t *__restrict__ n, int32_t *__restrict__ P_b,
+                              int32_t *__restrict__ gen_cap,
                               int32_t *__restrict__ kv_draft,
                               int32_t *__restrict__ l_last, unsigned long long *__restrict__ hist,
                               unsigned long long *__restrict__ counters) {
@@ -299,6 +307,7 @@ __global__ void k_state_reset(int B, int P, int ragged, int L_max, int s_max, co
   if (i < B) {
     const int Pi = (prompt && !ragged) ? P : P_b[i];
     P_b[i] = Pi;
+    gen_cap[i] = gen_max;
     n[i] = Pi; l_last[i] = 0;
     if (kv_draft) kv_draft[i] = Pi - 1;
   }
@@ -307,16 +316,17 @@ __global__ void k_state_reset(int B, int P, int ragged, int L_max, int s_max, co
 }
 // One batch slot back to "prompt just given": its tokens, length, draft-cache length.  Counters and the
 // accepted-length histogram belong to the whole batch and are left alone.
-__global__ void k_state_admit(int P, const int32_t *__restrict__ prompt, int32_t *__restrict__ seq_b,
-                              int32_t *__restrict__ n_b, int32_t *__restrict__ P_b_b, int32_t *__restrict__ kv_draft_b,
+__global__ void k_state_admit(int P, int gen_max, const int32_t *__restrict__ prompt, int32_t *__restrict__ seq_b,
+                              int32_t *__restrict__ n_b, int32_t *__restrict__ P_b_b, int32_t *__restrict__ gen_cap_b,
+                              int32_t *__restrict__ kv_draft_b,
                               int32_t *__restrict__ l_last_b) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < P) seq_b[i] = prompt[i];
-  if (i == 0) { *n_b = P; *P_b_b = P; *l_last_b = 0; if (kv_draft_b) *kv_draft_b = P - 1; }
+  if (i == 0) { *n_b = P; *P_b_b = P; *gen_cap_b = gen_max; *l_last_b = 0; if (kv_draft_b) *kv_draft_b = P - 1; }
 }
 void launch_state_admit(spec_ctx *c, int b, const int32_t *d_prompt, int P, hipStream_t st) {
-  hipLaunchKernelGGL(k_state_admit, dim3((P + 255) / 256), dim3(256), 0, st, P, d_prompt,
-                     c->st.seq + (size_t)b * c->run.L_max, c->st.n + b, c->st.P_b + b,
+  hipLaunchKernelGGL(k_state_admit, dim3((P + 255) / 256), dim3(256), 0, st, P, c->run.gen_max, d_prompt,
+                     c->st.seq + (size_t)b * c->run.L_max, c->st.n + b, c->st.P_b + b, c->st.gen_cap + b,
                      c->drf.kv_len ? c->drf.kv_len + b : nullptr, c->st.l_last + b);
 }
 void launch_state_reset(spec_ctx *c, const int32_t *d_prompt, int P_stride, bool ragged, hipStream_t st) {
@@ -324,7 +334,7 @@ void launch_state_reset(spec_ctx *c, const int32_t *d_prompt, int P_stride, bool
   if (work < c->run.s_max + 1) work = c->run.s_max + 1;
   if (work < 2) work = 2;
   hipLaunchKernelGGL(k_state_reset, dim3((work + 255) / 256), dim3(256), 0, st, c->B, P_stride, (int)ragged, c->run.L_max,
-                     c->run.s_max, d_prompt, c->st.seq, c->st.n, c->st.P_b, c->drf.kv_len, c->st.l_last, c->st.hist,
+                     c->run.s_max, c->run.gen_max, d_prompt, c->st.seq, c->st.n, c->st.P_b, c->st.gen_cap, c->drf.kv_len, c->st.l_last, c->st.hist,
                      c->st.counters);
 }
 

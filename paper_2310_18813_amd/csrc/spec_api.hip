@@ -91,7 +91,7 @@ static Sizes compute_sizes(const spec_model_desc *tgt, const spec_model_desc *dr
   z.M_max = run->B_max * z.q_pass;
   z.L_pad = (run->L_max + KV_LPAD - 1) / KV_LPAD * KV_LPAD;
   const size_t B = run->B_max, L = run->L_max, s = run->s_max, M = z.M_max;
-  z.state = al256(B * L * 4) + 5 * al256(B * 4) + al256(B * std::max<size_t>(s, 1) * 4) + al256(B * (s + 1) * 4) +
+  z.state = al256(B * L * 4) + 6 * al256(B * 4) + al256(B * std::max<size_t>(s, 1) * 4) + al256(B * (s + 1) * 4) +
             al256((s + 1) * 8) + al256(16);
   size_t d = tgt->d_model, f = tgt->d_ffn, V = tgt->vocab;
   size_t kf = tgt->ffn_kind == SPEC_FFN_SWIGLU ? 2 : 1;
@@ -225,6 +225,7 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
   S.seq = (int32_t *)carve(p, B * L * 4);
   S.n = (int32_t *)carve(p, B * 4);
   S.P_b = (int32_t *)carve(p, B * 4);
+  S.gen_cap = (int32_t *)carve(p, B * 4);
   S.l_last = (int32_t *)carve(p, B * 4);
   S.draft_arg = (int32_t *)carve(p, B * 4);
   c->drf.kv_len = (int32_t *)carve(p, B * 4);
@@ -300,6 +301,17 @@ extern "C" int spec_set_seq_s(spec_ctx *c, const int32_t *d_s_or_null) {
   if (c->draft_j != 0 || c->verified_s >= 0)
     return fail(c, SPEC_ERR_STATE, "spec_set_seq_s: a round is in progress; finish it with spec_accept_commit first");
   c->seq_s = d_s_or_null;
+  return SPEC_OK;
+}
+
+// End-of-sequence token (beyond the paper, whose sequences all run to a fixed length).
+extern "C" int spec_set_eos(spec_ctx *c, int32_t eos_token) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_set_eos: ctx is null");
+  if (eos_token < -1 || eos_token >= c->tgt.desc.vocab)
+    return fail(c, SPEC_ERR_INVALID_ARG, "spec_set_eos: token %d outside -1..vocab-1=%d", eos_token, c->tgt.desc.vocab - 1);
+  if (c->draft_j != 0 || c->verified_s >= 0)
+    return fail(c, SPEC_ERR_STATE, "spec_set_eos: a round is in progress; finish it with spec_accept_commit first");
+  c->eos = eos_token;
   return SPEC_OK;
 }
 
@@ -681,10 +693,10 @@ extern "C" int spec_profile_and_choose_s(spec_ctx *c, const int32_t *h_batch_siz
   const int nS = s_max_profile + 1;
   std::vector<double> grid((size_t)n_b * nS);
   std::vector<int32_t> lut(n_b);
-  struct CapsOff {  // the profiling stage times uniform rounds: per-sequence caps are set aside until it returns
-    spec_ctx *c; const int32_t *saved;
-    explicit CapsOff(spec_ctx *ctx) : c(ctx), saved(ctx->seq_s) { c->seq_s = nullptr; }
-    ~CapsOff() { c->seq_s = saved; }
+  struct CapsOff {  // the profiling stage times uniform rounds: per-sequence caps and the end token are set aside until it returns
+    spec_ctx *c; const int32_t *saved; int32_t saved_eos;
+    explicit CapsOff(spec_ctx *ctx) : c(ctx), saved(ctx->seq_s), saved_eos(ctx->eos) { c->seq_s = nullptr; c->eos = -1; }
+    ~CapsOff() { c->seq_s = saved; c->eos = saved_eos; }
   } caps_off(c);
   for (int bi = 0; bi < n_b; ++bi) {
     const int B = h_batch_sizes[bi];

@@ -92,6 +92,7 @@ struct State {
   int32_t *seq = nullptr;     // [B_max][L_max] committed tokens (prompt + emitted)
   int32_t *n = nullptr;       // [B_max] committed length
   int32_t *P_b = nullptr;     // [B_max] prompt length of the sequence in the slot (admissions may differ from the batch's)
+  int32_t *gen_cap = nullptr; // [B_max] tokens the sequence may emit: gen_max, or fewer once it has emitted the end token
   int32_t *t = nullptr;       // [B_max][s_max]   proposals of the round
   int32_t *a = nullptr;       // [B_max][s_max+1] target greedy tokens of the round
   int32_t *l_last = nullptr;  // [B_max]
@@ -113,6 +114,7 @@ struct spec_ctx {
   int n_ub = 0;           // host upper bound of every sequence's committed length
   // host-side bookkeeping
   int B = 0, P = 0;       // current batch; P: prompt length given to the last reset
+  int32_t eos = -1;       // end-of-sequence token (-1: none)
   std::vector<int32_t> P_host;  // [B] prompt length per slot (host mirror of st.P_b)
   bool active = false;
   int draft_j = 0;        // draft steps done this round
