@@ -188,6 +188,8 @@ def main():
         if grid is not None:
             entry["us_per_token_by_s"] = [round(x, 2) for x in grid[i]]
             entry["best_fixed_s"] = int(np.argmin(grid[i]))
+            # the table takes the smaller s among those within 1 % of the minimum (timing noise): never worse than this
+            entry["s_star_over_best_fixed"] = round(float(grid[i][s_b] / min(grid[i])), 4) if s_b < len(grid[i]) else None
         curve[str(b)] = entry
 
     vgrid = None if args.no_grid else verify_grid(ctx, torch, prompts, tdesc, P, B_list)
