@@ -272,7 +272,8 @@ int spec_measure_peaks(void *hip_stream, void *d_buf, size_t bytes, double *h_hb
 
 /* Test aid: pin the launch shape of the 16-bit verify attention.  0 = chosen from the batch size
    (default), 1 = one wave per (sequence, head, chunk) plus a merge kernel, 2 = one wave per
-   (sequence, head).  Results must not depend on it.                                          */
+   (sequence, head), 3 = one workgroup per (sequence, head) with a wave per chunk (falls back to 1 beyond 8
+   chunks).  Results must not depend on it.                                          */
 int spec_set_attention_shape(spec_ctx *ctx, int32_t shape);
 
 /* Per-kernel timing for benchmarks.  While enabled, every launch of the target model's

@@ -306,13 +306,95 @@ __global__ __launch_bounds__(256) void k_attn_seq(AttnArgs a) {
   }
 }
 
+// Launch shape 3: one workgroup per (sequence, head) with one wave per chunk; the partials meet in LDS and are
+// merged there in ascending chunk order, the head-dimension tiles dealt to the waves.  The same partials and the
+// same merge arithmetic as the other two shapes, without the merge launch and the partials' trip through memory:
+// for the few sequences of a small batch, where the attention is a chain of load latencies.
+template <class T, int HD, bool STREAM>
+__global__ __launch_bounds__(512) void k_attn_group(AttnArgs a) {
+  constexpr int KK = HD / 32, HT = HD / 16;
+  extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];  // [NC][HT][64] f32x4, then [NC][64] (max, sum)
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, W = blockDim.x >> 6;
+  const int bh = blockIdx.x, hh = bh % a.H, b = bh / a.H;
+  const WaveSetup w = wave_setup(a, b, lane);
+  const int d = a.H * HD;
+  const float scale = rsqrtf((float)HD) * LOG2E;  // score scale in base-2 exponent units
+  u32x4_v qf[KK];
+  const T *qrow = (const T *)a.q + (size_t)w.m_row * d + (size_t)hh * HD;
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) qf[kk] = *(const u32x4_v *)(qrow + kk * 32 + 8 * w.g);
+  const size_t cbh = a.seq_groups > 1 ? (size_t)(b / a.seq_groups) * a.H + hh : (size_t)bh;  // whose cache: the group's sequence
+  const T *kbase = (const T *)a.kc + cbh * a.L_pad * HD;
+  const T *vbase = (const T *)a.vc + cbh * (a.L_pad / KV_VBLOCK) * HD * KV_VBLOCK;
+  f32x4_v *pacc = (f32x4_v *)attn_smem;
+  float2 *pml = (float2 *)(attn_smem + (size_t)a.NC * HT * 64 * sizeof(f32x4_v));
+  for (int c = wv; c < a.NC; c += W) {
+    const int k0 = c * ATTN_CHUNK;
+    if (k0 > w.pmax) break;  // same for the whole wave; no row of the sequence reaches this chunk or a later one
+    const int kend = min(k0 + ATTN_CHUNK, w.pmax + 1);
+    float mc, lc;
+    f32x4_v ac[HT];
+    chunk_partial<T, HD, STREAM>(kbase, vbase, qf, k0, kend, w.j, w.g, w.pos_j, scale, mc, lc, ac);
+#pragma unroll
+    for (int ht = 0; ht < HT; ++ht) pacc[(c * HT + ht) * 64 + lane] = ac[ht];
+    pml[c * 64 + lane] = make_float2(mc, lc);
+  }
+  __syncthreads();
+  // row j needs the chunks up to its own position; every one of them was computed (pmax >= pos_j)
+  const int nc = w.pos_j >= 0 ? w.pos_j / ATTN_CHUNK + 1 : 0;
+  if (w.j >= a.q_rows) return;
+  const int m = b * a.q_rows + w.j;
+  for (int ht = wv; ht < HT; ht += W) {
+    float mr = 0.f, lr = 1.f;
+    f32x4_v ar = (f32x4_v){0.f, 0.f, 0.f, 0.f};
+    if (nc > 0) {
+      const float2 ml0 = pml[lane];
+      mr = ml0.x; lr = ml0.y;
+      ar = pacc[ht * 64 + lane];
+      for (int c = 1; c < nc; ++c) {
+        const float2 mlc = pml[c * 64 + lane];
+        const f32x4_v ac = pacc[(c * HT + ht) * 64 + lane];
+        float mn, wa, wb;
+        merge_weights(mr, mlc.x, scale, mn, wa, wb);
+        lr = merge_value(lr, wa, mlc.y, wb);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ar[i] = merge_value(ar[i], wa, ac[i], wb);
+        mr = mn;
+      }
+    }
+    const float inv = nc > 0 ? 1.0f / lr : 0.f;
+    op_t o4[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o4[i] = to_op(nc > 0 ? ar[i] * inv : 0.f);
+    const size_t at = xpack_index(m, hh * HD + ht * 16 + 4 * w.g, d >> 5);
+    *(uint2 *)((op_t *)a.out + at) = *(const uint2 *)o4;
+  }
+}
+
+template <class T, int HD, bool STREAM>
+static void launch_attn_group(const AttnArgs &a, int pairs, hipStream_t st) {
+  const size_t lds = (size_t)a.NC * ((HD / 16) * 64 * 16 + 64 * 8);
+  static size_t lds_set = 64 * 1024;  // more than the default 64 KB of LDS needs to be asked for
+  if (lds > lds_set) {
+    (void)hipFuncSetAttribute((const void *)k_attn_group<T, HD, STREAM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    lds_set = lds;
+  }
+  const int waves = a.NC < ATTN_GROUP_MAX_WAVES ? a.NC : ATTN_GROUP_MAX_WAVES;
+  hipLaunchKernelGGL((k_attn_group<T, HD, STREAM>), dim3(pairs), dim3(64 * waves), lds, st, a);
+}
+
 template <class T, int HD>
 static void launch_attn_hd(const AttnArgs &a, hipStream_t st) {
   const int M = a.B * a.q_rows;
   const int pairs = a.B * a.H;
   const bool seq = a.shape == 2 || (a.shape == 0 && (pairs >= ATTN_SEQ_MIN_PAIRS || a.NC == 1));
+  // few sequences: a workgroup per (sequence, head), as long as its partials fit into LDS with a wave per chunk
+  const bool group = !seq && (a.shape == 3 || a.shape == 0) && a.NC <= ATTN_GROUP_MAX_WAVES;
   if (seq) {
     hipLaunchKernelGGL((k_attn_seq<T, HD>), dim3((pairs + 3) / 4), dim3(256), 0, st, a);
+  } else if (group) {
+    if (pairs * a.NC >= ATTN_STREAM_MIN_WAVES) launch_attn_group<T, HD, true>(a, pairs, st);
+    else launch_attn_group<T, HD, false>(a, pairs, st);
   } else {
     if (pairs * a.NC >= ATTN_STREAM_MIN_WAVES)  // enough waves that the cache rows are a stream (measured)
       hipLaunchKernelGGL((k_attn_split<T, HD, true>), dim3((pairs * a.NC + 3) / 4), dim3(256), 0, st, a);

@@ -86,13 +86,14 @@ struct AttnArgs {
   void *out;                // [M][d] fp16, canonical element order, fragment layout
   float *part_acc;          // [M][H][NC][hd] un-normalised partial outputs
   float *part_ml;           // [M][H][NC][2] running max (raw score units) and sum
-  int shape;                // 0 auto, 1 split + merge, 2 one wave per (sequence, head)
+  int shape;                // 0 auto, 1 split + merge, 2 one wave per (sequence, head), 3 one workgroup per (sequence, head)
   int B, q_rows, H, hd, L_pad, NC;  // NC = chunks launched (upper bound over the batch)
   int seq_groups;           // consecutive groups of q_rows rows that belong to one sequence and share its cache (0 or 1: one)
 };
 constexpr int ATTN_CHUNK = 256;  // keys per split; boundaries at multiples of this position
 constexpr int ATTN_STREAM_MIN_WAVES = 1024;  // (sequence, head, chunk) waves from which the split kernel loads non-temporally
 constexpr int ATTN_SEQ_MIN_PAIRS = 768;   // (sequence, head) pairs from which one wave walks all chunks (measured: 24 sequences x 32 heads 55 -> 45 us)
+constexpr int ATTN_GROUP_MAX_WAVES = 8;  // chunks (= waves) of the one-workgroup-per-(sequence, head) shape: 70 KB of partials at head_dim 128 (four waves with the register budget of the split kernel were measured no faster, and slower at 16 sequences)
 void launch_attention_mfma(int dtype, const AttnArgs &a, hipStream_t st);
 
 }  // namespace spec

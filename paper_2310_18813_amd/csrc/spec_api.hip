@@ -317,7 +317,7 @@ extern "C" int spec_set_eos(spec_ctx *c, int32_t eos_token) {
 
 extern "C" int spec_set_attention_shape(spec_ctx *c, int32_t shape) {
   if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_set_attention_shape: ctx is null");
-  if (shape < 0 || shape > 2) return fail(c, SPEC_ERR_INVALID_ARG, "spec_set_attention_shape: shape must be 0, 1 or 2");
+  if (shape < 0 || shape > 3) return fail(c, SPEC_ERR_INVALID_ARG, "spec_set_attention_shape: shape must be 0, 1, 2 or 3");
   c->attn_shape = shape;
   return SPEC_OK;
 }

@@ -288,8 +288,8 @@ def test_call_order_and_capacity_errors(orc, B):
 
 
 def test_attention_launch_shapes_give_identical_bits(orc, B):
-    """The two launch shapes of the verify attention (split over chunks + merge kernel; one wave
-    per sequence and head) must agree bit for bit: the batch size picks between them."""
+    """The launch shapes of the verify attention (split over chunks + merge kernel; one wave per sequence and
+    head; one workgroup per sequence and head) must agree bit for bit: the batch size picks between them."""
     dtype, seed = "bf16", 5
     tdesc = si.llama_desc(1, 256, 2, 416, 300, 700)
     w = si.make_weights(tdesc, dtype, seed, device=DEV, emb_std=1.0)
@@ -300,12 +300,12 @@ def test_attention_launch_shapes_give_identical_bits(orc, B):
     prompts = si.make_prompts(3, kv + 1, 300, seed)
     props = si.make_prompts(3, 4, 300, seed + 1)
     got = []
-    for shape in (1, 2, 0):
+    for shape in (1, 2, 3, 0):
         ctx.spec_set_attention_shape(shape)
         ctx.spec_reset_noprefill(prompts)
         ctx.spec_set_proposals(torch.tensor(props))
         got.append(ctx.spec_verify_step(4, want_logits=True).clone())
         ctx.spec_accept_commit(4)
-    assert torch.equal(got[0], got[1]) and torch.equal(got[0], got[2])
+    assert all(torch.equal(got[0], g) for g in got[1:])
     with pytest.raises(B.SpecError):
-        ctx.spec_set_attention_shape(3)
+        ctx.spec_set_attention_shape(4)
