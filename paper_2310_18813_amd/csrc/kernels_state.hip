@@ -205,17 +205,6 @@ void launch_argmax_rows(const float *logits, int M, int V, int q, int out_stride
 
 // -------------------------------------------------------------------------
 // -------------------------------------------------------------------------
-// Draft step epilogue: in draft-proposal mode the draft's greedy token becomes t_j.
-__global__ void k_store_draft_token(int B, int j, int s_max, int write, const int32_t *__restrict__ arg,
-                                    int32_t *__restrict__ t) {
-  int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b < B && write) t[(size_t)b * s_max + j - 1] = arg[b];
-}
-void launch_store_draft_token(spec_ctx *c, int j, bool write_proposal, hipStream_t st) {
-  hipLaunchKernelGGL(k_store_draft_token, dim3((c->B + 63) / 64), dim3(64), 0, st, c->B, j, c->run.s_max,
-                     (int)write_proposal, c->st.draft_arg, c->st.t);
-}
-
 // External proposals: t_j = table[b][n_b + j - 1] (absolute position), or a plain copy.
 __global__ void k_fill_proposals(int B, int s, int s_max, int L_max, const int32_t *__restrict__ table,
                                  const int32_t *__restrict__ n, int32_t *__restrict__ t) {

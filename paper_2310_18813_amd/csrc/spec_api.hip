@@ -552,6 +552,10 @@ extern "C" int spec_draft_step(spec_ctx *c, int32_t j) {
   if (ext && j >= 2 && !c->proposals_ready)
     return fail(c, SPEC_ERR_STATE, "spec_draft_step: external proposals must be set before draft step 2");
   int rc;
+  // the draft's greedy token is t_j: the arg-max kernel writes it straight into the proposals (row stride s_max);
+  // with external proposals it goes to a scratch word per sequence instead
+  int32_t *arg_out = ext ? c->st.draft_arg : c->st.t + (j - 1);
+  const int arg_stride = ext ? 1 : c->run.s_max;
   if (j == 1) {
     const int q = c->draft_lag;
     if (q > Q_LIMIT || c->B * q > c->M_max)
@@ -562,13 +566,12 @@ extern "C" int spec_draft_step(spec_ctx *c, int32_t j) {
       c->proposals_ready = true;
     }
     PassArgs pa{PASS_DRAFT_FIRST, c->B, q, 1, c->P, c->run.s_max, c->run.L_max};
-    rc = forward_pass(c, c->drf, pa, HEAD_LAST, nullptr, c->st.draft_arg, 1, c->n_ub - 1);
+    rc = forward_pass(c, c->drf, pa, HEAD_LAST, nullptr, arg_out, arg_stride, c->n_ub - 1);
   } else {
     PassArgs pa{PASS_DRAFT_NEXT, c->B, 1, j, c->P, c->run.s_max, c->run.L_max};
-    rc = forward_pass(c, c->drf, pa, HEAD_LAST, nullptr, c->st.draft_arg, 1, c->n_ub + j - 2);
+    rc = forward_pass(c, c->drf, pa, HEAD_LAST, nullptr, arg_out, arg_stride, c->n_ub + j - 2);
   }
   if (rc) return rc;
-  if (!ext) launch_store_draft_token(c, j, true, c->stream);  // external proposals: nothing to store
   c->draft_j = j;
   HIPCHK(c, hipGetLastError());
   return SPEC_OK;

@@ -96,7 +96,7 @@ struct State {
   int32_t *t = nullptr;       // [B_max][s_max]   proposals of the round
   int32_t *a = nullptr;       // [B_max][s_max+1] target greedy tokens of the round
   int32_t *l_last = nullptr;  // [B_max]
-  int32_t *draft_arg = nullptr;  // [B_max] the draft's own greedy token of the last step
+  int32_t *draft_arg = nullptr;  // [B_max] where the draft's greedy token goes when the proposals come from outside
   unsigned long long *hist = nullptr;  // [s_max+1]
   unsigned long long *counters = nullptr;  // [0] emitted tokens total, [1] rounds
 };
@@ -181,7 +181,6 @@ void launch_argmax_rows(const float *logits, int M, int V, int q, int out_stride
 void launch_accept(spec_ctx *c, int s, hipStream_t st);
 void launch_fill_proposals(spec_ctx *c, int s, hipStream_t st);
 void launch_copy_proposals(spec_ctx *c, const int32_t *d_tok, int s, hipStream_t st);
-void launch_store_draft_token(spec_ctx *c, int j, bool write_proposal, hipStream_t st);
 void launch_state_reset(spec_ctx *c, const int32_t *d_prompt, int P_stride, bool ragged, hipStream_t st);
 void launch_state_admit(spec_ctx *c, int b, const int32_t *d_prompt, int P, hipStream_t st);
 void launch_kv_convert(spec_ctx *c, const Model &m, int layer, int B, int len, void *k, void *v, bool import_,
