@@ -86,8 +86,9 @@ bool fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&curso
     return amax + word;
   };
   void *head = bumpf(cursor, f.head.bytes(e));
-  launch_pack_weight(dt, 0, f.head, (int)d, hd, w->d_lm_head, nullptr, nullptr, nullptr, head,
-                     amax_of(n_amax - 1, w->d_lm_head, (size_t)D.vocab * d), st);
+  const void *gh = m.fold_norm ? m.final_norm_w : nullptr;  // the final norm's gain goes into the LM head the same way
+  launch_pack_weight(dt, 0, f.head, (int)d, hd, w->d_lm_head, nullptr, nullptr, gh, head,
+                     amax_of(n_amax - 1, w->d_lm_head, (size_t)D.vocab * d, gh), st);
   m.lm_head = head;
   m.rope = nullptr;
   if (D.pos_kind == SPEC_POS_ROPE) {
@@ -245,18 +246,28 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
   }
 }
 
-// Final norm over the rows that need a token, LM head with the arg-max fused in.
+// Final norm and LM head with the arg-max fused in, for the rows that need a token: all Mh rows of the pass, or
+// (last_of_q > 0) the last row of each of Mh groups of last_of_q rows.
+// RMS norm: folded into the LM head like the layers' norms (gain in the packed weights, 1 / rms taken by the GEMM
+// from the fp16 rows the last layer left); the GEMM then runs over every row of the pass and the second arg-max
+// stage picks the rows that are wanted.  Layer norm: k_norm gathers and normalises the wanted rows first.
 void fast_head(spec_ctx *c, const Model &m, int Mh, int last_of_q, float *logits_or_null, int q, int arg_stride, int32_t *arg_out,
                hipStream_t st) {
   const bool tgt = &m == &c->tgt;
-  { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, last_of_q, st); }
-  GemmArgs a = base_args(m.p_head, m.lm_head, m.s_head, nullptr, c->ws.x, Mh);
+  const bool fold = m.fold_norm;
+  const int rows = fold && last_of_q > 0 ? Mh * last_of_q : Mh;
+  if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, last_of_q, st); }
+  GemmArgs a = base_args(m.p_head, m.lm_head, m.s_head, nullptr, c->ws.x, rows);
   a.logits = logits_or_null;
   a.part_val = c->ws.head_part;
   a.part_idx = c->ws.head_part_idx;
+  if (fold) {
+    a.fold_x = 1; a.ss_d = m.desc.d_model; a.ss_eps = m.desc.norm_eps; a.rinv_ws = c->ws.row_inv;
+    if (gemm_wants_row_inv(a, EPI_LOGITS)) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_row_inv_x(a, st); }
+  }
   { KScope k(c, tgt ? SPEC_KCLASS_GEMM_HEAD : -1); launch_gemm_mfma(c->run.dtype, a, EPI_LOGITS, st); }
   { KScope k(c, tgt ? SPEC_KCLASS_OTHER : -1);
-    launch_argmax_partials(a.part_val, a.part_idx, Mh, m.p_head.NT, m.desc.vocab, q, arg_stride, arg_out, st); }
+    launch_argmax_partials(a.part_val, a.part_idx, Mh, fold ? last_of_q : 0, m.p_head.NT, m.desc.vocab, q, arg_stride, arg_out, st); }
 }
 
 }  // namespace spec

@@ -226,7 +226,7 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
 
-  constexpr bool FOLDX = EPI == EPI_QKV || EPI == EPI_SWIGLU;  // the GEMMs behind an RMS norm
+  constexpr bool FOLDX = EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LOGITS;  // the GEMMs behind an RMS norm
   const bool foldx = FOLDX && a.fold_x;
   float ssq[MT];  // this lane's part of the sum of squares of its rows over the wave's k-slice
 #pragma unroll
@@ -389,14 +389,16 @@ void launch_gemm_mfma(int dtype, const GemmArgs &a, int epi, hipStream_t st) {
 }
 
 // Second stage of the fused arg-max: one block per row over the per-strip partials.
-__global__ void k_argmax_partials(const float *__restrict__ pv, const int32_t *__restrict__ pi, int NT, int V, int q,
-                                  int out_stride, int32_t *__restrict__ out) {
+// row_step > 0: output row m takes the partials of GEMM row m * row_step + row_step - 1 (the last row of its group).
+__global__ void k_argmax_partials(const float *__restrict__ pv, const int32_t *__restrict__ pi, int row_step, int NT, int V,
+                                  int q, int out_stride, int32_t *__restrict__ out) {
   __shared__ float shv[4];
   __shared__ int shi[4];
   const int m = blockIdx.x;
   float bv = -INFINITY;
   int bi = 0x7fffffff;
-  for (int t = threadIdx.x; t < NT; t += 256) argmax_combine(bv, bi, pv[(size_t)m * NT + t], pi[(size_t)m * NT + t]);
+  const size_t src = row_step > 0 ? (size_t)m * row_step + row_step - 1 : (size_t)m;
+  for (int t = threadIdx.x; t < NT; t += 256) argmax_combine(bv, bi, pv[src * NT + t], pi[src * NT + t]);
   wave_argmax(bv, bi);
   if ((threadIdx.x & 63) == 0) { shv[threadIdx.x >> 6] = bv; shi[threadIdx.x >> 6] = bi; }
   __syncthreads();
@@ -406,10 +408,10 @@ __global__ void k_argmax_partials(const float *__restrict__ pv, const int32_t *_
     out[(size_t)(m / q) * out_stride + m % q] = bi;
   }
 }
-void launch_argmax_partials(const float *pv, const int32_t *pi, int M, int NT, int V, int q, int out_stride,
+void launch_argmax_partials(const float *pv, const int32_t *pi, int M, int row_step, int NT, int V, int q, int out_stride,
                             int32_t *out, hipStream_t st) {
   if (M <= 0) return;
-  hipLaunchKernelGGL(k_argmax_partials, dim3(M), dim3(256), 0, st, pv, pi, NT, V, q, out_stride, out);
+  hipLaunchKernelGGL(k_argmax_partials, dim3(M), dim3(256), 0, st, pv, pi, row_step, NT, V, q, out_stride, out);
 }
 
 }  // namespace spec

@@ -94,7 +94,7 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   // Folded norm.  With one row tile per wave the sum of squares comes from the operand fragments inside the
   // loop (frag_ssq: per lane, one chain per k-slice, slices added in order), where it costs nothing; with larger
   // wave tiles the loop has no issue slots to spare (measured: +10 %) and k_row_inv_x has left 1 / rms per row.
-  constexpr bool FOLD_EPI = EPI == EPI_QKV || EPI == EPI_SWIGLU;
+  constexpr bool FOLD_EPI = EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LOGITS;
   constexpr bool INLOOP = FOLD_EPI && MTW == 1;
   const bool inloop = INLOOP && a.fold_x;
   float ssq_cur = 0.f, ssq_tot = 0.f;
@@ -366,7 +366,7 @@ static void tile_for(const GemmArgs &a, int epi, int &MTW, int &NBW) {
 // With more than one row tile per wave the kernel reads 1 / rms of its rows from a.rinv_ws: the caller runs
 // launch_row_inv_x first when this says so.
 bool gemm_tile_wants_row_inv(const GemmArgs &a, int epi) {
-  if (!a.fold_x || (epi != EPI_QKV && epi != EPI_SWIGLU)) return false;
+  if (!a.fold_x || (epi != EPI_QKV && epi != EPI_SWIGLU && epi != EPI_LOGITS)) return false;
   int MTW, NBW;
   tile_for(a, epi, MTW, NBW);
   return MTW > 1;

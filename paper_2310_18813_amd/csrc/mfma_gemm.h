@@ -76,7 +76,7 @@ void launch_gemm_tile(int dtype, GemmArgs a, int epi, hipStream_t st);  // more 
 bool gemm_wants_row_inv(const GemmArgs &a, int epi);
 bool gemm_tile_wants_row_inv(const GemmArgs &a, int epi);
 void launch_row_inv_x(const GemmArgs &a, hipStream_t st);
-void launch_argmax_partials(const float *pv, const int32_t *pi, int M, int NT, int V, int q, int out_stride,
+void launch_argmax_partials(const float *pv, const int32_t *pi, int M, int row_step, int NT, int V, int q, int out_stride,
                             int32_t *out, hipStream_t st);
 
 struct AttnArgs {
