@@ -182,7 +182,9 @@ def main():
     curve = {}
     for i, b in enumerate([] if args.no_curve else B_list):
         s_b = ctx.spec_choose_s(b)
-        tk, tt, hb = run_timed(b, s_b, max(4, N // (s_b + 1) // 2), 1)
+        # enough rounds for a few hundred acceptance draws also at small batches, within what gen_max leaves room for
+        n_rounds = max(8, min(gen_max // (s_b + 1) - 2, -(-256 // b)))
+        tk, tt, hb = run_timed(b, s_b, n_rounds, 1)
         entry = {"s_star": s_b, "tokens_per_s": tk / tt,
                  "mean_accepted": round(sum(l * c for l, c in enumerate(hb)) / max(1, sum(hb)), 3)}
         if grid is not None:
