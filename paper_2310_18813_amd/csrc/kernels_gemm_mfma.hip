@@ -255,19 +255,37 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
         for (int mt = 0; mt < MT; ++mt) ssq[mt] = frag_ssq(xf[u][mt], ssq[mt]);
     }
   }
-  for (; kt < kt1; ++kt) {
-    u32x4_v wf[NB], xf[MT];
+  // the steps left over (fewer than U): all their loads go out together as well, so the end of a slice costs one
+  // memory latency, not one per step (a slice of the 7B down projection has 43 = 5 * 8 + 3 steps)
+  const int rem = __builtin_amdgcn_readfirstlane(kt1 - kt);  // same for the whole wave: scalar branches
+  if (U > 1 && rem > 0) {
+    u32x4_v wf[U][NB], xf[U][MT];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) wf[nb] = __builtin_nontemporal_load(Wp[nb] + (size_t)kt * 64);
+    for (int u = 0; u < U - 1; ++u) {
+      if (u < rem) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) xf[mt] = xlive[mt] ? Xp[mt][(size_t)kt * 64] : zero4;
+        for (int nb = 0; nb < NB; ++nb) wf[u][nb] = __builtin_nontemporal_load(Wp[nb] + (size_t)(kt + u) * 64);
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+        for (int mt = 0; mt < MT; ++mt) xf[u][mt] = xlive[mt] ? Xp[mt][(size_t)(kt + u) * 64] : zero4;
+      }
+    }
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = Mfma16::run(wf[nb], xf[mt], acc[nb][mt]);
+    for (int u = 0; u < U - 1; ++u) {
+      if (u < rem) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = Mfma16::run(wf[u][nb], xf[u][mt], acc[nb][mt]);
+      }
+    }
     if (foldx) {
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) ssq[mt] = frag_ssq(xf[mt], ssq[mt]);
+      for (int u = 0; u < U - 1; ++u) {
+        if (u < rem) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) ssq[mt] = frag_ssq(xf[u][mt], ssq[mt]);
+        }
+      }
     }
   }
 
