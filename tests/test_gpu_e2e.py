@@ -287,13 +287,15 @@ def test_call_order_and_capacity_errors(orc, B):
     assert e.value.code == B.ERR_CAPACITY
 
 
-def test_attention_launch_shapes_give_identical_bits(orc, B):
+@pytest.mark.parametrize("L_max,kv", [(640, 600), (2048, 1990), (2304, 2250)])
+def test_attention_launch_shapes_give_identical_bits(orc, B, L_max, kv):
     """The launch shapes of the verify attention (split over chunks + merge kernel; one wave per sequence and
     head; one workgroup per sequence and head) must agree bit for bit: the batch size picks between them."""
     dtype, seed = "bf16", 5
-    tdesc = si.llama_desc(1, 256, 2, 416, 300, 700)
+    tdesc = si.llama_desc(1, 256, 2, 416, 300, L_max + 8)
     w = si.make_weights(tdesc, dtype, seed, device=DEV, emb_std=1.0)
-    L_max, kv = 640, 600                       # three 256-key chunks, the last one ragged
+    # 600 cached positions: three 256-key chunks, the last one ragged; 1990: eight, the most the one-workgroup
+    # shape takes (70 KB of partials in LDS); 2250: nine, where that shape hands over to split + merge
     ctx = B.Context(tdesc, w, None, None, dtype, 3, 4, L_max, 4, B.PROPOSALS_EXTERNAL, DEV)
     K, V = si.make_kv(3, 256, kv, dtype, seed, DEV)
     ctx.spec_kv_import(B.MODEL_TARGET, 0, K, V)
