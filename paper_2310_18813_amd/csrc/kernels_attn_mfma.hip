@@ -162,18 +162,25 @@ __device__ __forceinline__ void chunk_partial(const T *kbase, const T *vbase, co
   l_run = 0.f;
 #pragma unroll
   for (int ht = 0; ht < HD / 16; ++ht) acc[ht] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
+  // Steps in pairs; inside the loop every load is unconditional, so the wait in front of a step can leave exactly
+  // the next step's loads in flight (a load behind a branch makes the compiler wait for everything at the join).
   Frags<HD> fa, fb;
   load_step<T, HD, STREAM>(fa, kbase, vbase, k0, r, g);
+  const int klast = k0 + ((kend - k0 - 1) & ~31);  // where the chunk's last step starts
   int ks = k0;
-  while (true) {
-    if (ks + 32 < kend) load_step<T, HD, STREAM>(fb, kbase, vbase, ks + 32, r, g);
+  while (ks + 64 <= klast) {  // steps ks and ks + 32, and a step behind them to prefetch
+    load_step<T, HD, STREAM>(fb, kbase, vbase, ks + 32, r, g);
     compute_step<T, HD>(fa, qf, ks, g, pos_j, scale, m_run, l_run, acc);
-    ks += 32;
-    if (ks >= kend) break;
-    if (ks + 32 < kend) load_step<T, HD, STREAM>(fa, kbase, vbase, ks + 32, r, g);
-    compute_step<T, HD>(fb, qf, ks, g, pos_j, scale, m_run, l_run, acc);
-    ks += 32;
-    if (ks >= kend) break;
+    load_step<T, HD, STREAM>(fa, kbase, vbase, ks + 64, r, g);
+    compute_step<T, HD>(fb, qf, ks + 32, g, pos_j, scale, m_run, l_run, acc);
+    ks += 64;
+  }
+  if (ks + 32 <= klast) {  // two steps left
+    load_step<T, HD, STREAM>(fb, kbase, vbase, ks + 32, r, g);
+    compute_step<T, HD>(fa, qf, ks, g, pos_j, scale, m_run, l_run, acc);
+    compute_step<T, HD>(fb, qf, ks + 32, g, pos_j, scale, m_run, l_run, acc);
+  } else {                 // one
+    compute_step<T, HD>(fa, qf, ks, g, pos_j, scale, m_run, l_run, acc);
   }
 }
 
