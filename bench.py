@@ -283,15 +283,15 @@ def model_fit_object(ctx, prompts, B_list, vgrid, alpha, lut):
 
 def cpu_baseline(si, tdesc, ddesc, host_w, ctx, dtype, seed):
     """The fp32 oracle as it stands, on the host cores, on a bounded sample of the same
-    workload: one sequence, an 8-token prompt, two rounds at s=4 on the same 7B-shape
-    weights.  Prefill is timed apart and left out, as on the GPU side."""
+    workload: one sequence, an 8-token prompt, 24 tokens at s=4 (about ten seconds of CPU work) on the
+    same 7B-shape weights.  Prefill is timed apart and left out, as on the GPU side."""
     import numpy as np
     from oracle import oracle as om
     orc = om.Oracle("f32")
     code = {"fp32": 0, "bf16": 1, "fp16": 2}[dtype]
     ot = orc.model(tdesc, host_w[0], code)
     od = orc.model(ddesc, host_w[1], code)
-    P8, s, n_tok = 8, 4, 6
+    P8, s, n_tok = 8, 4, 24
     prompt = si.make_prompts(1, P8, tdesc["vocab"], seed + 1)
     # true continuation of the short prompt from the GPU, so that acceptance looks like the workload's
     ctx.spec_reset(prompt)
