@@ -283,7 +283,7 @@ def model_fit_object(ctx, prompts, B_list, vgrid, alpha, lut):
 
 def cpu_baseline(si, tdesc, ddesc, host_w, ctx, dtype, seed):
     """The fp32 oracle as it stands, on the host cores, on a bounded sample of the same
-    workload: one sequence, an 8-token prompt, 24 tokens at s=4 (about ten seconds of CPU work) on the
+    workload: one sequence, an 8-token prompt, 24 tokens at s=4 (about fifteen seconds of CPU work) on the
     same 7B-shape weights.  Prefill is timed apart and left out, as on the GPU side."""
     import numpy as np
     from oracle import oracle as om
