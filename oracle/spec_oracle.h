@@ -18,7 +18,10 @@
  * the HuggingFace LLaMA / OPT implementations (the model layer the paper's
  * prototype ran on, Sec. 3.1), RoPE/softmax/norms against closed forms, the
  * speculative loop against plain autoregressive greedy decoding (the defining
- * invariant, Sec. 2), acceptance against hand-worked cases, acceptance
+ * invariant, Sec. 2), its draft-cache bookkeeping by running it with the target's
+ * own weights as the draft (every round must then accept all s proposals, which
+ * a wrong cache length or a mis-sized first draft step breaks), acceptance
+ * against hand-worked cases, acceptance
  * statistics against Eq. 6 in closed form, the LUT rule against enumerated
  * cases of Sec. 4.  Parity unpinned: the fitted constants 0.9 and 0.548 of
  * Eq. 5 (they need the paper's trained models and dataset); they are not

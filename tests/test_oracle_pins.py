@@ -318,6 +318,69 @@ def test_speculative_equals_greedy_every_source(o64, tiny_pair, s):
     assert np.array_equal(out, ref[:N])
 
 
+@pytest.mark.parametrize("s", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_draft_equal_to_target_gets_every_proposal_accepted(o64, tiny_pair, s):
+    """Pins the draft side of Alg. 1 (the call speculate(S, kv_SSM, s)): with the target's own weights as the
+    draft every proposal is the target's greedy token, so every round accepts all s proposals and emits s + 1
+    tokens (Sec. 2: at least one, at most s + 1 per round) -- but only if the draft's cache is exactly the
+    committed prefix when a round starts: a wrong cache length after the roll-back, a first step that ingests one
+    token where two are due (after l = s the draft never read t_s), or a stale row all change a proposal."""
+    dt, wt, _, _ = tiny_pair
+    tgt, twin = omodel(o64, dt, wt), omodel(o64, dt, wt)
+    for P, N in ((5, 23), (1, 17), (2, 9 * (s + 1))):
+        prompt = si.make_prompts(1, P, dt["vocab"], 33 + P)[0]
+        ref = tgt.greedy(prompt, N)
+        out, ls = tgt.spec_generate(twin, prompt, N, s, proposal_mode=0)
+        assert np.array_equal(out, ref)
+        assert ls == [s] * math.ceil(N / (s + 1)), (P, N, s, ls)
+
+
+def _alg1_with_draft_rule(tgt, drf, prompt, N, s, L, keep_rule, first_rule):
+    """Alg. 1 written on the oracle's forward alone, the draft-cache bookkeeping left open: keep_rule(n_old, l, s)
+    -> draft cache length kept after a round; first_rule(n, kvD) -> how many committed tokens the round's first
+    draft step ingests (they end at position n - 1).  Returns the accepted counts per round."""
+    ct, cd = tgt.cache(L), drf.cache(L)
+    S = list(prompt)
+    P = len(S)
+    if P > 1:
+        tgt.forward(ct, S[:P - 1], 0, want_logits=False)
+        drf.forward(cd, S[:P - 1], 0, want_logits=False)
+    kvD, ls = P - 1, []
+    while len(S) - P < N:
+        n, t = len(S), []
+        for j in range(1, s + 1):
+            if j == 1:
+                cnt = first_rule(n, kvD)
+                lg = drf.forward(cd, S[n - cnt:n], n - cnt)
+            else:
+                lg = drf.forward(cd, [t[-1]], n + j - 2)
+            t.append(int(lg[-1].argmax()))
+        a = tgt.forward(ct, [S[n - 1]] + t, n - 1).argmax(-1)
+        l, em = tgt.orc.accept(t, a)
+        S += em
+        ls.append(l)
+        kvD = min(keep_rule(n, l, s), len(S) - 1)
+    return ls
+
+
+def test_draft_equal_to_target_pin_catches_planted_bookkeeping_mistakes(o64, tiny_pair):
+    """The pin above has teeth: the same construction run with a planted mistake in the draft bookkeeping (on the
+    CPU, through the oracle's own forward) no longer accepts everything."""
+    dt, wt, _, _ = tiny_pair
+    tgt, twin = omodel(o64, dt, wt), omodel(o64, dt, wt)
+    P, N, s, L = 5, 24, 3, 64
+    prompt = si.make_prompts(1, P, dt["vocab"], 38)[0]
+    right_keep = lambda n, l, s_: n + min(l, s_ - 1)
+    right_first = lambda n, kvD: n - kvD
+    assert _alg1_with_draft_rule(tgt, twin, prompt, N, s, L, right_keep, right_first) == [s] * (N // (s + 1))
+    # forgets that t_s was never ingested (keeps n + l): position n + s - 1 of the draft cache is stale
+    ls = _alg1_with_draft_rule(tgt, twin, prompt, N, s, L, lambda n, l, s_: n + l, right_first)
+    assert min(ls) < s
+    # first step always ingests one token: the draft cache gets a hole after every fully accepted round
+    ls = _alg1_with_draft_rule(tgt, twin, prompt, N, s, L, right_keep, lambda n, kvD: 1)
+    assert min(ls) < s
+
+
 def test_verify_logits_equal_single_steps(o64, tiny_pair):
     dt, wt, _, _ = tiny_pair
     m = omodel(o64, dt, wt)
