@@ -106,7 +106,8 @@ typedef struct {
   int32_t L_max;         /* KV-cache positions per sequence; needs P + gen_max + s_max     */
   int32_t gen_max;       /* tokens to emit per sequence; a sequence that reached it is
                             frozen (still computed, emits nothing)                         */
-  int32_t eos_id;        /* must be -1 (fixed-length generation only)                      */
+  int32_t eos_id;        /* end-of-sequence token the context starts with, -1 = none (every
+                            workload of the paper generates a fixed count); see spec_set_eos   */
   int32_t proposal_mode; /* SPEC_PROPOSALS_DRAFT: t_j = the draft model's greedy token.
                             SPEC_PROPOSALS_EXTERNAL: t_j supplied by the caller; a draft
                             model, if present, still runs and ingests those tokens          */
@@ -194,8 +195,10 @@ int spec_set_proposals(spec_ctx *ctx, const int32_t *d_tok, int32_t s);
 
 /* Draft step j (1-based) of the current round: the call speculate(S, kv_SSM, s) of
    Alg. 1 is s of these in order.  Step 1 ingests the committed tokens the draft has
-   not read yet (one or two per sequence), step j >= 2 ingests t_{j-1}; each appends
-   the draft's KV and, in SPEC_PROPOSALS_DRAFT mode, writes t_j = argmax.             */
+   not read yet (one or two per sequence after a round with draft steps; one more for
+   every round that ran without them, ingested in as many passes as it takes), step
+   j >= 2 ingests t_{j-1}; each appends the draft's KV and, in SPEC_PROPOSALS_DRAFT
+   mode, writes t_j = argmax.                                                          */
 int spec_draft_step(spec_ctx *ctx, int32_t j);
 
 /* Target verification: the call LLM(S, t_1..t_s, kv_LLM) of Alg. 1.  One forward pass
@@ -261,6 +264,33 @@ int spec_kv_export(spec_ctx *ctx, int32_t which_model, int32_t layer, int32_t B,
    slice 0 after the embedding, slice l after layer l (M = rows of that pass).  NULL turns it
    off.  The buffer is the caller's and must hold (n_layers + 1) * B_max * 16 * d_model floats. */
 int spec_set_hidden_dump(spec_ctx *ctx, float *d_hidden);
+
+/* Greedy tokens and acceptance on logits the caller already has, without a context: for a caller that runs the
+   target model itself (Alg. 1: a_i = argmax o_i; Sec. 2: a proposal is accepted while every earlier one
+   was, then the target's own token follows).
+     d_logits     [B][s+1][vocab] fp32, device: o_0..o_s of every sequence
+     d_proposals  [B][s] int32, device: t_1..t_s (may be NULL when s = 0)
+     d_accepted   [B] int32, device, out: l_b
+     d_emitted    [B][s+1] int32, device, out: t_1..t_l, a_l, then -1
+     d_workspace  device scratch for the arg-max partials, 8-byte aligned, at least
+                  spec_greedy_accept_workspace_bytes(B, s, vocab) bytes; contents before and after are of no meaning
+   Ties go to the lowest token id; a row of NaNs yields token 0.  Enqueues two kernels on hip_stream (NULL = the
+   default stream) and returns without waiting.  Limits: s <= 15, B <= 65535, vocab <= 2^28 (SPEC_ERR_CAPACITY);
+   SPEC_ERR_WORKSPACE for a missing, misaligned or short workspace.  All buffers are the caller's.             */
+int spec_greedy_accept_workspace_bytes(int32_t B, int32_t s, int32_t vocab, size_t *bytes);
+int spec_greedy_accept(void *hip_stream, const float *d_logits, const int32_t *d_proposals, int32_t B, int32_t s,
+                       int32_t vocab, void *d_workspace, size_t workspace_bytes, int32_t *d_accepted,
+                       int32_t *d_emitted);
+
+/* Parity aids for the draft step (the call speculate(S, kv_SSM, s) of Alg. 1).
+   spec_set_draft_logits: if d_logits is not NULL, every following spec_draft_step also writes the draft
+   model's logits behind t_j -- the logits of the last token each sequence fed in -- as fp32 [B][vocab]
+   into d_logits (the caller's device memory, B_max * vocab floats); NULL turns it off.  Needs a draft model
+   (SPEC_ERR_STATE otherwise).
+   spec_read_proposals: the proposals of the current round, h_t [B][s_max] (row stride s_max): t_1..t_j after
+   draft step j in SPEC_PROPOSALS_DRAFT mode, the external ones once they were fetched.  Synchronises.      */
+int spec_set_draft_logits(spec_ctx *ctx, float *d_logits);
+int spec_read_proposals(spec_ctx *ctx, int32_t *h_t);
 
 /* Measurement aid: what this GPU delivers, for roofline fractions against measured as well as nominal peaks.
    Streams d_buf (device, 16-byte aligned, `bytes` long; at least 64 KB per compute unit, a few hundred MB

@@ -29,7 +29,8 @@ EXPORTS = ["spec_last_error", "spec_workspace_bytes", "spec_init", "spec_destroy
            "spec_set_proposals", "spec_draft_step", "spec_verify_step", "spec_accept_commit", "spec_round",
            "spec_profile_and_choose_s", "spec_set_lut", "spec_choose_s", "spec_read_output",
            "spec_read_state", "spec_kv_import", "spec_kv_export", "spec_kernel_timing",
-           "spec_read_kernel_timing", "spec_set_hidden_dump", "spec_set_attention_shape", "spec_measure_peaks"]
+           "spec_read_kernel_timing", "spec_set_hidden_dump", "spec_set_attention_shape", "spec_measure_peaks",
+           "spec_set_draft_logits", "spec_read_proposals", "spec_greedy_accept_workspace_bytes", "spec_greedy_accept"]
 KCLASS_NAMES = ["gemm_qkv", "gemm_o", "gemm_ffn_in", "gemm_ffn_out", "gemm_head", "attention", "norm", "other",
                 "draft_pass"]
 
@@ -78,6 +79,10 @@ lib.spec_read_state.argtypes = [_vp, _i32p, _i32p, _i32p, _i32p]
 lib.spec_kv_import.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp]
 lib.spec_kv_export.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp]
 lib.spec_set_hidden_dump.argtypes = [_vp, _vp]
+lib.spec_set_draft_logits.argtypes = [_vp, _vp]
+lib.spec_read_proposals.argtypes = [_vp, _i32p]
+lib.spec_greedy_accept_workspace_bytes.argtypes = [_i32, _i32, _i32, C.POINTER(C.c_size_t)]
+lib.spec_greedy_accept.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _vp, C.c_size_t, _vp, _vp]
 lib.spec_set_attention_shape.argtypes = [_vp, _i32]
 lib.spec_kernel_timing.argtypes = [_vp, _i32]
 lib.spec_read_kernel_timing.argtypes = [_vp, _i64p, C.POINTER(C.c_double)]
@@ -130,6 +135,30 @@ def spec_measure_peaks(device="cuda:0", nbytes=1 << 30):
         st = torch.cuda.current_stream(dev)
         _check(lib.spec_measure_peaks(C.c_void_p(st.cuda_stream), _dp(buf), buf.numel() * 8, C.byref(g), C.byref(t)))
     return g.value, t.value
+
+
+def spec_greedy_accept(logits, proposals, accepted=None, emitted=None, workspace=None):
+    """logits [B][s+1][V] fp32 device tensor, proposals [B][s] int32 device tensor (or None when s = 0).
+    -> (accepted [B], emitted [B][s+1]) int32 device tensors."""
+    assert logits.dim() == 3 and logits.dtype == torch.float32 and logits.is_contiguous()
+    nB, q, V = logits.shape
+    s = q - 1
+    if s:
+        assert proposals.dtype == torch.int32 and proposals.shape == (nB, s) and proposals.is_contiguous()
+    dev = logits.device
+    st = C.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+    if accepted is None:
+        accepted = torch.empty(nB, dtype=torch.int32, device=dev)
+    if emitted is None:
+        emitted = torch.empty((nB, q), dtype=torch.int32, device=dev)
+    n = C.c_size_t(0)
+    _check(lib.spec_greedy_accept_workspace_bytes(nB, s, V, C.byref(n)))
+    if workspace is None:
+        workspace = torch.empty(max(8, n.value), dtype=torch.uint8, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib.spec_greedy_accept(st, _dp(logits), _dp(proposals) if s else None, nB, s, V, _dp(workspace),
+                                      workspace.numel(), _dp(accepted), _dp(emitted)))
+    return accepted, emitted
 
 
 def spec_workspace_bytes(tgt_desc, drf_desc, run):
@@ -308,6 +337,22 @@ class Context:
         self._hidden = torch.zeros((nl + 1) * self.B_max * 16 * d, dtype=torch.float32, device=self.device)
         _check(lib.spec_set_hidden_dump(self.h, _dp(self._hidden)), self.h)
         return self._hidden
+
+    def spec_set_draft_logits(self, on):
+        """on=True allocates [B_max][vocab] fp32 for the draft steps' logits and returns it."""
+        if not on:
+            self._draft_logits = None
+            _check(lib.spec_set_draft_logits(self.h, None), self.h)
+            return None
+        self._draft_logits = torch.zeros((self.B_max, self.drf_desc["vocab"]), dtype=torch.float32, device=self.device)
+        _check(lib.spec_set_draft_logits(self.h, _dp(self._draft_logits)), self.h)
+        return self._draft_logits
+
+    def spec_read_proposals(self):
+        """-> [B][s_max] proposals of the current round."""
+        t = (C.c_int32 * max(1, self.B * self.s_max))()
+        _check(lib.spec_read_proposals(self.h, t), self.h)
+        return [[t[b * self.s_max + j] for j in range(self.s_max)] for b in range(self.B)]
 
     def spec_set_attention_shape(self, shape):
         _check(lib.spec_set_attention_shape(self.h, shape), self.h)

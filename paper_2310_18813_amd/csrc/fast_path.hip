@@ -259,6 +259,7 @@ void fast_head(spec_ctx *c, const Model &m, int Mh, int last_of_q, float *logits
   if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, last_of_q, st); }
   GemmArgs a = base_args(m.p_head, m.lm_head, m.s_head, nullptr, c->ws.x, rows);
   a.logits = logits_or_null;
+  a.logit_step = fold ? last_of_q : 0;  // the folded head runs over every row of the pass: dump the wanted ones only
   a.part_val = c->ws.head_part;
   a.part_idx = c->ws.head_part_idx;
   if (fold) {

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void k_assemble_embed(int kind, int q, int j, 
       tok = (i == 0) ? seq[(size_t)b * L_max + nb - 1] : t[(size_t)b * s_max + i - 1];
     }
   } else if (kind == PASS_DRAFT_FIRST) {
-    int p = nb - q + i;
+    int p = nb - j - q + i;  // j: positions the pass ends before n_b (catch-up passes of a draft cache far behind)
     if (p >= 0 && p >= kv_draft[b]) { pos = p; tok = seq[(size_t)b * L_max + p]; }
   } else if (kind == PASS_DRAFT_NEXT) {  // draft step j >= 2 yields t_j: wanted only up to s_b
     if (j <= sb) {

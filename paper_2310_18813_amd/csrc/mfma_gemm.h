@@ -48,6 +48,7 @@ struct GemmArgs {
   void *act;                 // EPI_SWIGLU / EPI_RELU: fp16, fragment order, row length f (resp. N)
   int f;
   float *logits;             // EPI_LOGITS: optional [M][N] fp32
+  int logit_step;            // EPI_LOGITS: > 1: only the last row of every group of logit_step rows is dumped, as row m / logit_step
   float *part_val;           // EPI_LOGITS: [M][NT]
   int32_t *part_idx;
 };

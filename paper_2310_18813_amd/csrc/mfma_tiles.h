@@ -124,10 +124,15 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int 
   } else {  // EPI_LOGITS: optional dump, per-strip arg-max partial (lowest index wins ties)
     float bv = -INFINITY;
     int bi = 0x7fffffff;
+    float *dump = nullptr;  // debug / parity only
+    if (live && a.logits) {
+      if (a.logit_step <= 1) dump = a.logits + (size_t)m * a.N;
+      else if (m % a.logit_step == a.logit_step - 1) dump = a.logits + (size_t)(m / a.logit_step) * a.N;
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       if (n + i < a.N) {
-        if (live && a.logits) a.logits[(size_t)m * a.N + n + i] = v[i];
+        if (dump) dump[n + i] = v[i];
         argmax_combine(bv, bi, v[i], n + i);
       }
     for (int o = 16; o <= 32; o <<= 1) {

@@ -23,6 +23,16 @@ static int fail(spec_ctx *c, int code, const char *fmt, ...) {
   if (c) c->err = buf;
   return code;
 }
+// for the entry points that live in other files and have no context
+int spec::fail_noctx(int code, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
 #define HIPCHK(c, call)                                                                      \
   do {                                                                                       \
     hipError_t e_ = (call);                                                                  \
@@ -67,7 +77,7 @@ static int check_run(const spec_run_desc *r) {
   if (r->gen_max < 1) return fail(nullptr, SPEC_ERR_INVALID_ARG, "run: gen_max must be positive");
   if (r->L_max < r->gen_max + r->s_max + 1)
     return fail(nullptr, SPEC_ERR_INVALID_ARG, "run: L_max must be at least gen_max + s_max + 1");
-  if (r->eos_id != -1) return fail(nullptr, SPEC_ERR_UNSUPPORTED, "run: eos_id must be -1 (fixed-length generation)");
+  if (r->eos_id < -1) return fail(nullptr, SPEC_ERR_INVALID_ARG, "run: eos_id must be -1 (none) or a token id");
   if (r->proposal_mode != SPEC_PROPOSALS_DRAFT && r->proposal_mode != SPEC_PROPOSALS_EXTERNAL)
     return fail(nullptr, SPEC_ERR_INVALID_ARG, "run: unknown proposal_mode %d", r->proposal_mode);
   return SPEC_OK;
@@ -132,6 +142,8 @@ extern "C" int spec_workspace_bytes(const spec_model_desc *tgt, const spec_model
   if (drf && (rc = check_model(drf, "draft", run->dtype))) return rc;
   if (drf && drf->vocab != tgt->vocab)
     return fail(nullptr, SPEC_ERR_INVALID_ARG, "draft and target must share one vocabulary");
+  if (run->eos_id >= tgt->vocab)
+    return fail(nullptr, SPEC_ERR_INVALID_ARG, "run: eos_id %d outside the vocabulary (%d tokens)", run->eos_id, tgt->vocab);
   *bytes = compute_sizes(tgt, drf, run).total;
   return SPEC_OK;
 }
@@ -216,6 +228,7 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
   spec_ctx *c = new (std::nothrow) spec_ctx();
   if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_init: out of host memory");
   c->run = *run;
+  c->eos = run->eos_id;
   c->stream = (hipStream_t)hip_stream;
   Sizes z = compute_sizes(tgt, drf, run);
   c->M_max = z.M_max;
@@ -292,6 +305,22 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
 extern "C" int spec_set_hidden_dump(spec_ctx *c, float *d_hidden) {
   if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_set_hidden_dump: ctx is null");
   c->hidden_dump = d_hidden;
+  return SPEC_OK;
+}
+
+extern "C" int spec_set_draft_logits(spec_ctx *c, float *d_logits) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_set_draft_logits: ctx is null");
+  if (!c->drf.present) return fail(c, SPEC_ERR_STATE, "spec_set_draft_logits: no draft model");
+  c->draft_logits = d_logits;
+  return SPEC_OK;
+}
+
+extern "C" int spec_read_proposals(spec_ctx *c, int32_t *h_t) {
+  if (!c || !h_t) return fail(c, SPEC_ERR_INVALID_ARG, "spec_read_proposals: null argument");
+  if (!c->active) return fail(c, SPEC_ERR_STATE, "spec_read_proposals: no batch; call spec_reset first");
+  if (c->run.s_max == 0) return SPEC_OK;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(h_t, c->st.t, (size_t)c->B * c->run.s_max * 4, hipMemcpyDeviceToHost));
   return SPEC_OK;
 }
 
@@ -556,20 +585,31 @@ extern "C" int spec_draft_step(spec_ctx *c, int32_t j) {
   // with external proposals it goes to a scratch word per sequence instead
   int32_t *arg_out = ext ? c->st.draft_arg : c->st.t + (j - 1);
   const int arg_stride = ext ? 1 : c->run.s_max;
+  float *lg = c->draft_logits;
   if (j == 1) {
-    const int q = c->draft_lag;
-    if (q > Q_LIMIT || c->B * q > c->M_max)
-      return fail(c, SPEC_ERR_STATE, "spec_draft_step: the draft cache is %d tokens behind (rounds ran without draft steps)", q);
     if (ext && c->prop_table && !c->proposals_ready) {
       // later draft steps ingest t_1.. : fetch them now (all s_max; verify uses the first s)
       launch_fill_proposals(c, c->run.s_max, c->stream);
       c->proposals_ready = true;
     }
-    PassArgs pa{PASS_DRAFT_FIRST, c->B, q, 1, c->P, c->run.s_max, c->run.L_max};
-    rc = forward_pass(c, c->drf, pa, HEAD_LAST, nullptr, arg_out, arg_stride, c->n_ub - 1);
+    // The draft's cache is at most draft_lag tokens behind the committed sequences (2 after a round with draft
+    // steps, one more per round without).  A pass takes q_cap positions per sequence: what lies further back is
+    // ingested by passes without a head first, the last pass ends at position n_b - 1 and yields t_1.
+    const int q_cap = std::max(1, std::min(Q_LIMIT, c->M_max / c->B));
+    int lag = std::max(1, std::min(c->draft_lag, c->n_ub));
+    rc = SPEC_OK;
+    while (lag > q_cap && !rc) {
+      PassArgs pa{PASS_DRAFT_FIRST, c->B, q_cap, lag - q_cap, c->P, c->run.s_max, c->run.L_max};
+      rc = forward_pass(c, c->drf, pa, HEAD_NONE, nullptr, nullptr, 0, c->n_ub - 1);
+      lag -= q_cap;
+    }
+    if (!rc) {
+      PassArgs pa{PASS_DRAFT_FIRST, c->B, lag, 0, c->P, c->run.s_max, c->run.L_max};
+      rc = forward_pass(c, c->drf, pa, HEAD_LAST, lg, arg_out, arg_stride, c->n_ub - 1);
+    }
   } else {
     PassArgs pa{PASS_DRAFT_NEXT, c->B, 1, j, c->P, c->run.s_max, c->run.L_max};
-    rc = forward_pass(c, c->drf, pa, HEAD_LAST, nullptr, arg_out, arg_stride, c->n_ub + j - 2);
+    rc = forward_pass(c, c->drf, pa, HEAD_LAST, lg, arg_out, arg_stride, c->n_ub + j - 2);
   }
   if (rc) return rc;
   c->draft_j = j;
@@ -604,7 +644,7 @@ extern "C" int spec_accept_commit(spec_ctx *c, int32_t s) {
   if (s != c->verified_s) return fail(c, SPEC_ERR_STATE, "spec_accept_commit: verify step ran with s=%d, got s=%d", c->verified_s, s);
   { KScope k(c, SPEC_KCLASS_OTHER); launch_accept(c, s, c->stream); }
   c->n_ub = std::min(c->n_ub + s + 1, *std::max_element(c->P_host.begin(), c->P_host.end()) + c->run.gen_max);
-  if (c->drf.present) c->draft_lag = c->draft_j > 0 ? 2 : std::min(c->draft_lag + 1, Q_LIMIT + 1);
+  if (c->drf.present) c->draft_lag = c->draft_j > 0 ? 2 : std::min(c->draft_lag + 1, c->n_ub);
   c->draft_j = 0;
   c->verified_s = -1;
   c->proposals_ready = false;

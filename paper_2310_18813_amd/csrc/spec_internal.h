@@ -66,7 +66,7 @@ struct Model {
 // What a forward pass feeds in.
 enum PassKind {
   PASS_VERIFY = 0,      // rows (b,i), i=0..q-1: pending token then proposals, positions n_b-1+i
-  PASS_DRAFT_FIRST = 1, // rows (b,i): committed tokens at positions n_b-q+i; rows before kv_len_b are dead
+  PASS_DRAFT_FIRST = 1, // rows (b,i): committed tokens at positions n_b-j-q+i; rows before kv_len_b are dead
   PASS_DRAFT_NEXT = 2,  // q = 1: proposal t_{j-1} at position n_b+j-2
   PASS_PREFILL = 3      // rows (b,i): prompt tokens at positions base+i; rows >= P-1 are dead
 };
@@ -124,6 +124,7 @@ struct spec_ctx {
   const int32_t *prop_table = nullptr;
   const int32_t *seq_s = nullptr;  // [B] per-sequence cap of the speculation length (caller's device memory), or null
   float *hidden_dump = nullptr;
+  float *draft_logits = nullptr;  // parity aid: where every draft step leaves the logits behind its proposals
   int attn_shape = 0;
   std::vector<int32_t> lut_B, lut_s;
   std::string err;
@@ -166,7 +167,8 @@ namespace spec {
 struct PassArgs {
   PassKind kind;
   int B, q;      // rows M = B*q
-  int j;         // draft step index (PASS_DRAFT_NEXT) / prefill base position (PASS_PREFILL)
+  int j;         // draft step index (PASS_DRAFT_NEXT) / prefill base position (PASS_PREFILL) /
+                 // PASS_DRAFT_FIRST: how many positions before n_b the pass ends (0: at n_b - 1)
   int P;         // prompt length (PASS_PREFILL)
   int s_max, L_max;
   int b0 = 0;    // first batch slot of the pass: its rows are the sequences b0 .. b0 + B - 1
@@ -196,6 +198,7 @@ void generic_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
 void generic_zero(void *dst, size_t bytes, hipStream_t st);
 
 size_t dtype_bytes(int dtype);
+int fail_noctx(int code, const char *fmt, ...);  // records the message spec_last_error(NULL) returns; returns code
 
 // matrix-core path (16-bit dtypes)
 bool fast_supported(const spec_model_desc &D, int dtype);

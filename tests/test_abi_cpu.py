@@ -55,7 +55,8 @@ def test_workspace_bytes_and_argument_validation(B):
         (tgt, None, run_desc(B, B_max=0), B.ERR_INVALID_ARG),
         (tgt, None, run_desc(B, s_max=16), B.ERR_INVALID_ARG),
         (tgt, None, run_desc(B, L_max=10), B.ERR_INVALID_ARG),                 # < gen_max + s_max + 1
-        (tgt, None, run_desc(B, eos_id=2), B.ERR_UNSUPPORTED),
+        (tgt, None, run_desc(B, eos_id=-2), B.ERR_INVALID_ARG),
+        (tgt, None, run_desc(B, eos_id=1000), B.ERR_INVALID_ARG),              # outside the vocabulary
         (tgt, None, run_desc(B, proposal_mode=5), B.ERR_INVALID_ARG),
     ]
     for t, d, r, code in bad:
@@ -102,3 +103,15 @@ def test_init_rejects_bad_arguments_without_touching_the_device(B):
     assert B.lib.spec_round(None, 0, 1) == B.ERR_INVALID_ARG
     assert B.lib.spec_choose_s(None, 1, None) == B.ERR_INVALID_ARG
     assert B.lib.spec_destroy(None) == B.OK
+
+
+def test_greedy_accept_validates_before_any_device_call(B):
+    n = C.c_size_t(0)
+    assert B.lib.spec_greedy_accept_workspace_bytes(64, 8, 32000, C.byref(n)) == B.OK
+    assert n.value == 64 * 9 * 8 * 8          # rows x chunks of 4096 logits x (value, index)
+    assert B.lib.spec_greedy_accept_workspace_bytes(0, 8, 32000, C.byref(n)) == B.ERR_INVALID_ARG
+    assert B.lib.spec_greedy_accept_workspace_bytes(1, 16, 32000, C.byref(n)) == B.ERR_CAPACITY
+    fake = C.c_void_p(4096)                   # never dereferenced: validation fails first
+    assert B.lib.spec_greedy_accept(None, None, fake, 1, 1, 10, fake, 64, fake, fake) == B.ERR_INVALID_ARG
+    assert B.lib.spec_greedy_accept(None, fake, fake, 1, 1, 10, None, 64, fake, fake) == B.ERR_WORKSPACE
+    assert B.lib.spec_greedy_accept(None, fake, fake, 1, 1, 10, fake, 4, fake, fake) == B.ERR_WORKSPACE
