@@ -41,6 +41,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_v;
 
 template <class T> struct MfmaA;
 template <> struct MfmaA<bf16_t> {
+  static constexpr bool HILO = true;   // queries and softmax weights as a bf16 pair (value + remainder): 16 significant bits
   static __device__ __forceinline__ f32x4_v run(u32x4_v a, u32x4_v b, f32x4_v c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_v, a), __builtin_bit_cast(bf16x8_v, b), c,
                                                    0, 0, 0);
@@ -50,6 +51,7 @@ template <> struct MfmaA<bf16_t> {
   }
 };
 template <> struct MfmaA<f16_t> {
+  static constexpr bool HILO = false;  // one fp16 word has 11 significant bits: enough
   static __device__ __forceinline__ f32x4_v run(u32x4_v a, u32x4_v b, f32x4_v c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_v, a), __builtin_bit_cast(f16x8_v, b), c,
                                                   0, 0, 0);
@@ -81,6 +83,31 @@ __device__ __forceinline__ void merge_weights(float m, float mc, float scale, fl
 }
 __device__ __forceinline__ float merge_value(float a, float wa, float b, float wb) { return fmaf(a, wa, b * wb); }
 
+// The query fragments of a wave: row j's elements 32 kk + 8 g .. + 7 of the head, from the fp32 queries the QKV
+// epilogue left.  bf16 caches: hi = bf16(q), lo = bf16(q - hi), both multiplied with every key fragment (the cache
+// streams from HBM and the matrix pipes idle, so the second product is free), which takes the query's rounding
+// out of the scores.
+template <class T, int HD> struct QFrags {
+  u32x4_v hi[HD / 32], lo[MfmaA<T>::HILO ? HD / 32 : 1];
+};
+template <class T, int HD>
+__device__ __forceinline__ void load_q(QFrags<T, HD> &qf, const float *qrow, int g) {
+#pragma unroll
+  for (int kk = 0; kk < HD / 32; ++kk) {
+    const float4 a = *(const float4 *)(qrow + kk * 32 + 8 * g), b = *(const float4 *)(qrow + kk * 32 + 8 * g + 4);
+    const float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    float r[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r[i] = Conv<T>::round(x[i]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) qf.hi[kk][i] = MfmaA<T>::pack2(r[2 * i], r[2 * i + 1]);
+    if (MfmaA<T>::HILO) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) qf.lo[kk][i] = MfmaA<T>::pack2(x[2 * i] - r[2 * i], x[2 * i + 1] - r[2 * i + 1]);
+    }
+  }
+}
+
 template <int HD> struct Frags {
   u32x4_v k0[HD / 32], k1[HD / 32], v[HD / 16];
 };
@@ -105,14 +132,21 @@ __device__ __forceinline__ void load_step(Frags<HD> &f, const T *kbase, const T 
 
 // One 32-key step of the online softmax for the 16 query columns of the wave.
 template <class T, int HD>
-__device__ __forceinline__ void compute_step(const Frags<HD> &f, const u32x4_v (&qf)[HD / 32], int ks, int g,
+__device__ __forceinline__ void compute_step(const Frags<HD> &f, const QFrags<T, HD> &qf, int ks, int g,
                                              int pos_j, float scale, float &m_run, float &l_run,
                                              f32x4_v (&acc)[HD / 16]) {
   f32x4_v s0 = (f32x4_v){0.f, 0.f, 0.f, 0.f}, s1 = s0;
 #pragma unroll
   for (int kk = 0; kk < HD / 32; ++kk) {
-    s0 = MfmaA<T>::run(f.k0[kk], qf[kk], s0);
-    s1 = MfmaA<T>::run(f.k1[kk], qf[kk], s1);
+    s0 = MfmaA<T>::run(f.k0[kk], qf.hi[kk], s0);
+    s1 = MfmaA<T>::run(f.k1[kk], qf.hi[kk], s1);
+  }
+  if (MfmaA<T>::HILO) {
+#pragma unroll
+    for (int kk = 0; kk < HD / 32; ++kk) {
+      s0 = MfmaA<T>::run(f.k0[kk], qf.lo[kk], s0);
+      s1 = MfmaA<T>::run(f.k1[kk], qf.lo[kk], s1);
+    }
   }
   // lane (query j, group g): s0[i] <-> key ks + 8g + i, s1[i] <-> key ks + 8g + 4 + i
   float sv[8];
@@ -129,33 +163,43 @@ __device__ __forceinline__ void compute_step(const Frags<HD> &f, const u32x4_v (
   smax = fmaxf(smax, __shfl_xor(smax, 32, 64));
   const float m_new = fmaxf(m_run, smax);
   const float corr = exp_diff(m_run, m_new, scale);
-  float p[8];
+  // The products below see the weight rounded to the cache's type -- for bf16 as a pair (value + remainder, both
+  // multiplied with the value fragments) -- and the denominator sums exactly what they see.
+  float p[8], plo[8];
   float psum = 0.f;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     float e = (sv[i] > 0.5f * NEG_BIG) ? exp_diff(sv[i], m_new, scale) : 0.f;
-    p[i] = Conv<T>::round(e);  // the product below sees the rounded weight; sum the same value
-    psum += p[i];
+    p[i] = Conv<T>::round(e);
+    if (MfmaA<T>::HILO) {
+      plo[i] = Conv<T>::round(e - p[i]);
+      psum += p[i] + plo[i];  // 16 significant bits: exact in fp32
+    } else {
+      psum += p[i];
+    }
   }
   psum += __shfl_xor(psum, 16, 64);
   psum += __shfl_xor(psum, 32, 64);
   l_run = fmaf(l_run, corr, psum);
   m_run = m_new;
-  u32x4_v pf;
-  pf[0] = MfmaA<T>::pack2(p[0], p[1]);
-  pf[1] = MfmaA<T>::pack2(p[2], p[3]);
-  pf[2] = MfmaA<T>::pack2(p[4], p[5]);
-  pf[3] = MfmaA<T>::pack2(p[6], p[7]);
+  u32x4_v pf, pfl;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) pf[i] = MfmaA<T>::pack2(p[2 * i], p[2 * i + 1]);
+  if (MfmaA<T>::HILO) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) pfl[i] = MfmaA<T>::pack2(plo[2 * i], plo[2 * i + 1]);
+  }
 #pragma unroll
   for (int ht = 0; ht < HD / 16; ++ht) {
     acc[ht][0] *= corr; acc[ht][1] *= corr; acc[ht][2] *= corr; acc[ht][3] *= corr;
     acc[ht] = MfmaA<T>::run(f.v[ht], pf, acc[ht]);
+    if (MfmaA<T>::HILO) acc[ht] = MfmaA<T>::run(f.v[ht], pfl, acc[ht]);
   }
 }
 
 // Fresh partial of the chunk [k0, kend): steps of 32 keys, next step's loads in flight.
 template <class T, int HD, bool STREAM>
-__device__ __forceinline__ void chunk_partial(const T *kbase, const T *vbase, const u32x4_v (&qf)[HD / 32], int k0,
+__device__ __forceinline__ void chunk_partial(const T *kbase, const T *vbase, const QFrags<T, HD> &qf, int k0,
                                               int kend, int r, int g, int pos_j, float scale, float &m_run,
                                               float &l_run, f32x4_v (&acc)[HD / 16]) {
   m_run = NEG_BIG;
@@ -203,7 +247,7 @@ __device__ __forceinline__ WaveSetup wave_setup(const AttnArgs &a, int b, int la
 // Launch shape 1: one wave per (sequence, head, chunk); partials go to the workspace.
 template <class T, int HD, bool STREAM>
 __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a) {
-  constexpr int KK = HD / 32, HT = HD / 16;
+  constexpr int HT = HD / 16;
   const int lane = threadIdx.x & 63;
   const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (unit >= a.B * a.H * a.NC) return;
@@ -214,10 +258,8 @@ __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a) {
   const int kend = min(k0 + ATTN_CHUNK, w.pmax + 1);
   const float scale = rsqrtf((float)HD) * LOG2E;  // score scale in base-2 exponent units
   const int d = a.H * HD;
-  u32x4_v qf[KK];
-  const T *qrow = (const T *)a.q + (size_t)w.m_row * d + (size_t)hh * HD;
-#pragma unroll
-  for (int kk = 0; kk < KK; ++kk) qf[kk] = *(const u32x4_v *)(qrow + kk * 32 + 8 * w.g);
+  QFrags<T, HD> qf;
+  load_q<T, HD>(qf, (const float *)a.q + (size_t)w.m_row * d + (size_t)hh * HD, w.g);
   const size_t cbh = a.seq_groups > 1 ? (size_t)(b / a.seq_groups) * a.H + hh : (size_t)bh;  // whose cache: the group's sequence
   const T *kbase = (const T *)a.kc + cbh * a.L_pad * HD;
   const T *vbase = (const T *)a.vc + cbh * (a.L_pad / KV_VBLOCK) * HD * KV_VBLOCK;
@@ -260,7 +302,7 @@ __global__ void k_attn_merge(AttnArgs a) {
 // Launch shape 2: one wave per (sequence, head) walks all chunks, merging in registers.
 template <class T, int HD>
 __global__ __launch_bounds__(256) void k_attn_seq(AttnArgs a) {
-  constexpr int KK = HD / 32, HT = HD / 16;
+  constexpr int HT = HD / 16;
   const int lane = threadIdx.x & 63;
   const int bh = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (bh >= a.B * a.H) return;
@@ -268,10 +310,8 @@ __global__ __launch_bounds__(256) void k_attn_seq(AttnArgs a) {
   const WaveSetup w = wave_setup(a, b, lane);
   const int d = a.H * HD;
   const float scale = rsqrtf((float)HD) * LOG2E;  // score scale in base-2 exponent units
-  u32x4_v qf[KK];
-  const T *qrow = (const T *)a.q + (size_t)w.m_row * d + (size_t)hh * HD;
-#pragma unroll
-  for (int kk = 0; kk < KK; ++kk) qf[kk] = *(const u32x4_v *)(qrow + kk * 32 + 8 * w.g);
+  QFrags<T, HD> qf;
+  load_q<T, HD>(qf, (const float *)a.q + (size_t)w.m_row * d + (size_t)hh * HD, w.g);
   const size_t cbh = a.seq_groups > 1 ? (size_t)(b / a.seq_groups) * a.H + hh : (size_t)bh;  // whose cache: the group's sequence
   const T *kbase = (const T *)a.kc + cbh * a.L_pad * HD;
   const T *vbase = (const T *)a.vc + cbh * (a.L_pad / KV_VBLOCK) * HD * KV_VBLOCK;
@@ -319,17 +359,15 @@ __global__ __launch_bounds__(256) void k_attn_seq(AttnArgs a) {
 // for the few sequences of a small batch, where the attention is a chain of load latencies.
 template <class T, int HD, bool STREAM>
 __global__ __launch_bounds__(512) void k_attn_group(AttnArgs a) {
-  constexpr int KK = HD / 32, HT = HD / 16;
+  constexpr int HT = HD / 16;
   extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];  // [NC][HT][64] f32x4, then [NC][64] (max, sum)
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, W = blockDim.x >> 6;
   const int bh = blockIdx.x, hh = bh % a.H, b = bh / a.H;
   const WaveSetup w = wave_setup(a, b, lane);
   const int d = a.H * HD;
   const float scale = rsqrtf((float)HD) * LOG2E;  // score scale in base-2 exponent units
-  u32x4_v qf[KK];
-  const T *qrow = (const T *)a.q + (size_t)w.m_row * d + (size_t)hh * HD;
-#pragma unroll
-  for (int kk = 0; kk < KK; ++kk) qf[kk] = *(const u32x4_v *)(qrow + kk * 32 + 8 * w.g);
+  QFrags<T, HD> qf;
+  load_q<T, HD>(qf, (const float *)a.q + (size_t)w.m_row * d + (size_t)hh * HD, w.g);
   const size_t cbh = a.seq_groups > 1 ? (size_t)(b / a.seq_groups) * a.H + hh : (size_t)bh;  // whose cache: the group's sequence
   const T *kbase = (const T *)a.kc + cbh * a.L_pad * HD;
   const T *vbase = (const T *)a.vc + cbh * (a.L_pad / KV_VBLOCK) * HD * KV_VBLOCK;

@@ -40,7 +40,7 @@ struct GemmArgs {
   void *x_out;               // EPI_RESIDUAL producer: fp16 copy of the updated rows, fragment order
   float *part;               // EPI_RESIDUAL with more than 64 rows: scratch [KS][part_rows][N] fp32, or null
   int part_rows;             // M rounded up to 16
-  void *q, *kc, *vc;         // EPI_QKV
+  void *q, *kc, *vc;         // EPI_QKV: q [M][d] fp32 (un-rounded: the attention kernel decides how to feed it), caches in the model dtype
   const int32_t *row_pos;    // EPI_QKV: absolute position per row, -1 = dead row
   const float2 *rope;        // EPI_QKV: (cos, sin) table [L][hd/2] or null
   int q_rows, d, hd, H, L_pad;
@@ -81,7 +81,7 @@ void launch_argmax_partials(const float *pv, const int32_t *pi, int M, int row_s
                             int32_t *out, hipStream_t st);
 
 struct AttnArgs {
-  const void *q;            // [M][d] model dtype, pair-interleaved heads
+  const void *q;            // [M][d] fp32, pair-interleaved heads (rounded to the cache's type, as a pair for bf16, by the kernel)
   const void *kc, *vc;      // this layer's cache areas
   const int32_t *row_pos;   // [M]
   void *out;                // [M][d] fp16, canonical element order, fragment layout

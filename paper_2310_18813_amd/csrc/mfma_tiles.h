@@ -92,11 +92,11 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int 
           r0 = v[0] * cs0.x - v[1] * cs0.y; r1 = v[1] * cs0.x + v[0] * cs0.y;
           r2 = v[2] * cs1.x - v[3] * cs1.y; r3 = v[3] * cs1.x + v[2] * cs1.y;
         }
-        T o4[4];
-        Conv<T>::st(o4, 0, r0); Conv<T>::st(o4, 1, r1); Conv<T>::st(o4, 2, r2); Conv<T>::st(o4, 3, r3);
-        if (region == 0) {
-          *(uint2 *)((T *)a.q + (size_t)m * a.d + cc) = *(const uint2 *)o4;
+        if (region == 0) {  // queries stay fp32: they are never cached, and the attention kernel feeds them at full width
+          *(float4 *)((float *)a.q + (size_t)m * a.d + cc) = make_float4(r0, r1, r2, r3);
         } else if (pos >= 0) {
+          T o4[4];
+          Conv<T>::st(o4, 0, r0); Conv<T>::st(o4, 1, r1); Conv<T>::st(o4, 2, r2); Conv<T>::st(o4, 3, r3);
           *(uint2 *)((T *)a.kc + kv_k_index(a.L_pad, a.H, a.hd, b, hh, pos, e)) = *(const uint2 *)o4;
         }
       } else if (pos >= 0) {

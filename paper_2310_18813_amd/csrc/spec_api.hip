@@ -114,7 +114,7 @@ static Sizes compute_sizes(const spec_model_desc *tgt, const spec_model_desc *dr
     wide = std::max(wide, std::max<size_t>(3 * (size_t)drf->d_model, kfd * drf->d_ffn));
   }
   const size_t Mp = (M + 15) / 16 * 16;  // fragment-order activation buffers hold whole 16-row tiles
-  z.act = al256(M * d * 4) + 3 * al256(Mp * d * e) + al256(Mp * f * e) + al256(M * wide * 4) + al256(M * V * 4) +
+  z.act = al256(M * d * 4) + 2 * al256(Mp * d * e) + al256(Mp * d * 4) + al256(Mp * f * e) + al256(M * wide * 4) + al256(M * V * 4) +
           3 * al256(M * 4);
   // matrix-core path: split-KV attention partials and per-strip arg-max partials
   const size_t NC = (L + ATTN_CHUNK - 1) / ATTN_CHUNK, NTh = (V + 15) / 16;
@@ -259,7 +259,7 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
   W.h = (float *)carve(p, M * d * 4);
   const size_t Mp = (M + 15) / 16 * 16;
   W.x = carve(p, Mp * d * e);
-  W.q = carve(p, Mp * d * e);
+  W.q = carve(p, Mp * d * 4);  // fp32 on the matrix-core path, the model dtype on the generic one
   W.attn = carve(p, Mp * d * e);
   W.act = carve(p, Mp * f * e);
   W.y32 = (float *)carve(p, M * wide * 4);

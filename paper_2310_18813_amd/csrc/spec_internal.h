@@ -75,7 +75,7 @@ struct Workspace {
   // activations (shared by both models; sized for the larger)
   float *h = nullptr;       // [M_max][d]   fp32 residual stream
   void *x = nullptr;        // [M_max][d]   normed rows, model dtype (MFMA path: fp16 operands, as attn and act)
-  void *q = nullptr;        // [M_max][d]   queries, model dtype, pair-interleaved per head
+  void *q = nullptr;        // [M_max][d]   queries, pair-interleaved per head: fp32 (matrix-core path) or model dtype (generic)
   void *attn = nullptr;     // [M_max][d]   attention output, model dtype
   void *act = nullptr;      // [M_max][f]   FFN activation, model dtype
   float *y32 = nullptr;     // [M_max][max(3d, 2f)] fp32 GEMM output (generic path)
