@@ -306,6 +306,12 @@ int spec_measure_peaks(void *hip_stream, void *d_buf, size_t bytes, double *h_hb
    chunks).  Results must not depend on it.                                          */
 int spec_set_attention_shape(spec_ctx *ctx, int32_t shape);
 
+/* Test and tuning aid: pin launch shapes of the 16-bit GEMMs.  tile_mtw x tile_nbw (1..4 x 2..4; 0, 0 = chosen
+   from the shape) is the wave tile of the LDS-tiled kernel (more than 64 rows); flags: bit 0 = never take the
+   row-resident kernel, bit 1 = take it for every row count it covers (1..16) instead of the 9..16 where it is
+   the faster one.  Results must not depend on any of it.                                                      */
+int spec_set_gemm_tuning(spec_ctx *ctx, int32_t tile_mtw, int32_t tile_nbw, int32_t flags);
+
 /* Per-kernel timing for benchmarks.  While enabled, every launch of the target model's
    kernels is bracketed by a HIP event pair on the context's stream (this adds a few
    microseconds per launch: leave it off in production).  spec_read_kernel_timing

@@ -30,7 +30,8 @@ EXPORTS = ["spec_last_error", "spec_workspace_bytes", "spec_init", "spec_destroy
            "spec_profile_and_choose_s", "spec_set_lut", "spec_choose_s", "spec_read_output",
            "spec_read_state", "spec_kv_import", "spec_kv_export", "spec_kernel_timing",
            "spec_read_kernel_timing", "spec_set_hidden_dump", "spec_set_attention_shape", "spec_measure_peaks",
-           "spec_set_draft_logits", "spec_read_proposals", "spec_greedy_accept_workspace_bytes", "spec_greedy_accept"]
+           "spec_set_draft_logits", "spec_read_proposals", "spec_greedy_accept_workspace_bytes", "spec_greedy_accept",
+           "spec_set_gemm_tuning"]
 KCLASS_NAMES = ["gemm_qkv", "gemm_o", "gemm_ffn_in", "gemm_ffn_out", "gemm_head", "attention", "norm", "other",
                 "draft_pass"]
 
@@ -84,6 +85,7 @@ lib.spec_read_proposals.argtypes = [_vp, _i32p]
 lib.spec_greedy_accept_workspace_bytes.argtypes = [_i32, _i32, _i32, C.POINTER(C.c_size_t)]
 lib.spec_greedy_accept.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _vp, C.c_size_t, _vp, _vp]
 lib.spec_set_attention_shape.argtypes = [_vp, _i32]
+lib.spec_set_gemm_tuning.argtypes = [_vp, _i32, _i32, _i32]
 lib.spec_kernel_timing.argtypes = [_vp, _i32]
 lib.spec_read_kernel_timing.argtypes = [_vp, _i64p, C.POINTER(C.c_double)]
 lib.spec_measure_peaks.argtypes = [_vp, _vp, C.c_size_t, C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -356,6 +358,9 @@ class Context:
 
     def spec_set_attention_shape(self, shape):
         _check(lib.spec_set_attention_shape(self.h, shape), self.h)
+
+    def spec_set_gemm_tuning(self, tile_mtw=0, tile_nbw=0, flags=0):
+        _check(lib.spec_set_gemm_tuning(self.h, tile_mtw, tile_nbw, flags), self.h)
 
     def spec_kernel_timing(self, enable):
         _check(lib.spec_kernel_timing(self.h, 1 if enable else 0), self.h)

@@ -11,7 +11,7 @@ OUT = os.path.join(HERE, "libspecdec.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
 SOURCES = ["spec_api.hip", "kernels_state.hip", "kernels_generic.hip", "kernels_gemm_mfma.hip", "kernels_greedy_accept.hip",
-           "kernels_gemm_tile.hip", "kernels_peaks.hip", "kernels_attn_mfma.hip", "fast_path.hip"]
+           "kernels_gemm_tile.hip", "kernels_gemm_rowres.hip", "kernels_peaks.hip", "kernels_attn_mfma.hip", "fast_path.hip"]
 
 # packed-fp32 VALU forms are kept out of the generated code (they have produced wrong
 # results on the test machines); the host pass warns that it does not know the feature

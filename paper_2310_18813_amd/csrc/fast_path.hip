@@ -164,8 +164,9 @@ bool fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&curso
   return true;
 }
 
-static GemmArgs base_args(const PackedDims &p, const void *W, float inv_scale, const void *bias, const void *X, int M) {
+static GemmArgs base_args(const spec_ctx *c, const PackedDims &p, const void *W, float inv_scale, const void *bias, const void *X, int M) {
   GemmArgs a{};
+  a.n_cu = c->n_cu; a.tune = c->gemm_tune;
   a.W = W; a.bias = (const float *)bias; a.X = X; a.out_scale = inv_scale;
   a.M = M; a.N = p.N; a.NT = p.NT; a.KT = p.KT; a.KS = p.KS; a.K_pad = p.K_pad;
   return a;
@@ -201,7 +202,7 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
   };
   if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, 0, st); }
   {
-    GemmArgs a = base_args(m.p_qkv, L.wqkv, L.s_qkv, L.bqkv, ws.x, M);
+    GemmArgs a = base_args(c, m.p_qkv, L.wqkv, L.s_qkv, L.bqkv, ws.x, M);
     consume_norm(a);
     a.q = ws.q; a.kc = kc; a.vc = vc; a.row_pos = ws.row_pos; a.rope = m.rope;
     a.q_rows = q_rows; a.d = d; a.hd = m.hd; a.H = D.n_heads; a.L_pad = m.L_pad; a.seq_groups = seq_groups;
@@ -217,19 +218,20 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
     t.B = B; t.q_rows = q_rows; t.H = D.n_heads; t.hd = m.hd; t.L_pad = m.L_pad;
     t.seq_groups = seq_groups;
     t.shape = c->attn_shape;
+    t.n_cu = c->n_cu;
     t.NC = std::min(c->NC_max, max_pos / ATTN_CHUNK + 1);
     launch_attention_mfma(dt, t, st);
   }
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_O : -1);
-    GemmArgs a = base_args(m.p_o, L.wo, L.s_o, L.bo, ws.attn, M);
+    GemmArgs a = base_args(c, m.p_o, L.wo, L.s_o, L.bo, ws.attn, M);
     a.h = ws.h; a.part = ws.gemm_part; a.part_rows = (M + 15) / 16 * 16;
     produce_norm(a);
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
   }
   if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, 0, st); }
   {
-    GemmArgs a = base_args(m.p_13, L.w13, L.s_13, L.b13, ws.x, M);
+    GemmArgs a = base_args(c, m.p_13, L.w13, L.s_13, L.b13, ws.x, M);
     consume_norm(a);
     a.act = ws.act; a.f = D.d_ffn;
     const int epi = D.ffn_kind == SPEC_FFN_SWIGLU ? EPI_SWIGLU : EPI_RELU;
@@ -239,7 +241,7 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
   }
   {
     KScope k(c, tgt ? SPEC_KCLASS_GEMM_FFN_OUT : -1);
-    GemmArgs a = base_args(m.p_2, L.w2, L.s_2, L.b2, ws.act, M);
+    GemmArgs a = base_args(c, m.p_2, L.w2, L.s_2, L.b2, ws.act, M);
     a.h = ws.h; a.part = ws.gemm_part; a.part_rows = (M + 15) / 16 * 16;
     produce_norm(a);
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
@@ -257,7 +259,7 @@ void fast_head(spec_ctx *c, const Model &m, int Mh, int last_of_q, float *logits
   const bool fold = m.fold_norm;
   const int rows = fold && last_of_q > 0 ? Mh * last_of_q : Mh;
   if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, last_of_q, st); }
-  GemmArgs a = base_args(m.p_head, m.lm_head, m.s_head, nullptr, c->ws.x, rows);
+  GemmArgs a = base_args(c, m.p_head, m.lm_head, m.s_head, nullptr, c->ws.x, rows);
   a.logits = logits_or_null;
   a.logit_step = fold ? last_of_q : 0;  // the folded head runs over every row of the pass: dump the wanted ones only
   a.part_val = c->ws.head_part;

@@ -416,23 +416,35 @@ __global__ __launch_bounds__(512) void k_attn_group(AttnArgs a) {
   }
 }
 
+constexpr size_t attn_group_lds(int HD, int NC) { return (size_t)NC * ((HD / 16) * 64 * 16 + 64 * 8); }
+
 template <class T, int HD, bool STREAM>
 static void launch_attn_group(const AttnArgs &a, int pairs, hipStream_t st) {
-  const size_t lds = (size_t)a.NC * ((HD / 16) * 64 * 16 + 64 * 8);
-  static size_t lds_set = 64 * 1024;  // more than the default 64 KB of LDS needs to be asked for
-  if (lds > lds_set) {
-    (void)hipFuncSetAttribute((const void *)k_attn_group<T, HD, STREAM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    lds_set = lds;
-  }
   const int waves = a.NC < ATTN_GROUP_MAX_WAVES ? a.NC : ATTN_GROUP_MAX_WAVES;
-  hipLaunchKernelGGL((k_attn_group<T, HD, STREAM>), dim3(pairs), dim3(64 * waves), lds, st, a);
+  hipLaunchKernelGGL((k_attn_group<T, HD, STREAM>), dim3(pairs), dim3(64 * waves), attn_group_lds(HD, a.NC), st, a);
+}
+template <class T, int HD>
+static void prepare_attn_group() {  // more than the default 64 KB of LDS has to be asked for
+  const int lds = (int)attn_group_lds(HD, ATTN_GROUP_MAX_WAVES);
+  (void)hipFuncSetAttribute((const void *)k_attn_group<T, HD, true>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  (void)hipFuncSetAttribute((const void *)k_attn_group<T, HD, false>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+}
+void attention_prepare() {
+  prepare_attn_group<bf16_t, 128>(); prepare_attn_group<bf16_t, 64>();
+  prepare_attn_group<f16_t, 128>(); prepare_attn_group<f16_t, 64>();
 }
 
 template <class T, int HD>
 static void launch_attn_hd(const AttnArgs &a, hipStream_t st) {
   const int M = a.B * a.q_rows;
   const int pairs = a.B * a.H;
-  const bool seq = a.shape == 2 || (a.shape == 0 && (pairs >= ATTN_SEQ_MIN_PAIRS || a.NC == 1));
+  // One wave per (sequence, head) once there are enough pairs to fill the chip -- unless they leave the last of
+  // several rounds of n_cu * 4 resident waves mostly empty: a wave walks its whole sequence alone, so a round costs
+  // the same however few waves it holds (measured, 512 cached positions: 33 sequences x 32 heads 86 us against 64
+  // with a workgroup per pair; 48 x 32: 92 against 81; 32 x 32 and 64 x 32: 53 and 101 against 57 and 104).
+  const int slots = (a.n_cu > 0 ? a.n_cu : 256) * 4, rounds = (pairs + slots - 1) / slots;
+  const bool fills = rounds == 1 || (double)pairs >= 0.85 * (double)rounds * slots;
+  const bool seq = a.shape == 2 || (a.shape == 0 && ((pairs >= ATTN_SEQ_MIN_PAIRS && fills) || a.NC == 1));
   // few sequences: a workgroup per (sequence, head), as long as its partials fit into LDS with a wave per chunk
   const bool group = !seq && (a.shape == 3 || a.shape == 0) && a.NC <= ATTN_GROUP_MAX_WAVES;
   if (seq) {

@@ -377,6 +377,7 @@ static void launch_gemm_t(GemmArgs a, int epi, hipStream_t st) {
     launch_gemm_tile(std::is_same<T, bf16_t>::value ? SPEC_DTYPE_BF16 : SPEC_DTYPE_F16, a, epi, st);
     return;
   }
+  if (launch_gemm_rowres(std::is_same<T, bf16_t>::value ? SPEC_DTYPE_BF16 : SPEC_DTYPE_F16, a, epi, st)) return;
   const int KS = a.KS;
   // rows per pass: MT tiles of 16; strips per workgroup: NB.  Neither changes any result.
   const int MT = a.M <= 16 ? 1 : a.M <= 32 ? 2 : 4;

@@ -19,8 +19,6 @@
 // Results are bit-identical to the streaming kernel: the same instruction, every k-slice a
 // chain of MFMAs from zero in ascending k, the slices added in order, the same epilogue code.
 #include "mfma_tiles.h"
-#include <cstdio>
-#include <cstdlib>
 
 namespace spec {
 
@@ -296,11 +294,10 @@ __global__ __launch_bounds__(512) void k_row_inv_x(const void *__restrict__ X, i
 template <class T, int MTW, int NBW, int EPI>
 static void launch_one(const GemmArgs &a, int blocks, hipStream_t st) {
   constexpr size_t lds = 3 * (size_t)(2 * NBW + 4 * MTW) * 1024;
-  static bool attr_set = false;  // the kernel may use more than the default 64 KB of LDS
-  if (!attr_set) {
+  if (blocks < 0) {  // preparation pass: the kernel may use more than the default 64 KB of LDS
     (void)hipFuncSetAttribute((const void *)k_gemm_tile<T, MTW, NBW, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
                               (int)lds);
-    attr_set = true;
+    return;
   }
   hipLaunchKernelGGL((k_gemm_tile<T, MTW, NBW, EPI>), dim3(blocks), dim3(512), lds, st, a);
 }
@@ -326,17 +323,8 @@ static void launch_nb_tile(const GemmArgs &a, int NBW, int epi, int blocks, hipS
 // Wave tile (MTW 16-row tiles x NBW strips) for M rows and NT strips.  One workgroup occupies a CU, so
 // a launch takes ceil(workgroups / CUs) rounds of KT steps.  Measured on MI355X a step costs about
 // 150 + 45 * MTW * NBW + 40 * (MTW + NBW) clocks (two waves per SIMD at 16 clocks per MFMA are 32 of the
-// 45; the last term is the LDS traffic).  SPEC_GEMM_TILE="mtw,nbw" in the environment overrides the
-// choice (tuning aid).
+// 45; the last term is the LDS traffic).
 static void choose_tile(int M, int NT, int n_cu, int steps, int wg_mult, int &MTW, int &NBW) {
-  static int force_mt = -1, force_nb = 0;
-  if (force_mt < 0) {
-    force_mt = 0;
-    const char *e = getenv("SPEC_GEMM_TILE");
-    int mt = 0, nb = 0;
-    if (e && sscanf(e, "%d,%d", &mt, &nb) == 2 && mt >= 1 && mt <= 4 && nb >= 2 && nb <= 4) { force_mt = mt; force_nb = nb; }
-  }
-  if (force_mt > 0) { MTW = force_mt; NBW = force_nb; return; }
   long best = -1;
   for (int mt = 1; mt <= 4; ++mt)
     for (int nb = 2; nb <= 4; ++nb) {
@@ -351,16 +339,11 @@ static void choose_tile(int M, int NT, int n_cu, int steps, int wg_mult, int &MT
 
 // wave tile of the launch for these arguments (epi as given by the caller, EPI_RESIDUAL = split by k-slice)
 static void tile_for(const GemmArgs &a, int epi, int &MTW, int &NBW) {
-  static int n_cu = 0;
-  if (!n_cu) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
-    if (n_cu <= 0) n_cu = 256;
-  }
+  const int f_mt = a.tune & TUNE_TILE_MTW_MASK, f_nb = (a.tune >> TUNE_TILE_NBW_SHIFT) & 0xf;
+  if (f_mt >= 1 && f_mt <= 4 && f_nb >= 2 && f_nb <= 4) { MTW = f_mt; NBW = f_nb; return; }  // test / tuning aid
   const bool split = epi == EPI_RESIDUAL;
   MTW = 2; NBW = 2;
-  choose_tile(a.M, a.NT, n_cu, split ? a.KT / a.KS : a.KT, split ? a.KS : 1, MTW, NBW);
+  choose_tile(a.M, a.NT, a.n_cu > 0 ? a.n_cu : 256, split ? a.KT / a.KS : a.KT, split ? a.KS : 1, MTW, NBW);
 }
 
 // With more than one row tile per wave the kernel reads 1 / rms of its rows from a.rinv_ws: the caller runs
@@ -394,6 +377,17 @@ static void launch_tile_t(GemmArgs a, int epi, hipStream_t st) {
     const size_t total = (size_t)a.M * (a.N >> 2);
     hipLaunchKernelGGL(k_partial_reduce<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a);
   }
+}
+
+void gemm_tile_prepare() {
+  GemmArgs a{};
+  for (int epi : {(int)EPI_QKV, (int)EPI_SWIGLU, (int)EPI_RELU, (int)EPI_PARTIAL, (int)EPI_LOGITS})
+    for (int nbw = 2; nbw <= 4; ++nbw) {
+      launch_nb_tile<bf16_t, 1>(a, nbw, epi, -1, nullptr); launch_nb_tile<f16_t, 1>(a, nbw, epi, -1, nullptr);
+      launch_nb_tile<bf16_t, 2>(a, nbw, epi, -1, nullptr); launch_nb_tile<f16_t, 2>(a, nbw, epi, -1, nullptr);
+      launch_nb_tile<bf16_t, 3>(a, nbw, epi, -1, nullptr); launch_nb_tile<f16_t, 3>(a, nbw, epi, -1, nullptr);
+      launch_nb_tile<bf16_t, 4>(a, nbw, epi, -1, nullptr); launch_nb_tile<f16_t, 4>(a, nbw, epi, -1, nullptr);
+    }
 }
 
 void launch_gemm_tile(int dtype, GemmArgs a, int epi, hipStream_t st) {

@@ -28,6 +28,8 @@ struct GemmArgs {
   float out_scale;    // 1 / (power of two the packed weights were multiplied by)
   int M, N, NT, KT, KS, K_pad;
   int passes, groups;  // filled by the launcher
+  int n_cu;            // compute units of the device (0: 256)
+  int tune;            // launch-shape overrides of spec_set_gemm_tuning (0: none); never change a result
   // epilogue targets (those the chosen epilogue uses)
   float *h;                  // EPI_RESIDUAL: [M][N] fp32
   // RMS norm folded into the GEMMs around it: the gain sits in the packed weights of the consumer, whose
@@ -79,6 +81,20 @@ bool gemm_tile_wants_row_inv(const GemmArgs &a, int epi);
 void launch_row_inv_x(const GemmArgs &a, hipStream_t st);
 void launch_argmax_partials(const float *pv, const int32_t *pi, int M, int row_step, int NT, int V, int q, int out_stride,
                             int32_t *out, hipStream_t st);
+// once per context, with its device current: lets the kernels that need it use more than 64 KB of LDS
+void gemm_tile_prepare();
+void attention_prepare();
+// Up to 16 rows, wide outputs with a short k-slice: a wave keeps its slice of the activations in registers and
+// walks several weight strips (kernels_gemm_rowres.hip).  launch_gemm_rowres returns false when the shape is not
+// covered (the caller then takes the streaming kernel).
+bool launch_gemm_rowres(int dtype, const GemmArgs &a, int epi, hipStream_t st);
+// bits of GemmArgs::tune
+enum GemmTune {
+  TUNE_TILE_MTW_MASK = 0x00f,   // tiled kernel: force MTW (1..4) ...
+  TUNE_TILE_NBW_SHIFT = 4,      // ... and NBW (2..4), both or neither
+  TUNE_ROWRES_OFF = 0x100,      // never take the row-resident kernel
+  TUNE_ROWRES_ALWAYS = 0x200    // take it for every row count it covers (1..16), not only where it was measured faster
+};
 
 struct AttnArgs {
   const void *q;            // [M][d] fp32, pair-interleaved heads (rounded to the cache's type, as a pair for bf16, by the kernel)
@@ -90,6 +106,7 @@ struct AttnArgs {
   int shape;                // 0 auto, 1 split + merge, 2 one wave per (sequence, head), 3 one workgroup per (sequence, head)
   int B, q_rows, H, hd, L_pad, NC;  // NC = chunks launched (upper bound over the batch)
   int seq_groups;           // consecutive groups of q_rows rows that belong to one sequence and share its cache (0 or 1: one)
+  int n_cu;                 // compute units of the device (0: 256)
 };
 constexpr int ATTN_CHUNK = 256;  // keys per split; boundaries at multiples of this position
 constexpr int ATTN_STREAM_MIN_WAVES = 1024;  // (sequence, head, chunk) waves from which the split kernel loads non-temporally

@@ -230,6 +230,14 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
   c->run = *run;
   c->eos = run->eos_id;
   c->stream = (hipStream_t)hip_stream;
+  {  // per device: the CU count the launch shapes are chosen for, and the kernels' LDS allowances
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+      c->n_cu = prop.multiProcessorCount;
+    gemm_tile_prepare();
+    attention_prepare();
+  }
   Sizes z = compute_sizes(tgt, drf, run);
   c->M_max = z.M_max;
   char *p = (char *)d_workspace;
@@ -341,6 +349,19 @@ extern "C" int spec_set_eos(spec_ctx *c, int32_t eos_token) {
   if (c->draft_j != 0 || c->verified_s >= 0)
     return fail(c, SPEC_ERR_STATE, "spec_set_eos: a round is in progress; finish it with spec_accept_commit first");
   c->eos = eos_token;
+  return SPEC_OK;
+}
+
+extern "C" int spec_set_gemm_tuning(spec_ctx *c, int32_t tile_mtw, int32_t tile_nbw, int32_t flags) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_set_gemm_tuning: ctx is null");
+  const bool tile_auto = tile_mtw == 0 && tile_nbw == 0;
+  if (!tile_auto && (tile_mtw < 1 || tile_mtw > 4 || tile_nbw < 2 || tile_nbw > 4))
+    return fail(c, SPEC_ERR_INVALID_ARG, "spec_set_gemm_tuning: wave tile must be 0,0 (automatic) or 1..4 x 2..4");
+  if (flags < 0 || flags > 3) return fail(c, SPEC_ERR_INVALID_ARG, "spec_set_gemm_tuning: unknown flag bits");
+  int t = tile_auto ? 0 : (tile_mtw | (tile_nbw << TUNE_TILE_NBW_SHIFT));
+  if (flags & 1) t |= TUNE_ROWRES_OFF;
+  if (flags & 2) t |= TUNE_ROWRES_ALWAYS;
+  c->gemm_tune = t;
   return SPEC_OK;
 }
 

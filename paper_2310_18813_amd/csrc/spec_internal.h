@@ -126,6 +126,8 @@ struct spec_ctx {
   float *hidden_dump = nullptr;
   float *draft_logits = nullptr;  // parity aid: where every draft step leaves the logits behind its proposals
   int attn_shape = 0;
+  int gemm_tune = 0;      // GemmTune bits (spec_set_gemm_tuning)
+  int n_cu = 256;         // compute units of the context's device
   std::vector<int32_t> lut_B, lut_s;
   std::string err;
   hipEvent_t ev0 = nullptr, ev1 = nullptr;

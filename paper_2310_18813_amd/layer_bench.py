@@ -28,6 +28,8 @@ def main():
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--layers", type=int, default=4)
     ap.add_argument("--kv", type=int, default=512)
+    ap.add_argument("--tune", default="0,0,0", help="spec_set_gemm_tuning arguments: tile_mtw,tile_nbw,flags")
+    ap.add_argument("--attn-shape", type=int, default=0)
     args = ap.parse_args()
 
     import numpy as np
@@ -49,6 +51,8 @@ def main():
         ctx.spec_kv_import(B.MODEL_TARGET, layer, K, V)
     prompts = si.make_prompts(B_max, args.kv + 1, desc["vocab"], seed)
     ctx.spec_set_proposal_table(np.zeros((B_max, L_max), dtype=np.int32))
+    ctx.spec_set_gemm_tuning(*[int(x) for x in args.tune.split(",")])
+    ctx.spec_set_attention_shape(args.attn_shape)
     d, f, Vv, nl = desc["d_model"], desc["d_ffn"], desc["vocab"], args.layers
     w_layer = 4 * d * d + 3 * d * f
     out = []

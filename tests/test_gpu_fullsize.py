@@ -129,15 +129,36 @@ def test_rows_are_bit_identical_across_batch_and_speculation_length(world):
     assert torch.equal(small, big[:b1])
     again, _, _, _ = gpu_cell(wd, b2, s2)       # and the same launch twice
     assert torch.equal(again, big)
+    # pinned GEMM launch shapes: row-resident kernel never / wherever it applies; two other wave tiles of the tiled kernel
+    ctx = wd["ctx"]
+    try:
+        for flags in (1, 2):
+            ctx.spec_set_gemm_tuning(0, 0, flags)
+            for nB, s in ((1, 0), (3, 2), (16, 0)):
+                lg, _, _, _ = gpu_cell(wd, nB, s)
+                assert torch.equal(lg[0, 0], base[0, 0]), (flags, nB, s)
+        for mtw, nbw in ((1, 2), (3, 4)):
+            ctx.spec_set_gemm_tuning(mtw, nbw, 0)
+            lg, _, _, _ = gpu_cell(wd, b2, s2)
+            assert torch.equal(lg, big), (mtw, nbw)
+    finally:
+        ctx.spec_set_gemm_tuning(0, 0, 0)
 
 
 # ------------------------------------------------------------------ full depth
-# End-to-end bound for the 32-layer 7B shape in bf16 (max |logit error| against the fp64 oracle).  One layer's
-# output differs from the oracle's by at most about 1e-2 of the stream's rms (the bf16 storage of the K/V rows
-# the pass appends, which the method's cache fixes; queries and softmax weights carry 16 bits), and every branch
-# matrix of the random-initialised stack has gain 0.02 * sqrt(4096) = 1.28, so the stack amplifies what each layer
-# adds: measured 0.06 - 0.09 over seeds and prompts.  The bound leaves a third on top of the largest seen.
-E2E_TOL_7B = 0.12
+# End-to-end bounds for the 32-layer 7B shape in bf16 (max |logit error|).  Every branch matrix of the random-initialised
+# stack has gain 0.02 * sqrt(4096) = 1.28, so the stack amplifies what each layer adds, and one thing each layer adds is
+# fixed by the configuration, not by the arithmetic: the K/V rows are stored in bf16.  Rounding the fp64 oracle's own
+# cached rows to bf16 (nothing else) moves its logits by 0.089 / 0.096 max, 0.0198 / 0.0194 rms on the two sequences
+# below (CPU experiment); the GPU differs from the plain fp64 oracle by 0.107 max, 0.023 rms.  So the test compares
+# with both: the plain oracle within 0.15 (the storage effect plus the arithmetic), and the oracle whose cached rows
+# are rounded to the cache's type within a tighter bound that is the arithmetic's alone.
+E2E_TOL_7B = 0.15
+E2E_TOL_7B_BF16_CACHE = 0.08
+
+
+def bf16_round(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).to(torch.float64).numpy()
 
 
 def one_layer_oracle(orc, tdesc, layer_w, rows, L_max):
@@ -245,11 +266,12 @@ def test_llama7b_every_layer_matches_oracle_at_full_depth():
     ctx.spec_accept_commit(s)
     _, _, _, a = ctx.spec_read_state()
     ot = orc.model(tdesc, si.weights_to_numpy(w), 1)
-    checked, e_max, e_rms = 0, 0.0, 0.0
+    checked, e_max, e_rms, c_max, c_rms = 0, 0.0, 0.0, 0.0, 0.0
     for b in range(nB):
+        toks = [int(x) for x in prompts[b][:Ps]] + [int(x) for x in props[b]]
         cache = ot.cache(L_max)
-        ot.forward(cache, prompts[b][:Ps - 1], 0, want_logits=False)
-        o = ot.forward(cache, [int(prompts[b][Ps - 1])] + [int(x) for x in props[b]], Ps - 1)
+        ot.forward(cache, toks[:Ps - 1], 0, want_logits=False)
+        o = ot.forward(cache, toks[Ps - 1:], Ps - 1)
         e2e = np.abs(lg[b] - o)
         e_max, e_rms = max(e_max, e2e.max()), max(e_rms, np.sqrt((e2e ** 2).mean()))
         marg = top2_margin(o)
@@ -257,9 +279,24 @@ def test_llama7b_every_layer_matches_oracle_at_full_depth():
             if marg[i] > 2 * E2E_TOL_7B:
                 assert a[b][i] == int(o[i].argmax()), (b, i)
                 checked += 1
-    print("7B shape end to end: max |logit err| %.4g, rms %.4g over %d layers (bound %g); %d greedy tokens checked"
-          % (e_max, e_rms, nl, E2E_TOL_7B, checked))
+        # the same oracle with its cached K/V rows rounded to the cache's storage type: token by token, every
+        # layer's new row rounded before the next token attends to it
+        cache = ot.cache(L_max)
+        oc = []
+        for i, t in enumerate(toks):
+            r = ot.forward(cache, [t], i, want_logits=(i >= Ps - 1))
+            if i >= Ps - 1:
+                oc.append(r[0])
+            for l in range(nl):
+                cache.k(l)[i] = bf16_round(cache.k(l)[i])
+                cache.v(l)[i] = bf16_round(cache.v(l)[i])
+        ec = np.abs(lg[b] - np.stack(oc))
+        c_max, c_rms = max(c_max, ec.max()), max(c_rms, np.sqrt((ec ** 2).mean()))
+    print("7B shape end to end over %d layers: vs the fp64 oracle max |logit err| %.4g, rms %.4g (bound %g); vs the oracle "
+          "with bf16-stored cache rows max %.4g, rms %.4g (bound %g); %d greedy tokens checked"
+          % (nl, e_max, e_rms, E2E_TOL_7B, c_max, c_rms, E2E_TOL_7B_BF16_CACHE, checked))
     assert e_max <= E2E_TOL_7B
+    assert c_max <= E2E_TOL_7B_BF16_CACHE
     assert checked > 0
     ctx.close()
 
