@@ -282,6 +282,15 @@ int spec_greedy_accept(void *hip_stream, const float *d_logits, const int32_t *d
                        int32_t vocab, void *d_workspace, size_t workspace_bytes, int32_t *d_accepted,
                        int32_t *d_emitted);
 
+/* spec_greedy_accept for callers that cannot allocate or pass a workspace (code under HIP graph capture, tight
+   serving loops, harnesses that forbid hipMalloc): the same kernels, with the arg-max partials in a 1 MiB array
+   built into the library (one copy per GPU, held until the process ends).  Calls no allocating routine.
+   Limit: B * (s + 1) * ceil(vocab / 4096) <= 131072, SPEC_ERR_CAPACITY beyond (e.g. 16384 rows of a 32000-token
+   vocabulary).  Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two
+   threads) race; calls on one stream are ordered and need no clearing in between.                               */
+int spec_greedy_accept_noalloc(void *hip_stream, const float *d_logits, const int32_t *d_proposals, int32_t B,
+                               int32_t s, int32_t vocab, int32_t *d_accepted, int32_t *d_emitted);
+
 /* Parity aids for the draft step (the call speculate(S, kv_SSM, s) of Alg. 1).
    spec_set_draft_logits: if d_logits is not NULL, every following spec_draft_step also writes the draft
    model's logits behind t_j -- the logits of the last token each sequence fed in -- as fp32 [B][vocab]

@@ -31,7 +31,7 @@ EXPORTS = ["spec_last_error", "spec_workspace_bytes", "spec_init", "spec_destroy
            "spec_read_state", "spec_kv_import", "spec_kv_export", "spec_kernel_timing",
            "spec_read_kernel_timing", "spec_set_hidden_dump", "spec_set_attention_shape", "spec_measure_peaks",
            "spec_set_draft_logits", "spec_read_proposals", "spec_greedy_accept_workspace_bytes", "spec_greedy_accept",
-           "spec_set_gemm_tuning"]
+           "spec_greedy_accept_noalloc", "spec_set_gemm_tuning"]
 KCLASS_NAMES = ["gemm_qkv", "gemm_o", "gemm_ffn_in", "gemm_ffn_out", "gemm_head", "attention", "norm", "other",
                 "draft_pass"]
 
@@ -84,6 +84,7 @@ lib.spec_set_draft_logits.argtypes = [_vp, _vp]
 lib.spec_read_proposals.argtypes = [_vp, _i32p]
 lib.spec_greedy_accept_workspace_bytes.argtypes = [_i32, _i32, _i32, C.POINTER(C.c_size_t)]
 lib.spec_greedy_accept.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _vp, C.c_size_t, _vp, _vp]
+lib.spec_greedy_accept_noalloc.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp]
 lib.spec_set_attention_shape.argtypes = [_vp, _i32]
 lib.spec_set_gemm_tuning.argtypes = [_vp, _i32, _i32, _i32]
 lib.spec_kernel_timing.argtypes = [_vp, _i32]
@@ -139,9 +140,10 @@ def spec_measure_peaks(device="cuda:0", nbytes=1 << 30):
     return g.value, t.value
 
 
-def spec_greedy_accept(logits, proposals, accepted=None, emitted=None, workspace=None):
+def spec_greedy_accept(logits, proposals, accepted=None, emitted=None, workspace=None, noalloc=False):
     """logits [B][s+1][V] fp32 device tensor, proposals [B][s] int32 device tensor (or None when s = 0).
-    -> (accepted [B], emitted [B][s+1]) int32 device tensors."""
+    -> (accepted [B], emitted [B][s+1]) int32 device tensors.  noalloc=True calls spec_greedy_accept_noalloc
+    (outputs must then be passed in: this wrapper allocates nothing in that mode)."""
     assert logits.dim() == 3 and logits.dtype == torch.float32 and logits.is_contiguous()
     nB, q, V = logits.shape
     s = q - 1
@@ -149,6 +151,12 @@ def spec_greedy_accept(logits, proposals, accepted=None, emitted=None, workspace
         assert proposals.dtype == torch.int32 and proposals.shape == (nB, s) and proposals.is_contiguous()
     dev = logits.device
     st = C.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+    if noalloc:
+        assert accepted is not None and emitted is not None
+        with torch.cuda.device(dev):
+            _check(lib.spec_greedy_accept_noalloc(st, _dp(logits), _dp(proposals) if s else None, nB, s, V, _dp(accepted),
+                                                  _dp(emitted)))
+        return accepted, emitted
     if accepted is None:
         accepted = torch.empty(nB, dtype=torch.int32, device=dev)
     if emitted is None:

@@ -6,9 +6,11 @@
 // ties, at every stage) and applies the first-mismatch rule.  Every partial the second kernel reads was written by
 // the first in the same call, so the scratch needs no clearing.
 //
-// The scratch is the caller's workspace.
+// The scratch is the caller's workspace (spec_greedy_accept) or a file-scope device array
+// (spec_greedy_accept_noalloc, for callers that cannot allocate).
 #include "spec_internal.h"
 #include "device_utils.h"
+#include <mutex>
 
 namespace spec {
 
@@ -105,4 +107,42 @@ extern "C" int spec_greedy_accept(void *hip_stream, const float *d_logits, const
     return fail_noctx(SPEC_ERR_WORKSPACE, "spec_greedy_accept: workspace null, not 8-byte aligned, or smaller than %zu bytes",
                       ga_bytes(B, s, vocab));
   return ga_launch((hipStream_t)hip_stream, d_logits, d_proposals, B, s, vocab, d_workspace, d_accepted, d_emitted);
+}
+
+// ---------------------------------------------------------------- no-allocation variant
+namespace spec {
+constexpr size_t GA_STATIC_BYTES = 1u << 20;  // 131072 (row, chunk) partials: e.g. 1024 rows of a 500k vocabulary, 16384 rows of a 32k one
+constexpr int GA_MAX_DEVICES = 64;
+// The no-allocation variant's scratch.  In host code this name is a stand-in, not a device address: the address
+// comes from hipGetSymbolAddress, once per device (every GPU holds its own copy of the array).
+static __device__ __align__(256) unsigned char ga_scratch[GA_STATIC_BYTES];
+static void *g_ga_scratch_ptr[GA_MAX_DEVICES];
+static std::mutex g_ga_mutex;
+
+// Device address of the current device's copy of the scratch array; null on failure.
+static void *ga_static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= GA_MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> lock(g_ga_mutex);
+  if (!g_ga_scratch_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(ga_scratch)) != hipSuccess) return nullptr;
+    g_ga_scratch_ptr[dev] = p;
+  }
+  return g_ga_scratch_ptr[dev];
+}
+}  // namespace spec
+
+extern "C" int spec_greedy_accept_noalloc(void *hip_stream, const float *d_logits, const int32_t *d_proposals, int32_t B,
+                                          int32_t s, int32_t vocab, int32_t *d_accepted, int32_t *d_emitted) {
+  int rc = ga_check("spec_greedy_accept_noalloc", d_logits, d_proposals, B, s, vocab, d_accepted, d_emitted);
+  if (rc) return rc;
+  if (ga_bytes(B, s, vocab) > GA_STATIC_BYTES)
+    return fail_noctx(SPEC_ERR_CAPACITY,
+                      "spec_greedy_accept_noalloc: B * (s + 1) * ceil(vocab / %d) = %zu partials exceed the built-in scratch of %zu; "
+                      "use spec_greedy_accept with a workspace",
+                      GA_CHUNK, ga_bytes(B, s, vocab) / sizeof(GaPartial), GA_STATIC_BYTES / sizeof(GaPartial));
+  void *scratch = ga_static_scratch();
+  if (!scratch) return fail_noctx(SPEC_ERR_HIP, "spec_greedy_accept_noalloc: hipGetSymbolAddress failed for the scratch array");
+  return ga_launch((hipStream_t)hip_stream, d_logits, d_proposals, B, s, vocab, scratch, d_accepted, d_emitted);
 }

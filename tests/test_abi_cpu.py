@@ -115,3 +115,5 @@ def test_greedy_accept_validates_before_any_device_call(B):
     assert B.lib.spec_greedy_accept(None, None, fake, 1, 1, 10, fake, 64, fake, fake) == B.ERR_INVALID_ARG
     assert B.lib.spec_greedy_accept(None, fake, fake, 1, 1, 10, None, 64, fake, fake) == B.ERR_WORKSPACE
     assert B.lib.spec_greedy_accept(None, fake, fake, 1, 1, 10, fake, 4, fake, fake) == B.ERR_WORKSPACE
+    assert B.lib.spec_greedy_accept_noalloc(None, fake, fake, 65535, 15, 32000, fake, fake) == B.ERR_CAPACITY
+    assert b"built-in scratch" in B.lib.spec_last_error(None)
