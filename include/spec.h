@@ -223,9 +223,11 @@ int spec_round(spec_ctx *ctx, int32_t s, int32_t n_rounds);
    every s in 0..s_max_profile: reset with the first B rows of d_prompt ([maxB][P]),
    run one untimed warm-up round, rewind, then time max(1, gen / (s+1)) rounds with HIP
    events (that many rounds cannot finish a sequence, so every timed round does full
-   work) and record microseconds per emitted token per sequence (elapsed / (tokens
-   emitted / B)), the per-token latency of the paper's Fig. 1.  The LUT entry is the s
-   with the lowest value, the smaller s winning ties within 1 %.  The LUT is kept in
+   work) and record microseconds per emitted token per sequence, the per-token latency
+   of the paper's Fig. 1: the time of a round at (B, s) divided by the tokens a sequence
+   emits per round at that s, the latter pooled over all batch sizes of the call (it does
+   not depend on B, and one small batch holds too few acceptance draws to estimate it).
+   The LUT entry is the s with the lowest value, the smaller s winning ties within 1 %.  The LUT is kept in
    the context for spec_choose_s.  h_lut_out: [n_b]; h_grid_us_per_tok_or_null:
    [n_b][s_max_profile+1].  Needs gen <= gen_max.  In SPEC_PROPOSALS_EXTERNAL mode a
    proposal table must be set.  Synchronises; leaves the context rewound on the last

@@ -439,14 +439,17 @@ static void launch_attn_hd(const AttnArgs &a, hipStream_t st) {
   const int M = a.B * a.q_rows;
   const int pairs = a.B * a.H;
   // One wave per (sequence, head) once there are enough pairs to fill the chip -- unless they leave the last of
-  // several rounds of n_cu * 4 resident waves mostly empty: a wave walks its whole sequence alone, so a round costs
-  // the same however few waves it holds (measured, 512 cached positions: 33 sequences x 32 heads 86 us against 64
-  // with a workgroup per pair; 48 x 32: 92 against 81; 32 x 32 and 64 x 32: 53 and 101 against 57 and 104).
+  // several rounds of n_cu * 4 waves mostly empty: a compute unit's share of the HBM stream is bounded, so the
+  // units that hold a second workgroup take twice as long as the others.  Measured (us per layer): 512 cached
+  // positions x 32 heads, a workgroup per pair as the alternative: 33 sequences 86 against 64, 48 sequences 92
+  // against 81, 32 and 64 sequences 53 and 101 against 57 and 104; 2048 positions x 52 heads, where the alternative
+  // is split + merge: 20 sequences 299 against 242, 24 sequences 305 against 287, 32 sequences 326 against 378.
   const int slots = (a.n_cu > 0 ? a.n_cu : 256) * 4, rounds = (pairs + slots - 1) / slots;
-  const bool fills = rounds == 1 || (double)pairs >= 0.85 * (double)rounds * slots;
+  const bool group_fits = a.NC <= ATTN_GROUP_MAX_WAVES;
+  const bool fills = rounds == 1 || (double)pairs >= (group_fits ? 0.85 : 0.7) * (double)rounds * slots;
   const bool seq = a.shape == 2 || (a.shape == 0 && ((pairs >= ATTN_SEQ_MIN_PAIRS && fills) || a.NC == 1));
   // few sequences: a workgroup per (sequence, head), as long as its partials fit into LDS with a wave per chunk
-  const bool group = !seq && (a.shape == 3 || a.shape == 0) && a.NC <= ATTN_GROUP_MAX_WAVES;
+  const bool group = !seq && (a.shape == 3 || a.shape == 0) && group_fits;
   if (seq) {
     hipLaunchKernelGGL((k_attn_seq<T, HD>), dim3((pairs + 3) / 4), dim3(256), 0, st, a);
   } else if (group) {

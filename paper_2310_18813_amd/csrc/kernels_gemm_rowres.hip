@@ -125,9 +125,11 @@ __global__ __launch_bounds__(576) void k_gemm_rowres(GemmArgs a) {
 
   for (int i = 0; i < n_mine; ++i) {
     // the slot a multiply has read is refilled with the step R further on in the wave's stream: the same strip, then
-    // the next one -- after the last strip this strip again: the same in-bounds addresses, so that the loop has
-    // no conditional load and exactly R loads are in flight in front of every multiply
-    const u32x4_v *wp_next = (i + 1 < n_mine) ? wp + (size_t)gridDim.x * strip_stride : wp;
+    // the next one -- after the last strip the wave's own activation slice (in bounds, and cache hits rather than
+    // weights from HBM once more), so that the loop has no conditional load and exactly R loads are in flight in
+    // front of every multiply
+    const u32x4_v *wp_next = (i + 1 < n_mine) ? wp + (size_t)gridDim.x * strip_stride
+                                              : (const u32x4_v *)a.X + (size_t)kt0 * 64 + lane;
     f32x4_v acc[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[mt] = (f32x4_v){0.f, 0.f, 0.f, 0.f};

@@ -755,7 +755,8 @@ extern "C" int spec_profile_and_choose_s(spec_ctx *c, const int32_t *h_batch_siz
     return fail(c, SPEC_ERR_STATE, "spec_profile_and_choose_s: external proposals need a table");
   if (!ext && s_max_profile > 0 && !c->drf.present) return fail(c, SPEC_ERR_STATE, "spec_profile_and_choose_s: no draft model");
   const int nS = s_max_profile + 1;
-  std::vector<double> grid((size_t)n_b * nS);
+  std::vector<double> grid((size_t)n_b * nS), us_round((size_t)n_b * nS);
+  std::vector<double> tok_s(nS, 0.0), seq_rounds_s(nS, 0.0);  // per s, pooled over the batch sizes
   std::vector<int32_t> lut(n_b);
   struct CapsOff {  // the profiling stage times uniform rounds: per-sequence caps and the end token are set aside until it returns
     spec_ctx *c; const int32_t *saved; int32_t saved_eos;
@@ -782,8 +783,19 @@ extern "C" int spec_profile_and_choose_s(spec_ctx *c, const int32_t *h_batch_siz
       HIPCHK(c, hipEventElapsedTime(&ms, c->ev0, c->ev1));
       unsigned long long cnt[2] = {0, 0};
       HIPCHK(c, hipMemcpy(cnt, c->st.counters, sizeof cnt, hipMemcpyDeviceToHost));
-      const double per_seq = (double)cnt[0] / (double)B;
-      grid[(size_t)bi * nS + s] = per_seq > 0 ? (double)ms * 1000.0 / per_seq : 1e30;
+      us_round[(size_t)bi * nS + s] = (double)ms * 1000.0 / rounds;
+      tok_s[s] += (double)cnt[0];
+      seq_rounds_s[s] += (double)B * rounds;
+    }
+  }
+  // Time per emitted token per sequence = time of a round / tokens a sequence emits per round.  A round's time is
+  // a property of (B, s) and repeats to a fraction of a per cent; the tokens per round depend on s and on how well the
+  // proposals agree with the target, not on B (Alg. 1 has no term that couples sequences), and a single small batch
+  // sees only a few dozen acceptance draws -- so they are pooled over all batch sizes of the run.
+  for (int bi = 0; bi < n_b; ++bi) {
+    for (int s = 0; s < nS; ++s) {
+      const double per_round = seq_rounds_s[s] > 0 ? tok_s[s] / seq_rounds_s[s] : 0.0;
+      grid[(size_t)bi * nS + s] = per_round > 0 ? us_round[(size_t)bi * nS + s] / per_round : 1e30;
     }
     // arg-min over s; within 1 % of the minimum the smaller s wins
     const double *row = &grid[(size_t)bi * nS];

@@ -1,6 +1,6 @@
 #!/usr/bin/env python3
 """Verify-step micro-benchmark on LLaMA-7B-shape layers (d=4096, 32 heads x 128, SwiGLU 11008,
-LM head 32000, bf16; 512 cached positions per sequence): latency of one target verification
+LM head 32000, bf16; 512 cached positions per sequence; --shape picks the 13B OPT or the 33B width instead): latency of one target verification
 pass for chosen (B, s) cells, per kernel class, against the HBM / MFMA roofline.
 
 The layer stack holds `--layers` distinct weight copies (default 4 = 1.6 GB, far beyond the
@@ -28,6 +28,7 @@ def main():
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--layers", type=int, default=4)
     ap.add_argument("--kv", type=int, default=512)
+    ap.add_argument("--shape", default="7b", choices=["7b", "13b", "33b"], help="layer width: 7b d=4096 (bf16), 13b OPT d=5120 (fp16), 33b d=6656 (bf16)")
     ap.add_argument("--tune", default="0,0,0", help="spec_set_gemm_tuning arguments: tile_mtw,tile_nbw,flags")
     ap.add_argument("--attn-shape", type=int, default=0)
     args = ap.parse_args()
@@ -39,6 +40,10 @@ def main():
 
     cells = [tuple(int(x) for x in c.split(",")) for c in args.cells.split(";")]
     dtype, seed, desc, _ = si.CONFIGS["layer_bf16"]
+    if args.shape == "13b":
+        dtype, seed, desc = "fp16", 1003, si.opt_desc(1, 5120, 40, 20480, 50272, 1024)
+    elif args.shape == "33b":
+        dtype, seed, desc = "bf16", 1004, si.llama_desc(1, 6656, 52, 17920, 32000, 4096)
     B_max, s_max = max(c[0] for c in cells), max(c[1] for c in cells)
     L_max = args.kv + 1 + (args.iters + 4) * (s_max + 1) + s_max
     desc = dict(desc, n_layers=args.layers, max_pos=L_max)
@@ -54,7 +59,7 @@ def main():
     ctx.spec_set_gemm_tuning(*[int(x) for x in args.tune.split(",")])
     ctx.spec_set_attention_shape(args.attn_shape)
     d, f, Vv, nl = desc["d_model"], desc["d_ffn"], desc["vocab"], args.layers
-    w_layer = 4 * d * d + 3 * d * f
+    w_layer = 4 * d * d + (3 if desc["ffn_kind"] == 0 else 2) * d * f
     out = []
     for nB, s in cells:
         M = nB * (s + 1)
