@@ -248,6 +248,12 @@ int spec_choose_s(const spec_ctx *ctx, int32_t B, int32_t *h_s_out);
    h_hist_or_null: [s_max+1] counts of rounds*sequences by accepted length l.         */
 int spec_read_output(spec_ctx *ctx, int32_t *h_tokens, int32_t *h_len, int64_t *h_hist_or_null);
 
+/* 16-bit runs feed their GEMMs fp16 operands: an activation beyond +-65504 (the residual stream of the layer
+   input, an FFN activation) is clamped to that range on the way, silently as far as the tokens go.  *h_count
+   receives how many values were clamped since spec_init (0 for fp32 runs and for every workload of this
+   repository; a non-zero count says the model's activations do not fit this build's operand type).  Synchronises. */
+int spec_read_saturation(spec_ctx *ctx, int64_t *h_count);
+
 /* Per-sequence state for tests: any pointer may be NULL.  h_n [B] committed lengths,
    h_kv_draft [B] draft cache lengths, h_l_last [B] accepted count of the last round,
    h_argmax [B][s_max+1] the a_i of the last verify step.                             */

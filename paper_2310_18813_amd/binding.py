@@ -31,7 +31,7 @@ EXPORTS = ["spec_last_error", "spec_workspace_bytes", "spec_init", "spec_destroy
            "spec_read_state", "spec_kv_import", "spec_kv_export", "spec_kernel_timing",
            "spec_read_kernel_timing", "spec_set_hidden_dump", "spec_set_attention_shape", "spec_measure_peaks",
            "spec_set_draft_logits", "spec_read_proposals", "spec_greedy_accept_workspace_bytes", "spec_greedy_accept",
-           "spec_greedy_accept_noalloc", "spec_set_gemm_tuning"]
+           "spec_greedy_accept_noalloc", "spec_set_gemm_tuning", "spec_read_saturation"]
 KCLASS_NAMES = ["gemm_qkv", "gemm_o", "gemm_ffn_in", "gemm_ffn_out", "gemm_head", "attention", "norm", "other",
                 "draft_pass"]
 
@@ -82,6 +82,7 @@ lib.spec_kv_export.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp]
 lib.spec_set_hidden_dump.argtypes = [_vp, _vp]
 lib.spec_set_draft_logits.argtypes = [_vp, _vp]
 lib.spec_read_proposals.argtypes = [_vp, _i32p]
+lib.spec_read_saturation.argtypes = [_vp, _i64p]
 lib.spec_greedy_accept_workspace_bytes.argtypes = [_i32, _i32, _i32, C.POINTER(C.c_size_t)]
 lib.spec_greedy_accept.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _vp, C.c_size_t, _vp, _vp]
 lib.spec_greedy_accept_noalloc.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp]
@@ -357,6 +358,11 @@ class Context:
         self._draft_logits = torch.zeros((self.B_max, self.drf_desc["vocab"]), dtype=torch.float32, device=self.device)
         _check(lib.spec_set_draft_logits(self.h, _dp(self._draft_logits)), self.h)
         return self._draft_logits
+
+    def spec_read_saturation(self):
+        n = C.c_int64(-1)
+        _check(lib.spec_read_saturation(self.h, C.byref(n)), self.h)
+        return n.value
 
     def spec_read_proposals(self):
         """-> [B][s_max] proposals of the current round."""

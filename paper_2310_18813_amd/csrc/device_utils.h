@@ -45,6 +45,12 @@ __device__ __forceinline__ op_t to_op(float f) {
   return (op_t)f;
 }
 
+// to_op that also counts the values it had to clamp (sat: a device counter, or null)
+__device__ __forceinline__ op_t to_op_counted(float f, unsigned int *sat) {
+  if (sat && (f > 65504.f || f < -65504.f)) atomicAdd(sat, 1u);
+  return to_op(f);
+}
+
 // Activations that feed a matrix-core GEMM are stored in the order the B operand is loaded:
 // 16-row x 32-k tiles of 1 KB, tile (m/16, k/32) at ((m/16) * KT + k/32), inside a tile lane
 // 16*((k%32)/8) + m%16 owns 8 consecutive k.  Element index of X[m][k] for a row length of 32*KT:

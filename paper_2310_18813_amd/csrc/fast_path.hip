@@ -166,7 +166,7 @@ bool fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&curso
 
 static GemmArgs base_args(const spec_ctx *c, const PackedDims &p, const void *W, float inv_scale, const void *bias, const void *X, int M) {
   GemmArgs a{};
-  a.n_cu = c->n_cu; a.tune = c->gemm_tune;
+  a.n_cu = c->n_cu; a.tune = c->gemm_tune; a.sat = c->st.sat;
   a.W = W; a.bias = (const float *)bias; a.X = X; a.out_scale = inv_scale;
   a.M = M; a.N = p.N; a.NT = p.NT; a.KT = p.KT; a.KS = p.KS; a.K_pad = p.K_pad;
   return a;

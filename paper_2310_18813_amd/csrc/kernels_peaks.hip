@@ -68,21 +68,21 @@ extern "C" int spec_measure_peaks(void *hip_stream, void *d_buf, size_t bytes, d
   int rc = SPEC_OK;
   double best_gbs = 0.0, best_tf = 0.0;
   for (int rep = 0; rep < 3 && rc == SPEC_OK; ++rep) {
-    hipEventRecord(e0, st);
+    (void)hipEventRecord(e0, st);
     hipLaunchKernelGGL(k_peak_stream, dim3(n_cu), dim3(512), 0, st, (const u32x4_v *)d_buf, pieces_per_wg);
-    hipEventRecord(e1, st);
+    (void)hipEventRecord(e1, st);
     if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { rc = SPEC_ERR_HIP; break; }
     if (rep > 0) best_gbs = std::max(best_gbs, (double)n_cu * pieces_per_wg * 1024.0 / (ms * 1e-3) / 1e9);
     const int iters = 20000, wgs = n_cu * 2;
-    hipEventRecord(e0, st);
+    (void)hipEventRecord(e0, st);
     hipLaunchKernelGGL(k_peak_mfma, dim3(wgs), dim3(256), 0, st, iters);
-    hipEventRecord(e1, st);
+    (void)hipEventRecord(e1, st);
     if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { rc = SPEC_ERR_HIP; break; }
     if (rep > 0) best_tf = std::max(best_tf, (double)wgs * 4 * 8.0 * iters * 16384.0 / (ms * 1e-3) / 1e12);
   }
   if (hipGetLastError() != hipSuccess) rc = SPEC_ERR_HIP;
-  hipEventDestroy(e0);
-  hipEventDestroy(e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
   *h_hbm_gbs = best_gbs;
   *h_mfma_tflops = best_tf;
   return rc;

@@ -26,7 +26,7 @@ __global__ __launch_bounds__(256) void k_assemble_embed(int kind, int q, int j, 
                                  const int32_t *__restrict__ seq_s, const int32_t *__restrict__ P_b,
                                  const T *__restrict__ tok_emb, const T *__restrict__ pos_emb,
                                  int32_t *__restrict__ row_tok, int32_t *__restrict__ row_pos, float *__restrict__ h,
-                                 op_t *__restrict__ x) {
+                                 op_t *__restrict__ x, unsigned int *__restrict__ sat) {
   // prefill with several row groups per sequence: group = m / q, sequence = group / seq_groups, and the row's
   // offset from the pass's base position counts the sequence's earlier groups
   const int m = blockIdx.x, grp = m / q;
@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256) void k_assemble_embed(int kind, int q, int j, 
   for (int c = threadIdx.x; c < nv; c += 256) {
     const float4 o = make_float4(value(4 * c), value(4 * c + 1), value(4 * c + 2), value(4 * c + 3));
     *(float4 *)(hr + 4 * c) = o;
-    op_t o4[4] = {to_op(o.x), to_op(o.y), to_op(o.z), to_op(o.w)};
+    op_t o4[4] = {to_op_counted(o.x, sat), to_op_counted(o.y, sat), to_op_counted(o.z, sat), to_op_counted(o.w, sat)};
     *(uint2 *)(x + xpack_index(m, 4 * c, d >> 5)) = *(const uint2 *)o4;
   }
 }
@@ -88,7 +88,7 @@ void launch_assemble_embed(const spec_ctx *c, const Model &m, const PassArgs &pa
                        c->st.n + pa.b0, c->drf.kv_len ? c->drf.kv_len + pa.b0 : nullptr,
                        c->st.t + (size_t)pa.b0 * c->run.s_max, c->seq_s ? c->seq_s + pa.b0 : nullptr, c->st.P_b + pa.b0,
                        (const T *)m.tok_emb, (const T *)m.pos_emb, c->ws.row_tok, c->ws.row_pos, c->ws.h,
-                       (op_t *)c->ws.x));
+                       (op_t *)c->ws.x, c->st.sat));
 }
 
 // -------------------------------------------------------------------------
@@ -108,11 +108,19 @@ __device__ __forceinline__ float block_sum_256(float v, float *sh) {
 // Row held in registers: thread t owns the float4 groups t, t+256, ... (all loads issued
 // before any arithmetic, so the kernel costs one memory round trip, not d/256 of them).
 constexpr int NORM_MAX_V4 = 8;  // d <= 8192
+// four consecutive parameters (index a multiple of 4) with one load
+template <class T>
+__device__ __forceinline__ void load4(const T *__restrict__ p, int i, float (&out)[4]) {
+  struct alignas(sizeof(T) * 4) Quad { T v[4]; };
+  const Quad q = *(const Quad *)(p + i);
+#pragma unroll
+  for (int k = 0; k < 4; ++k) out[k] = Conv<T>::ld(q.v, k);
+}
 template <class T>
 __global__ __launch_bounds__(256) void k_norm(int kind, int d, float eps, const float *__restrict__ h,
                                               const T *__restrict__ gain, const T *__restrict__ bias,
                                               int last_of_q, void *__restrict__ x,
-                                              int pack_kt) {
+                                              int pack_kt, unsigned int *__restrict__ sat) {
   __shared__ float sh[4];
   const int r = blockIdx.x;
   // last_of_q > 0: output row r is the last of input rows r * q .. r * q + q - 1 (the rows that need a token)
@@ -123,6 +131,18 @@ __global__ __launch_bounds__(256) void k_norm(int kind, int d, float eps, const 
   for (int i = 0; i < NORM_MAX_V4; ++i) {
     const int c = threadIdx.x + i * 256;
     v[i] = c < nv ? hr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  // gains and biases are requested now, beside the row, so that their latency passes behind the reductions
+  float gn[NORM_MAX_V4][4], bs[NORM_MAX_V4][4];
+#pragma unroll
+  for (int i = 0; i < NORM_MAX_V4; ++i) {
+    const int c = threadIdx.x + i * 256;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { gn[i][k] = 0.f; bs[i][k] = 0.f; }
+    if (c < nv) {
+      load4(gain, 4 * c, gn[i]);
+      if (kind != SPEC_NORM_RMS) load4(bias, 4 * c, bs[i]);
+    }
   }
   float mean = 0.f, inv;
   if (kind == SPEC_NORM_RMS) {
@@ -155,13 +175,20 @@ __global__ __launch_bounds__(256) void k_norm(int kind, int d, float eps, const 
     const int c = threadIdx.x + i * 256;
     if (c < nv) {
       const float e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+      float o[4];
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
-        float o = (e[k] - mean) * inv * Conv<T>::ld(gain, 4 * c + k);
-        if (kind != SPEC_NORM_RMS) o += Conv<T>::ld(bias, 4 * c + k);
-        // pack_kt > 0: the consumer is a matrix-core GEMM: fp16 operands, rows stored in fragment order
-        if (pack_kt > 0) ((op_t *)x)[xpack_index(r, 4 * c + k, pack_kt)] = to_op(o);
-        else Conv<T>::st((T *)x, (size_t)r * d + 4 * c + k, o);
+        o[k] = (e[k] - mean) * inv * gn[i][k];
+        if (kind != SPEC_NORM_RMS) o[k] += bs[i][k];
+      }
+      if (pack_kt > 0) {
+        // the consumer is a matrix-core GEMM: fp16 operands, rows stored in fragment order, where four consecutive
+        // elements of a row are eight contiguous bytes
+        op_t o4[4] = {to_op_counted(o[0], sat), to_op_counted(o[1], sat), to_op_counted(o[2], sat), to_op_counted(o[3], sat)};
+        *(uint2 *)((op_t *)x + xpack_index(r, 4 * c, pack_kt)) = *(const uint2 *)o4;
+      } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) Conv<T>::st((T *)x, (size_t)r * d + 4 * c + k, o[k]);
       }
     }
   }
@@ -173,7 +200,7 @@ void launch_norm(const spec_ctx *c, const Model &m, const float *h, const void *
   const int pack_kt = m.fast ? m.desc.d_model / 32 : 0;
   SPEC_DISPATCH_DTYPE(c->run.dtype, T,
     hipLaunchKernelGGL(k_norm<T>, dim3(M), dim3(256), 0, st, m.desc.norm_kind, m.desc.d_model, m.desc.norm_eps, h,
-                       (const T *)gain, (const T *)bias, last_of_q, x, pack_kt));
+                       (const T *)gain, (const T *)bias, last_of_q, x, pack_kt, c->st.sat));
 }
 
 // -------------------------------------------------------------------------

@@ -28,6 +28,7 @@ struct GemmArgs {
   float out_scale;    // 1 / (power of two the packed weights were multiplied by)
   int M, N, NT, KT, KS, K_pad;
   int passes, groups;  // filled by the launcher
+  unsigned int *sat;   // counts activations clamped to the fp16 range on their way to a GEMM operand (or null)
   int n_cu;            // compute units of the device (0: 256)
   int tune;            // launch-shape overrides of spec_set_gemm_tuning (0: none); never change a result
   // epilogue targets (those the chosen epilogue uses)
@@ -54,6 +55,10 @@ struct GemmArgs {
   float *part_val;           // EPI_LOGITS: [M][NT]
   int32_t *part_idx;
 };
+
+// The kernels take GemmArgs by value: it is the explicit part of their kernel-argument segment (the code objects
+// declare that size plus 256 bytes of hidden arguments).
+static_assert(sizeof(GemmArgs) % 8 == 0 && sizeof(GemmArgs) <= 256 && alignof(GemmArgs) == 8, "kernel argument block of the GEMM kernels");
 
 // Packed weights are fp16 = weight * 2^k, k per matrix so that the largest magnitude lands in
 // [2^13, 2^14): every bf16 value within 2^-31 of the largest is then an exact fp16 number (smaller

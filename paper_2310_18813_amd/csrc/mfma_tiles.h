@@ -66,7 +66,7 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int 
       o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
       *p = o;
       if (a.x_out) {  // the next GEMM's activations: the updated row, rounded to fp16
-        op_t o4[4] = {to_op(o.x), to_op(o.y), to_op(o.z), to_op(o.w)};
+        op_t o4[4] = {to_op_counted(o.x, a.sat), to_op_counted(o.y, a.sat), to_op_counted(o.z, a.sat), to_op_counted(o.w, a.sat)};
         *(uint2 *)((op_t *)a.x_out + xpack_index(m, n, a.N >> 5)) = *(const uint2 *)o4;
       }
     }
@@ -109,7 +109,7 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int 
     const int j = n >> 1;  // stored rows n..n+3 = gate_j, up_j, gate_{j+1}, up_{j+1}
     if (live && j < a.f) {
       const float r0 = v[0] / (1.0f + __expf(-v[0])) * v[1], r1 = v[2] / (1.0f + __expf(-v[2])) * v[3];
-      op_t o2[2] = {to_op(r0), to_op(r1)};
+      op_t o2[2] = {to_op_counted(r0, a.sat), to_op_counted(r1, a.sat)};
       const size_t at = xpack_index(m, j, a.f >> 5);
       *(uint32_t *)((op_t *)a.act + at) = *(const uint32_t *)o2;
     }
@@ -117,7 +117,7 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int 
     if (live && n < a.N) {
       op_t o4[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) o4[i] = to_op(v[i] > 0.f ? v[i] : 0.f);
+      for (int i = 0; i < 4; ++i) o4[i] = to_op_counted(v[i] > 0.f ? v[i] : 0.f, a.sat);
       const size_t at = xpack_index(m, n, a.N >> 5);
       *(uint2 *)((op_t *)a.act + at) = *(const uint2 *)o4;
     }

@@ -102,7 +102,7 @@ static Sizes compute_sizes(const spec_model_desc *tgt, const spec_model_desc *dr
   z.L_pad = (run->L_max + KV_LPAD - 1) / KV_LPAD * KV_LPAD;
   const size_t B = run->B_max, L = run->L_max, s = run->s_max, M = z.M_max;
   z.state = al256(B * L * 4) + 6 * al256(B * 4) + al256(B * std::max<size_t>(s, 1) * 4) + al256(B * (s + 1) * 4) +
-            al256((s + 1) * 8) + al256(16);
+            al256((s + 1) * 8) + al256(16) + al256(4);
   size_t d = tgt->d_model, f = tgt->d_ffn, V = tgt->vocab;
   size_t kf = tgt->ffn_kind == SPEC_FFN_SWIGLU ? 2 : 1;
   size_t wide = std::max(3 * d, kf * f);
@@ -254,6 +254,7 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
   S.a = (int32_t *)carve(p, B * (s + 1) * 4);
   S.hist = (unsigned long long *)carve(p, (s + 1) * 8);
   S.counters = (unsigned long long *)carve(p, 16);
+  S.sat = (unsigned int *)carve(p, 4);
   size_t d = tgt->d_model, f = tgt->d_ffn, V = tgt->vocab;
   size_t wide = std::max(3 * d, (tgt->ffn_kind == SPEC_FFN_SWIGLU ? 2 : 1) * f);
   if (drf) {
@@ -320,6 +321,15 @@ extern "C" int spec_set_draft_logits(spec_ctx *c, float *d_logits) {
   if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_set_draft_logits: ctx is null");
   if (!c->drf.present) return fail(c, SPEC_ERR_STATE, "spec_set_draft_logits: no draft model");
   c->draft_logits = d_logits;
+  return SPEC_OK;
+}
+
+extern "C" int spec_read_saturation(spec_ctx *c, int64_t *h_count) {
+  if (!c || !h_count) return fail(c, SPEC_ERR_INVALID_ARG, "spec_read_saturation: null argument");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  unsigned int n = 0;
+  HIPCHK(c, hipMemcpy(&n, c->st.sat, sizeof n, hipMemcpyDeviceToHost));
+  *h_count = (int64_t)n;
   return SPEC_OK;
 }
 

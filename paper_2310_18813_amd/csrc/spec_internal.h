@@ -99,6 +99,7 @@ struct State {
   int32_t *draft_arg = nullptr;  // [B_max] where the draft's greedy token goes when the proposals come from outside
   unsigned long long *hist = nullptr;  // [s_max+1]
   unsigned long long *counters = nullptr;  // [0] emitted tokens total, [1] rounds
+  unsigned int *sat = nullptr;             // activations clamped to the fp16 range since spec_init (matrix-core path)
 };
 
 }  // namespace spec

@@ -1,7 +1,7 @@
-"""The paper's runtime model (Sec. 3.2) fitted to what the library measures on this GPU.
+"""The paper's runtime model (Sec. 3.3) fitted to what the library measures on this GPU.
 
     t(s) = N * (t_L(b, s) + s * t_S(b, 1)) / (l(s) + 1)                      (Eq. 1-3, 7)
-    t_L(b, s) ~ alpha_b * s + beta                                           (Sec. 3.2.1, the linear approximation)
+    t_L(b, s) ~ alpha_b * s + beta                                           (Sec. 3.3.1, the linear approximation)
     l(s)      ~ c * s**gamma                                                 (Eq. 5)
 
 Inputs are plain numbers: per-pass latencies from `spec_profile_and_choose_s` / `bench.py`'s verify grid, draft
@@ -15,7 +15,7 @@ import math
 
 def fit_line(xs, ys):
     """Least-squares (slope, intercept) of y ~ slope * x + intercept: the paper's t_L(b, s) ~ alpha_b * s + beta
-    for one batch size (Sec. 3.2.1)."""
+    for one batch size (Sec. 3.3.1)."""
     n = len(xs)
     if n < 2 or n != len(ys):
         raise ValueError("need at least two (x, y) pairs")

@@ -43,3 +43,26 @@ def truth_table(ref, P, L_max):
 def top2_margin(logits):
     s = np.sort(np.asarray(logits, dtype=np.float64), axis=-1)
     return s[..., -1] - s[..., -2]
+
+
+def assert_greedy_matches_oracle(ot, prompt, tokens, dtype):
+    """The GPU's plain greedy continuation of one prompt against the oracle: identical token for token in fp32; in the
+    16-bit types identical up to the first position where the oracle's own top-2 margin is within twice the logit
+    tolerance (from there on the two may legitimately follow different continuations).  The oracle is teacher-forced
+    with the GPU's tokens, so every compared position has the same prefix on both sides.  Returns how many tokens
+    were compared."""
+    tokens = [int(t) for t in tokens]
+    if dtype == "fp32":
+        assert tokens == [int(t) for t in ot.greedy(prompt, len(tokens))]
+        return len(tokens)
+    tol = LOGIT_TOL[dtype]
+    P = len(prompt)
+    seq = [int(t) for t in prompt] + tokens[:-1]
+    lg = ot.forward(ot.cache(len(seq) + 1), seq, 0)[P - 1:]
+    n = 0
+    for i, t in enumerate(tokens):
+        if top2_margin(lg[i]) <= 2 * tol:
+            break
+        assert t == int(lg[i].argmax()), (i, t, int(lg[i].argmax()))
+        n += 1
+    return n

@@ -311,3 +311,19 @@ def test_attention_launch_shapes_give_identical_bits(orc, B, L_max, kv):
     assert all(torch.equal(got[0], g) for g in got[1:])
     with pytest.raises(B.SpecError):
         ctx.spec_set_attention_shape(4)
+
+
+def test_saturation_counter_reports_activations_beyond_fp16(orc, B):
+    """16-bit runs feed fp16 GEMM operands; values beyond +-65504 are clamped and counted.  The workloads never get
+    there (count 0); an embedding table scaled into the hundreds of thousands does."""
+    c = CASES["small_bf16"]
+    for emb_std, expect_clamped in ((0.02, False), (2.0e5, True)):
+        w = si.make_weights(c["tgt"], c["dtype"], c["seed"], device=DEV, emb_std=emb_std, tag="tgt.")
+        L_max = c["P"] + 4 + 3
+        ctx = B.Context(c["tgt"], w, None, None, c["dtype"], c["B"], 2, L_max, 4, B.PROPOSALS_EXTERNAL, DEV)
+        assert ctx.spec_read_saturation() == 0
+        ctx.spec_reset(si.make_prompts(c["B"], c["P"], c["tgt"]["vocab"], c["seed"]))
+        ctx.spec_round(0, 2)
+        n = ctx.spec_read_saturation()
+        assert (n > 0) == expect_clamped, (emb_std, n)
+        ctx.close()

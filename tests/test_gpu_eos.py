@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 import synth_inputs as si
-from helpers import build_pair
+from helpers import build_pair, assert_greedy_matches_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -57,9 +57,8 @@ def test_sequences_stop_at_the_end_token(orc, B, name, mode):
     ctx.spec_round(0, N)
     toks, _ = ctx.spec_read_output()
     ref = [np.array(t) for t in toks]
-    if name == "tiny_fp32":
-        for b in range(nB):
-            assert np.array_equal(ref[b], ot.greedy(prompts[b], N))
+    for b in range(nB):  # the reference itself against the oracle (exact in fp32, margin rule in 16 bits)
+        assert_greedy_matches_oracle(ot, prompts[b], ref[b], c["dtype"])
     if mode == "table":
         truth = np.zeros((nB, L_max), dtype=np.int32)
         for b in range(nB):

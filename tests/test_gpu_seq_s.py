@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 import synth_inputs as si
-from helpers import build_pair
+from helpers import build_pair, assert_greedy_matches_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -52,9 +52,8 @@ def test_capped_rounds_follow_the_acceptance_rule(orc, B, name):
     prompts = si.make_prompts(nB, P, c["tgt"]["vocab"], c["seed"])
     ctx.spec_set_proposal_table(np.zeros((nB, L_max), dtype=np.int32))
     ref = greedy_reference(ctx, prompts, N)
-    if name == "tiny_fp32":
-        for b in range(nB):
-            assert np.array_equal(ref[b], ot.greedy(prompts[b], N))
+    for b in range(nB):  # the reference itself against the oracle (exact in fp32, margin rule in 16 bits)
+        assert_greedy_matches_oracle(ot, prompts[b], ref[b], c["dtype"])
     truth = np.zeros((nB, L_max), dtype=np.int32)
     for b in range(nB):
         truth[b, P:P + N] = ref[b]

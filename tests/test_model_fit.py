@@ -1,4 +1,4 @@
-"""Host-side runtime model of Sec. 3.2 (paper_2310_18813_amd/model_fit.py) against the oracle's plain
+"""Host-side runtime model of Sec. 3.3 (paper_2310_18813_amd/model_fit.py) against the oracle's plain
 definitions, closed forms and brute force.  No GPU."""
 import math
 
@@ -39,7 +39,7 @@ def test_delta_is_the_numerator_of_the_derivative():
 
 
 def test_s_opt_falls_as_the_slope_grows():
-    """The monotonicity argument that closes Sec. 3.2: larger alpha_b (larger batch) -> smaller s_opt."""
+    """The monotonicity argument that closes Sec. 3.3: larger alpha_b (larger batch) -> smaller s_opt."""
     prev = float("inf")
     for alpha_b in (0.005, 0.01, 0.05, 0.1, 0.5, 1.0, 5.0):
         s = mf.s_opt_continuous(alpha_b, 1.0, 0.9, 0.548)
