@@ -31,6 +31,7 @@ def main():
     ap.add_argument("--shape", default="7b", choices=["7b", "13b", "33b"], help="layer width: 7b d=4096 (bf16), 13b OPT d=5120 (fp16), 33b d=6656 (bf16)")
     ap.add_argument("--tune", default="0,0,0", help="spec_set_gemm_tuning arguments: tile_mtw,tile_nbw,flags")
     ap.add_argument("--attn-shape", type=int, default=0)
+    ap.add_argument("--samples", type=int, default=0, help="also time this many single passes, one by one: median, p10, p90")
     args = ap.parse_args()
 
     import numpy as np
@@ -45,7 +46,7 @@ def main():
     elif args.shape == "33b":
         dtype, seed, desc = "bf16", 1004, si.llama_desc(1, 6656, 52, 17920, 32000, 4096)
     B_max, s_max = max(c[0] for c in cells), max(c[1] for c in cells)
-    L_max = args.kv + 1 + (args.iters + 4) * (s_max + 1) + s_max
+    L_max = args.kv + 1 + (max(args.iters, args.samples) + 4) * (s_max + 1) + s_max
     desc = dict(desc, n_layers=args.layers, max_pos=L_max)
     w = si.make_weights(desc, dtype, seed, device="cuda:0", emb_std=1.0, tag="tgt.")
     ctx = B.Context(desc, w, None, None, dtype, B_max, s_max, L_max, L_max - args.kv - 1 - s_max,
@@ -71,6 +72,22 @@ def main():
         e1.record()
         e1.synchronize()
         us = e0.elapsed_time(e1) * 1000.0 / args.iters
+        spread = None
+        if args.samples > 0:
+            # one event pair per pass (each pair adds its own few microseconds): the run-to-run spread of a pass
+            ctx.spec_reset_noprefill(prompts[:nB])
+            ctx.spec_round(s, 2)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.samples + 1)]
+            ev[0].record()
+            for i in range(args.samples):
+                ctx.spec_round(s, 1)
+                ev[i + 1].record()
+            ev[-1].synchronize()
+            t = np.sort(np.array([ev[i].elapsed_time(ev[i + 1]) * 1000.0 for i in range(args.samples)]))
+            spread = {"samples": args.samples, "median_us": round(float(np.median(t)), 1),
+                      "p10_us": round(float(np.percentile(t, 10)), 1), "p90_us": round(float(np.percentile(t, 90)), 1)}
+            ctx.spec_reset_noprefill(prompts[:nB])
+            ctx.spec_round(s, 2 + args.iters)
         ctx.spec_kernel_timing(True)
         ctx.spec_read_kernel_timing()
         ctx.spec_round(s, 2)
@@ -84,6 +101,8 @@ def main():
                     "hbm_frac": round(nbytes / HBM_PEAK / (us * 1e-6), 3),
                     "mfma_frac": round(flops / MFMA_PEAK / (us * 1e-6), 3),
                     "kernels_us": {k: round(v[1] * 1000 / v[0], 1) for k, v in kt.items() if v[0]}})
+        if spread:
+            out[-1]["pass_spread"] = spread
         print(json.dumps(out[-1]), flush=True)
 
 
