@@ -355,3 +355,59 @@ def test_opt13b_sampled_layers_and_draft_match_oracle_at_full_depth():
     print("13B OPT shape: worst per-layer error %.4g at (layer, sequence) %s; 12-layer draft end to end %.4g (tol %g)"
           % (worst, where, worst_d, tol))
     ctx.close()
+
+
+def test_llama33b_sampled_layers_match_oracle_at_full_depth():
+    """The 33B shape at its full depth (60 layers, d=6656, 52 heads of 128, SwiGLU 17920, bf16; 65 GB of weights):
+    every third layer one by one and the LM head, as for the 7B shape, and the same two sequences inside the launch
+    configuration of the benchmark's cell for this shape (32 sequences) bit for bit.  Short prompts: the long-cache
+    attention of this shape is compared with the oracle at full width in
+    test_sampled_rows_match_oracle_at_full_width[llama33b_bf16]."""
+    from oracle import oracle as om
+    from paper_2310_18813_amd import binding as B
+    orc = om.Oracle("f64")
+    dtype, seed, tdesc, _ = si.CONFIGS["llama33b_bf16"]
+    P, s, nB, B_big = 40, 3, 2, 32
+    L_max = P + 8 + s
+    tdesc = dict(tdesc, max_pos=L_max)
+    d, V, nl = tdesc["d_model"], tdesc["vocab"], tdesc["n_layers"]
+    print("33B shape: weights ...", flush=True)
+    w = si.make_weights(tdesc, dtype, seed, device=DEV, tag="tgt.")
+    ctx = B.Context(tdesc, w, None, None, dtype, B_big, s, L_max, 8, B.PROPOSALS_EXTERNAL, DEV)
+    prompts_big = si.make_prompts(B_big, P, V, seed)
+    props_big = si.make_prompts(B_big, s, V, seed + 9)
+    prompts, props = prompts_big[:nB], props_big[:nB]
+    ctx.spec_reset(prompts)
+    ctx.spec_set_proposals(torch.tensor(props))
+    dump = ctx.spec_set_hidden_dump(True)
+    lg = ctx.spec_verify_step(s, want_logits=True).cpu().numpy()
+    ctx.spec_set_hidden_dump(False)
+    q, M = s + 1, nB * (s + 1)
+    hidden = dump[:(nl + 1) * M * d].view(nl + 1, M, d).cpu().numpy().astype(np.float64)
+    tol = LOGIT_TOL["bf16"]
+    print("33B shape: layers ...", flush=True)
+    layers = tuple(sorted(set(range(0, nl, 3)) | {1, nl - 1}))
+    worst, where = layer_by_layer(orc, B, ctx, tdesc, w, hidden, layers, range(nB), q, P - 1, L_max, nB, tol)
+    f32 = lambda t: None if t is None else t.float().cpu().numpy()
+    head_err = 0.0
+    for b in range(nB):
+        desc0 = dict(tdesc, n_layers=0)
+        emb = np.zeros((V, d), dtype=np.float32)
+        emb[:q] = hidden[nl][b * q:(b + 1) * q]
+        w0 = {"tok_emb": emb, "pos_emb": None, "final_norm_w": f32(w["final_norm_w"]), "final_norm_b": None,
+              "lm_head": f32(w["lm_head"]), "layers": []}
+        m0 = orc.model(desc0, w0, 0)
+        ref = m0.forward(m0.cache(L_max), list(range(q)), P - 1)
+        head_err = max(head_err, np.abs(lg[b] - ref).max())
+        # greedy tokens of the rows from the GPU's own last hidden state, where the oracle's margin allows
+        for i in range(q):
+            if top2_margin(ref[i]) > 2 * tol:
+                assert int(lg[b, i].argmax()) == int(ref[i].argmax())
+    assert head_err <= tol, ("head", head_err)
+    print("33B shape, %d of %d layers x %d sequences: worst per-layer error %.4g at (layer, sequence) %s, head %.4g (tol %g)"
+          % (len(layers), nl, nB, worst, where, head_err, tol))
+    ctx.spec_reset(prompts_big)
+    ctx.spec_set_proposals(torch.tensor(props_big))
+    lg_big = ctx.spec_verify_step(s, want_logits=True)
+    assert torch.equal(lg_big[:nB].cpu(), torch.from_numpy(lg)), "rows depend on the batch they run in"
+    ctx.close()
