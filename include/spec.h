@@ -299,6 +299,43 @@ int spec_greedy_accept(void *hip_stream, const float *d_logits, const int32_t *d
 int spec_greedy_accept_noalloc(void *hip_stream, const float *d_logits, const int32_t *d_proposals, int32_t B,
                                int32_t s, int32_t vocab, int32_t *d_accepted, int32_t *d_emitted);
 
+/* Speculative sampling: the non-greedy form of the acceptance step.  Sec. 2 describes speculative decoding and
+   cites this rule for sampling from the models instead of taking their most likely token; Alg. 1 is the greedy
+   case.  With q_j = softmax(draft logits of step j / T) and p_j = softmax(target logits of row j / T):
+   proposal t_j is kept if u * q_j[t_j] < p_j[t_j]; at the first j that fails one token drawn from
+   max(0, p_j - q_j), normalised, is emitted and the round ends; if all s are kept, one token drawn from p_{s+1}
+   follows.  The emitted tokens are distributed as if the target alone had been sampled.  Proposals that were not
+   drawn from a distribution count as point masses (q_j[t_j] = 1).  A draw from weights w with a uniform number u
+   takes the smallest index whose cumulative weight exceeds u * sum(w).  Arithmetic: fp32.
+
+   Every random number is the caller's: uniform numbers in [0, 1), three per decided token --
+   [.][0] draws a proposal, [.][1] decides whether it is kept, [.][2] draws the token emitted at that place.
+
+   spec_sample_tokens: one draw per row.  d_logits [rows][vocab] fp32, d_uniforms [rows], d_tokens [rows] out.
+   spec_sample_accept: the rule for B sequences on logits the caller has.
+     d_target_logits [B][s+1][vocab]; d_draft_logits [s][B][vocab] (step-major), or NULL for point-mass proposals;
+     d_proposals [B][s] (may be NULL when s = 0); d_uniforms [B][s+1][3], row j for the token at place j of the round
+     ([.][j][0] is not read); out: d_chosen [B][s+1] (the token chosen at each place up to the one that ended the
+     round, -1 behind it), d_accepted [B] = l_b, d_emitted [B][s+1] = the l_b kept proposals, the drawn token, -1.
+   Both enqueue on hip_stream (NULL = the default stream), need no context and no workspace, and do not wait.
+   temperature > 0, s <= 15 (SPEC_ERR_INVALID_ARG, SPEC_ERR_CAPACITY).  All device pointers, all the caller's.
+
+   spec_set_sampling: the same rule inside a context, for every following round (spec_draft_step draws t_j, the
+   verify step applies the rule; commit, roll-back, end token, budgets and per-sequence s work as in the greedy
+   case).  d_uniforms [B_max][L_max][3] is indexed by sequence slot and by the absolute position of the token a
+   number decides, so a token's random numbers do not depend on how the rounds fall.  The library needs the logits
+   of a round in memory: d_target_logits [B_max * (s_max + 1)][vocab] and, with SPEC_PROPOSALS_DRAFT,
+   d_draft_logits [s_max][B_max][vocab], both fp32 device buffers of the caller's, written every round (their
+   contents after a round are that round's logits: tests read them).  External proposals are point masses.
+   d_uniforms = NULL switches back to the greedy rule.  Only between rounds (SPEC_ERR_STATE).                    */
+int spec_sample_tokens(void *hip_stream, const float *d_logits, int32_t rows, int32_t vocab, float temperature,
+                       const float *d_uniforms, int32_t *d_tokens);
+int spec_sample_accept(void *hip_stream, const float *d_target_logits, const float *d_draft_logits,
+                       const int32_t *d_proposals, const float *d_uniforms, int32_t B, int32_t s, int32_t vocab,
+                       float temperature, int32_t *d_chosen, int32_t *d_accepted, int32_t *d_emitted);
+int spec_set_sampling(spec_ctx *ctx, float temperature, const float *d_uniforms, float *d_target_logits,
+                      float *d_draft_logits);
+
 /* Parity aids for the draft step (the call speculate(S, kv_SSM, s) of Alg. 1).
    spec_set_draft_logits: if d_logits is not NULL, every following spec_draft_step also writes the draft
    model's logits behind t_j -- the logits of the last token each sequence fed in -- as fp32 [B][vocab]

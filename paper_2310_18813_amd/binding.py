@@ -31,7 +31,8 @@ EXPORTS = ["spec_last_error", "spec_workspace_bytes", "spec_init", "spec_destroy
            "spec_read_state", "spec_kv_import", "spec_kv_export", "spec_kernel_timing",
            "spec_read_kernel_timing", "spec_set_hidden_dump", "spec_set_attention_shape", "spec_measure_peaks",
            "spec_set_draft_logits", "spec_read_proposals", "spec_greedy_accept_workspace_bytes", "spec_greedy_accept",
-           "spec_greedy_accept_noalloc", "spec_set_gemm_tuning", "spec_read_saturation"]
+           "spec_greedy_accept_noalloc", "spec_set_gemm_tuning", "spec_read_saturation", "spec_sample_tokens",
+           "spec_sample_accept", "spec_set_sampling"]
 KCLASS_NAMES = ["gemm_qkv", "gemm_o", "gemm_ffn_in", "gemm_ffn_out", "gemm_head", "attention", "norm", "other",
                 "draft_pass"]
 
@@ -86,6 +87,9 @@ lib.spec_read_saturation.argtypes = [_vp, _i64p]
 lib.spec_greedy_accept_workspace_bytes.argtypes = [_i32, _i32, _i32, C.POINTER(C.c_size_t)]
 lib.spec_greedy_accept.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _vp, C.c_size_t, _vp, _vp]
 lib.spec_greedy_accept_noalloc.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp]
+lib.spec_sample_tokens.argtypes = [_vp, _vp, _i32, _i32, C.c_float, _vp, _vp]
+lib.spec_sample_accept.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, C.c_float, _vp, _vp, _vp]
+lib.spec_set_sampling.argtypes = [_vp, C.c_float, _vp, _vp, _vp]
 lib.spec_set_attention_shape.argtypes = [_vp, _i32]
 lib.spec_set_gemm_tuning.argtypes = [_vp, _i32, _i32, _i32]
 lib.spec_kernel_timing.argtypes = [_vp, _i32]
@@ -170,6 +174,42 @@ def spec_greedy_accept(logits, proposals, accepted=None, emitted=None, workspace
         _check(lib.spec_greedy_accept(st, _dp(logits), _dp(proposals) if s else None, nB, s, V, _dp(workspace),
                                       workspace.numel(), _dp(accepted), _dp(emitted)))
     return accepted, emitted
+
+
+def spec_sample_tokens(logits, uniforms, temperature):
+    """logits [rows][V] fp32, uniforms [rows] fp32, device tensors -> tokens [rows] int32."""
+    assert logits.dim() == 2 and logits.dtype == torch.float32 and logits.is_contiguous()
+    assert uniforms.dtype == torch.float32 and uniforms.shape == (logits.shape[0],) and uniforms.is_contiguous()
+    dev = logits.device
+    out = torch.empty(logits.shape[0], dtype=torch.int32, device=dev)
+    with torch.cuda.device(dev):
+        st = C.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+        _check(lib.spec_sample_tokens(st, _dp(logits), logits.shape[0], logits.shape[1], float(temperature), _dp(uniforms),
+                                      _dp(out)))
+    return out
+
+
+def spec_sample_accept(target_logits, draft_logits, proposals, uniforms, temperature):
+    """target_logits [B][s+1][V], draft_logits [s][B][V] or None, proposals [B][s] int32 (None when s = 0),
+    uniforms [B][s+1][3]: device tensors -> (chosen [B][s+1], accepted [B], emitted [B][s+1]) int32."""
+    assert target_logits.dim() == 3 and target_logits.dtype == torch.float32 and target_logits.is_contiguous()
+    nB, q, V = target_logits.shape
+    s = q - 1
+    if draft_logits is not None:
+        assert draft_logits.dtype == torch.float32 and draft_logits.shape == (s, nB, V) and draft_logits.is_contiguous()
+    if s:
+        assert proposals.dtype == torch.int32 and proposals.shape == (nB, s) and proposals.is_contiguous()
+    assert uniforms.dtype == torch.float32 and uniforms.shape == (nB, q, 3) and uniforms.is_contiguous()
+    dev = target_logits.device
+    chosen = torch.empty((nB, q), dtype=torch.int32, device=dev)
+    accepted = torch.empty(nB, dtype=torch.int32, device=dev)
+    emitted = torch.empty((nB, q), dtype=torch.int32, device=dev)
+    with torch.cuda.device(dev):
+        st = C.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+        _check(lib.spec_sample_accept(st, _dp(target_logits), _dp(draft_logits) if draft_logits is not None and s else None,
+                                      _dp(proposals) if s else None, _dp(uniforms), nB, s, V, float(temperature),
+                                      _dp(chosen), _dp(accepted), _dp(emitted)))
+    return chosen, accepted, emitted
 
 
 def spec_workspace_bytes(tgt_desc, drf_desc, run):
@@ -358,6 +398,24 @@ class Context:
         self._draft_logits = torch.zeros((self.B_max, self.drf_desc["vocab"]), dtype=torch.float32, device=self.device)
         _check(lib.spec_set_draft_logits(self.h, _dp(self._draft_logits)), self.h)
         return self._draft_logits
+
+    def spec_set_sampling(self, temperature, uniforms):
+        """uniforms: [B_max][L_max][3] fp32 device tensor (None: back to the greedy rule).  Allocates the logits
+        buffers the library needs and returns them: (target [B_max*(s_max+1)][V], draft [s_max][B_max][V] or None)."""
+        if uniforms is None:
+            _check(lib.spec_set_sampling(self.h, 0.0, None, None, None), self.h)
+            self._smp = None
+            return None, None
+        assert uniforms.dtype == torch.float32 and uniforms.shape == (self.B_max, self.L_max, 3) and uniforms.is_contiguous()
+        V = self.tgt_desc["vocab"]
+        tl = torch.zeros((self.B_max * (self.s_max + 1), V), dtype=torch.float32, device=self.device)
+        dl = None
+        if self.drf_desc is not None:
+            dl = torch.zeros((max(1, self.s_max), self.B_max, V), dtype=torch.float32, device=self.device)
+        _check(lib.spec_set_sampling(self.h, float(temperature), _dp(uniforms), _dp(tl), _dp(dl) if dl is not None else None),
+               self.h)
+        self._smp = (uniforms, tl, dl)
+        return tl, dl
 
     def spec_read_saturation(self):
         n = C.c_int64(-1)

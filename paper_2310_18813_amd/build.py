@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libspecdec.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["spec_api.hip", "kernels_state.hip", "kernels_generic.hip", "kernels_gemm_mfma.hip", "kernels_greedy_accept.hip",
+SOURCES = ["spec_api.hip", "kernels_state.hip", "kernels_generic.hip", "kernels_gemm_mfma.hip", "kernels_greedy_accept.hip", "kernels_sampling.hip",
            "kernels_gemm_tile.hip", "kernels_gemm_rowres.hip", "kernels_peaks.hip", "kernels_attn_mfma.hip", "fast_path.hip"]
 
 # packed-fp32 VALU forms are kept out of the generated code (they have produced wrong

@@ -317,6 +317,23 @@ extern "C" int spec_set_hidden_dump(spec_ctx *c, float *d_hidden) {
   return SPEC_OK;
 }
 
+extern "C" int spec_set_sampling(spec_ctx *c, float temperature, const float *d_uniforms, float *d_target_logits,
+                                 float *d_draft_logits) {
+  if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_set_sampling: ctx is null");
+  if (c->draft_j != 0 || c->verified_s >= 0) return fail(c, SPEC_ERR_STATE, "spec_set_sampling: a round is in progress");
+  if (!d_uniforms) {  // back to the greedy rule
+    c->smp_u = nullptr; c->smp_tl = c->smp_dl = nullptr; c->smp_T = 0.f;
+    return SPEC_OK;
+  }
+  if (!(temperature > 0.f)) return fail(c, SPEC_ERR_INVALID_ARG, "spec_set_sampling: temperature must be positive");
+  if (!d_target_logits) return fail(c, SPEC_ERR_INVALID_ARG, "spec_set_sampling: a buffer for the target's logits is needed");
+  if (c->run.proposal_mode == SPEC_PROPOSALS_DRAFT && !d_draft_logits)
+    return fail(c, SPEC_ERR_INVALID_ARG, "spec_set_sampling: proposals drawn by the draft model need a buffer for its logits");
+  c->smp_T = temperature; c->smp_u = d_uniforms; c->smp_tl = d_target_logits;
+  c->smp_dl = c->run.proposal_mode == SPEC_PROPOSALS_DRAFT ? d_draft_logits : nullptr;
+  return SPEC_OK;
+}
+
 extern "C" int spec_set_draft_logits(spec_ctx *c, float *d_logits) {
   if (!c) return fail(nullptr, SPEC_ERR_INVALID_ARG, "spec_set_draft_logits: ctx is null");
   if (!c->drf.present) return fail(c, SPEC_ERR_STATE, "spec_set_draft_logits: no draft model");
@@ -617,6 +634,13 @@ extern "C" int spec_draft_step(spec_ctx *c, int32_t j) {
   int32_t *arg_out = ext ? c->st.draft_arg : c->st.t + (j - 1);
   const int arg_stride = ext ? 1 : c->run.s_max;
   float *lg = c->draft_logits;
+  // sampling: the step's logits are kept for the verification, and t_j is drawn from them instead of their arg-max
+  const bool draw = c->smp_u && !ext;
+  if (draw) {
+    lg = c->smp_dl + (size_t)(j - 1) * c->run.B_max * c->drf.desc.vocab;
+    arg_out = c->st.draft_arg;
+  }
+  const int arg_stride_used = draw ? 1 : arg_stride;
   if (j == 1) {
     if (ext && c->prop_table && !c->proposals_ready) {
       // later draft steps ingest t_1.. : fetch them now (all s_max; verify uses the first s)
@@ -636,13 +660,18 @@ extern "C" int spec_draft_step(spec_ctx *c, int32_t j) {
     }
     if (!rc) {
       PassArgs pa{PASS_DRAFT_FIRST, c->B, lag, 0, c->P, c->run.s_max, c->run.L_max};
-      rc = forward_pass(c, c->drf, pa, HEAD_LAST, lg, arg_out, arg_stride, c->n_ub - 1);
+      rc = forward_pass(c, c->drf, pa, HEAD_LAST, lg, arg_out, arg_stride_used, c->n_ub - 1);
     }
   } else {
     PassArgs pa{PASS_DRAFT_NEXT, c->B, 1, j, c->P, c->run.s_max, c->run.L_max};
-    rc = forward_pass(c, c->drf, pa, HEAD_LAST, lg, arg_out, arg_stride, c->n_ub + j - 2);
+    rc = forward_pass(c, c->drf, pa, HEAD_LAST, lg, arg_out, arg_stride_used, c->n_ub + j - 2);
   }
   if (rc) return rc;
+  if (draw) {  // t_j decides the token at position n_b + j - 1
+    const int V = c->drf.desc.vocab;
+    launch_sample_rows(lg, c->B, V, c->smp_T, c->smp_u, c->st.n, j - 1, c->run.L_max, c->st.t + (j - 1), c->run.s_max, c->stream);
+    if (c->draft_logits) generic_copy(lg, c->draft_logits, (size_t)c->B * V * sizeof(float), c->stream);
+  }
   c->draft_j = j;
   HIPCHK(c, hipGetLastError());
   return SPEC_OK;
@@ -661,8 +690,15 @@ extern "C" int spec_verify_step(spec_ctx *c, int32_t s, float *d_logits_or_null)
   int rc = ensure_proposals(c, s, "spec_verify_step");
   if (rc) return rc;
   PassArgs pa{PASS_VERIFY, c->B, s + 1, 0, c->P, c->run.s_max, c->run.L_max};
-  rc = forward_pass(c, c->tgt, pa, HEAD_ALL, d_logits_or_null, c->st.a, c->run.s_max + 1, c->n_ub - 1 + s);
+  float *lg = d_logits_or_null ? d_logits_or_null : c->smp_u ? c->smp_tl : nullptr;
+  rc = forward_pass(c, c->tgt, pa, HEAD_ALL, lg, c->st.a, c->run.s_max + 1, c->n_ub - 1 + s);
   if (rc) return rc;
+  if (c->smp_u) {  // the sampling rule in place of the arg-max: row j decides the token at position n_b + j
+    KScope k(c, SPEC_KCLASS_OTHER);
+    launch_sample_verify(lg, c->smp_dl, c->run.B_max, c->B, s, c->tgt.desc.vocab, c->smp_T, c->st.t, c->run.s_max, c->seq_s,
+                         c->smp_u, c->st.n, c->run.L_max, c->st.a, c->run.s_max + 1, c->stream);
+    HIPCHK(c, hipGetLastError());
+  }
   c->verified_s = s;
   return SPEC_OK;
 }

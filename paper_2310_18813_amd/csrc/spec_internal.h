@@ -126,6 +126,12 @@ struct spec_ctx {
   const int32_t *seq_s = nullptr;  // [B] per-sequence cap of the speculation length (caller's device memory), or null
   float *hidden_dump = nullptr;
   float *draft_logits = nullptr;  // parity aid: where every draft step leaves the logits behind its proposals
+  // speculative sampling (off while smp_u is null): temperature, the caller's table of uniform numbers
+  // [B_max][L_max][3], and the caller's buffers for the target's logits [M_max][vocab] and the draft's
+  // [s_max][B_max][vocab] of a round
+  float smp_T = 0.f;
+  const float *smp_u = nullptr;
+  float *smp_tl = nullptr, *smp_dl = nullptr;
   int attn_shape = 0;
   int gemm_tune = 0;      // GemmTune bits (spec_set_gemm_tuning)
   int n_cu = 256;         // compute units of the context's device
@@ -184,6 +190,13 @@ void launch_norm(const spec_ctx *c, const Model &m, const float *h, const void *
                  int M, int last_of_q, hipStream_t st);
 void launch_argmax_rows(const float *logits, int M, int V, int q, int out_stride, int32_t *out, hipStream_t st);
 void launch_accept(spec_ctx *c, int s, hipStream_t st);
+// speculative sampling (kernels_sampling.hip): one draw per row from softmax(logits / T); the verification of a
+// round's proposals, which leaves in a[] the tokens under which the longest-matching-prefix rule gives the outcome
+void launch_sample_rows(const float *logits, int rows, int V, float temperature, const float *u, const int32_t *n, int off,
+                        int u_rows, int32_t *out, int out_stride, hipStream_t st);
+void launch_sample_verify(const float *tl, const float *dl, int d_rows, int B, int s, int V, float temperature,
+                          const int32_t *t, int t_stride, const int32_t *seq_s, const float *u, const int32_t *n, int u_rows,
+                          int32_t *a, int a_stride, hipStream_t st);
 void launch_fill_proposals(spec_ctx *c, int s, hipStream_t st);
 void launch_copy_proposals(spec_ctx *c, const int32_t *d_tok, int s, hipStream_t st);
 void launch_state_reset(spec_ctx *c, const int32_t *d_prompt, int P_stride, bool ragged, hipStream_t st);

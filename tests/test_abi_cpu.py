@@ -117,3 +117,16 @@ def test_greedy_accept_validates_before_any_device_call(B):
     assert B.lib.spec_greedy_accept(None, fake, fake, 1, 1, 10, fake, 4, fake, fake) == B.ERR_WORKSPACE
     assert B.lib.spec_greedy_accept_noalloc(None, fake, fake, 65535, 15, 32000, fake, fake) == B.ERR_CAPACITY
     assert b"built-in scratch" in B.lib.spec_last_error(None)
+
+
+def test_sampling_entry_points_validate_before_any_device_call(B):
+    fake = C.c_void_p(4096)                   # never dereferenced: validation fails first
+    assert B.lib.spec_sample_tokens(None, fake, 4, 100, 0.0, fake, fake) == B.ERR_INVALID_ARG       # temperature
+    assert B.lib.spec_sample_tokens(None, fake, -1, 100, 1.0, fake, fake) == B.ERR_INVALID_ARG
+    assert B.lib.spec_sample_tokens(None, None, 4, 100, 1.0, fake, fake) == B.ERR_INVALID_ARG
+    assert B.lib.spec_sample_tokens(None, fake, 0, 100, 1.0, fake, fake) == B.OK                    # nothing to do
+    assert B.lib.spec_sample_accept(None, fake, fake, fake, fake, 2, 16, 100, 1.0, fake, fake, fake) == B.ERR_CAPACITY
+    assert B.lib.spec_sample_accept(None, fake, None, None, fake, 2, 3, 100, 1.0, fake, fake, fake) == B.ERR_INVALID_ARG
+    assert B.lib.spec_sample_accept(None, fake, None, fake, fake, 2, 3, 100, -2.0, fake, fake, fake) == B.ERR_INVALID_ARG
+    assert B.lib.spec_sample_accept(None, fake, None, fake, fake, 0, 3, 100, 1.0, fake, fake, fake) == B.OK
+    assert B.lib.spec_set_sampling(None, 1.0, fake, fake, fake) == B.ERR_INVALID_ARG                # no context
