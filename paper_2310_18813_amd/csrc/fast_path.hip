@@ -191,14 +191,18 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
     if (!fold) return;
     a.fold_x = 1; a.ss_d = d; a.ss_eps = D.norm_eps; a.rinv_ws = ws.row_inv;
   };
-  // the tiled kernel's larger wave tiles read 1 / rms per row from scratch: a small kernel fills it first
+  // the tiled kernel's larger wave tiles read 1 / rms per row from scratch: a small kernel fills it first, unless
+  // the producer of the rows has left what is needed
   auto row_inv_first = [&](const GemmArgs &a, int epi) {
-    if (!fold || !gemm_wants_row_inv(a, epi)) return;
+    if (!fold || c->x_ssq || !gemm_wants_row_inv(a, epi)) return;
     KScope k(c, tgt ? SPEC_KCLASS_NORM : -1);
     launch_row_inv_x(a, st);
   };
   auto produce_norm = [&](GemmArgs &a) {
-    if (fold) a.x_out = ws.x;
+    if (!fold) return;
+    a.x_out = ws.x;
+    c->x_ssq = gemm_can_leave_ssq(a);  // then the reduction leaves 1 / rms of the new rows where the next GEMM looks for it
+    if (c->x_ssq) { a.rinv_ws = ws.row_inv; a.ssq_ks = gemm_ks_for(a.N >> 5); a.ss_d = a.N; a.ss_eps = D.norm_eps; }
   };
   if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, 0, st); }
   {
@@ -266,7 +270,8 @@ void fast_head(spec_ctx *c, const Model &m, int Mh, int last_of_q, float *logits
   a.part_idx = c->ws.head_part_idx;
   if (fold) {
     a.fold_x = 1; a.ss_d = m.desc.d_model; a.ss_eps = m.desc.norm_eps; a.rinv_ws = c->ws.row_inv;
-    if (gemm_wants_row_inv(a, EPI_LOGITS)) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_row_inv_x(a, st); }
+    // unless the last layer's down projection has left them
+    if (!c->x_ssq && gemm_wants_row_inv(a, EPI_LOGITS)) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_row_inv_x(a, st); }
   }
   { KScope k(c, tgt ? SPEC_KCLASS_GEMM_HEAD : -1); launch_gemm_mfma(c->run.dtype, a, EPI_LOGITS, st); }
   { KScope k(c, tgt ? SPEC_KCLASS_OTHER : -1);

@@ -133,7 +133,7 @@ PackedDims packed_dims(int N, int K) {
   p.K_pad = (K + 31) / 32 * 32;
   p.NT = p.N_pad / 16;
   p.KT = p.K_pad / 32;
-  p.KS = (p.KT % 8 == 0) ? 8 : (p.KT % 4 == 0) ? 4 : (p.KT % 2 == 0) ? 2 : 1;
+  p.KS = gemm_ks_for(p.KT);
   return p;
 }
 
@@ -365,6 +365,9 @@ static bool goes_to_tile_kernel(const GemmArgs &a, int epi) {
   const bool split_ok = a.part && a.KS > 1 && (a.N & 3) == 0 && (a.KT / a.KS >= 32 || a.M > 256);
   const int tile_min_m = a.NT >= 1024 ? 33 : 65;
   return a.NT >= 64 && (epi != EPI_RESIDUAL ? a.M >= tile_min_m : (split_ok && a.M >= 33));
+}
+bool gemm_can_leave_ssq(const GemmArgs &a) {
+  return a.M > 64 && a.x_out && (a.N & 31) == 0 && goes_to_tile_kernel(a, EPI_RESIDUAL);
 }
 bool gemm_wants_row_inv(const GemmArgs &a, int epi) {
   return a.M > 0 && goes_to_tile_kernel(a, epi) && gemm_tile_wants_row_inv(a, epi);

@@ -96,12 +96,6 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   constexpr bool INLOOP = FOLD_EPI && MTW == 1;
   const bool inloop = INLOOP && a.fold_x;
   float ssq_cur = 0.f, ssq_tot = 0.f;
-  float rv[MTW];  // 1 / rms of this lane's rows
-#pragma unroll
-  for (int mt = 0; mt < MTW; ++mt) {
-    const int m = (mtile0 + wm * MTW + mt) * 16 + c;
-    rv[mt] = (FOLD_EPI && !INLOOP && a.fold_x && m < a.M) ? a.rinv_ws[m] : 1.0f;
-  }
 
   u32x4_v r0[LPW], r1[LPW], r2[LPW];  // three steps on their way from global memory
   auto fetch = [&](u32x4_v (&r)[LPW], int kt) {
@@ -223,6 +217,14 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   if (kt + 4 < KTL) SPEC_TILE_STEP(f0, f1, r0, kt + 4, 4)
 #undef SPEC_TILE_STEP
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the over-fetched tail before the epilogue
+  // 1 / rms of this lane's rows, fetched only now: the loop has no register to spare for them
+  float rv[MTW];
+#pragma unroll
+  for (int mt = 0; mt < MTW; ++mt) {
+    const int m = (mtile0 + wm * MTW + mt) * 16 + c;
+    rv[mt] = 1.0f;
+    if (FOLD_EPI && !INLOOP && a.fold_x && m < a.M) rv[mt] = a.rinv_ws[m];
+  }
   if (inloop) rv[0] = row_inv_from_lane_ssq(ssq_tot, a.ss_d, a.ss_eps);
 
 #pragma unroll
@@ -259,6 +261,52 @@ __global__ __launch_bounds__(256) void k_partial_reduce(GemmArgs a) {
   tile_epilogue<T, EPI_RESIDUAL>(a, v, n >> 4, m, (n & 15) >> 2);
 }
 
+
+// The same reduction, one workgroup per row, for the producer of the next GEMM's activations.  After the update the
+// row's fp16-rounded values sit in LDS, and one thread per (k-slice of the next GEMM, lane group) adds their squares
+// up exactly as that GEMM would take them from its operand fragments (frag_ssq: eight consecutive elements per 32-k
+// step, ascending, one chain per k-slice); the slices are added in order, then the lane groups as
+// row_inv_from_lane_ssq pairs them: a.rinv_ws[m] = 1 / rms of the row, the very bits k_row_inv_x would leave --
+// which then need not run.  a.ssq_ks = the k-slices of the next GEMM (at most 8).
+template <class T>
+__global__ __launch_bounds__(1024) void k_partial_reduce_rows(GemmArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char reduce_smem[];
+  op_t *xs = (op_t *)reduce_smem;  // [N]
+  __shared__ float ssq_s[8][4];
+  const int m = blockIdx.x, n4 = a.N >> 2;
+  const size_t stride = (size_t)a.part_rows * a.N;
+  for (int i = threadIdx.x; i < n4; i += blockDim.x) {
+    const int n = i * 4;
+    const float *p = a.part + (size_t)m * a.N + n;
+    f32x4_v v = *(const f32x4_v *)p;
+    for (int s = 1; s < a.KS; ++s) {
+      const f32x4_v q = *(const f32x4_v *)(p + s * stride);
+      v[0] += q[0]; v[1] += q[1]; v[2] += q[2]; v[3] += q[3];
+    }
+    op_t o4[4];
+    residual_update(a, v, n, m, o4);
+    *(uint2 *)(xs + n) = *(const uint2 *)o4;
+  }
+  __syncthreads();
+  const int steps = (a.N >> 5) / a.ssq_ks;
+  if ((int)threadIdx.x < a.ssq_ks * 4) {
+    const int w = threadIdx.x >> 2, g = threadIdx.x & 3;
+    float s = 0.f;
+    for (int u = 0; u < steps; ++u) s = frag_ssq(*(const u32x4_v *)(xs + (w * steps + u) * 32 + g * 8), s);
+    ssq_s[w][g] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      t[g] = ssq_s[0][g];
+      for (int w = 1; w < a.ssq_ks; ++w) t[g] += ssq_s[w][g];
+    }
+    const float tt = (t[0] + t[1]) + (t[2] + t[3]);
+    a.rinv_ws[m] = 1.0f / sqrtf(tt / (float)a.ss_d + a.ss_eps);
+  }
+}
 
 // 1 / rms of every row of the fp16 activations X, in exactly the order the GEMM kernels add the squares up
 // themselves (frag_ssq): one workgroup per 16-row tile, wave w walks k-slice w, the slice sums meet in LDS and are
@@ -373,7 +421,10 @@ static void launch_tile_t(GemmArgs a, int epi, hipStream_t st) {
   else if (MTW == 2) launch_nb_tile<T, 2>(a, NBW, epi, blocks, st);
   else if (MTW == 3) launch_nb_tile<T, 3>(a, NBW, epi, blocks, st);
   else launch_nb_tile<T, 4>(a, NBW, epi, blocks, st);
-  if (split) {
+  if (split && a.ssq_ks > 0 && a.x_out) {
+    const int threads = std::min(1024, ((a.N >> 2) + 63) / 64 * 64);  // one float4 of outputs per thread where that fits
+    hipLaunchKernelGGL(k_partial_reduce_rows<T>, dim3(a.M), dim3(threads), (size_t)a.N * sizeof(op_t), st, a);
+  } else if (split) {
     const size_t total = (size_t)a.M * (a.N >> 2);
     hipLaunchKernelGGL(k_partial_reduce<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a);
   }

@@ -19,6 +19,8 @@ struct PackedDims {
   size_t bytes(size_t esz) const { return (size_t)N_pad * K_pad * esz; }
 };
 PackedDims packed_dims(int N, int K);
+// k-slices of a GEMM with KT 32-k steps: fixed by the shape alone (it fixes the order of every sum)
+inline int gemm_ks_for(int KT) { return (KT % 8 == 0) ? 8 : (KT % 4 == 0) ? 4 : (KT % 2 == 0) ? 2 : 1; }
 
 struct GemmArgs {
   // operands
@@ -39,7 +41,11 @@ struct GemmArgs {
   int fold_x;                // consumer: norm folded in (row length ss_d, epsilon ss_eps)
   int ss_d;
   float ss_eps;
-  float *rinv_ws;            // consumer: [M] scratch for 1 / rms per row (tiled kernel with more than one row tile per wave)
+  int ssq_ks;                // producer (below): the k-slices of the GEMM that will consume x_out, gemm_ks_for(N / 32); else 0
+  // consumer (tiled kernel with more than one row tile per wave): [M] 1 / rms per row, left by k_row_inv_x or by the
+  // split residual GEMM that produced X.  producer (EPI_RESIDUAL, split by k-slice, x_out set, ssq_ks > 0): where the
+  // 1 / rms of the updated rows goes (row length ss_d = N, epsilon ss_eps).
+  float *rinv_ws;
   void *x_out;               // EPI_RESIDUAL producer: fp16 copy of the updated rows, fragment order
   float *part;               // EPI_RESIDUAL with more than 64 rows: scratch [KS][part_rows][N] fp32, or null
   int part_rows;             // M rounded up to 16
@@ -84,6 +90,10 @@ void launch_gemm_tile(int dtype, GemmArgs a, int epi, hipStream_t st);  // more 
 bool gemm_wants_row_inv(const GemmArgs &a, int epi);
 bool gemm_tile_wants_row_inv(const GemmArgs &a, int epi);
 void launch_row_inv_x(const GemmArgs &a, hipStream_t st);
+// True when this EPI_RESIDUAL launch (x_out set) goes through the split kernel's row-wise reduction, which can leave
+// 1 / rms of the updated rows behind (set ssq_ks, ss_d, ss_eps and rinv_ws before the launch): the consumer then needs
+// no k_row_inv_x.
+bool gemm_can_leave_ssq(const GemmArgs &a);
 void launch_argmax_partials(const float *pv, const int32_t *pi, int M, int row_step, int NT, int V, int q, int out_stride,
                             int32_t *out, hipStream_t st);
 // once per context, with its device current: lets the kernels that need it use more than 64 KB of LDS

@@ -42,6 +42,25 @@ __device__ __forceinline__ float row_inv_from_lane_ssq(float t, int d, float eps
   return 1.0f / sqrtf(t / (float)d + eps);
 }
 
+// h[m][n..n+3] += v (scaled, biased): the residual update of one lane's four outputs; o4 = the updated values
+// rounded to the next GEMM's operand type (also written to x_out in fragment order when that is set).
+__device__ __forceinline__ void residual_update(const GemmArgs &a, f32x4_v v, int n, int m, op_t (&o4)[4]) {
+  v[0] *= a.out_scale; v[1] *= a.out_scale; v[2] *= a.out_scale; v[3] *= a.out_scale;  // exact: a power of two
+  if (a.bias) {
+    const float4 b4 = *(const float4 *)(a.bias + n);
+    v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
+  }
+  float4 *p = (float4 *)(a.h + (size_t)m * a.N + n);
+  float4 o = *p;
+  o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
+  *p = o;
+  if (a.x_out) {  // the next GEMM's activations: the updated row, rounded to fp16
+    o4[0] = to_op_counted(o.x, a.sat); o4[1] = to_op_counted(o.y, a.sat);
+    o4[2] = to_op_counted(o.z, a.sat); o4[3] = to_op_counted(o.w, a.sat);
+    *(uint2 *)((op_t *)a.x_out + xpack_index(m, n, a.N >> 5)) = *(const uint2 *)o4;
+  }
+}
+
 // ------------------------------------------------------------------------- epilogues
 // One finished 16x16 tile: this lane holds stored rows n .. n+3 (n = 16*nt + 4g) of
 // activation row m.  The element-wise work of the layer happens here, on fp32 sums.
@@ -50,27 +69,20 @@ template <class T, int EPI>
 __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int nt, int m, int g, float rinv = 1.0f) {
   if (nt >= a.NT) return;
   const int n = nt * 16 + 4 * g;
+  if (EPI == EPI_RESIDUAL) {
+    op_t o4[4];
+    if (m < a.M && n < a.N) residual_update(a, v, n, m, o4);
+    return;
+  }
   v[0] *= a.out_scale; v[1] *= a.out_scale; v[2] *= a.out_scale; v[3] *= a.out_scale;  // exact: a power of two
-  if (EPI != EPI_RESIDUAL) { v[0] *= rinv; v[1] *= rinv; v[2] *= rinv; v[3] *= rinv; }
+  v[0] *= rinv; v[1] *= rinv; v[2] *= rinv; v[3] *= rinv;
   if (a.bias) {
     const float4 b4 = *(const float4 *)(a.bias + n);
     v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
   }
   const bool live = m < a.M;
 
-  if (EPI == EPI_RESIDUAL) {
-    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (live && n < a.N) {
-      float4 *p = (float4 *)(a.h + (size_t)m * a.N + n);
-      o = *p;
-      o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
-      *p = o;
-      if (a.x_out) {  // the next GEMM's activations: the updated row, rounded to fp16
-        op_t o4[4] = {to_op_counted(o.x, a.sat), to_op_counted(o.y, a.sat), to_op_counted(o.z, a.sat), to_op_counted(o.w, a.sat)};
-        *(uint2 *)((op_t *)a.x_out + xpack_index(m, n, a.N >> 5)) = *(const uint2 *)o4;
-      }
-    }
-  } else if (EPI == EPI_QKV) {
+  if (EPI == EPI_QKV) {
     if (live && n < a.N) {
       // No per-lane integer division (it would be most of this epilogue).  A strip of 16 stored rows lies
       // inside one head of one of q, k, v (d and hd are multiples of 16), and the strip number is the same for
