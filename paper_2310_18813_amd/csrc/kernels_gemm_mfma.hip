@@ -385,24 +385,56 @@ static void launch_gemm_t(GemmArgs a, int epi, hipStream_t st) {
   // rows per pass: MT tiles of 16; strips per workgroup: NB.  Neither changes any result.
   const int MT = a.M <= 16 ? 1 : a.M <= 32 ? 2 : 4;
   a.passes = (a.M + MT * 16 - 1) / (MT * 16);
-  // as many strips per workgroup as row tiles (activation traffic = weight traffic), while the
-  // launch still has workgroups for 160 of the 256 CUs (measured: fewer, fuller workgroups win down to there)
+  // Strips per workgroup.  A compute unit keeps a bounded number of cache-line requests in flight, and that is what
+  // a launch here is bound by; a workgroup asks for NB weight fragments (from HBM the first time a strip is read,
+  // from L2 for the other row passes) and MT activation fragments (L2) per 32-k step, so the unit with the most
+  // workgroups sets the time: ceil(workgroups / units) * (NB * weight cost + MT * activation cost), with a request
+  // that goes to HBM about three times as dear as one that hits L2 (measured).  Against doubling NB up to MT:
+  // QKV at d_model 4096 with 17..64 rows 27..36 -> 23..31 us (three strips per workgroup: one workgroup per unit).
+  // Never changes a result.
+  const int n_cu = a.n_cu > 0 ? a.n_cu : 256;
   int NB = 1;
-  while (NB < MT && (a.NT / (NB * 2)) * a.passes >= 160) NB *= 2;
-  // eight strips halve the activation traffic again; worth it once enough workgroups remain
-  if (MT == 4 && NB == 4 && (a.NT / 8) * a.passes >= 160) NB = 8;
+  if (MT > 1 && epi != EPI_LOGITS) {
+    static const int cand[] = {1, 2, 3, 4, 6, 8};
+    long best = -1;
+    for (int nb : cand) {
+      const long wgs = (long)((a.NT + nb - 1) / nb) * a.passes;
+      const long per_cu = (wgs + n_cu - 1) / n_cu;
+      const long w_cost = (3000 + 1000 * (a.passes - 1)) / a.passes;  // per strip and step, averaged over the row passes
+      const long cost = per_cu * (nb * w_cost + MT * 1000);
+      if (best < 0 || cost < best) { best = cost; NB = nb; }
+    }
+  } else if (MT > 1) {
+    // the LM head, with its arg-max epilogue per strip, measured better with fewer strips per workgroup than that
+    // estimate picks: as many as row tiles while 160 workgroups remain
+    while (NB < MT && (a.NT / (NB * 2)) * a.passes >= 160) NB *= 2;
+    if (MT == 4 && NB == 4 && (a.NT / 8) * a.passes >= 160) NB = 8;
+  }
   a.groups = (a.NT + NB - 1) / NB;
   const int blocks = a.passes == 1 ? a.groups : ((a.groups + 7) / 8) * 8 * a.passes;
   dim3 grid(blocks), block(KS * 64);
   const int tiles = NB * MT;
   const size_t lds = KS > 1 ? (size_t)KS * (tiles < 8 ? tiles : 8) * 1024 : 0;
   if (MT == 1) launch_epi<T, 1, 1>(a, epi, grid, block, lds, st);
-  else if (MT == 2 && NB == 1) launch_epi<T, 2, 1>(a, epi, grid, block, lds, st);
-  else if (MT == 2) launch_epi<T, 2, 2>(a, epi, grid, block, lds, st);
-  else if (NB == 1) launch_epi<T, 4, 1>(a, epi, grid, block, lds, st);
-  else if (NB == 2) launch_epi<T, 4, 2>(a, epi, grid, block, lds, st);
-  else if (NB == 4) launch_epi<T, 4, 4>(a, epi, grid, block, lds, st);
-  else launch_epi<T, 4, 8>(a, epi, grid, block, lds, st);
+  else if (MT == 2) {
+    switch (NB) {
+      case 1: launch_epi<T, 2, 1>(a, epi, grid, block, lds, st); break;
+      case 2: launch_epi<T, 2, 2>(a, epi, grid, block, lds, st); break;
+      case 3: launch_epi<T, 2, 3>(a, epi, grid, block, lds, st); break;
+      case 4: launch_epi<T, 2, 4>(a, epi, grid, block, lds, st); break;
+      case 6: launch_epi<T, 2, 6>(a, epi, grid, block, lds, st); break;
+      default: launch_epi<T, 2, 8>(a, epi, grid, block, lds, st); break;
+    }
+  } else {
+    switch (NB) {
+      case 1: launch_epi<T, 4, 1>(a, epi, grid, block, lds, st); break;
+      case 2: launch_epi<T, 4, 2>(a, epi, grid, block, lds, st); break;
+      case 3: launch_epi<T, 4, 3>(a, epi, grid, block, lds, st); break;
+      case 4: launch_epi<T, 4, 4>(a, epi, grid, block, lds, st); break;
+      case 6: launch_epi<T, 4, 6>(a, epi, grid, block, lds, st); break;
+      default: launch_epi<T, 4, 8>(a, epi, grid, block, lds, st); break;
+    }
+  }
 }
 
 void launch_gemm_mfma(int dtype, const GemmArgs &a, int epi, hipStream_t st) {
