@@ -243,6 +243,25 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
     }
 }
 
+// ((P_0 + P_1) + ...) + P_{KS-1} for four consecutive outputs; with eight slices all loads go out before the first add
+__device__ __forceinline__ f32x4_v sum_slices(const float *__restrict__ p, size_t stride, int KS) {
+  if (KS == 8) {
+    f32x4_v q[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) q[s] = *(const f32x4_v *)(p + s * stride);
+    f32x4_v v = q[0];
+#pragma unroll
+    for (int s = 1; s < 8; ++s) { v[0] += q[s][0]; v[1] += q[s][1]; v[2] += q[s][2]; v[3] += q[s][3]; }
+    return v;
+  }
+  f32x4_v v = *(const f32x4_v *)p;
+  for (int s = 1; s < KS; ++s) {
+    const f32x4_v q = *(const f32x4_v *)(p + s * stride);
+    v[0] += q[0]; v[1] += q[1]; v[2] += q[2]; v[3] += q[3];
+  }
+  return v;
+}
+
 // Second half of a split residual GEMM: out = ((P_0 + P_1) + ...) + P_{KS-1}, then the same epilogue as
 // everywhere (scale, bias, h += out).  One thread per four consecutive outputs of a row.
 template <class T>
@@ -253,12 +272,7 @@ __global__ __launch_bounds__(256) void k_partial_reduce(GemmArgs a) {
   const int m = (int)(idx / n4), n = (int)(idx % n4) * 4;
   const float *p = a.part + (size_t)m * a.N + n;
   const size_t stride = (size_t)a.part_rows * a.N;
-  f32x4_v v = *(const f32x4_v *)p;
-  for (int s = 1; s < a.KS; ++s) {
-    const f32x4_v q = *(const f32x4_v *)(p + s * stride);
-    v[0] += q[0]; v[1] += q[1]; v[2] += q[2]; v[3] += q[3];
-  }
-  tile_epilogue<T, EPI_RESIDUAL>(a, v, n >> 4, m, (n & 15) >> 2);
+  tile_epilogue<T, EPI_RESIDUAL>(a, sum_slices(p, stride, a.KS), n >> 4, m, (n & 15) >> 2);
 }
 
 
@@ -278,13 +292,8 @@ __global__ __launch_bounds__(1024) void k_partial_reduce_rows(GemmArgs a) {
   for (int i = threadIdx.x; i < n4; i += blockDim.x) {
     const int n = i * 4;
     const float *p = a.part + (size_t)m * a.N + n;
-    f32x4_v v = *(const f32x4_v *)p;
-    for (int s = 1; s < a.KS; ++s) {
-      const f32x4_v q = *(const f32x4_v *)(p + s * stride);
-      v[0] += q[0]; v[1] += q[1]; v[2] += q[2]; v[3] += q[3];
-    }
     op_t o4[4];
-    residual_update(a, v, n, m, o4);
+    residual_update(a, sum_slices(p, stride, a.KS), n, m, o4);
     *(uint2 *)(xs + n) = *(const uint2 *)o4;
   }
   __syncthreads();
@@ -296,15 +305,13 @@ __global__ __launch_bounds__(1024) void k_partial_reduce_rows(GemmArgs a) {
     ssq_s[w][g] = s;
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
-    float t[4];
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      t[g] = ssq_s[0][g];
-      for (int w = 1; w < a.ssq_ks; ++w) t[g] += ssq_s[w][g];
-    }
-    const float tt = (t[0] + t[1]) + (t[2] + t[3]);
-    a.rinv_ws[m] = 1.0f / sqrtf(tt / (float)a.ss_d + a.ss_eps);
+  if (threadIdx.x < 4) {  // one lane per lane group: the slices in order, then the pairs as row_inv_from_lane_ssq adds them
+    const int g = threadIdx.x;
+    float t = ssq_s[0][g];
+    for (int w = 1; w < a.ssq_ks; ++w) t += ssq_s[w][g];
+    t += __shfl_xor(t, 1, 64);
+    t += __shfl_xor(t, 2, 64);
+    if (g == 0) a.rinv_ws[m] = 1.0f / sqrtf(t / (float)a.ss_d + a.ss_eps);
   }
 }
 
