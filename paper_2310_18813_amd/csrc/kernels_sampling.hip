@@ -44,33 +44,67 @@ __device__ __forceinline__ void load4z(const float *__restrict__ z, int k, int V
 }
 __device__ __forceinline__ bool row_vec(const float *z, int V) { return (V & 3) == 0 && ((uintptr_t)z & 15) == 0; }
 
+// Workgroup-wide maximum / sum / exclusive prefix of one value per thread.  The order of the additions is fixed by the
+// thread numbers alone (shuffles inside a wave, then the waves in order), so every thread sees the same bits and a
+// row's result does not depend on anything but the row.  sh: at least SMP_THREADS / 64 + 1 floats.
+__device__ __forceinline__ float block_max_all(float v, float *sh) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  __syncthreads();  // sh may still be read by the previous user
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float m = sh[0];
+#pragma unroll
+  for (int i = 1; i < SMP_THREADS / 64; ++i) m = fmaxf(m, sh[i]);
+  return m;
+}
+// inclusive prefix inside the wave (lane l: v_0 + ... + v_l, added pairwise by doubling distances), the waves' totals
+// through LDS; returns the exclusive prefix of this thread, *total = the sum over the workgroup
+__device__ __forceinline__ float block_prefix(float v, float *sh, float *total) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  float inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const float up = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += up;
+  }
+  __syncthreads();
+  if (lane == 63) sh[wv] = inc;
+  __syncthreads();
+  float before = 0.f, all = 0.f;
+#pragma unroll
+  for (int i = 0; i < SMP_THREADS / 64; ++i) {
+    if (i == wv) before = all;
+    all += sh[i];
+  }
+  *total = all;
+  return before + (inc - v);
+}
+
 // max over the row and sum of exp((z - max) * inv_T), the same bits in every thread
+template <bool WANT_SUM = true>
 __device__ __forceinline__ void row_stats(const float *__restrict__ z, int V, float inv_T, float *sh, float &m, float &Z) {
   const Chunk c = my_chunk(V);
   const bool vec = row_vec(z, V);
   float lm = -INFINITY;
+#pragma unroll 8
   for (int k = c.k0; k < c.k1; k += 4) {
     float v[4];
     load4z(z, k, V, vec, -INFINITY, v);
     lm = fmaxf(fmaxf(lm, v[0]), fmaxf(fmaxf(v[1], v[2]), v[3]));
   }
-  __syncthreads();  // sh may still be read by the previous user
-  sh[threadIdx.x] = lm;
-  __syncthreads();
-  m = sh[0];
-  for (int i = 1; i < SMP_THREADS; ++i) m = fmaxf(m, sh[i]);
+  m = block_max_all(lm, sh);
+  Z = 0.f;
+  if (!WANT_SUM) return;
   float ls = 0.f;
+#pragma unroll 8
   for (int k = c.k0; k < c.k1; k += 4) {
     float v[4];
     load4z(z, k, V, vec, -INFINITY, v);  // exp(-inf) = 0 beyond the row
 #pragma unroll
-    for (int i = 0; i < 4; ++i) ls += expf((v[i] - m) * inv_T);
+    for (int i = 0; i < 4; ++i) ls += __expf((v[i] - m) * inv_T);
   }
-  __syncthreads();
-  sh[threadIdx.x] = ls;
-  __syncthreads();
-  Z = sh[0];
-  for (int i = 1; i < SMP_THREADS; ++i) Z += sh[i];
+  block_prefix(ls, sh, &Z);
 }
 
 // Draw with u from the weights w4(k, out) -> weights of k .. k+3 (zero beyond the row), k a multiple of four:
@@ -79,29 +113,31 @@ template <class W4>
 __device__ __forceinline__ int block_draw(int V, W4 w4, float u, float *sh, int *sh_i, float *total_out = nullptr) {
   const Chunk c = my_chunk(V);
   float local = 0.f;
+#pragma unroll 8
   for (int k = c.k0; k < c.k1; k += 4) {
     float w[4];
     w4(k, w);
 #pragma unroll
     for (int i = 0; i < 4; ++i) local += w[i];
   }
-  __syncthreads();
-  sh[threadIdx.x] = local;
+  float total;
+  const float excl = block_prefix(local, sh, &total);
   if (threadIdx.x == 0) *sh_i = -1;
-  __syncthreads();
-  float excl = 0.f, total = 0.f;  // sums of the chunks in thread order: the same additions in every thread
-  for (int i = 0; i < SMP_THREADS; ++i) {
-    if (i == (int)threadIdx.x) excl = total;
-    total += sh[i];
-  }
   if (total_out) *total_out = total;
   float x = u * total;
   if (!(x < total)) x = total * 0.99999994f;  // u < 1, but the product may round up to the total
-  const float next = excl + local;            // = the next thread's excl, bit for bit
-  if (local > 0.f && excl <= x && x < next) {
+  __syncthreads();
+  // the owner of x: the last thread with weight whose prefix does not exceed x (the prefixes come from sums in
+  // different associations, so "prefix <= x < prefix + local" could leave a hair's gap between neighbours)
+  if (local > 0.f && excl <= x) atomicMax(sh_i, (int)threadIdx.x);
+  __syncthreads();
+  const int owner = *sh_i;
+  __syncthreads();
+  if ((int)threadIdx.x == owner) {
     float run = excl;
     int pick = -1, last = -1;
-    for (int k = c.k0; k < c.k1; k += 4) {
+  #pragma unroll 8
+  for (int k = c.k0; k < c.k1; k += 4) {
       float w[4];
       w4(k, w);
 #pragma unroll
@@ -111,11 +147,12 @@ __device__ __forceinline__ int block_draw(int V, W4 w4, float u, float *sh, int 
         if (pick < 0 && run > x) pick = k + i;
       }
     }
-    *sh_i = pick >= 0 ? pick : last;  // the walk's sum can end a hair below the chunk's: then the chunk's last token
+    *sh_i = pick >= 0 ? pick : last;  // the walk may end a hair below x: then the chunk's last token
+  } else if (owner < 0 && threadIdx.x == 0) {
+    *sh_i = 0;  // all weights zero or not finite: the lowest index, as the greedy rule does for a row of NaNs
   }
   __syncthreads();
-  const int r = *sh_i;
-  return r < 0 ? 0 : r;  // all weights zero or not finite: the lowest index, as the greedy rule does for a row of NaNs
+  return *sh_i;
 }
 
 // weights exp((z - m) * inv_T) of a row, optionally with one token removed
@@ -125,7 +162,7 @@ struct ExpW {
     float v[4];
     load4z(z, k, V, vec, -INFINITY, v);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) w[i] = (k + i == drop) ? 0.f : expf((v[i] - m) * inv_T);
+    for (int i = 0; i < 4; ++i) w[i] = (k + i == drop) ? 0.f : __expf((v[i] - m) * inv_T);
   }
 };
 // residual weights max(0, p - q) of a target and a draft row
@@ -155,8 +192,8 @@ __global__ __launch_bounds__(SMP_THREADS) void k_sample_rows(const float *__rest
   __shared__ int sh_i;
   const int b = blockIdx.x;
   const float *z = logits + (size_t)b * V;
-  float m, Z;
-  row_stats(z, V, inv_T, sh, m, Z);
+  float m, Z;  // a draw needs the maximum only: its own pass over the row adds the weights up
+  row_stats<false>(z, V, inv_T, sh, m, Z);
   const float uu = n ? uniform_at(u, n, b, off, u_rows, 0) : u[b];
   const int tok = block_draw(V, ExpW{z, V, row_vec(z, V), m, inv_T, -1}, uu, sh, &sh_i);
   if (threadIdx.x == 0) out[(size_t)b * out_stride] = tok;
@@ -189,13 +226,13 @@ __global__ __launch_bounds__(SMP_THREADS) void k_sample_verify(const float *__re
     const int tj = t[(size_t)b * t_stride + j];
     const bool valid = tj >= 0 && tj < V;
     const float ua = uniform_at(u, n, b, j, u_rows, 1);
-    const float pt = valid ? expf((zp[tj] - mp) * inv_T) * (1.0f / Zp) : 0.f;
+    const float pt = valid ? __expf((zp[tj] - mp) * inv_T) * (1.0f / Zp) : 0.f;
     int tok;
     if (dl) {
       const float *zq = dl + ((size_t)j * d_rows + b) * V;
       float mq, Zq;
       row_stats(zq, V, inv_T, sh, mq, Zq);
-      const float qt = valid ? expf((zq[tj] - mq) * inv_T) * (1.0f / Zq) : 1.f;
+      const float qt = valid ? __expf((zq[tj] - mq) * inv_T) * (1.0f / Zq) : 1.f;
       if (ua * qt < pt) {
         if (threadIdx.x == 0) ab[j] = tj;
         continue;
