@@ -204,7 +204,9 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
     c->x_ssq = gemm_can_leave_ssq(a);  // then the reduction leaves 1 / rms of the new rows where the next GEMM looks for it
     if (c->x_ssq) { a.rinv_ws = ws.row_inv; a.ssq_ks = gemm_ks_for(a.N >> 5); a.ss_d = a.N; a.ss_eps = D.norm_eps; }
   };
-  if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, 0, st); }
+  // a norm that is not folded runs as a kernel of its own -- unless the producer of these rows has applied it already
+  if (!fold && !c->x_normed) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, 0, st); }
+  c->x_normed = false;
   {
     GemmArgs a = base_args(c, m.p_qkv, L.wqkv, L.s_qkv, L.bqkv, ws.x, M);
     consume_norm(a);
@@ -248,6 +250,15 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
     GemmArgs a = base_args(c, m.p_2, L.w2, L.s_2, L.b2, ws.act, M);
     a.h = ws.h; a.part = ws.gemm_part; a.part_rows = (M + 15) / 16 * 16;
     produce_norm(a);
+    if (!fold && D.norm_kind == SPEC_NORM_LAYER && m.fast && gemm_reduces_by_rows(a)) {
+      // the row-wise reduction holds the whole updated row: it applies the next layer's first norm (or the final one)
+      const bool last = layer + 1 == D.n_layers;
+      a.ln_gain = last ? m.final_norm_w : m.layers[layer + 1].attn_norm_w;
+      a.ln_bias = last ? m.final_norm_b : m.layers[layer + 1].attn_norm_b;
+      a.ln_x = ws.x; a.ss_eps = D.norm_eps;
+      c->x_normed = a.ln_gain && a.ln_bias;
+      if (!c->x_normed) a.ln_gain = a.ln_bias = nullptr;
+    }
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
   }
 }
@@ -262,7 +273,10 @@ void fast_head(spec_ctx *c, const Model &m, int Mh, int last_of_q, float *logits
   const bool tgt = &m == &c->tgt;
   const bool fold = m.fold_norm;
   const int rows = fold && last_of_q > 0 ? Mh * last_of_q : Mh;
-  if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, last_of_q, st); }
+  // the final norm, unless the last layer's down projection has applied it (to every row in place: not when the rows
+  // that need a token are gathered)
+  if (!fold && !(c->x_normed && last_of_q == 0)) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, last_of_q, st); }
+  c->x_normed = false;
   GemmArgs a = base_args(c, m.p_head, m.lm_head, m.s_head, nullptr, c->ws.x, rows);
   a.logits = logits_or_null;
   a.logit_step = fold ? last_of_q : 0;  // the folded head runs over every row of the pass: dump the wanted ones only

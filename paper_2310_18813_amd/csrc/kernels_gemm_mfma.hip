@@ -366,9 +366,10 @@ static bool goes_to_tile_kernel(const GemmArgs &a, int epi) {
   const int tile_min_m = a.NT >= 1024 ? 33 : 65;
   return a.NT >= 64 && (epi != EPI_RESIDUAL ? a.M >= tile_min_m : (split_ok && a.M >= 33));
 }
-bool gemm_can_leave_ssq(const GemmArgs &a) {
-  return a.M > 64 && a.x_out && (a.N & 31) == 0 && goes_to_tile_kernel(a, EPI_RESIDUAL);
+bool gemm_reduces_by_rows(const GemmArgs &a) {
+  return a.M > 64 && (a.N & 31) == 0 && a.N <= NORM_ROW_MAX && goes_to_tile_kernel(a, EPI_RESIDUAL);
 }
+bool gemm_can_leave_ssq(const GemmArgs &a) { return a.x_out && gemm_reduces_by_rows(a); }
 bool gemm_wants_row_inv(const GemmArgs &a, int epi) {
   return a.M > 0 && goes_to_tile_kernel(a, epi) && gemm_tile_wants_row_inv(a, epi);
 }

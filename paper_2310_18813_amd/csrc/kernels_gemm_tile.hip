@@ -282,21 +282,33 @@ __global__ __launch_bounds__(256) void k_partial_reduce(GemmArgs a) {
 // step, ascending, one chain per k-slice); the slices are added in order, then the lane groups as
 // row_inv_from_lane_ssq pairs them: a.rinv_ws[m] = 1 / rms of the row, the very bits k_row_inv_x would leave --
 // which then need not run.  a.ssq_ks = the k-slices of the next GEMM (at most 8).
-template <class T>
-__global__ __launch_bounds__(1024) void k_partial_reduce_rows(GemmArgs a) {
+// LN: the model's norm is a LayerNorm that is not folded into the next GEMM: the updated row is kept in fp32 and the
+// first 256 threads apply the norm that follows (norm_row: the norm kernel's own instructions, so the same bits),
+// which takes that kernel's launch out of the pass.
+template <class T, bool LN>
+__global__ __launch_bounds__(1024) void k_partial_reduce_rows(GemmArgs a, int ln_kind) {
   extern __shared__ __attribute__((aligned(16))) unsigned char reduce_smem[];
-  op_t *xs = (op_t *)reduce_smem;  // [N]
+  op_t *xs = (op_t *)reduce_smem;      // [N] fp16 (sums of squares) ...
+  float4 *hs = (float4 *)reduce_smem;  // ... or [N] fp32 (LayerNorm)
   __shared__ float ssq_s[8][4];
   const int m = blockIdx.x, n4 = a.N >> 2;
   const size_t stride = (size_t)a.part_rows * a.N;
+  float gn[LN ? NORM_MAX_V4 : 1][4], bs[LN ? NORM_MAX_V4 : 1][4];
+  if constexpr (LN) norm_params<T, true>(ln_kind, a.N, (const T *)a.ln_gain, (const T *)a.ln_bias, gn, bs);  // on their way during the reduction
   for (int i = threadIdx.x; i < n4; i += blockDim.x) {
     const int n = i * 4;
     const float *p = a.part + (size_t)m * a.N + n;
     op_t o4[4];
-    residual_update(a, sum_slices(p, stride, a.KS), n, m, o4);
-    *(uint2 *)(xs + n) = *(const uint2 *)o4;
+    float4 hn;
+    residual_update(a, sum_slices(p, stride, a.KS), n, m, o4, &hn);
+    if (LN) hs[i] = hn;
+    else *(uint2 *)(xs + n) = *(const uint2 *)o4;
   }
   __syncthreads();
+  if constexpr (LN) {
+    norm_row<T, true>(ln_kind, a.N, a.ss_eps, hs, gn, bs, m, a.ln_x, a.N >> 5, a.sat, &ssq_s[0][0]);
+    return;
+  }
   const int steps = (a.N >> 5) / a.ssq_ks;
   if ((int)threadIdx.x < a.ssq_ks * 4) {
     const int w = threadIdx.x >> 2, g = threadIdx.x & 3;
@@ -428,9 +440,12 @@ static void launch_tile_t(GemmArgs a, int epi, hipStream_t st) {
   else if (MTW == 2) launch_nb_tile<T, 2>(a, NBW, epi, blocks, st);
   else if (MTW == 3) launch_nb_tile<T, 3>(a, NBW, epi, blocks, st);
   else launch_nb_tile<T, 4>(a, NBW, epi, blocks, st);
-  if (split && a.ssq_ks > 0 && a.x_out) {
-    const int threads = std::min(1024, ((a.N >> 2) + 63) / 64 * 64);  // one float4 of outputs per thread where that fits
-    hipLaunchKernelGGL(k_partial_reduce_rows<T>, dim3(a.M), dim3(threads), (size_t)a.N * sizeof(op_t), st, a);
+  const int rr_threads = std::min(1024, ((a.N >> 2) + 63) / 64 * 64);  // one float4 of outputs per thread where that fits
+  if (split && a.ln_gain && a.ln_x) {
+    hipLaunchKernelGGL((k_partial_reduce_rows<T, true>), dim3(a.M), dim3(std::max(256, rr_threads)), (size_t)a.N * sizeof(float), st,
+                       a, (int)SPEC_NORM_LAYER);
+  } else if (split && a.ssq_ks > 0 && a.x_out) {
+    hipLaunchKernelGGL((k_partial_reduce_rows<T, false>), dim3(a.M), dim3(rr_threads), (size_t)a.N * sizeof(op_t), st, a, 0);
   } else if (split) {
     const size_t total = (size_t)a.M * (a.N >> 2);
     hipLaunchKernelGGL(k_partial_reduce<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a);

@@ -96,26 +96,6 @@ void launch_assemble_embed(const spec_ctx *c, const Model &m, const PassArgs &pa
 // One 256-thread block per output row; statistics in fp32 with a fixed reduction tree
 // (per-thread strided partial, wave butterfly, then the four wave results in order), so a
 // row's result never depends on which other rows are in the pass.
-__device__ __forceinline__ float block_sum_256(float v, float *sh) {
-  v = wave_sum(v);
-  const int w = threadIdx.x >> 6;
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) sh[w] = v;
-  __syncthreads();
-  return ((sh[0] + sh[1]) + sh[2]) + sh[3];
-}
-
-// Row held in registers: thread t owns the float4 groups t, t+256, ... (all loads issued
-// before any arithmetic, so the kernel costs one memory round trip, not d/256 of them).
-constexpr int NORM_MAX_V4 = 8;  // d <= 8192
-// four consecutive parameters (index a multiple of 4) with one load
-template <class T>
-__device__ __forceinline__ void load4(const T *__restrict__ p, int i, float (&out)[4]) {
-  struct alignas(sizeof(T) * 4) Quad { T v[4]; };
-  const Quad q = *(const Quad *)(p + i);
-#pragma unroll
-  for (int k = 0; k < 4; ++k) out[k] = Conv<T>::ld(q.v, k);
-}
 template <class T>
 __global__ __launch_bounds__(256) void k_norm(int kind, int d, float eps, const float *__restrict__ h,
                                               const T *__restrict__ gain, const T *__restrict__ bias,
@@ -125,73 +105,10 @@ __global__ __launch_bounds__(256) void k_norm(int kind, int d, float eps, const 
   const int r = blockIdx.x;
   // last_of_q > 0: output row r is the last of input rows r * q .. r * q + q - 1 (the rows that need a token)
   const float4 *hr = (const float4 *)(h + (size_t)(last_of_q > 0 ? r * last_of_q + last_of_q - 1 : r) * d);
-  const int nv = d >> 2;
-  float4 v[NORM_MAX_V4];
-#pragma unroll
-  for (int i = 0; i < NORM_MAX_V4; ++i) {
-    const int c = threadIdx.x + i * 256;
-    v[i] = c < nv ? hr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
-  }
-  // gains and biases are requested now, beside the row, so that their latency passes behind the reductions
+  // gains and biases are requested first, beside the row, so that their latency passes behind the reductions
   float gn[NORM_MAX_V4][4], bs[NORM_MAX_V4][4];
-#pragma unroll
-  for (int i = 0; i < NORM_MAX_V4; ++i) {
-    const int c = threadIdx.x + i * 256;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) { gn[i][k] = 0.f; bs[i][k] = 0.f; }
-    if (c < nv) {
-      load4(gain, 4 * c, gn[i]);
-      if (kind != SPEC_NORM_RMS) load4(bias, 4 * c, bs[i]);
-    }
-  }
-  float mean = 0.f, inv;
-  if (kind == SPEC_NORM_RMS) {
-    float ss = 0.f;
-#pragma unroll
-    for (int i = 0; i < NORM_MAX_V4; ++i) {
-      ss = fmaf(v[i].x, v[i].x, ss); ss = fmaf(v[i].y, v[i].y, ss);
-      ss = fmaf(v[i].z, v[i].z, ss); ss = fmaf(v[i].w, v[i].w, ss);
-    }
-    ss = block_sum_256(ss, sh);
-    inv = 1.0f / sqrtf(ss / (float)d + eps);
-  } else {
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < NORM_MAX_V4; ++i) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
-    mean = block_sum_256(s, sh) / (float)d;
-    float vs = 0.f;
-#pragma unroll
-    for (int i = 0; i < NORM_MAX_V4; ++i) {
-      const int c = threadIdx.x + i * 256;
-      if (c < nv) {
-        float a0 = v[i].x - mean, a1 = v[i].y - mean, a2 = v[i].z - mean, a3 = v[i].w - mean;
-        vs = fmaf(a0, a0, vs); vs = fmaf(a1, a1, vs); vs = fmaf(a2, a2, vs); vs = fmaf(a3, a3, vs);
-      }
-    }
-    inv = 1.0f / sqrtf(block_sum_256(vs, sh) / (float)d + eps);
-  }
-#pragma unroll
-  for (int i = 0; i < NORM_MAX_V4; ++i) {
-    const int c = threadIdx.x + i * 256;
-    if (c < nv) {
-      const float e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
-      float o[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        o[k] = (e[k] - mean) * inv * gn[i][k];
-        if (kind != SPEC_NORM_RMS) o[k] += bs[i][k];
-      }
-      if (pack_kt > 0) {
-        // the consumer is a matrix-core GEMM: fp16 operands, rows stored in fragment order, where four consecutive
-        // elements of a row are eight contiguous bytes
-        op_t o4[4] = {to_op_counted(o[0], sat), to_op_counted(o[1], sat), to_op_counted(o[2], sat), to_op_counted(o[3], sat)};
-        *(uint2 *)((op_t *)x + xpack_index(r, 4 * c, pack_kt)) = *(const uint2 *)o4;
-      } else {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) Conv<T>::st((T *)x, (size_t)r * d + 4 * c + k, o[k]);
-      }
-    }
-  }
+  norm_params<T, false>(kind, d, gain, bias, gn, bs);
+  norm_row<T, false>(kind, d, eps, hr, gn, bs, r, x, pack_kt, sat, sh);
 }
 
 void launch_norm(const spec_ctx *c, const Model &m, const float *h, const void *gain, const void *bias, void *x,

@@ -47,6 +47,11 @@ struct GemmArgs {
   // 1 / rms of the updated rows goes (row length ss_d = N, epsilon ss_eps).
   float *rinv_ws;
   void *x_out;               // EPI_RESIDUAL producer: fp16 copy of the updated rows, fragment order
+  // EPI_RESIDUAL producer in front of a LayerNorm (models whose norm is not folded), row-wise reduction only: gain and
+  // bias of that norm in the model dtype; the reduction then writes the normalised rows (fp16, fragment order) to
+  // ln_x with epsilon ss_eps, and the norm kernel need not run.  Null: off.
+  const void *ln_gain, *ln_bias;
+  void *ln_x;
   float *part;               // EPI_RESIDUAL with more than 64 rows: scratch [KS][part_rows][N] fp32, or null
   int part_rows;             // M rounded up to 16
   void *q, *kc, *vc;         // EPI_QKV: q [M][d] fp32 (un-rounded: the attention kernel decides how to feed it), caches in the model dtype
@@ -64,7 +69,7 @@ struct GemmArgs {
 
 // The kernels take GemmArgs by value: it is the explicit part of their kernel-argument segment (the code objects
 // declare that size plus 256 bytes of hidden arguments).
-static_assert(sizeof(GemmArgs) % 8 == 0 && sizeof(GemmArgs) <= 256 && alignof(GemmArgs) == 8, "kernel argument block of the GEMM kernels");
+static_assert(sizeof(GemmArgs) % 8 == 0 && sizeof(GemmArgs) <= 288 && alignof(GemmArgs) == 8, "kernel argument block of the GEMM kernels");
 
 // Packed weights are fp16 = weight * 2^k, k per matrix so that the largest magnitude lands in
 // [2^13, 2^14): every bf16 value within 2^-31 of the largest is then an exact fp16 number (smaller
@@ -94,6 +99,9 @@ void launch_row_inv_x(const GemmArgs &a, hipStream_t st);
 // 1 / rms of the updated rows behind (set ssq_ks, ss_d, ss_eps and rinv_ws before the launch): the consumer then needs
 // no k_row_inv_x.
 bool gemm_can_leave_ssq(const GemmArgs &a);
+// True when this EPI_RESIDUAL launch goes through the row-wise reduction (which can apply the LayerNorm that follows:
+// set ln_gain, ln_bias, ln_x, ss_eps before the launch).
+bool gemm_reduces_by_rows(const GemmArgs &a);
 void launch_argmax_partials(const float *pv, const int32_t *pi, int M, int row_step, int NT, int V, int q, int out_stride,
                             int32_t *out, hipStream_t st);
 // once per context, with its device current: lets the kernels that need it use more than 64 KB of LDS

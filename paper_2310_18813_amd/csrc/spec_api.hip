@@ -444,6 +444,7 @@ static int forward_pass(spec_ctx *c, Model &m, const PassArgs &pa, HeadMode head
   const size_t hbytes = (size_t)M * m.desc.d_model * sizeof(float);
   if (dump) generic_copy(c->ws.h, dump, hbytes, st);
   c->x_ssq = false;  // the rows in ws.x come from the embedding
+  c->x_normed = false;
   for (int l = 0; l < m.desc.n_layers; ++l) {
     if (m.fast) fast_layer(c, m, l, pa.B, pa.q, pa.b0, pa.seq_groups, max_pos, st);
     else generic_layer(c, m, l, M, pa.q, pa.b0, pa.seq_groups, st);

@@ -129,6 +129,7 @@ struct spec_ctx {
   // speculative sampling (off while smp_u is null): temperature, the caller's table of uniform numbers
   // [B_max][L_max][3], and the caller's buffers for the target's logits [M_max][vocab] and the draft's
   // [s_max][B_max][vocab] of a round
+  bool x_normed = false;  // ws.x already holds the rows normalised by the LayerNorm that follows (done by a split residual GEMM)
   bool x_ssq = false;  // ws.row_inv already holds 1 / rms of the rows now in ws.x (left by a split residual GEMM)
   float smp_T = 0.f;
   const float *smp_u = nullptr;
