@@ -37,8 +37,9 @@ size_t fast_packed_bytes(const spec_model_desc &D, int dtype, int L_max) {
   size_t per_layer = 4 * al256f(d * e) + al256f(f.qkv.bytes(e)) + al256f(f.o.bytes(e)) + al256f(f.w13.bytes(e)) +
                      al256f(f.w2.bytes(e)) +
                      al256f((size_t)f.qkv.N_pad * 4) + al256f((size_t)f.o.N_pad * 4) + al256f((size_t)f.w13.N_pad * 4) +
-                     al256f((size_t)f.w2.N_pad * 4);
-  size_t top = al256f((size_t)D.vocab * d * e) + al256f((size_t)D.max_pos * d * e) + 2 * al256f(d * e) +
+                     al256f((size_t)f.w2.N_pad * 4) +
+                     al256f((size_t)f.qkv.N_pad * 4) + al256f((size_t)f.w13.N_pad * 4);  // row sums of the packed weights (folded LayerNorm)
+  size_t top = 2 * al256f((size_t)f.head.N_pad * 4) + al256f((size_t)D.vocab * d * e) + al256f((size_t)D.max_pos * d * e) + 2 * al256f(d * e) +
                al256f(f.head.bytes(e)) + al256f((size_t)L_max * (d / D.n_heads / 2) * sizeof(float2)) +
                al256f((4 * (size_t)D.n_layers + 1) * sizeof(uint32_t));
   return top + per_layer * (size_t)D.n_layers;
@@ -65,9 +66,9 @@ bool fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&curso
   m.p_qkv = f.qkv; m.p_o = f.o; m.p_13 = f.w13; m.p_2 = f.w2; m.p_head = f.head;
   const bool ln = D.norm_kind == SPEC_NORM_LAYER, hb = D.has_bias != 0, swi = D.ffn_kind == SPEC_FFN_SWIGLU;
   // RMS norm: y = W (g * h / rms) = (W diag(g)) h / rms, so the gain goes into the packed weights and the
-  // division into the GEMM's epilogue; the layer then needs no norm kernel.  (Layer norm subtracts the mean
-  // first, which does not commute with the rounding of h to fp16 as harmlessly: it keeps its kernel.)
-  m.fold_norm = !ln;
+  // division into the GEMM's epilogue; no norm kernel runs on this path.  LayerNorm the same way with two more
+  // terms: W (g * (h - mean) / std + b) = ((W diag(g)) h - mean * rowsum(W diag(g))) / std + W b.
+  m.fold_ln = ln;
 
   m.tok_emb = takef(w->d_tok_emb, (size_t)D.vocab * d * e, cursor, st);
   m.pos_emb = D.pos_kind == SPEC_POS_LEARNED ? takef(w->d_pos_emb, (size_t)D.max_pos * d * e, cursor, st) : nullptr;
@@ -86,10 +87,16 @@ bool fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&curso
     return amax + word;
   };
   void *head = bumpf(cursor, f.head.bytes(e));
-  const void *gh = m.fold_norm ? m.final_norm_w : nullptr;  // the final norm's gain goes into the LM head the same way
+  const void *gh = m.final_norm_w;  // the final norm's gain goes into the LM head the same way
   launch_pack_weight(dt, 0, f.head, (int)d, hd, w->d_lm_head, nullptr, nullptr, gh, head,
                      amax_of(n_amax - 1, w->d_lm_head, (size_t)D.vocab * d, gh), st);
   m.lm_head = head;
+  if (ln) {
+    float *ws_ = (float *)bumpf(cursor, (size_t)f.head.N_pad * 4), *bh = (float *)bumpf(cursor, (size_t)f.head.N_pad * 4);
+    generic_zero(bh, (size_t)f.head.N_pad * 4, st);
+    launch_fold_ln(dt, 0, f.head, (int)d, hd, w->d_lm_head, nullptr, nullptr, m.final_norm_b, head, ws_, bh, st);
+    m.wsum_head = ws_; m.b_head = bh;
+  }
   m.rope = nullptr;
   if (D.pos_kind == SPEC_POS_ROPE) {
     float2 *tab = (float2 *)bumpf(cursor, (size_t)c->run.L_max * (hd / 2) * sizeof(float2));
@@ -105,7 +112,7 @@ bool fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&curso
     L.ffn_norm_b = ln ? takef(T[SPEC_T_FFN_NORM_B], d * e, cursor, st) : nullptr;
     void *p;
     const size_t a0 = 4 * (size_t)l, ff = D.d_ffn;
-    const void *g1 = m.fold_norm ? L.attn_norm_w : nullptr, *g2 = m.fold_norm ? L.ffn_norm_w : nullptr;
+    const void *g1 = L.attn_norm_w, *g2 = L.ffn_norm_w;
     p = bumpf(cursor, f.qkv.bytes(e));
     amax_of(a0, T[SPEC_T_WQ], d * d, g1);
     amax_of(a0, T[SPEC_T_WK], d * d, g1);
@@ -129,6 +136,14 @@ bool fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&curso
     launch_pack_weight(dt, 0, f.w2, (int)d, hd, T[SPEC_T_W2], nullptr, nullptr, nullptr, p, amax_of(a0 + 3, T[SPEC_T_W2], d * ff), st);
     L.w2 = p;
     L.bqkv = L.bo = L.b13 = L.b2 = nullptr;
+    float *fold_bqkv = nullptr, *fold_b13 = nullptr;  // folded LayerNorm: these two GEMMs get a bias whatever the model has
+    if (ln && !hb) {
+      fold_bqkv = (float *)bumpf(cursor, (size_t)f.qkv.N_pad * 4);
+      generic_zero(fold_bqkv, (size_t)f.qkv.N_pad * 4, st);
+      fold_b13 = (float *)bumpf(cursor, (size_t)f.w13.N_pad * 4);
+      generic_zero(fold_b13, (size_t)f.w13.N_pad * 4, st);
+      L.bqkv = fold_bqkv; L.b13 = fold_b13;
+    }
     if (hb) {
       float *b = (float *)bumpf(cursor, (size_t)f.qkv.N_pad * 4);
       launch_pack_bias(dt, 1, f.qkv, (int)d, hd, T[SPEC_T_BQ], T[SPEC_T_BK], T[SPEC_T_BV], b, st);
@@ -143,16 +158,27 @@ bool fast_setup_model(spec_ctx *c, Model &m, const spec_weights *w, void *&curso
         b = (float *)bumpf(cursor, (size_t)f.w2.N_pad * 4);
         launch_pack_bias(dt, 0, f.w2, (int)d, hd, T[SPEC_T_B2], nullptr, nullptr, b, st);
         L.b2 = b;
+      } else if (ln) {
+        b = (float *)bumpf(cursor, (size_t)f.w13.N_pad * 4);
+        generic_zero(b, (size_t)f.w13.N_pad * 4, st);
+        L.b13 = b;
       }
+    }
+    if (ln) {
+      float *ws_ = (float *)bumpf(cursor, (size_t)f.qkv.N_pad * 4);
+      launch_fold_ln(dt, 1, f.qkv, (int)d, hd, T[SPEC_T_WQ], T[SPEC_T_WK], T[SPEC_T_WV], L.attn_norm_b, L.wqkv, ws_, (float *)L.bqkv, st);
+      L.wsum_qkv = ws_;
+      ws_ = (float *)bumpf(cursor, (size_t)f.w13.N_pad * 4);
+      if (swi) launch_fold_ln(dt, 2, f.w13, (int)d, hd, T[SPEC_T_W1], T[SPEC_T_W3], nullptr, L.ffn_norm_b, L.w13, ws_, (float *)L.b13, st);
+      else launch_fold_ln(dt, 0, f.w13, (int)d, hd, T[SPEC_T_W1], nullptr, nullptr, L.ffn_norm_b, L.w13, ws_, (float *)L.b13, st);
+      L.wsum_13 = ws_;
     }
   }
   // the GEMM epilogues undo the scaling: 1 / scale per matrix, from the same words the packing read
   std::vector<uint32_t> h_amax(n_amax, 0u);
-  if (scaled || m.fold_norm) {
-    if (hipMemcpyAsync(h_amax.data(), amax, n_amax * sizeof(uint32_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
-        hipStreamSynchronize(st) != hipSuccess)
-      return false;
-  }
+  if (hipMemcpyAsync(h_amax.data(), amax, n_amax * sizeof(uint32_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
+      hipStreamSynchronize(st) != hipSuccess)
+    return false;
   for (int l = 0; l < D.n_layers; ++l) {
     LayerW &L = m.layers[l];
     L.s_qkv = 1.0f / weight_scale(h_amax[4 * l]);
@@ -186,30 +212,30 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
   void *vc = (char *)m.vcache + ((size_t)layer * m.kv_area_elems + slot0) * esz;
 
   const bool tgt = &m == &c->tgt;  // only the target model's kernels are timed one by one
-  const bool fold = m.fold_norm;  // then ws.x holds fp16(h), left by the producer of h, and the consumer takes 1 / rms from it
-  auto consume_norm = [&](GemmArgs &a) {
-    if (!fold) return;
+  // the norms are folded: ws.x holds fp16(h), left by the producer of h, and the consumer takes 1 / rms (LayerNorm:
+  // mean and 1 / std) of its rows from it
+  auto consume_norm = [&](GemmArgs &a, const float *wsum) {
     a.fold_x = 1; a.ss_d = d; a.ss_eps = D.norm_eps; a.rinv_ws = ws.row_inv;
+    if (m.fold_ln) { a.wsum = wsum; a.mean_ws = ws.row_mean; }
   };
   // the tiled kernel's larger wave tiles read 1 / rms per row from scratch: a small kernel fills it first, unless
   // the producer of the rows has left what is needed
   auto row_inv_first = [&](const GemmArgs &a, int epi) {
-    if (!fold || c->x_ssq || !gemm_wants_row_inv(a, epi)) return;
+    if (c->x_ssq || !gemm_wants_row_inv(a, epi)) return;
     KScope k(c, tgt ? SPEC_KCLASS_NORM : -1);
     launch_row_inv_x(a, st);
   };
   auto produce_norm = [&](GemmArgs &a) {
-    if (!fold) return;
     a.x_out = ws.x;
     c->x_ssq = gemm_can_leave_ssq(a);  // then the reduction leaves 1 / rms of the new rows where the next GEMM looks for it
-    if (c->x_ssq) { a.rinv_ws = ws.row_inv; a.ssq_ks = gemm_ks_for(a.N >> 5); a.ss_d = a.N; a.ss_eps = D.norm_eps; }
+    if (c->x_ssq) {
+      a.rinv_ws = ws.row_inv; a.ssq_ks = gemm_ks_for(a.N >> 5); a.ss_d = a.N; a.ss_eps = D.norm_eps;
+      if (m.fold_ln) a.mean_ws = ws.row_mean;
+    }
   };
-  // a norm that is not folded runs as a kernel of its own -- unless the producer of these rows has applied it already
-  if (!fold && !c->x_normed) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.attn_norm_w, L.attn_norm_b, ws.x, M, 0, st); }
-  c->x_normed = false;
   {
     GemmArgs a = base_args(c, m.p_qkv, L.wqkv, L.s_qkv, L.bqkv, ws.x, M);
-    consume_norm(a);
+    consume_norm(a, L.wsum_qkv);
     a.q = ws.q; a.kc = kc; a.vc = vc; a.row_pos = ws.row_pos; a.rope = m.rope;
     a.q_rows = q_rows; a.d = d; a.hd = m.hd; a.H = D.n_heads; a.L_pad = m.L_pad; a.seq_groups = seq_groups;
     row_inv_first(a, EPI_QKV);
@@ -235,10 +261,9 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
     produce_norm(a);
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
   }
-  if (!fold) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, ws.h, L.ffn_norm_w, L.ffn_norm_b, ws.x, M, 0, st); }
   {
     GemmArgs a = base_args(c, m.p_13, L.w13, L.s_13, L.b13, ws.x, M);
-    consume_norm(a);
+    consume_norm(a, L.wsum_13);
     a.act = ws.act; a.f = D.d_ffn;
     const int epi = D.ffn_kind == SPEC_FFN_SWIGLU ? EPI_SWIGLU : EPI_RELU;
     row_inv_first(a, epi);
@@ -250,48 +275,31 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
     GemmArgs a = base_args(c, m.p_2, L.w2, L.s_2, L.b2, ws.act, M);
     a.h = ws.h; a.part = ws.gemm_part; a.part_rows = (M + 15) / 16 * 16;
     produce_norm(a);
-    // (up to about one and a half workgroups per compute unit: measured at d_model 5120, 256 rows 17 us against
-    // 11 + 12 for reduction and norm kernel, 576 rows 42 against 19 + 12)
-    if (!fold && D.norm_kind == SPEC_NORM_LAYER && m.fast && gemm_reduces_by_rows(a) && 2 * M <= 3 * (c->n_cu > 0 ? c->n_cu : 256)) {
-      // the row-wise reduction holds the whole updated row: it applies the next layer's first norm (or the final one)
-      const bool last = layer + 1 == D.n_layers;
-      a.ln_gain = last ? m.final_norm_w : m.layers[layer + 1].attn_norm_w;
-      a.ln_bias = last ? m.final_norm_b : m.layers[layer + 1].attn_norm_b;
-      a.ln_x = ws.x; a.ss_eps = D.norm_eps;
-      c->x_normed = a.ln_gain && a.ln_bias;
-      if (!c->x_normed) a.ln_gain = a.ln_bias = nullptr;
-    }
     launch_gemm_mfma(dt, a, EPI_RESIDUAL, st);
   }
 }
 
 // Final norm and LM head with the arg-max fused in, for the rows that need a token: all Mh rows of the pass, or
 // (last_of_q > 0) the last row of each of Mh groups of last_of_q rows.
-// RMS norm: folded into the LM head like the layers' norms (gain in the packed weights, 1 / rms taken by the GEMM
-// from the fp16 rows the last layer left); the GEMM then runs over every row of the pass and the second arg-max
-// stage picks the rows that are wanted.  Layer norm: k_norm gathers and normalises the wanted rows first.
+// The final norm is folded into the LM head like the layers' norms (gain in the packed weights, the row statistics
+// taken by the GEMM from the fp16 rows the last layer left); the GEMM runs over every row of the pass and the second
+// arg-max stage picks the rows that are wanted.
 void fast_head(spec_ctx *c, const Model &m, int Mh, int last_of_q, float *logits_or_null, int q, int arg_stride, int32_t *arg_out,
                hipStream_t st) {
   const bool tgt = &m == &c->tgt;
-  const bool fold = m.fold_norm;
-  const int rows = fold && last_of_q > 0 ? Mh * last_of_q : Mh;
-  // the final norm, unless the last layer's down projection has applied it (to every row in place: not when the rows
-  // that need a token are gathered)
-  if (!fold && !(c->x_normed && last_of_q == 0)) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_norm(c, m, c->ws.h, m.final_norm_w, m.final_norm_b, c->ws.x, Mh, last_of_q, st); }
-  c->x_normed = false;
-  GemmArgs a = base_args(c, m.p_head, m.lm_head, m.s_head, nullptr, c->ws.x, rows);
+  const int rows = last_of_q > 0 ? Mh * last_of_q : Mh;
+  GemmArgs a = base_args(c, m.p_head, m.lm_head, m.s_head, m.fold_ln ? m.b_head : nullptr, c->ws.x, rows);
   a.logits = logits_or_null;
-  a.logit_step = fold ? last_of_q : 0;  // the folded head runs over every row of the pass: dump the wanted ones only
+  a.logit_step = last_of_q;  // the head runs over every row of the pass: dump the wanted ones only
   a.part_val = c->ws.head_part;
   a.part_idx = c->ws.head_part_idx;
-  if (fold) {
-    a.fold_x = 1; a.ss_d = m.desc.d_model; a.ss_eps = m.desc.norm_eps; a.rinv_ws = c->ws.row_inv;
-    // unless the last layer's down projection has left them
-    if (!c->x_ssq && gemm_wants_row_inv(a, EPI_LOGITS)) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_row_inv_x(a, st); }
-  }
+  a.fold_x = 1; a.ss_d = m.desc.d_model; a.ss_eps = m.desc.norm_eps; a.rinv_ws = c->ws.row_inv;
+  if (m.fold_ln) { a.wsum = m.wsum_head; a.mean_ws = c->ws.row_mean; }
+  // the row statistics, unless the last layer's down projection has left them
+  if (!c->x_ssq && gemm_wants_row_inv(a, EPI_LOGITS)) { KScope k(c, tgt ? SPEC_KCLASS_NORM : -1); launch_row_inv_x(a, st); }
   { KScope k(c, tgt ? SPEC_KCLASS_GEMM_HEAD : -1); launch_gemm_mfma(c->run.dtype, a, EPI_LOGITS, st); }
   { KScope k(c, tgt ? SPEC_KCLASS_OTHER : -1);
-    launch_argmax_partials(a.part_val, a.part_idx, Mh, fold ? last_of_q : 0, m.p_head.NT, m.desc.vocab, q, arg_stride, arg_out, st); }
+    launch_argmax_partials(a.part_val, a.part_idx, Mh, last_of_q, m.p_head.NT, m.desc.vocab, q, arg_stride, arg_out, st); }
 }
 
 }  // namespace spec

@@ -126,6 +126,59 @@ __global__ void k_pack_bias(int mode, int N, int N_pad, int d, int hd, const T *
   dst[n] = v;
 }
 
+// Folded LayerNorm, set-up side: for every stored row n of a packed matrix (one wave per row, fixed lane assignment
+// and butterfly: the same bits on every run) wsum[n] = the sum of the packed fp16 elements of the row -- what the
+// epilogue multiplies the row mean with, in the packed weights' own scaled units -- and bias[n] += sum_k W[n][k] *
+// b[k], the norm's bias pushed through the original weights (stored-row order as in k_pack_weight).
+template <class T>
+__global__ __launch_bounds__(256) void k_fold_ln(int mode, int N, int K, int N_pad, int K_pad, int d, int hd,
+                                                 const T *__restrict__ s0, const T *__restrict__ s1, const T *__restrict__ s2,
+                                                 const T *__restrict__ ln_bias, const op_t *__restrict__ packed,
+                                                 float *__restrict__ wsum, float *__restrict__ bias) {
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (n >= N_pad) return;
+  const int KT = K_pad / 32, nt = n >> 4, r = n & 15;
+  float s = 0.f;
+  for (int k = lane * 8; k < K_pad; k += 512) {
+    const op_t *p = packed + ((((size_t)nt * KT + (k >> 5)) * 64 + (((k & 31) >> 3) << 4) + r) << 3);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += (float)p[i];
+  }
+  s = wave_sum(s);
+  float wb = 0.f;
+  if (n < N) {
+    const T *src;
+    int row;
+    if (mode == 0) { src = s0; row = n; }
+    else if (mode == 1) {
+      int region = n / d, c = n % d, hh = c / hd, e = c % hd;
+      if (region < 2) { int half = hd >> 1; e = (e & 1) ? (e >> 1) + half : (e >> 1); }
+      src = region == 0 ? s0 : region == 1 ? s1 : s2;
+      row = hh * hd + e;
+    } else {
+      int p = n >> 2, q = n & 3;
+      src = (q & 1) ? s1 : s0;
+      row = 2 * p + (q >> 1);
+    }
+    for (int k = lane; k < K; k += 64) wb += Conv<T>::ld(src, (size_t)row * K + k) * Conv<T>::ld(ln_bias, k);
+  }
+  wb = wave_sum(wb);
+  if (lane == 0) {
+    wsum[n] = s;
+    if (n < N) bias[n] += wb;
+  }
+}
+void launch_fold_ln(int dtype, int mode, const PackedDims &p, int d, int hd, const void *s0, const void *s1, const void *s2,
+                    const void *ln_bias, const void *packed, float *wsum, float *bias, hipStream_t st) {
+  const unsigned blocks = (unsigned)((p.N_pad + 3) / 4);
+  if (dtype == SPEC_DTYPE_BF16)
+    hipLaunchKernelGGL(k_fold_ln<bf16_t>, dim3(blocks), dim3(256), 0, st, mode, p.N, p.K, p.N_pad, p.K_pad, d, hd, (const bf16_t *)s0,
+                       (const bf16_t *)s1, (const bf16_t *)s2, (const bf16_t *)ln_bias, (const op_t *)packed, wsum, bias);
+  else
+    hipLaunchKernelGGL(k_fold_ln<f16_t>, dim3(blocks), dim3(256), 0, st, mode, p.N, p.K, p.N_pad, p.K_pad, d, hd, (const f16_t *)s0,
+                       (const f16_t *)s1, (const f16_t *)s2, (const f16_t *)ln_bias, (const op_t *)packed, wsum, bias);
+}
+
 PackedDims packed_dims(int N, int K) {
   PackedDims p;
   p.N = N; p.K = K;
@@ -226,11 +279,12 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
 
-  constexpr bool FOLDX = EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LOGITS;  // the GEMMs behind an RMS norm
+  constexpr bool FOLDX = EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_RELU || EPI == EPI_LOGITS;  // the GEMMs behind a norm
   const bool foldx = FOLDX && a.fold_x;
-  float ssq[MT];  // this lane's part of the sum of squares of its rows over the wave's k-slice
+  const bool lnx = foldx && a.wsum;  // the folded norm is a LayerNorm: the plain sums as well
+  float ssq[MT], sm[MT];  // this lane's part of the sum of squares (and of the sum) of its rows over the wave's k-slice
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) ssq[mt] = 0.f;
+  for (int mt = 0; mt < MT; ++mt) { ssq[mt] = 0.f; sm[mt] = 0.f; }
   constexpr int U = (NB + MT >= 12) ? 1 : (NB + MT >= 6) ? 2 : (NB + MT >= 3) ? 4 : 8;
   int kt = kt0;
   for (; kt + U <= kt1; kt += U) {
@@ -253,6 +307,12 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
       for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) ssq[mt] = frag_ssq(xf[u][mt], ssq[mt]);
+      if (lnx) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) sm[mt] = frag_sum(xf[u][mt], sm[mt]);
+      }
     }
   }
   // the steps left over (fewer than U): all their loads go out together as well, so the end of a slice costs one
@@ -284,6 +344,10 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
         if (u < rem) {
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) ssq[mt] = frag_ssq(xf[u][mt], ssq[mt]);
+          if (lnx) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) sm[mt] = frag_sum(xf[u][mt], sm[mt]);
+          }
         }
       }
     }
@@ -293,10 +357,14 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
   // folded norm from the operand fragments: the waves' slice sums meet in LDS (behind the same barrier as the
   // first round of partial tiles) and are added in slice order
   __shared__ float ssq_s[FOLDX ? 8 : 1][FOLDX ? MT * 64 : 1];
-  float rinv_x[MT];
+  __shared__ float sum_s[FOLDX ? 8 : 1][FOLDX ? MT * 64 : 1];
+  float rinv_x[MT], mean_x[MT];
   if (foldx && KS > 1) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) ssq_s[w][mt * 64 + lane] = ssq[mt];
+    for (int mt = 0; mt < MT; ++mt) {
+      ssq_s[w][mt * 64 + lane] = ssq[mt];
+      if (lnx) sum_s[w][mt * 64 + lane] = sm[mt];
+    }
   }
   auto finish_rinv = [&]() {
     if (!foldx) return;
@@ -307,15 +375,26 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
         t = ssq_s[0][mt * 64 + lane];
         for (int s = 1; s < KS; ++s) t += ssq_s[s][mt * 64 + lane];
       }
-      rinv_x[mt] = row_inv_from_lane_ssq(t, a.ss_d, a.ss_eps);
+      mean_x[mt] = 0.f;
+      if (lnx) {
+        float ts = sm[mt];
+        if (KS > 1) {
+          ts = sum_s[0][mt * 64 + lane];
+          for (int s = 1; s < KS; ++s) ts += sum_s[s][mt * 64 + lane];
+        }
+        row_ln_from_lane(t, ts, a.ss_d, a.ss_eps, rinv_x[mt], mean_x[mt]);
+      } else {
+        rinv_x[mt] = row_inv_from_lane_ssq(t, a.ss_d, a.ss_eps);
+      }
     }
   };
   auto rinv_of = [&](int mt) { return foldx ? rinv_x[mt] : 1.0f; };
+  auto mean_of = [&](int mt) { return foldx ? mean_x[mt] : 0.f; };
   if (KS == 1) {
     finish_rinv();
 #pragma unroll
     for (int t = 0; t < TILES; ++t)
-      tile_epilogue<T, EPI>(a, acc[t / MT][t % MT], nt0 + t / MT, m_base + (t % MT) * 16 + c, g, rinv_of(t % MT));
+      tile_epilogue<T, EPI>(a, acc[t / MT][t % MT], nt0 + t / MT, m_base + (t % MT) * 16 + c, g, rinv_of(t % MT), mean_of(t % MT));
     return;
   }
   constexpr int ROUNDS = (TILES + 7) / 8;
@@ -340,7 +419,7 @@ __global__ __launch_bounds__(512) void k_gemm_stream(GemmArgs a) {
         f32x4_v p = *(const f32x4_v *)&red[((size_t)(s * SLOTS + slot) * 64 + lane) * 4];
         v[0] += p[0]; v[1] += p[1]; v[2] += p[2]; v[3] += p[3];
       }
-      tile_epilogue<T, EPI>(a, v, nt0 + t / MT, m_base + (t % MT) * 16 + c, g, rinv_of(t % MT));
+      tile_epilogue<T, EPI>(a, v, nt0 + t / MT, m_base + (t % MT) * 16 + c, g, rinv_of(t % MT), mean_of(t % MT));
     }
   }
 }
@@ -366,10 +445,9 @@ static bool goes_to_tile_kernel(const GemmArgs &a, int epi) {
   const int tile_min_m = a.NT >= 1024 ? 33 : 65;
   return a.NT >= 64 && (epi != EPI_RESIDUAL ? a.M >= tile_min_m : (split_ok && a.M >= 33));
 }
-bool gemm_reduces_by_rows(const GemmArgs &a) {
-  return a.M > 64 && (a.N & 31) == 0 && a.N <= NORM_ROW_MAX && goes_to_tile_kernel(a, EPI_RESIDUAL);
+bool gemm_can_leave_ssq(const GemmArgs &a) {  // the row-wise reduction keeps the fp16 row in LDS: rows of up to 8192
+  return a.x_out && a.M > 64 && (a.N & 31) == 0 && a.N <= 8192 && goes_to_tile_kernel(a, EPI_RESIDUAL);
 }
-bool gemm_can_leave_ssq(const GemmArgs &a) { return a.x_out && gemm_reduces_by_rows(a); }
 bool gemm_wants_row_inv(const GemmArgs &a, int epi) {
   return a.M > 0 && goes_to_tile_kernel(a, epi) && gemm_tile_wants_row_inv(a, epi);
 }

@@ -40,6 +40,8 @@ __global__ __launch_bounds__(576) void k_gemm_rowres(GemmArgs a) {
   static_assert(KTP % R == 0 && R <= 32, "ring slots per strip slice");
   __shared__ f32x4_v red[2][8][MT][64];
   __shared__ float ssq_s[8][MT * 64];
+  __shared__ float sum_s[8][MT * 64];
+  const bool lnx = a.fold_x && a.wsum;  // the folded norm is a LayerNorm: the plain sums as well
   const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = lane & 15, g = lane >> 4;
   const int n_mine = (a.NT - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;  // host: gridDim.x <= NT
@@ -54,15 +56,22 @@ __global__ __launch_bounds__(576) void k_gemm_rowres(GemmArgs a) {
     // the ninth wave streams nothing: per strip it adds the eight slices in slice order and runs the epilogue,
     // so that the streaming waves' loop holds no memory operation but its own loads
     wg_barrier();  // the sums of squares are in LDS
-    float rinv[MT];  // folded norm: 1 / rms of this lane's rows, the slice sums added in slice order
+    float rinv[MT], mean[MT];  // folded norm: 1 / rms (or 1 / std and mean) of this lane's rows, the slice sums added in slice order
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      rinv[mt] = 1.0f;
+      rinv[mt] = 1.0f; mean[mt] = 0.f;
       if (a.fold_x) {
         float t = ssq_s[0][mt * 64 + lane];
 #pragma unroll
         for (int s = 1; s < 8; ++s) t += ssq_s[s][mt * 64 + lane];
-        rinv[mt] = row_inv_from_lane_ssq(t, a.ss_d, a.ss_eps);
+        if (lnx) {
+          float ts = sum_s[0][mt * 64 + lane];
+#pragma unroll
+          for (int s = 1; s < 8; ++s) ts += sum_s[s][mt * 64 + lane];
+          row_ln_from_lane(t, ts, a.ss_d, a.ss_eps, rinv[mt], mean[mt]);
+        } else {
+          rinv[mt] = row_inv_from_lane_ssq(t, a.ss_d, a.ss_eps);
+        }
       }
     }
     int strip = blockIdx.x;
@@ -77,7 +86,7 @@ __global__ __launch_bounds__(576) void k_gemm_rowres(GemmArgs a) {
           const f32x4_v p = red[buf][s][mt][lane];
           v[0] += p[0]; v[1] += p[1]; v[2] += p[2]; v[3] += p[3];
         }
-        tile_epilogue<T, EPI>(a, v, strip, mt * 16 + c, g, rinv[mt]);
+        tile_epilogue<T, EPI>(a, v, strip, mt * 16 + c, g, rinv[mt], mean[mt]);
       }
       // buffer `buf` is written again two strips on, behind the next barrier, which this wave reaches only now
       strip += gridDim.x;
@@ -112,6 +121,12 @@ __global__ __launch_bounds__(576) void k_gemm_rowres(GemmArgs a) {
 #pragma unroll
       for (int u = 0; u < KTP; ++u) s = frag_ssq(xf[mt][u], s);
       ssq_s[w][mt * 64 + lane] = s;
+      if (lnx) {
+        float t = 0.f;
+#pragma unroll
+        for (int u = 0; u < KTP; ++u) t = frag_sum(xf[mt][u], t);
+        sum_s[w][mt * 64 + lane] = t;
+      }
     }
   }
   // A use of every activation fragment in front of the loop: the compiler places its wait for those loads here and

@@ -92,10 +92,11 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   // Folded norm.  With one row tile per wave the sum of squares comes from the operand fragments inside the
   // loop (frag_ssq: per lane, one chain per k-slice, slices added in order), where it costs nothing; with larger
   // wave tiles the loop has no issue slots to spare (measured: +10 %) and k_row_inv_x has left 1 / rms per row.
-  constexpr bool FOLD_EPI = EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LOGITS;
+  constexpr bool FOLD_EPI = EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_RELU || EPI == EPI_LOGITS;
   constexpr bool INLOOP = FOLD_EPI && MTW == 1;
   const bool inloop = INLOOP && a.fold_x;
-  float ssq_cur = 0.f, ssq_tot = 0.f;
+  const bool lnx = a.fold_x && a.wsum;  // the folded norm is a LayerNorm: the plain sums as well
+  float ssq_cur = 0.f, ssq_tot = 0.f, sum_cur = 0.f, sum_tot = 0.f;
 
   u32x4_v r0[LPW], r1[LPW], r2[LPW];  // three steps on their way from global memory
   auto fetch = [&](u32x4_v (&r)[LPW], int kt) {
@@ -130,7 +131,10 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
     for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
       for (int mt = 0; mt < MTW; ++mt) cur[nb][mt] = Mfma16::run(f.wf[nb], f.xf[mt], cur[nb][mt]);
-    if (inloop) ssq_cur = frag_ssq(f.xf[0], ssq_cur);
+    if (inloop) {
+      ssq_cur = frag_ssq(f.xf[0], ssq_cur);
+      if (lnx) sum_cur = frag_sum(f.xf[0], sum_cur);
+    }
   };
   auto slice_end = [&]() {
     if (++in_slice == kt_per) {  // slice finished: add it to the running total, in slice order
@@ -148,6 +152,8 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
       if (inloop) {
         ssq_tot = slice == 0 ? ssq_cur : ssq_tot + ssq_cur;
         ssq_cur = 0.f;
+        sum_tot = slice == 0 ? sum_cur : sum_tot + sum_cur;
+        sum_cur = 0.f;
       }
       in_slice = 0;
       ++slice;
@@ -218,14 +224,20 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
 #undef SPEC_TILE_STEP
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the over-fetched tail before the epilogue
   // 1 / rms of this lane's rows, fetched only now: the loop has no register to spare for them
-  float rv[MTW];
+  float rv[MTW], mv[MTW];
 #pragma unroll
   for (int mt = 0; mt < MTW; ++mt) {
     const int m = (mtile0 + wm * MTW + mt) * 16 + c;
-    rv[mt] = 1.0f;
-    if (FOLD_EPI && !INLOOP && a.fold_x && m < a.M) rv[mt] = a.rinv_ws[m];
+    rv[mt] = 1.0f; mv[mt] = 0.f;
+    if (FOLD_EPI && !INLOOP && a.fold_x && m < a.M) {
+      rv[mt] = a.rinv_ws[m];
+      if (lnx) mv[mt] = a.mean_ws[m];
+    }
   }
-  if (inloop) rv[0] = row_inv_from_lane_ssq(ssq_tot, a.ss_d, a.ss_eps);
+  if (inloop) {
+    if (lnx) row_ln_from_lane(ssq_tot, sum_tot, a.ss_d, a.ss_eps, rv[0], mv[0]);
+    else rv[0] = row_inv_from_lane_ssq(ssq_tot, a.ss_d, a.ss_eps);
+  }
 
 #pragma unroll
   for (int nb = 0; nb < NBW; ++nb)
@@ -238,7 +250,7 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
           *(f32x4_v *)(a.part + ((size_t)slice_id * a.part_rows + m) * a.N + n) = tot[nb][mt];
       } else {
         tile_epilogue<T, EPI == EPI_PARTIAL ? EPI_RESIDUAL : EPI>(a, tot[nb][mt], nt, m, g,
-                                                                 rv[mt]);
+                                                                 rv[mt], mv[mt]);
       }
     }
 }
@@ -282,48 +294,55 @@ __global__ __launch_bounds__(256) void k_partial_reduce(GemmArgs a) {
 // step, ascending, one chain per k-slice); the slices are added in order, then the lane groups as
 // row_inv_from_lane_ssq pairs them: a.rinv_ws[m] = 1 / rms of the row, the very bits k_row_inv_x would leave --
 // which then need not run.  a.ssq_ks = the k-slices of the next GEMM (at most 8).
-// LN: the model's norm is a LayerNorm that is not folded into the next GEMM: the updated row is kept in fp32 and the
-// first 256 threads apply the norm that follows (norm_row: the norm kernel's own instructions, so the same bits),
-// which takes that kernel's launch out of the pass.
-template <class T, bool LN>
-__global__ __launch_bounds__(1024) void k_partial_reduce_rows(GemmArgs a, int ln_kind) {
+// A LayerNorm folded into the next GEMM (a.mean_ws set) wants the plain sums too, taken the same way (frag_sum):
+// a.mean_ws[m] = the row's mean and a.rinv_ws[m] = 1 / std, as row_ln_from_lane computes them.
+template <class T>
+__global__ __launch_bounds__(1024) void k_partial_reduce_rows(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char reduce_smem[];
-  op_t *xs = (op_t *)reduce_smem;      // [N] fp16 (sums of squares) ...
-  float4 *hs = (float4 *)reduce_smem;  // ... or [N] fp32 (LayerNorm)
+  op_t *xs = (op_t *)reduce_smem;  // [N] fp16: the updated row as the next GEMM will read it
   __shared__ float ssq_s[8][4];
   const int m = blockIdx.x, n4 = a.N >> 2;
   const size_t stride = (size_t)a.part_rows * a.N;
-  float gn[LN ? NORM_MAX_V4 : 1][4], bs[LN ? NORM_MAX_V4 : 1][4];
-  if constexpr (LN) norm_params<T, true>(ln_kind, a.N, (const T *)a.ln_gain, (const T *)a.ln_bias, gn, bs);  // on their way during the reduction
   for (int i = threadIdx.x; i < n4; i += blockDim.x) {
     const int n = i * 4;
     const float *p = a.part + (size_t)m * a.N + n;
     op_t o4[4];
-    float4 hn;
-    residual_update(a, sum_slices(p, stride, a.KS), n, m, o4, &hn);
-    if (LN) hs[i] = hn;
-    else *(uint2 *)(xs + n) = *(const uint2 *)o4;
+    residual_update(a, sum_slices(p, stride, a.KS), n, m, o4);
+    *(uint2 *)(xs + n) = *(const uint2 *)o4;
   }
   __syncthreads();
-  if constexpr (LN) {
-    norm_row<T, true>(ln_kind, a.N, a.ss_eps, hs, gn, bs, m, a.ln_x, a.N >> 5, a.sat, &ssq_s[0][0]);
-    return;
-  }
   const int steps = (a.N >> 5) / a.ssq_ks;
+  __shared__ float sum_s2[8][4];
+  const bool lnx = a.mean_ws != nullptr;  // the next GEMM folds a LayerNorm: the plain sums and the mean as well
   if ((int)threadIdx.x < a.ssq_ks * 4) {
     const int w = threadIdx.x >> 2, g = threadIdx.x & 3;
-    float s = 0.f;
-    for (int u = 0; u < steps; ++u) s = frag_ssq(*(const u32x4_v *)(xs + (w * steps + u) * 32 + g * 8), s);
+    float s = 0.f, t = 0.f;
+    for (int u = 0; u < steps; ++u) {
+      const u32x4_v f = *(const u32x4_v *)(xs + (w * steps + u) * 32 + g * 8);
+      s = frag_ssq(f, s);
+      if (lnx) t = frag_sum(f, t);
+    }
     ssq_s[w][g] = s;
+    sum_s2[w][g] = t;
   }
   __syncthreads();
-  if (threadIdx.x < 4) {  // one lane per lane group: the slices in order, then the pairs as row_inv_from_lane_ssq adds them
+  if (threadIdx.x < 4) {  // one lane per lane group: the slices in order, then the pairs as the GEMM kernels add them
     const int g = threadIdx.x;
-    float t = ssq_s[0][g];
-    for (int w = 1; w < a.ssq_ks; ++w) t += ssq_s[w][g];
+    float t = ssq_s[0][g], ts = sum_s2[0][g];
+    for (int w = 1; w < a.ssq_ks; ++w) { t += ssq_s[w][g]; ts += sum_s2[w][g]; }
     t += __shfl_xor(t, 1, 64);
     t += __shfl_xor(t, 2, 64);
-    if (g == 0) a.rinv_ws[m] = 1.0f / sqrtf(t / (float)a.ss_d + a.ss_eps);
+    ts += __shfl_xor(ts, 1, 64);
+    ts += __shfl_xor(ts, 2, 64);
+    if (g == 0) {
+      if (lnx) {
+        const float mean = ts / (float)a.ss_d, var = fmaxf(t / (float)a.ss_d - mean * mean, 0.f);
+        a.rinv_ws[m] = 1.0f / sqrtf(var + a.ss_eps);
+        a.mean_ws[m] = mean;
+      } else {
+        a.rinv_ws[m] = 1.0f / sqrtf(t / (float)a.ss_d + a.ss_eps);
+      }
+    }
   }
 }
 
@@ -331,8 +350,11 @@ __global__ __launch_bounds__(1024) void k_partial_reduce_rows(GemmArgs a, int ln
 // themselves (frag_ssq): one workgroup per 16-row tile, wave w walks k-slice w, the slice sums meet in LDS and are
 // added in slice order.  For the tiled kernel with more than one row tile per wave.
 __global__ __launch_bounds__(512) void k_row_inv_x(const void *__restrict__ X, int M, int KT, int KS, int d, float eps,
-                                                   float *__restrict__ rinv) {
+                                                   float *__restrict__ rinv, float *__restrict__ mean_out) {
   __shared__ float ssq_s[8][64];
+  __shared__ float sum_s[8][64];
+  const bool lnx = mean_out != nullptr;  // folded LayerNorm: mean and 1 / std instead of 1 / rms
+  float t = 0.f;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, c = lane & 15, g = lane >> 4;
   const int tile = blockIdx.x, kt_per = KT / KS;
   const u32x4_v *xp = (const u32x4_v *)X + (size_t)tile * KT * 64 + lane;
@@ -345,17 +367,32 @@ __global__ __launch_bounds__(512) void k_row_inv_x(const void *__restrict__ X, i
     for (int u = 0; u < 8; ++u) xf[u] = xp[(size_t)(kt + u) * 64];
 #pragma unroll
     for (int u = 0; u < 8; ++u) s = frag_ssq(xf[u], s);
+    if (lnx) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t = frag_sum(xf[u], t);
+    }
   }
-  for (; kt < kt1; ++kt) s = frag_ssq(xp[(size_t)kt * 64], s);
+  for (; kt < kt1; ++kt) {
+    const u32x4_v f = xp[(size_t)kt * 64];
+    s = frag_ssq(f, s);
+    if (lnx) t = frag_sum(f, t);
+  }
   if (KS > 1) {
     ssq_s[w][lane] = s;
+    sum_s[w][lane] = t;
     __syncthreads();
     s = ssq_s[0][lane];
-    for (int i = 1; i < KS; ++i) s += ssq_s[i][lane];
+    t = sum_s[0][lane];
+    for (int i = 1; i < KS; ++i) { s += ssq_s[i][lane]; t += sum_s[i][lane]; }
   }
-  const float v = row_inv_from_lane_ssq(s, d, eps);
+  float v, mean = 0.f;
+  if (lnx) row_ln_from_lane(s, t, d, eps, v, mean);
+  else v = row_inv_from_lane_ssq(s, d, eps);
   const int m = tile * 16 + c;
-  if (w == 0 && g == 0 && m < M) rinv[m] = v;
+  if (w == 0 && g == 0 && m < M) {
+    rinv[m] = v;
+    if (lnx) mean_out[m] = mean;
+  }
 }
 
 template <class T, int MTW, int NBW, int EPI>
@@ -416,14 +453,15 @@ static void tile_for(const GemmArgs &a, int epi, int &MTW, int &NBW) {
 // With more than one row tile per wave the kernel reads 1 / rms of its rows from a.rinv_ws: the caller runs
 // launch_row_inv_x first when this says so.
 bool gemm_tile_wants_row_inv(const GemmArgs &a, int epi) {
-  if (!a.fold_x || (epi != EPI_QKV && epi != EPI_SWIGLU && epi != EPI_LOGITS)) return false;
+  if (!a.fold_x || (epi != EPI_QKV && epi != EPI_SWIGLU && epi != EPI_RELU && epi != EPI_LOGITS)) return false;
   int MTW, NBW;
   tile_for(a, epi, MTW, NBW);
   return MTW > 1;
 }
 void launch_row_inv_x(const GemmArgs &a, hipStream_t st) {
   if (a.M <= 0) return;
-  hipLaunchKernelGGL(k_row_inv_x, dim3((a.M + 15) / 16), dim3(a.KS * 64), 0, st, a.X, a.M, a.KT, a.KS, a.ss_d, a.ss_eps, a.rinv_ws);
+  hipLaunchKernelGGL(k_row_inv_x, dim3((a.M + 15) / 16), dim3(a.KS * 64), 0, st, a.X, a.M, a.KT, a.KS, a.ss_d, a.ss_eps, a.rinv_ws,
+                     a.wsum ? a.mean_ws : nullptr);
 }
 
 template <class T>
@@ -441,11 +479,8 @@ static void launch_tile_t(GemmArgs a, int epi, hipStream_t st) {
   else if (MTW == 3) launch_nb_tile<T, 3>(a, NBW, epi, blocks, st);
   else launch_nb_tile<T, 4>(a, NBW, epi, blocks, st);
   const int rr_threads = std::min(1024, ((a.N >> 2) + 63) / 64 * 64);  // one float4 of outputs per thread where that fits
-  if (split && a.ln_gain && a.ln_x) {
-    hipLaunchKernelGGL((k_partial_reduce_rows<T, true>), dim3(a.M), dim3(std::max(256, rr_threads)), (size_t)a.N * sizeof(float), st,
-                       a, (int)SPEC_NORM_LAYER);
-  } else if (split && a.ssq_ks > 0 && a.x_out) {
-    hipLaunchKernelGGL((k_partial_reduce_rows<T, false>), dim3(a.M), dim3(rr_threads), (size_t)a.N * sizeof(op_t), st, a, 0);
+  if (split && a.ssq_ks > 0 && a.x_out) {
+    hipLaunchKernelGGL(k_partial_reduce_rows<T>, dim3(a.M), dim3(rr_threads), (size_t)a.N * sizeof(op_t), st, a);
   } else if (split) {
     const size_t total = (size_t)a.M * (a.N >> 2);
     hipLaunchKernelGGL(k_partial_reduce<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a);

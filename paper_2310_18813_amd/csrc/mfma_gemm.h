@@ -47,11 +47,13 @@ struct GemmArgs {
   // 1 / rms of the updated rows goes (row length ss_d = N, epsilon ss_eps).
   float *rinv_ws;
   void *x_out;               // EPI_RESIDUAL producer: fp16 copy of the updated rows, fragment order
-  // EPI_RESIDUAL producer in front of a LayerNorm (models whose norm is not folded), row-wise reduction only: gain and
-  // bias of that norm in the model dtype; the reduction then writes the normalised rows (fp16, fragment order) to
-  // ln_x with epsilon ss_eps, and the norm kernel need not run.  Null: off.
-  const void *ln_gain, *ln_bias;
-  void *ln_x;
+  // LayerNorm folded into the GEMM behind it: (W diag(g)) (x - mean) / std + (W b + bias) = ((W diag(g)) x - mean * wsum) / std
+  // + bias', with wsum[n] the sum of row n of the packed weights (in their scaled units) and bias' folded at set-up.
+  // consumer: wsum non-null says the folded norm is a LayerNorm; mean_ws [M]: the row means where the kernel reads
+  // 1 / std from rinv_ws instead of taking both from its operand fragments.  producer (row-wise reduction): where the
+  // mean goes beside rinv_ws.
+  const float *wsum;
+  float *mean_ws;
   float *part;               // EPI_RESIDUAL with more than 64 rows: scratch [KS][part_rows][N] fp32, or null
   int part_rows;             // M rounded up to 16
   void *q, *kc, *vc;         // EPI_QKV: q [M][d] fp32 (un-rounded: the attention kernel decides how to feed it), caches in the model dtype
@@ -86,6 +88,9 @@ void launch_pack_weight(int dtype, int mode, const PackedDims &p, int d, int hd,
                         const void *s2, const void *gain, void *dst, const uint32_t *d_amax_bits, hipStream_t st);
 void launch_pack_bias(int dtype, int mode, const PackedDims &p, int d, int hd, const void *s0, const void *s1,
                       const void *s2, float *dst, hipStream_t st);
+// folded LayerNorm: wsum[n] = sum of the packed row n; bias[n] += (W b)[n] (bias must hold the GEMM's own bias, or zeros)
+void launch_fold_ln(int dtype, int mode, const PackedDims &p, int d, int hd, const void *s0, const void *s1, const void *s2,
+                    const void *ln_bias, const void *packed, float *wsum, float *bias, hipStream_t st);
 void launch_rope_table(int L, int hd, float theta, float2 *tab, hipStream_t st);
 void launch_gemm_mfma(int dtype, const GemmArgs &a, int epi, hipStream_t st);
 void launch_gemm_tile(int dtype, GemmArgs a, int epi, hipStream_t st);  // more than 64 rows, wide outputs
@@ -99,9 +104,6 @@ void launch_row_inv_x(const GemmArgs &a, hipStream_t st);
 // 1 / rms of the updated rows behind (set ssq_ks, ss_d, ss_eps and rinv_ws before the launch): the consumer then needs
 // no k_row_inv_x.
 bool gemm_can_leave_ssq(const GemmArgs &a);
-// True when this EPI_RESIDUAL launch goes through the row-wise reduction (which can apply the LayerNorm that follows:
-// set ln_gain, ln_bias, ln_x, ss_eps before the launch).
-bool gemm_reduces_by_rows(const GemmArgs &a);
 void launch_argmax_partials(const float *pv, const int32_t *pi, int M, int row_step, int NT, int V, int q, int out_stride,
                             int32_t *out, hipStream_t st);
 // once per context, with its device current: lets the kernels that need it use more than 64 KB of LDS

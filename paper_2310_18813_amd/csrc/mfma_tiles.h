@@ -35,6 +35,24 @@ __device__ __forceinline__ float frag_ssq(u32x4_v x, float s) {
   for (int i = 0; i < 8; ++i) s = fmaf((float)h[i], (float)h[i], s);
   return s;
 }
+// the same chain for the plain sum of the row (folded LayerNorm: the mean)
+__device__ __forceinline__ float frag_sum(u32x4_v x, float s) {
+  const f16x8_v h = __builtin_bit_cast(f16x8_v, x);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) s += (float)h[i];
+  return s;
+}
+// folded LayerNorm: per-lane slice-ordered sums of squares and sums -> 1 / std and mean of the lane's row (lane groups
+// combined as below; variance as mean of squares minus squared mean, in fp32)
+__device__ __forceinline__ void row_ln_from_lane(float ssq, float sum, int d, float eps, float &rinv, float &mean) {
+  ssq += __shfl_xor(ssq, 16, 64);
+  ssq += __shfl_xor(ssq, 32, 64);
+  sum += __shfl_xor(sum, 16, 64);
+  sum += __shfl_xor(sum, 32, 64);
+  mean = sum / (float)d;
+  const float var = fmaxf(ssq / (float)d - mean * mean, 0.f);
+  rinv = 1.0f / sqrtf(var + eps);
+}
 // per-lane slice-ordered sum -> 1 / rms of the lane's row (all four lanes of a row get the same bits)
 __device__ __forceinline__ float row_inv_from_lane_ssq(float t, int d, float eps) {
   t += __shfl_xor(t, 16, 64);
@@ -44,7 +62,7 @@ __device__ __forceinline__ float row_inv_from_lane_ssq(float t, int d, float eps
 
 // h[m][n..n+3] += v (scaled, biased): the residual update of one lane's four outputs; o4 = the updated values
 // rounded to the next GEMM's operand type (also written to x_out in fragment order when that is set).
-__device__ __forceinline__ void residual_update(const GemmArgs &a, f32x4_v v, int n, int m, op_t (&o4)[4], float4 *h_new = nullptr) {
+__device__ __forceinline__ void residual_update(const GemmArgs &a, f32x4_v v, int n, int m, op_t (&o4)[4]) {
   v[0] *= a.out_scale; v[1] *= a.out_scale; v[2] *= a.out_scale; v[3] *= a.out_scale;  // exact: a power of two
   if (a.bias) {
     const float4 b4 = *(const float4 *)(a.bias + n);
@@ -54,118 +72,10 @@ __device__ __forceinline__ void residual_update(const GemmArgs &a, f32x4_v v, in
   float4 o = *p;
   o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
   *p = o;
-  if (h_new) *h_new = o;
   if (a.x_out) {  // the next GEMM's activations: the updated row, rounded to fp16
     o4[0] = to_op_counted(o.x, a.sat); o4[1] = to_op_counted(o.y, a.sat);
     o4[2] = to_op_counted(o.z, a.sat); o4[3] = to_op_counted(o.w, a.sat);
     *(uint2 *)((op_t *)a.x_out + xpack_index(m, n, a.N >> 5)) = *(const uint2 *)o4;
-  }
-}
-
-// -------------------------------------------------------------------------
-// RMSNorm / LayerNorm of one row of the fp32 residual stream by the first 256 threads of a workgroup.  Statistics in
-// fp32 with a fixed reduction tree (per-thread strided partial, wave butterfly, then the four wave results in order),
-// so a row's result never depends on which other rows are in the pass -- nor on which kernel runs this: the norm
-// kernel (a 256-thread workgroup per row, row in memory) and the row-wise reduction of a split residual GEMM (a wider
-// workgroup, WIDE: the others only keep the barriers company; row in LDS) execute these very instructions.
-template <bool WIDE>
-__device__ __forceinline__ float block_sum_256(float v, float *sh) {
-  v = wave_sum(v);
-  const int w = threadIdx.x >> 6;
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0 && (!WIDE || w < 4)) sh[w] = v;
-  __syncthreads();
-  return ((sh[0] + sh[1]) + sh[2]) + sh[3];
-}
-
-// Row held in registers: thread t owns the float4 groups t, t+256, ... (all loads issued
-// before any arithmetic, so the kernel costs one memory round trip, not d/256 of them).
-constexpr int NORM_MAX_V4 = 8;  // d <= 8192
-constexpr int NORM_ROW_MAX = NORM_MAX_V4 * 1024;
-// four consecutive parameters (index a multiple of 4) with one load
-template <class T>
-__device__ __forceinline__ void load4(const T *__restrict__ p, int i, float (&out)[4]) {
-  struct alignas(sizeof(T) * 4) Quad { T v[4]; };
-  const Quad q = *(const Quad *)(p + i);
-#pragma unroll
-  for (int k = 0; k < 4; ++k) out[k] = Conv<T>::ld(q.v, k);
-}
-// the gains and biases of the elements a thread owns (float4 groups t, t + 256, ...); zero where it owns none
-template <class T, bool WIDE>
-__device__ __forceinline__ void norm_params(int kind, int d, const T *__restrict__ gain, const T *__restrict__ bias,
-                                            float (&gn)[NORM_MAX_V4][4], float (&bs)[NORM_MAX_V4][4]) {
-  const int nv = (!WIDE || threadIdx.x < 256) ? d >> 2 : 0;
-#pragma unroll
-  for (int i = 0; i < NORM_MAX_V4; ++i) {
-    const int c = threadIdx.x + i * 256;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) { gn[i][k] = 0.f; bs[i][k] = 0.f; }
-    if (c < nv) {
-      load4(gain, 4 * c, gn[i]);
-      if (kind != SPEC_NORM_RMS) load4(bias, 4 * c, bs[i]);
-    }
-  }
-}
-// gn, bs: from norm_params, fetched by the caller as early as it can (their latency then passes behind other work)
-template <class T, bool WIDE>
-__device__ __forceinline__ void norm_row(int kind, int d, float eps, const float4 *hr, const float (&gn)[NORM_MAX_V4][4],
-                                         const float (&bs)[NORM_MAX_V4][4], int r, void *__restrict__ x, int pack_kt,
-                                         unsigned int *__restrict__ sat, float *sh) {
-  const bool act = !WIDE || threadIdx.x < 256;
-  const int nv = act ? d >> 2 : 0;  // the passive threads of a wide workgroup own no element
-  float4 v[NORM_MAX_V4];
-#pragma unroll
-  for (int i = 0; i < NORM_MAX_V4; ++i) {
-    const int c = threadIdx.x + i * 256;
-    v[i] = c < nv ? hr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
-  }
-  float mean = 0.f, inv;
-  if (kind == SPEC_NORM_RMS) {
-    float ss = 0.f;
-#pragma unroll
-    for (int i = 0; i < NORM_MAX_V4; ++i) {
-      ss = fmaf(v[i].x, v[i].x, ss); ss = fmaf(v[i].y, v[i].y, ss);
-      ss = fmaf(v[i].z, v[i].z, ss); ss = fmaf(v[i].w, v[i].w, ss);
-    }
-    ss = block_sum_256<WIDE>(ss, sh);
-    inv = 1.0f / sqrtf(ss / (float)d + eps);
-  } else {
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < NORM_MAX_V4; ++i) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
-    mean = block_sum_256<WIDE>(s, sh) / (float)d;
-    float vs = 0.f;
-#pragma unroll
-    for (int i = 0; i < NORM_MAX_V4; ++i) {
-      const int c = threadIdx.x + i * 256;
-      if (c < nv) {
-        float a0 = v[i].x - mean, a1 = v[i].y - mean, a2 = v[i].z - mean, a3 = v[i].w - mean;
-        vs = fmaf(a0, a0, vs); vs = fmaf(a1, a1, vs); vs = fmaf(a2, a2, vs); vs = fmaf(a3, a3, vs);
-      }
-    }
-    inv = 1.0f / sqrtf(block_sum_256<WIDE>(vs, sh) / (float)d + eps);
-  }
-#pragma unroll
-  for (int i = 0; i < NORM_MAX_V4; ++i) {
-    const int c = threadIdx.x + i * 256;
-    if (c < nv) {
-      const float e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
-      float o[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        o[k] = (e[k] - mean) * inv * gn[i][k];
-        if (kind != SPEC_NORM_RMS) o[k] += bs[i][k];
-      }
-      if (pack_kt > 0) {
-        // the consumer is a matrix-core GEMM: fp16 operands, rows stored in fragment order, where four consecutive
-        // elements of a row are eight contiguous bytes
-        op_t o4[4] = {to_op_counted(o[0], sat), to_op_counted(o[1], sat), to_op_counted(o[2], sat), to_op_counted(o[3], sat)};
-        *(uint2 *)((op_t *)x + xpack_index(r, 4 * c, pack_kt)) = *(const uint2 *)o4;
-      } else {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) Conv<T>::st((T *)x, (size_t)r * d + 4 * c + k, o[k]);
-      }
-    }
   }
 }
 
@@ -174,13 +84,17 @@ __device__ __forceinline__ void norm_row(int kind, int d, float eps, const float
 // activation row m.  The element-wise work of the layer happens here, on fp32 sums.
 // rinv: 1 / rms of row m when the norm in front of this GEMM is folded into it, else 1.
 template <class T, int EPI>
-__device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int nt, int m, int g, float rinv = 1.0f) {
+__device__ __forceinline__ void tile_epilogue(const GemmArgs &a, f32x4_v v, int nt, int m, int g, float rinv = 1.0f, float mean = 0.f) {
   if (nt >= a.NT) return;
   const int n = nt * 16 + 4 * g;
   if (EPI == EPI_RESIDUAL) {
     op_t o4[4];
     if (m < a.M && n < a.N) residual_update(a, v, n, m, o4);
     return;
+  }
+  if (a.wsum) {  // folded LayerNorm: take the mean's share out, in the packed weights' units
+    const float4 ws = *(const float4 *)(a.wsum + n);
+    v[0] -= mean * ws.x; v[1] -= mean * ws.y; v[2] -= mean * ws.z; v[3] -= mean * ws.w;
   }
   v[0] *= a.out_scale; v[1] *= a.out_scale; v[2] *= a.out_scale; v[3] *= a.out_scale;  // exact: a power of two
   v[0] *= rinv; v[1] *= rinv; v[2] *= rinv; v[3] *= rinv;

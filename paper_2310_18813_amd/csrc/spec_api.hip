@@ -120,7 +120,7 @@ static Sizes compute_sizes(const spec_model_desc *tgt, const spec_model_desc *dr
   const size_t NC = (L + ATTN_CHUNK - 1) / ATTN_CHUNK, NTh = (V + 15) / 16;
   z.act += al256(M * d * NC * 4) + al256(M * (d / 64 + 1) * NC * 2 * 4) + 2 * al256(M * NTh * 4);
   if (M > 32) z.act += al256(8 * Mp * d * 4);  // k-slice sums of the split residual GEMMs
-  z.act += al256(M * 4);  // 1 / rms per row (folded norm)
+  z.act += 2 * al256(M * 4);  // 1 / rms (or 1 / std) and mean per row (folded norm)
   z.tgt_w = packed_bytes(*tgt, run->dtype, run->L_max);
   z.kv_area_tgt = B * (size_t)tgt->d_model * z.L_pad;
   z.tgt_kv = 2 * al256((size_t)tgt->n_layers * z.kv_area_tgt * e);
@@ -285,6 +285,7 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
     W.head_part_idx = (int32_t *)carve(p, M * NTh * 4);
     W.gemm_part = M > 32 ? (float *)carve(p, 8 * Mp * d * 4) : nullptr;
     W.row_inv = (float *)carve(p, M * 4);
+    W.row_mean = (float *)carve(p, M * 4);
   }
 
   rc = setup_model(c, c->tgt, tgt, tgt_w, p, z.tgt_w, z.kv_area_tgt, z.tgt_kv, z.L_pad);
@@ -444,7 +445,6 @@ static int forward_pass(spec_ctx *c, Model &m, const PassArgs &pa, HeadMode head
   const size_t hbytes = (size_t)M * m.desc.d_model * sizeof(float);
   if (dump) generic_copy(c->ws.h, dump, hbytes, st);
   c->x_ssq = false;  // the rows in ws.x come from the embedding
-  c->x_normed = false;
   for (int l = 0; l < m.desc.n_layers; ++l) {
     if (m.fast) fast_layer(c, m, l, pa.B, pa.q, pa.b0, pa.seq_groups, max_pos, st);
     else generic_layer(c, m, l, M, pa.q, pa.b0, pa.seq_groups, st);

@@ -44,6 +44,7 @@ struct LayerW {
   const void *w13, *b13;    // SwiGLU: [2f][d] gate/up rows; ReLU: [f][d]
   const void *w2, *b2;      // [d][f]
   float s_qkv = 1.f, s_o = 1.f, s_13 = 1.f, s_2 = 1.f;  // MFMA path: 1 / scale of the packed fp16 weights
+  const float *wsum_qkv = nullptr, *wsum_13 = nullptr;   // MFMA path, folded LayerNorm: row sums of the packed weights
 };
 
 struct Model {
@@ -51,7 +52,9 @@ struct Model {
   spec_model_desc desc{};
   int hd = 0, L_pad = 0;
   bool fast = false;  // MFMA kernels (16-bit dtypes with supported shapes) or generic kernels
-  bool fold_norm = false;  // MFMA path, RMS norm: the layer norms live inside the GEMMs around them
+  // MFMA path: the norms live inside the GEMMs behind them (gain in the packed weights, 1 / rms in the epilogue)
+  bool fold_ln = false;    // ... and they are LayerNorms (mean taken out in the epilogue, bias pushed through the weights)
+  const float *wsum_head = nullptr, *b_head = nullptr;
   const void *tok_emb = nullptr, *pos_emb = nullptr, *final_norm_w = nullptr, *final_norm_b = nullptr,
              *lm_head = nullptr;
   std::vector<LayerW> layers;
@@ -81,6 +84,7 @@ struct Workspace {
   float *y32 = nullptr;     // [M_max][max(3d, 2f)] fp32 GEMM output (generic path)
   float *logits = nullptr;  // [M_max][vocab] fp32 (generic path / debug)
   float *attn_part = nullptr, *attn_ml = nullptr;  // split-KV partials (MFMA path)
+  float *row_mean = nullptr;                       // [M_max] their means (folded LayerNorm)
   float *row_inv = nullptr;                        // [M_max] 1 / rms of the rows of h (folded norm, tiled GEMM with large wave tiles)
   float *gemm_part = nullptr;                      // k-slice sums of the split residual GEMMs (M_max > 32)
   float *head_part = nullptr;                      // per-strip arg-max partials (MFMA path)
@@ -129,7 +133,6 @@ struct spec_ctx {
   // speculative sampling (off while smp_u is null): temperature, the caller's table of uniform numbers
   // [B_max][L_max][3], and the caller's buffers for the target's logits [M_max][vocab] and the draft's
   // [s_max][B_max][vocab] of a round
-  bool x_normed = false;  // ws.x already holds the rows normalised by the LayerNorm that follows (done by a split residual GEMM)
   bool x_ssq = false;  // ws.row_inv already holds 1 / rms of the rows now in ws.x (left by a split residual GEMM)
   float smp_T = 0.f;
   const float *smp_u = nullptr;
