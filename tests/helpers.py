@@ -11,8 +11,9 @@ ORC_WDTYPE = {"fp32": 0, "bf16": 1, "fp16": 2}
 LOGIT_TOL = {"fp32": 1e-4, "bf16": 2e-2, "fp16": 1e-2}
 
 
-def build_pair(orc, tdesc, ddesc, dtype, seed, device, emb_std=0.02, random_norms=False):
-    """-> (oracle target, oracle draft or None, gpu weights target, gpu weights draft or None)"""
+def build_pair(orc, tdesc, ddesc, dtype, seed, device, emb_std=0.02, random_norms=False, tweak=None):
+    """-> (oracle target, oracle draft or None, gpu weights target, gpu weights draft or None)
+    tweak(w): changes the seeded parameter set in place before either side sees it."""
     out = []
     gw = []
     for tag, desc in (("tgt.", tdesc), ("drf.", ddesc)):
@@ -23,6 +24,8 @@ def build_pair(orc, tdesc, ddesc, dtype, seed, device, emb_std=0.02, random_norm
         w = si.make_weights(desc, dtype, seed, device="cpu", emb_std=emb_std, tag=tag)
         if random_norms:
             si.randomize_norms(w, desc, dtype, seed)
+        if tweak:
+            tweak(w)
         out.append(orc.model(desc, si.weights_to_numpy(w), ORC_WDTYPE[dtype]))
         wg = {k: (v.to(device) if v is not None else None) for k, v in w.items() if k != "layers"}
         wg["layers"] = [{k: (v.to(device) if v is not None else None) for k, v in L.items()} for L in w["layers"]]

@@ -132,6 +132,38 @@ def test_teacher_forced_logits_and_commit(orc, B, name):
     print("%s: worst |logit err| %.3g over %d rounds (tol %g)" % (name, worst, rounds, tol))
 
 
+@pytest.mark.parametrize("shift", [0.0, 1.0, 4.0])
+def test_folded_layernorm_on_rows_off_centre(orc, B, shift):
+    """The matrix-core path takes a LayerNorm's mean and variance from the fp16 copy of the residual rows and subtracts
+    the mean's share after the product, so the rounding of a row to fp16 is relative to its mean, not to its spread.
+    Rows whose mean is up to four times their spread must keep the usual tolerance (measured: 7e-4, 9e-4, 1.3e-3 of
+    the allowed 1e-2).  The embeddings get a common offset of `shift` standard deviations on every channel."""
+    desc = si.opt_desc(2, 256, 4, 384, 777, 64)
+    nB, P, s, seed, dtype = 6, 5, 3, 91, "fp16"
+
+    def off_centre(w):
+        w["tok_emb"] = (w["tok_emb"].float() + shift * 0.03).to(w["tok_emb"].dtype)   # token + position: std 0.028
+
+    ot, _, gt, _ = build_pair(orc, desc, None, dtype, seed, DEV, random_norms=True, tweak=off_centre)
+    L_max = P + s + 4
+    ctx = B.Context(desc, gt, None, None, dtype, nB, s, L_max, 1, B.PROPOSALS_EXTERNAL, DEV)
+    prompts = si.make_prompts(nB, P, desc["vocab"], seed)
+    table = np.random.default_rng(seed).integers(desc["vocab"], size=(nB, L_max)).astype(np.int32)
+    ctx.spec_set_proposal_table(table)
+    ctx.spec_reset(prompts)
+    g_logits = ctx.spec_verify_step(s, want_logits=True).cpu().numpy()
+    tol = LOGIT_TOL[dtype]
+    worst = 0.0
+    for b in range(nB):
+        cache = ot.cache(L_max)
+        ot.forward(cache, prompts[b][:P - 1], 0, want_logits=False)
+        o_logits = ot.forward(cache, [prompts[b][P - 1]] + [int(t) for t in table[b][P:P + s]], P - 1)
+        worst = max(worst, np.abs(g_logits[b] - o_logits).max())
+    assert worst <= tol, (shift, worst)
+    print("shift %.0f sigma: worst |logit err| %.3g (tol %g)" % (shift, worst, tol))
+    ctx.close()
+
+
 @pytest.mark.parametrize("name", list(CASES))
 def test_speculative_equals_nonspeculative_on_gpu(orc, B, name):
     """The invariant of Sec. 2 on the GPU itself: every s, every proposal source and every
