@@ -493,7 +493,11 @@ static void launch_gemm_t(GemmArgs a, int epi, hipStream_t st) {
   const int blocks = a.passes == 1 ? a.groups : ((a.groups + 7) / 8) * 8 * a.passes;
   dim3 grid(blocks), block(KS * 64);
   const int tiles = NB * MT;
-  const size_t lds = KS > 1 ? (size_t)KS * (tiles < 8 ? tiles : 8) * 1024 : 0;
+  size_t lds = KS > 1 ? (size_t)KS * (tiles < 8 ? tiles : 8) * 1024 : 0;
+  // Up to 16 rows the kernel needs few registers and little LDS, and three workgroups would fit a compute unit; two
+  // measured best (QKV and LM head at 8 rows: three +2..5 us, one +25 %): more requests than the unit keeps in flight
+  // only queue up.  Asking for more LDS than a third of the unit's holds the third workgroup off.
+  if (MT == 1 && lds < 56 * 1024) lds = 56 * 1024;
   if (MT == 1) launch_epi<T, 1, 1>(a, epi, grid, block, lds, st);
   else if (MT == 2) {
     switch (NB) {

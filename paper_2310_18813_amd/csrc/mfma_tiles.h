@@ -23,23 +23,33 @@ struct Mfma16 {
   }
 };
 
-// Folded RMS norm, consumer side: the sum of squares of a row of activations is taken from the fp16 operand
+// Folded norm, consumer side: the sum of squares of a row of activations is taken from the fp16 operand
 // fragments the GEMM reads anyway.  In the B operand lane (c, g) holds elements 8g .. 8g+7 of row c of a
-// 32-k step: a lane adds its eight squares (exact in fp32) to a running fp32 sum by fused multiply-adds in
-// ascending k, one chain per k-slice from zero; the slices are added in slice order per lane, then the four
-// lane groups of a row as (g0 + g1) + (g2 + g3).  Every GEMM kernel follows exactly this order, so the value
-// depends on the row alone.
+// 32-k step: a lane adds its eight squares to a running fp32 sum, two at a time in ascending k (the two-element
+// dot-product instruction: four instead of sixteen operations per fragment), one chain per k-slice from zero; the
+// slices are added in slice order per lane, then the four lane groups of a row as (g0 + g1) + (g2 + g3).  Every
+// GEMM kernel follows exactly this order, so the value depends on the row alone.
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_v;
+// (the pairs are taken from the fragment cast as a whole: a bit cast of one element of a vector, x[i], compiles to a
+// read of element 0 whatever i)
 __device__ __forceinline__ float frag_ssq(u32x4_v x, float s) {
   const f16x8_v h = __builtin_bit_cast(f16x8_v, x);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) s = fmaf((float)h[i], (float)h[i], s);
+  for (int i = 0; i < 4; ++i) {
+    const f16x2_v p = {h[2 * i], h[2 * i + 1]};
+    s = __builtin_amdgcn_fdot2(p, p, s, false);
+  }
   return s;
 }
 // the same chain for the plain sum of the row (folded LayerNorm: the mean)
 __device__ __forceinline__ float frag_sum(u32x4_v x, float s) {
   const f16x8_v h = __builtin_bit_cast(f16x8_v, x);
+  const f16x2_v one = {(_Float16)1.0f, (_Float16)1.0f};
 #pragma unroll
-  for (int i = 0; i < 8; ++i) s += (float)h[i];
+  for (int i = 0; i < 4; ++i) {
+    const f16x2_v p = {h[2 * i], h[2 * i + 1]};
+    s = __builtin_amdgcn_fdot2(p, one, s, false);
+  }
   return s;
 }
 // folded LayerNorm: per-lane slice-ordered sums of squares and sums -> 1 / std and mean of the lane's row (lane groups
