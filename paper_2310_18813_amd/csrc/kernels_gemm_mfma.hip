@@ -462,33 +462,38 @@ static void launch_gemm_t(GemmArgs a, int epi, hipStream_t st) {
   if (launch_gemm_rowres(std::is_same<T, bf16_t>::value ? SPEC_DTYPE_BF16 : SPEC_DTYPE_F16, a, epi, st)) return;
   const int KS = a.KS;
   // rows per pass: MT tiles of 16; strips per workgroup: NB.  Neither changes any result.
-  const int MT = a.M <= 16 ? 1 : a.M <= 32 ? 2 : 4;
-  a.passes = (a.M + MT * 16 - 1) / (MT * 16);
-  // Strips per workgroup.  A compute unit keeps a bounded number of cache-line requests in flight, and that is what
-  // a launch here is bound by; a workgroup asks for NB weight fragments (from HBM the first time a strip is read,
-  // from L2 for the other row passes) and MT activation fragments (L2) per 32-k step, so the unit with the most
-  // workgroups sets the time: ceil(workgroups / units) * (NB * weight cost + MT * activation cost), with a request
-  // that goes to HBM about three times as dear as one that hits L2 (measured).  Against doubling NB up to MT:
-  // QKV at d_model 4096 with 17..64 rows 27..36 -> 23..31 us (three strips per workgroup: one workgroup per unit).
-  // Never changes a result.
+  // A compute unit keeps a bounded number of cache-line requests in flight, and that is what a launch here is bound
+  // by; a workgroup asks for NB weight fragments (from HBM the first time a strip is read, from L2 for the other row
+  // passes) and MT activation fragments (L2) per 32-k step, so the unit with the most workgroups sets the time:
+  // ceil(workgroups / units) * (NB * weight cost + MT * activation cost), with a request that goes to HBM about three
+  // times as dear as one that hits L2 (measured).  Against doubling NB up to MT: QKV at d_model 4096 with 17..64
+  // rows 27..36 -> 23..31 us (three strips per workgroup: one workgroup per unit).  Small matrices (a draft model's)
+  // come out with two row tiles per workgroup and more row passes: their few strips then spread over more units.
   const int n_cu = a.n_cu > 0 ? a.n_cu : 256;
-  int NB = 1;
-  if (MT > 1 && epi != EPI_LOGITS) {
+  const int mt_max = a.M <= 16 ? 1 : a.M <= 32 ? 2 : 4;
+  int MT = mt_max, NB = 1;
+  if (mt_max > 1 && epi != EPI_LOGITS) {
     static const int cand[] = {1, 2, 3, 4, 6, 8};
     long best = -1;
-    for (int nb : cand) {
-      const long wgs = (long)((a.NT + nb - 1) / nb) * a.passes;
-      const long per_cu = (wgs + n_cu - 1) / n_cu;
-      const long w_cost = (3000 + 1000 * (a.passes - 1)) / a.passes;  // per strip and step, averaged over the row passes
-      const long cost = per_cu * (nb * w_cost + MT * 1000);
-      if (best < 0 || cost < best) { best = cost; NB = nb; }
+    for (int mt = mt_max; mt >= 1; mt >>= 1) {
+      const int passes = (a.M + mt * 16 - 1) / (mt * 16);
+      for (int nb : cand) {
+        if (mt == 1 && nb > 1) break;  // one row tile per workgroup is built with one strip only
+        const long wgs = (long)((a.NT + nb - 1) / nb) * passes;
+        const long per_cu = (wgs + n_cu - 1) / n_cu;
+        const long w_cost = (3000 + 1000 * (passes - 1)) / passes;  // per strip and step, averaged over the row passes
+        const long cost = per_cu * (nb * w_cost + mt * 1000);
+        if (best < 0 || cost < best) { best = cost; NB = nb; MT = mt; }
+      }
     }
-  } else if (MT > 1) {
+  } else if (mt_max > 1) {
     // the LM head, with its arg-max epilogue per strip, measured better with fewer strips per workgroup than that
     // estimate picks: as many as row tiles while 160 workgroups remain
-    while (NB < MT && (a.NT / (NB * 2)) * a.passes >= 160) NB *= 2;
-    if (MT == 4 && NB == 4 && (a.NT / 8) * a.passes >= 160) NB = 8;
+    const int passes = (a.M + MT * 16 - 1) / (MT * 16);
+    while (NB < MT && (a.NT / (NB * 2)) * passes >= 160) NB *= 2;
+    if (MT == 4 && NB == 4 && (a.NT / 8) * passes >= 160) NB = 8;
   }
+  a.passes = (a.M + MT * 16 - 1) / (MT * 16);
   a.groups = (a.NT + NB - 1) / NB;
   const int blocks = a.passes == 1 ? a.groups : ((a.groups + 7) / 8) * 8 * a.passes;
   dim3 grid(blocks), block(KS * 64);
