@@ -378,7 +378,7 @@ enum {
   SPEC_KCLASS_GEMM_FFN_OUT,   /* down (or fc2) projection + residual            */
   SPEC_KCLASS_GEMM_HEAD,      /* LM head + arg-max partials                     */
   SPEC_KCLASS_ATTENTION,      /* verify attention (both kernels)                */
-  SPEC_KCLASS_NORM,           /* norm kernels (fp32 path); 16-bit path: the row  
+  SPEC_KCLASS_NORM,           /* norm kernels (fp32 path); 16-bit path: the row
                                  statistics kernel of the norms folded into GEMMs */
   SPEC_KCLASS_OTHER,          /* embedding, arg-max merge, accept/commit        */
   SPEC_KCLASS_DRAFT_PASS,     /* one whole forward pass of the draft model      */
