@@ -32,6 +32,15 @@ CASES = {
     # wider bf16 model: 8 k-slices, two row passes (M = 96), two strips per workgroup in the LM head
     "medium_bf16": dict(dtype="bf16", seed=79, B=24, P=12, N=12, s=3, alpha=0.7,
                         tgt=si.llama_desc(1, 512, 4, 1536, 20000, 64), drf=si.llama_desc(1, 256, 4, 512, 20000, 64)),
+    # mixed shapes, for the LayerNorm folded into the GEMMs: LayerNorm in front of a bias-free QKV and a gate/up pair
+    # (the fold has to bring its own bias arrays and the row sums of the interleaved gate/up rows), with rotary positions
+    "ln_swiglu_nobias_fp16": dict(dtype="fp16", seed=84, B=3, P=6, N=14, s=3, alpha=0.7,
+                                  tgt=dict(si.llama_desc(2, 256, 4, 448, 900, 64), norm_kind=si.NORM_LAYER),
+                                  drf=dict(si.llama_desc(1, 128, 2, 160, 900, 64), norm_kind=si.NORM_LAYER)),
+    # ... and with attention biases but none in the feed-forward block, bf16
+    "ln_swiglu_bias_bf16": dict(dtype="bf16", seed=85, B=2, P=7, N=12, s=4, alpha=0.7,
+                                tgt=dict(si.llama_desc(2, 256, 2, 416, 700, 64), norm_kind=si.NORM_LAYER, has_bias=1),
+                                drf=dict(si.llama_desc(1, 128, 2, 160, 700, 64), norm_kind=si.NORM_LAYER, has_bias=1)),
     # context spanning three 256-key attention chunks, ragged against the chunk boundary
     "longctx_bf16": dict(dtype="bf16", seed=80, B=2, P=530, N=12, s=4, alpha=0.8,
                          tgt=si.llama_desc(2, 256, 2, 416, 300, 600), drf=si.llama_desc(1, 128, 2, 160, 300, 600)),
