@@ -49,7 +49,13 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
     int rest = id >> 3;
     pass = rest % a.passes;
     rest /= a.passes;
-    if (PARTIAL) { slice_id = rest % a.KS; rest /= a.KS; }  // one k-slice per workgroup
+    if (PARTIAL) {
+      // one k-slice per workgroup; on an XCD the strip groups of a slice are neighbours in launch order, so the
+      // workgroups that run together read the same k-slice of the activations and its L2 fetches them once
+      const int gpx = (a.groups + 7) >> 3;
+      slice_id = rest / gpx;
+      rest %= gpx;
+    }
     G = rest * 8 + (id & 7);
   }
   if (G >= a.groups) return;
