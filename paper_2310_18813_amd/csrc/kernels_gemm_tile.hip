@@ -44,14 +44,19 @@ __global__ __launch_bounds__(512) void k_gemm_tile(GemmArgs a) {
   constexpr bool PARTIAL = EPI == EPI_PARTIAL;
   int G, pass, slice_id = 0;
   if (!PARTIAL && a.passes == 1) { G = blockIdx.x; pass = 0; }
-  else {  // all passes of a strip group on one XCD (see the streaming kernel)
+  else if (PARTIAL && a.KS == 8) {
+    // one k-slice per workgroup, and one k-slice per XCD (workgroups are dealt round-robin to the 8 XCDs): all
+    // workgroups on an XCD read the same k-slice of the activations, which its L2 then fetches once for the chip
+    const int id = blockIdx.x, rest = id >> 3;
+    slice_id = id & 7;
+    pass = rest % a.passes;
+    G = rest / a.passes;
+  } else {  // all passes of a strip group on one XCD (see the streaming kernel)
     const int id = blockIdx.x;
     int rest = id >> 3;
     pass = rest % a.passes;
     rest /= a.passes;
-    if (PARTIAL) {
-      // one k-slice per workgroup; on an XCD the strip groups of a slice are neighbours in launch order, so the
-      // workgroups that run together read the same k-slice of the activations and its L2 fetches them once
+    if (PARTIAL) {  // one k-slice per workgroup, the strip groups of a slice neighbours in launch order
       const int gpx = (a.groups + 7) >> 3;
       slice_id = rest / gpx;
       rest %= gpx;
@@ -478,7 +483,7 @@ static void launch_tile_t(GemmArgs a, int epi, hipStream_t st) {
   if (split) epi = EPI_PARTIAL;
   a.passes = (a.M + 64 * MTW - 1) / (64 * MTW);
   a.groups = (a.NT + 2 * NBW - 1) / (2 * NBW);
-  const int blocks = split ? ((a.groups + 7) / 8) * 8 * a.passes * a.KS
+  const int blocks = split ? (a.KS == 8 ? a.groups * a.passes * 8 : ((a.groups + 7) / 8) * 8 * a.passes * a.KS)
                            : a.passes == 1 ? a.groups : ((a.groups + 7) / 8) * 8 * a.passes;
   if (MTW == 1) launch_nb_tile<T, 1>(a, NBW, epi, blocks, st);
   else if (MTW == 2) launch_nb_tile<T, 2>(a, NBW, epi, blocks, st);
