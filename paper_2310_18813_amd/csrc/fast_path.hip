@@ -251,7 +251,7 @@ void fast_layer(spec_ctx *c, const Model &m, int layer, int B, int q_rows, int b
     t.seq_groups = seq_groups;
     t.shape = c->attn_shape;
     t.n_cu = c->n_cu;
-    t.NC = std::min(c->NC_max, max_pos / ATTN_CHUNK + 1);
+    t.NC = std::min(c->NC_max, attn_chunk_of(std::max(max_pos, 0)) + 1);
     launch_attention_mfma(dt, t, st);
   }
   {

@@ -253,9 +253,9 @@ __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a) {
   if (unit >= a.B * a.H * a.NC) return;
   const int c = unit % a.NC, bh = unit / a.NC, hh = bh % a.H, b = bh / a.H;
   const WaveSetup w = wave_setup(a, b, lane);
-  const int k0 = c * ATTN_CHUNK;
+  const int k0 = attn_chunk_begin(c);
   if (k0 > w.pmax) return;  // same for the whole wave
-  const int kend = min(k0 + ATTN_CHUNK, w.pmax + 1);
+  const int kend = min(attn_chunk_begin(c + 1), w.pmax + 1);
   const float scale = rsqrtf((float)HD) * LOG2E;  // score scale in base-2 exponent units
   const int d = a.H * HD;
   QFrags<T, HD> qf;
@@ -284,7 +284,7 @@ __global__ void k_attn_merge(AttnArgs a) {
   const size_t at = xpack_index(m, hh * HD + e, d >> 5);
   op_t *out = (op_t *)a.out + at;
   if (pos < 0) { *out = (op_t)0.f; return; }
-  const int nc = pos / ATTN_CHUNK + 1;
+  const int nc = attn_chunk_of(pos) + 1;
   const size_t slot0 = ((size_t)m * a.H + hh) * a.NC;
   const float scale = rsqrtf((float)HD) * LOG2E;  // score scale in base-2 exponent units
   float mr = a.part_ml[slot0 * 2], lr = a.part_ml[slot0 * 2 + 1], ar = a.part_acc[slot0 * HD + e];
@@ -319,8 +319,8 @@ __global__ __launch_bounds__(256) void k_attn_seq(AttnArgs a) {
   f32x4_v ar[HT];
 #pragma unroll
   for (int ht = 0; ht < HT; ++ht) ar[ht] = (f32x4_v){0.f, 0.f, 0.f, 0.f};
-  for (int k0 = 0; k0 <= w.pmax; k0 += ATTN_CHUNK) {
-    const int kend = min(k0 + ATTN_CHUNK, w.pmax + 1);
+  for (int c = 0, k0 = 0; k0 <= w.pmax; k0 = attn_chunk_begin(++c)) {
+    const int kend = min(attn_chunk_begin(c + 1), w.pmax + 1);
     float mc, lc;
     f32x4_v ac[HT];
     chunk_partial<T, HD, true>(kbase, vbase, qf, k0, kend, w.j, w.g, w.pos_j, scale, mc, lc, ac);
@@ -374,9 +374,9 @@ __global__ __launch_bounds__(512) void k_attn_group(AttnArgs a) {
   f32x4_v *pacc = (f32x4_v *)attn_smem;
   float2 *pml = (float2 *)(attn_smem + (size_t)a.NC * HT * 64 * sizeof(f32x4_v));
   for (int c = wv; c < a.NC; c += W) {
-    const int k0 = c * ATTN_CHUNK;
+    const int k0 = attn_chunk_begin(c);
     if (k0 > w.pmax) break;  // same for the whole wave; no row of the sequence reaches this chunk or a later one
-    const int kend = min(k0 + ATTN_CHUNK, w.pmax + 1);
+    const int kend = min(attn_chunk_begin(c + 1), w.pmax + 1);
     float mc, lc;
     f32x4_v ac[HT];
     chunk_partial<T, HD, STREAM>(kbase, vbase, qf, k0, kend, w.j, w.g, w.pos_j, scale, mc, lc, ac);
@@ -386,7 +386,7 @@ __global__ __launch_bounds__(512) void k_attn_group(AttnArgs a) {
   }
   __syncthreads();
   // row j needs the chunks up to its own position; every one of them was computed (pmax >= pos_j)
-  const int nc = w.pos_j >= 0 ? w.pos_j / ATTN_CHUNK + 1 : 0;
+  const int nc = w.pos_j >= 0 ? attn_chunk_of(w.pos_j) + 1 : 0;
   if (w.j >= a.q_rows) return;
   const int m = b * a.q_rows + w.j;
   for (int ht = wv; ht < HT; ht += W) {
@@ -425,7 +425,7 @@ static void launch_attn_group(const AttnArgs &a, int pairs, hipStream_t st) {
 }
 template <class T, int HD>
 static void prepare_attn_group() {  // more than the default 64 KB of LDS has to be asked for
-  const int lds = (int)attn_group_lds(HD, ATTN_GROUP_MAX_WAVES);
+  const int lds = (int)attn_group_lds(HD, ATTN_GROUP_MAX_CHUNKS);
   (void)hipFuncSetAttribute((const void *)k_attn_group<T, HD, true>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   (void)hipFuncSetAttribute((const void *)k_attn_group<T, HD, false>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
 }
@@ -445,7 +445,9 @@ static void launch_attn_hd(const AttnArgs &a, hipStream_t st) {
   // against 81, 32 and 64 sequences 53 and 101 against 57 and 104; 2048 positions x 52 heads, where the alternative
   // is split + merge: 20 sequences 299 against 242, 24 sequences 305 against 287, 32 sequences 326 against 378.
   const int slots = (a.n_cu > 0 ? a.n_cu : 256) * 4, rounds = (pairs + slots - 1) / slots;
-  const bool group_fits = a.NC <= ATTN_GROUP_MAX_WAVES;
+  // ... with a wave per chunk, or every eighth chunk per wave -- unless the waves of the split shape all find a slot at
+  // once: then their shorter chains win (one sequence x 32 heads x 2048 positions: 20.9 us against 26.5)
+  const bool group_fits = a.NC <= ATTN_GROUP_MAX_WAVES || (a.NC <= ATTN_GROUP_MAX_CHUNKS && pairs * a.NC > slots);
   const bool fills = rounds == 1 || (double)pairs >= (group_fits ? 0.85 : 0.7) * (double)rounds * slots;
   const bool seq = a.shape == 2 || (a.shape == 0 && ((pairs >= ATTN_SEQ_MIN_PAIRS && fills) || a.NC == 1));
   // few sequences: a workgroup per (sequence, head), as long as its partials fit into LDS with a wave per chunk

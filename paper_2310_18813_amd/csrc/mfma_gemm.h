@@ -133,10 +133,20 @@ struct AttnArgs {
   int seq_groups;           // consecutive groups of q_rows rows that belong to one sequence and share its cache (0 or 1: one)
   int n_cu;                 // compute units of the device (0: 256)
 };
-constexpr int ATTN_CHUNK = 256;  // keys per split; boundaries at multiples of this position
+// Keys per split.  The chunk boundaries are fixed positions, the same for every launch shape and batch (they decide
+// the order of the softmax merges, hence the bits): 128 keys each up to position 512, where the attention of a small
+// batch is a chain of load latencies and twice the waves halve it, 256 keys beyond.
+constexpr int ATTN_CHUNK = 256, ATTN_FINE_CHUNK = 128, ATTN_FINE_END = 512, ATTN_FINE_CHUNKS = ATTN_FINE_END / ATTN_FINE_CHUNK;
+__host__ __device__ inline int attn_chunk_begin(int c) {
+  return c < ATTN_FINE_CHUNKS ? c * ATTN_FINE_CHUNK : ATTN_FINE_END + (c - ATTN_FINE_CHUNKS) * ATTN_CHUNK;
+}
+__host__ __device__ inline int attn_chunk_of(int pos) {  // the chunk that holds key position pos >= 0
+  return pos < ATTN_FINE_END ? pos / ATTN_FINE_CHUNK : ATTN_FINE_CHUNKS + (pos - ATTN_FINE_END) / ATTN_CHUNK;
+}
 constexpr int ATTN_STREAM_MIN_WAVES = 1024;  // (sequence, head, chunk) waves from which the split kernel loads non-temporally
 constexpr int ATTN_SEQ_MIN_PAIRS = 768;   // (sequence, head) pairs from which one wave walks all chunks (measured: 24 sequences x 32 heads 55 -> 45 us)
-constexpr int ATTN_GROUP_MAX_WAVES = 8;  // chunks (= waves) of the one-workgroup-per-(sequence, head) shape: 70 KB of partials at head_dim 128 (four waves with the register budget of the split kernel were measured no faster, and slower at 16 sequences)
+constexpr int ATTN_GROUP_MAX_WAVES = 8;  // waves of the one-workgroup-per-(sequence, head) shape, a chunk each (four waves with the register budget of the split kernel were measured no faster, and slower at 16 sequences)
+constexpr int ATTN_GROUP_MAX_CHUNKS = 16;  // ... or every eighth chunk each when there are more: 139 KB of partials at head_dim 128 (2560 positions)
 void launch_attention_mfma(int dtype, const AttnArgs &a, hipStream_t st);
 
 }  // namespace spec

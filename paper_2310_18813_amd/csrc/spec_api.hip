@@ -117,7 +117,7 @@ static Sizes compute_sizes(const spec_model_desc *tgt, const spec_model_desc *dr
   z.act = al256(M * d * 4) + 2 * al256(Mp * d * e) + al256(Mp * d * 4) + al256(Mp * f * e) + al256(M * wide * 4) + al256(M * V * 4) +
           3 * al256(M * 4);
   // matrix-core path: split-KV attention partials and per-strip arg-max partials
-  const size_t NC = (L + ATTN_CHUNK - 1) / ATTN_CHUNK, NTh = (V + 15) / 16;
+  const size_t NC = (size_t)attn_chunk_of((int)std::max<size_t>(L, 1) - 1) + 1, NTh = (V + 15) / 16;
   z.act += al256(M * d * NC * 4) + al256(M * (d / 64 + 1) * NC * 2 * 4) + 2 * al256(M * NTh * 4);
   if (M > 32) z.act += al256(8 * Mp * d * 4);  // k-slice sums of the split residual GEMMs
   z.act += 2 * al256(M * 4);  // 1 / rms (or 1 / std) and mean per row (folded norm)
@@ -277,7 +277,7 @@ extern "C" int spec_init(const spec_model_desc *tgt, const spec_weights *tgt_w, 
   W.row_pos = (int32_t *)carve(p, M * 4);
   W.row_seq = (int32_t *)carve(p, M * 4);
   {
-    const size_t NC = (L + ATTN_CHUNK - 1) / ATTN_CHUNK, NTh = (V + 15) / 16;
+    const size_t NC = (size_t)attn_chunk_of((int)std::max<size_t>(L, 1) - 1) + 1, NTh = (V + 15) / 16;
     c->NC_max = (int)NC;
     W.attn_part = (float *)carve(p, M * d * NC * 4);
     W.attn_ml = (float *)carve(p, M * (d / 64 + 1) * NC * 2 * 4);

@@ -41,7 +41,7 @@ CASES = {
     "ln_swiglu_bias_bf16": dict(dtype="bf16", seed=85, B=2, P=7, N=12, s=4, alpha=0.7,
                                 tgt=dict(si.llama_desc(2, 256, 2, 416, 700, 64), norm_kind=si.NORM_LAYER, has_bias=1),
                                 drf=dict(si.llama_desc(1, 128, 2, 160, 700, 64), norm_kind=si.NORM_LAYER, has_bias=1)),
-    # context spanning three 256-key attention chunks, ragged against the chunk boundary
+    # context spanning five attention chunks (four of 128 keys, one of 256), ragged against the chunk boundary
     "longctx_bf16": dict(dtype="bf16", seed=80, B=2, P=530, N=12, s=4, alpha=0.8,
                          tgt=si.llama_desc(2, 256, 2, 416, 300, 600), drf=si.llama_desc(1, 128, 2, 160, 300, 600)),
 }
@@ -328,15 +328,16 @@ def test_call_order_and_capacity_errors(orc, B):
     assert e.value.code == B.ERR_CAPACITY
 
 
-@pytest.mark.parametrize("L_max,kv", [(640, 600), (2048, 1990), (2304, 2250)])
+@pytest.mark.parametrize("L_max,kv", [(640, 600), (2048, 1990), (3840, 3700)])
 def test_attention_launch_shapes_give_identical_bits(orc, B, L_max, kv):
     """The launch shapes of the verify attention (split over chunks + merge kernel; one wave per sequence and
     head; one workgroup per sequence and head) must agree bit for bit: the batch size picks between them."""
     dtype, seed = "bf16", 5
     tdesc = si.llama_desc(1, 256, 2, 416, 300, L_max + 8)
     w = si.make_weights(tdesc, dtype, seed, device=DEV, emb_std=1.0)
-    # 600 cached positions: three 256-key chunks, the last one ragged; 1990: eight, the most the one-workgroup
-    # shape takes (70 KB of partials in LDS); 2250: nine, where that shape hands over to split + merge
+    # 600 cached positions: five chunks (four of 128 keys, then 256-key ones), the last one ragged; 1990: ten, more
+    # than the one-workgroup shape has waves (they take two chunks each); 3700: seventeen, where that shape hands over
+    # to split + merge
     ctx = B.Context(tdesc, w, None, None, dtype, 3, 4, L_max, 4, B.PROPOSALS_EXTERNAL, DEV)
     K, V = si.make_kv(3, 256, kv, dtype, seed, DEV)
     ctx.spec_kv_import(B.MODEL_TARGET, 0, K, V)

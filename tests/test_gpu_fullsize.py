@@ -3,8 +3,8 @@
     positions per sequence), M = 1 .. 576;
   * the width of the 13B OPT shape (fp16, d=5120, 40 heads, ReLU 20480, LayerNorm, biases, learned positions,
     ragged vocabulary 50272);
-  * the width of the 33B shape with long prompts (bf16, d=6656, 52 heads, SwiGLU 17920, 2100 cached positions: nine
-    256-key attention chunks, i.e. the split + merge and the one-wave-per-(sequence, head) launch shapes);
+  * the width of the 33B shape with long prompts (bf16, d=6656, 52 heads, SwiGLU 17920, 2100 cached positions: eleven
+    attention chunks, i.e. the one-workgroup and the one-wave-per-(sequence, head) launch shapes);
   * full depth: every layer of the 7B shape (32) and sampled layers of the 13B shape (40), each against the oracle on
     the very rows the GPU fed it, the end-to-end logits and tokens, and the 13B shape's 12-layer draft end to end.
 The oracle recomputes sampled sequences one by one; properties that hold at any size cover the rest."""
