@@ -443,12 +443,15 @@ static void launch_attn_hd(const AttnArgs &a, hipStream_t st) {
   // units that hold a second workgroup take twice as long as the others.  Measured (us per layer): 512 cached
   // positions x 32 heads, a workgroup per pair as the alternative: 33 sequences 86 against 64, 48 sequences 92
   // against 81, 32 and 64 sequences 53 and 101 against 57 and 104; 2048 positions x 52 heads, where the alternative
-  // is split + merge: 20 sequences 299 against 242, 24 sequences 305 against 287, 32 sequences 326 against 378.
+  // was split + merge: 20 sequences 299 against 242, 24 sequences 305 against 287, 32 sequences 326 against 378.
   const int slots = (a.n_cu > 0 ? a.n_cu : 256) * 4, rounds = (pairs + slots - 1) / slots;
   // ... with a wave per chunk, or every eighth chunk per wave -- unless the waves of the split shape all find a slot at
   // once: then their shorter chains win (one sequence x 32 heads x 2048 positions: 20.9 us against 26.5)
   const bool group_fits = a.NC <= ATTN_GROUP_MAX_WAVES || (a.NC <= ATTN_GROUP_MAX_CHUNKS && pairs * a.NC > slots);
-  const bool fills = rounds == 1 || (double)pairs >= (group_fits ? 0.85 : 0.7) * (double)rounds * slots;
+  // (2048 positions x 52 heads, the workgroup shape with its waves at two chunks each as the alternative: 28 sequences
+  // 303 against 276 us, 32 sequences 312 against 318)
+  const double full = !group_fits ? 0.7 : a.NC <= ATTN_GROUP_MAX_WAVES ? 0.85 : 0.8;
+  const bool fills = rounds == 1 || (double)pairs >= full * (double)rounds * slots;
   const bool seq = a.shape == 2 || (a.shape == 0 && ((pairs >= ATTN_SEQ_MIN_PAIRS && fills) || a.NC == 1));
   // few sequences: a workgroup per (sequence, head), as long as its partials fit into LDS with a wave per chunk
   const bool group = !seq && (a.shape == 3 || a.shape == 0) && group_fits;
