@@ -472,7 +472,12 @@ static int forward_pass(spec_ctx *c, Model &m, const PassArgs &pa, HeadMode head
 // consecutive positions; all groups of a sequence read and write that sequence's cache, so few sequences with
 // long prompts need few passes over the weights (one sequence, M_max >= P-1: a single pass).
 static int prefill(spec_ctx *c, int b0, int B, int P) {
-  const int per = std::max(1, c->M_max / B);
+  int per = std::max(1, c->M_max / B);
+  // The tiled GEMMs' time grows in steps of 128 rows (a pass of 576 rows costs what 640 would): the largest row count
+  // that is a whole number of such steps, if it is within a quarter of the largest that fits, costs least per row
+  // (64 sequences: 8 positions per pass, 512 rows, instead of 9: 7B shape 204 -> 169 ms for 8128 prompt tokens).
+  for (int p = per; p >= 1 && 4 * p >= 3 * per; --p)
+    if ((B * p) % 128 == 0) { per = p; break; }
   const int q = std::min(Q_LIMIT, per), g = std::max(1, per / q);
   for (int base = 0; base < P - 1; base += g * q) {
     const int left = P - 1 - base;
