@@ -301,10 +301,10 @@ __global__ void k_attn_merge(AttnArgs a) {
 
 // Launch shape 2: one wave per (sequence, head) walks all chunks, merging in registers.
 template <class T, int HD>
-__global__ __launch_bounds__(256) void k_attn_seq(AttnArgs a) {
+__global__ __launch_bounds__(256) void k_attn_seq(AttnArgs a) {  // launched with 64: the bound only keeps the register budget
   constexpr int HT = HD / 16;
   const int lane = threadIdx.x & 63;
-  const int bh = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);  // workgroups of one wave or of four
+  const int bh = blockIdx.x;  // a workgroup is one wave
   if (bh >= a.B * a.H) return;
   const int hh = bh % a.H, b = bh / a.H;
   const WaveSetup w = wave_setup(a, b, lane);
@@ -456,10 +456,10 @@ static void launch_attn_hd(const AttnArgs &a, hipStream_t st) {
   // few sequences: a workgroup per (sequence, head), as long as its partials fit into LDS with a wave per chunk
   const bool group = !seq && (a.shape == 3 || a.shape == 0) && group_fits;
   if (seq) {
-    // fewer pairs than one round of wave slots: workgroups of one wave, so that they spread over all compute units
-    // (measured, us per layer at 32 heads: 4 sequences x 100 positions 15.1 -> 11.8, 24 x 250 29.6 -> 26.6)
-    if (pairs < slots) hipLaunchKernelGGL((k_attn_seq<T, HD>), dim3(pairs), dim3(64), 0, st, a);
-    else hipLaunchKernelGGL((k_attn_seq<T, HD>), dim3((pairs + 3) / 4), dim3(256), 0, st, a);
+    // workgroups of one wave: few pairs then spread over all compute units (measured, us per layer at 32 heads: 4
+    // sequences x 100 positions 15.1 -> 11.8, 24 x 250 29.6 -> 26.6), and many pairs drain evenly (64 sequences x 300
+    // positions 72.5 -> 71.4 against workgroups of four waves; 32 sequences x 52 heads x 2048 positions: the same)
+    hipLaunchKernelGGL((k_attn_seq<T, HD>), dim3(pairs), dim3(64), 0, st, a);
   } else if (group) {
     if (pairs * a.NC >= ATTN_STREAM_MIN_WAVES) launch_attn_group<T, HD, true>(a, pairs, st);
     else launch_attn_group<T, HD, false>(a, pairs, st);
