@@ -143,7 +143,7 @@ __host__ __device__ inline int attn_chunk_begin(int c) {
 __host__ __device__ inline int attn_chunk_of(int pos) {  // the chunk that holds key position pos >= 0
   return pos < ATTN_FINE_END ? pos / ATTN_FINE_CHUNK : ATTN_FINE_CHUNKS + (pos - ATTN_FINE_END) / ATTN_CHUNK;
 }
-constexpr int ATTN_STREAM_MIN_WAVES = 1024;  // (sequence, head, chunk) waves from which the split kernel loads non-temporally
+constexpr int ATTN_STREAM_MIN_WAVES = 2048;  // (sequence, head, chunk) waves from which the chunk kernels load non-temporally (8 sequences x 32 heads x 512 positions: 18.8 us with, 17.1 without; 16 sequences: 32.7 with, 34.2 without)
 constexpr int ATTN_SEQ_MIN_PAIRS = 768;   // (sequence, head) pairs from which one wave walks all chunks (measured: 24 sequences x 32 heads 55 -> 45 us)
 constexpr int ATTN_GROUP_MAX_WAVES = 8;  // waves of the one-workgroup-per-(sequence, head) shape, a chunk each (four waves with the register budget of the split kernel were measured no faster, and slower at 16 sequences)
 constexpr int ATTN_GROUP_MAX_CHUNKS = 16;  // ... or every eighth chunk each when there are more: 139 KB of partials at head_dim 128 (2560 positions)
